@@ -1,0 +1,168 @@
+/*
+ * kfac.h -- C ABI of the MI355X (gfx950) K-FAC hot path.
+ *
+ * One natural-gradient step of SP-NGD (arXiv 2002.06015) for the layers that
+ * live on one GPU: Kronecker factors A and G of every Conv/FC layer (Sec. 3.3),
+ * their running averages, the pi-split damped inverses (Eq. 12), the
+ * preconditioned gradient G^-1 dW A^-1 (Eq. 6 with Eq. 7), and the unit-wise
+ * 2x2 Fisher of BatchNorm scale/shift (Sec. 4.2).
+ *
+ * General rules for every entry point
+ *   - "dev" pointers are device (HBM) pointers owned by the caller; "host"
+ *     pointers are ordinary host memory, read during the call only.
+ *   - Every entry point that takes a layer list processes all listed layers in
+ *     a few grouped launches; per-layer device pointers are passed as HOST
+ *     arrays of device pointers.
+ *   - All work is enqueued on the HIP stream given to kfac_create; calls return
+ *     without waiting for the GPU.  A context is used by one host thread at a time.
+ *   - The library allocates no device memory: scratch comes from the caller's
+ *     workspace (size from kfac_workspace_bytes for the same layer list).
+ *   - Matrices are dense, row-major, leading dimension = number of columns.
+ *     Factors and inverses are stored in full (both triangles, exactly symmetric).
+ *   - Argument errors are found before anything is launched and leave all
+ *     buffers untouched.  Numerical failure (a non-positive pivot) is reported
+ *     through the device array `info`, never by aborting.
+ *   - Outputs must not overlap inputs unless stated.
+ */
+#ifndef KFAC_H
+#define KFAC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KFAC_OK = 0,
+    KFAC_ERR_INVALID = 1,    /* null pointer, bad dimension, bad scalar */
+    KFAC_ERR_WORKSPACE = 2,  /* caller's workspace is too small for this call */
+    KFAC_ERR_NOT_PD = 3,     /* reserved for host-side reporting by callers that read `info` */
+    KFAC_ERR_DEVICE = 4      /* a HIP runtime call failed */
+} kfac_status;
+
+typedef enum {
+    KFAC_F32 = 0,            /* activations / output gradients are float32 */
+    KFAC_BF16 = 1            /* ... are bfloat16 (products exact in fp32, fp32 accumulation) */
+} kfac_dtype;
+
+/*
+ * One Conv or FC layer (Sec. 3.3).  A fully-connected layer is k=1, stride=1,
+ * pad=0, h_in=w_in=1.  Square kernels, zero padding, dilation 1, output size
+ * h = floor((h_in + 2 pad - k)/stride) + 1.  dA = c_in*k*k + bias, dG = c_out.
+ * bias != 0 appends a constant-one row LAST to the patch matrix (the paper
+ * drops the bias; this is the homogeneous-coordinate extension), so A gains a
+ * row/column and the last column of grad_W is the bias gradient.
+ */
+typedef struct {
+    int32_t N;        /* samples in the local mini-batch */
+    int32_t c_in, c_out;
+    int32_t k, stride, pad;
+    int32_t h_in, w_in;
+    int32_t bias;     /* 0 or 1 */
+} kfac_layer;
+
+typedef struct kfac_ctx kfac_ctx;
+
+const char *kfac_status_string(kfac_status s);
+
+/* Validates a layer and returns its derived sizes (any out pointer may be NULL). Host only. */
+kfac_status kfac_layer_dims(const kfac_layer *L, int32_t *dA, int32_t *dG, int32_t *h, int32_t *w);
+
+/*
+ * Bytes of device workspace that any single call below needs for the layer list
+ * L[0..n_layers) with inputs of type `in`.  Returns 0 on invalid arguments.  Host only.
+ */
+size_t kfac_workspace_bytes(const kfac_layer *L, int32_t n_layers, kfac_dtype in);
+
+/*
+ * Creates a context bound to a HIP stream (hipStream_t passed as void*, NULL =
+ * the default stream) and a caller-owned device workspace (256-byte aligned).
+ * Touches no GPU state until the first launch.
+ */
+kfac_status kfac_create(kfac_ctx **out, void *hip_stream, void *workspace_dev, size_t workspace_bytes);
+void kfac_destroy(kfac_ctx *ctx);
+
+/*
+ * Patch extraction, Sec. 3.3 Eq. 10:  M_A = im2col(A) in R^{c_in k^2 x h w}.
+ * act: dev [N, c_in, h_in, w_in] (NCHW) of type `dt`.  patches: dev, same type,
+ * [c_in*k*k, ld] row-major; row r = (c*k + ky)*k + kx, column m = n*h*w + y*w + x
+ * holds act[n, c, y*stride+ky-pad, x*stride+kx-pad] (0 outside the image).
+ * ld >= N*h*w; columns [N*h*w, ld) are left untouched.  The bias row is not
+ * materialised (kfac_stats supplies it on the fly).
+ */
+kfac_status kfac_im2col(kfac_ctx *ctx, const kfac_layer *L, kfac_dtype dt,
+                        const void *act, void *patches, int64_t ld);
+
+/*
+ * Factor construction + running average, Sec. 3.3 Eq. 9 (FC) and Eq. 11 (Conv):
+ *   A_batch = 1/(N h w) sum_n M_A(n) M_A(n)^T     (with the bias row if L.bias)
+ *   G_batch = 1/N sum_n D_n D_n^T,  D_n = grad_out[n] as a c_out x hw matrix
+ *             (also divided by h*w if g_spatial_mean != 0; the paper does not)
+ *   X_ema  <- decay * X_ema + (1 - decay) * X_batch         (0 <= decay < 1;
+ *             decay == 0 overwrites and never reads the old contents)
+ * act[l]:      dev [N, c_in, h_in, w_in] of type `in`, or NULL to skip A of layer l
+ *              (act == NULL skips A for all layers).
+ * grad_out[l]: dev [N, c_out, h, w] of type `in`: PER-SAMPLE gradient of log p
+ *              w.r.t. the layer output (unscaled by 1/N); NULL skips G.
+ * A_ema[l]:    dev in/out [dA, dA] fp32;  G_ema[l]: dev in/out [dG, dG] fp32.
+ * E[.] is the mean over the N local samples.
+ */
+kfac_status kfac_stats(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
+                       const void *const *act, const void *const *grad_out,
+                       float decay, int32_t g_spatial_mean,
+                       float *const *A_ema, float *const *G_ema);
+
+/*
+ * Damped inversion of both factors, Sec. 3.3 Eq. 12 (right-hand side):
+ *   pi^2 = (tr A_ema / dA) / (tr G_ema / dG)   (pi = 1 if a trace is not positive)
+ *   A_inv = (A_ema + pi*gamma I)^-1,   G_inv = (G_ema + gamma/pi I)^-1,
+ * gamma = sqrt(lambda) >= 0.  The stored running averages are not modified.
+ * A_inv[l], G_inv[l]: dev out, full symmetric.  pi_out: dev [n_layers] or NULL.
+ * info: dev int32 [2*n_layers] or NULL; info[2l] (A) / info[2l+1] (G) is 0, or
+ * the 1-based index of a non-positive pivot (the matrix was not positive
+ * definite; its inverse is then meaningless).
+ * Passing a subset of the layers refreshes only their inverses (Algorithm 1).
+ */
+kfac_status kfac_invert(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L,
+                        const float *const *A_ema, const float *const *G_ema, float gamma,
+                        float *const *A_inv, float *const *G_inv, float *pi_out, int32_t *info);
+
+/*
+ * Natural-gradient direction, Eq. 6 with F = G (x) A (Eq. 7) and Eq. 12, in
+ * matrix form for W in R^{dG x dA} (row = output channel):
+ *   out = G_inv * grad_W * A_inv .
+ * grad_W[l], out[l]: dev [dG, dA]; out[l] may equal grad_W[l].
+ */
+kfac_status kfac_precondition(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L,
+                              const float *const *G_inv, const float *const *A_inv,
+                              const float *const *grad_W, float *const *out);
+
+/*
+ * Unit-wise natural gradient for BatchNorm, Sec. 4.2 Eq. 15-17.  Per layer l
+ * and channel i, with per-sample gradients gg = g_gamma[l][n, i], gb = g_beta[l][n, i]:
+ *   F_batch = mean_n (gg^2, gg*gb, gb^2);  F_ema[l][i, 0..2] <- decay F_ema + (1-decay) F_batch
+ *   [out_gamma, out_beta] = (F + lambda I)^-1 [mean_n gg, mean_n gb]   (2x2 closed form)
+ * g_gamma[l], g_beta[l]: dev [N, C[l]];  F_ema[l]: dev in/out [C[l], 3];
+ * out_gamma[l], out_beta[l]: dev [C[l]].  C: host array.  lambda >= 0 is used as is.
+ */
+kfac_status bn_unitwise_precondition(kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,
+                                     const float *const *g_gamma, const float *const *g_beta,
+                                     float decay, float lambda, float *const *F_ema,
+                                     float *const *out_gamma, float *const *out_beta);
+
+/*
+ * Producer of the per-sample BatchNorm gradients used above (Sec. 4.2): for
+ * y = gamma*xhat + beta,  g_gamma[n, c] = sum_t dy[n,c,t]*xhat[n,c,t],
+ * g_beta[n, c] = sum_t dy[n,c,t].  dy[l], xhat[l]: dev fp32 [N, C[l], HW[l]];
+ * g_gamma[l], g_beta[l]: dev out [N, C[l]].
+ */
+kfac_status bn_unitwise_reduce_nchw(kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,
+                                    const int32_t *HW, const float *const *dy, const float *const *xhat,
+                                    float *const *g_gamma, float *const *g_beta);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KFAC_H */

@@ -1,0 +1,481 @@
+// Grouped "NT" GEMM on the gfx950 matrix cores: for every problem in a device table,
+//     C[i][j] = alpha * sum_m a(i, m) * b(j, m) + beta * C[i][j]
+// where both operands have their rows along the contraction index (see Operand).
+// This one kernel carries every dense contraction of the K-FAC step:
+//   - the Kronecker factors A = E[M_A M_A^T], G = E[D D^T] (Sec. 3.3, Eq. 9 and 11):
+//     a == b, only lower-triangle tiles are computed and mirrored, the running average
+//     is the alpha/beta epilogue, long contractions are split along K into partial tiles
+//     that a second kernel sums in a fixed order (bitwise reproducible);
+//   - the Schur-complement products of the blocked inverse (Eq. 12);
+//   - the two products of the preconditioned gradient G^-1 dW A^-1 (Eq. 6).
+//
+// Tiling: a 256-thread workgroup (2x2 wavefronts of 64) owns a BM x BN tile; each
+// wavefront owns TM x TN blocks of 32x32 computed with v_mfma_f32_32x32x2_f32 (fp32)
+// or v_mfma_f32_32x32x16_bf16.  The contraction runs in tiles of 32 staged through LDS
+// (one stage in LDS, the next one in flight in registers).
+#include "kfac_internal.h"
+
+namespace kfac {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short ushortx8 __attribute__((ext_vector_type(8)));
+typedef unsigned short ushortx4 __attribute__((ext_vector_type(4)));
+
+constexpr int KT = 32;      // contraction tile
+constexpr int LDF = 36;     // LDS row length in floats (32 + 4 pad: conflict-free 16-byte reads)
+constexpr int LDH = 40;     // LDS row length in bf16 (32 + 8 pad)
+
+__device__ __forceinline__ int find_problem(const int *start, int n, int wg)
+{
+    int lo = 0, hi = n;  // invariant: start[lo] <= wg < start[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (start[mid] <= wg) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ void tri_decode(int t, int &tm, int &tn)
+{
+    int r = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
+    while (r * (r + 1) / 2 > t) --r;
+    while ((r + 1) * (r + 2) / 2 <= t) ++r;
+    tm = r;
+    tn = t - r * (r + 1) / 2;
+}
+
+// Final write of one element of C (and of its mirror / transposed copy).
+__device__ __forceinline__ void store_result(const GemmProblem &P, bool diag_tile, int i, int j, float acc)
+{
+    if (i >= P.M || j >= P.N) return;
+    const bool sym = (P.flags & GEMM_SYM) != 0;
+    if (sym && diag_tile && j > i) return;  // the mirror of (j, i) writes this one
+    float *c = P.C + (long long)i * P.ldc + j;
+    float v = P.alpha * acc;
+    if (P.beta != 0.0f) v += P.beta * (*c);
+    *c = v;
+    if (sym && i != j) P.C[(long long)j * P.ldc + i] = v;
+    if (P.Ct) P.Ct[(long long)j * P.ldct + i] = v;
+}
+
+// ------------------------------------------------------------------ operand loader (fp32)
+template <int BR>  // rows of the operand tile
+struct LoaderF32 {
+    static constexpr int NREG = BR / 8;  // floats held per thread for one tile
+    const float *base;
+    long long row_stride, batch_stride;
+    int rows, hw, ones_row, vec;
+    int row0;       // first row of the tile
+    int koff, r0;   // this thread's k offset inside the tile and first row slot
+    int m, n, t;    // current contraction index of this thread and its (batch, run) split
+    int kend;
+
+    __device__ __forceinline__ void init(const Operand &op, int tile_row0, int k0, int k1, int tid)
+    {
+        base = (const float *)op.base;
+        row_stride = op.row_stride; batch_stride = op.batch_stride;
+        rows = op.rows; hw = op.hw; ones_row = op.ones_row; vec = op.vec;
+        row0 = tile_row0; kend = k1;
+        if (vec == 4) { koff = (tid & 7) * 4; r0 = tid >> 3; }
+        else          { koff = tid & 31;      r0 = tid >> 5; }
+        m = k0 + koff;
+        n = m / hw;
+        t = m - n * hw;
+    }
+    __device__ __forceinline__ void advance()
+    {
+        m += KT; t += KT;
+        while (t >= hw) { t -= hw; ++n; }
+    }
+    __device__ __forceinline__ void load(float (&reg)[NREG]) const
+    {
+        const long long col = (long long)n * batch_stride + t;
+        if (vec == 4) {
+#pragma unroll
+            for (int s = 0; s < BR / 32; ++s) {
+                const int row = row0 + r0 + 32 * s;
+                floatx4 v = {0.f, 0.f, 0.f, 0.f};
+                if (row == ones_row) {
+                    v[0] = (m + 0 < kend) ? 1.f : 0.f; v[1] = (m + 1 < kend) ? 1.f : 0.f;
+                    v[2] = (m + 2 < kend) ? 1.f : 0.f; v[3] = (m + 3 < kend) ? 1.f : 0.f;
+                } else if (row < rows && m < kend) {
+                    const float *p = base + (long long)row * row_stride + col;
+                    if (m + 3 < kend) {
+                        v = *(const floatx4 *)p;
+                    } else {
+                        v[0] = p[0];
+                        if (m + 1 < kend) v[1] = p[1];
+                        if (m + 2 < kend) v[2] = p[2];
+                    }
+                }
+                reg[4 * s + 0] = v[0]; reg[4 * s + 1] = v[1]; reg[4 * s + 2] = v[2]; reg[4 * s + 3] = v[3];
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < BR / 8; ++s) {
+                const int row = row0 + r0 + 8 * s;
+                float v = 0.f;
+                if (m < kend) {
+                    if (row == ones_row) v = 1.f;
+                    else if (row < rows) v = base[(long long)row * row_stride + col];
+                }
+                reg[s] = v;
+            }
+        }
+    }
+    __device__ __forceinline__ void store_lds(const float (&reg)[NREG], float *lds) const
+    {
+        if (vec == 4) {
+#pragma unroll
+            for (int s = 0; s < BR / 32; ++s) {
+                floatx4 v = {reg[4 * s], reg[4 * s + 1], reg[4 * s + 2], reg[4 * s + 3]};
+                *(floatx4 *)(lds + (r0 + 32 * s) * LDF + koff) = v;
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < BR / 8; ++s) lds[(r0 + 8 * s) * LDF + koff] = reg[s];
+        }
+    }
+};
+
+// ------------------------------------------------------------------ fp32 kernel
+template <int TM, int TN>
+__global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__restrict__ probs,
+                                                          const int *__restrict__ tile_start, int n_probs)
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    __shared__ __attribute__((aligned(16))) float lds_a[BM * LDF];
+    __shared__ __attribute__((aligned(16))) float lds_b[BN * LDF];
+
+    const int wg = blockIdx.x;
+    const int pi = find_problem(tile_start, n_probs, wg);
+    const GemmProblem &P = probs[pi];
+    const int local = wg - tile_start[pi];
+    const int split = local % P.splits;
+    const int tile = local / P.splits;
+    int tm, tn;
+    if (P.flags & GEMM_SYM) tri_decode(tile, tm, tn);
+    else { tm = tile / P.tiles_n; tn = tile - tm * P.tiles_n; }
+    const int k0 = split * P.k_per_split;
+    const int k1 = min(P.K, k0 + P.k_per_split);
+    const int tid = threadIdx.x;
+
+    LoaderF32<BM> la;
+    LoaderF32<BN> lb;
+    la.init(P.a, tm * BM, k0, k1, tid);
+    lb.init(P.b, tn * BN, k0, k1, tid);
+    float ra[BM / 8], rb[BN / 8];
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int lane = tid & 63, wid = tid >> 6;
+    const int wave_m = wid >> 1, wave_n = wid & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    const int nk = (k1 - k0 + KT - 1) / KT;
+    if (nk > 0) { la.load(ra); lb.load(rb); }
+    for (int it = 0; it < nk; ++it) {
+        __syncthreads();
+        la.store_lds(ra, lds_a);
+        lb.store_lds(rb, lds_b);
+        __syncthreads();
+        if (it + 1 < nk) {
+            la.advance(); lb.advance();
+            la.load(ra); lb.load(rb);
+        }
+        // each half-wave takes 16 consecutive k of the tile (the same 16 for both operands)
+        floatx4 fa[TM][4], fb[TN][4];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const float *p = lds_a + (wave_m * 32 * TM + i * 32 + l32) * LDF + half * 16;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) fa[i][q] = *(const floatx4 *)(p + 4 * q);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const float *p = lds_b + (wave_n * 32 * TN + j * 32 + l32) * LDF + half * 16;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) fb[j][q] = *(const floatx4 *)(p + 4 * q);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][q][e], fb[j][q][e], acc[i][j], 0, 0, 0);
+    }
+
+    // accumulator layout of the 32x32 block: column = lane % 32,
+    // row = 8 * (v / 4) + 4 * (lane / 32) + v % 4 for register v = 0..15
+    const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
+    if (P.splits > 1) {
+        float *part = P.partial + ((long long)tile * P.splits + split) * (BM * BN);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = wave_m * 32 * TM + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                    const int c = wave_n * 32 * TN + j * 32 + l32;
+                    part[r * BN + c] = acc[i][j][v];
+                }
+    } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = tm * BM + wave_m * 32 * TM + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                    const int c = tn * BN + wave_n * 32 * TN + j * 32 + l32;
+                    store_result(P, diag_tile, r, c, acc[i][j][v]);
+                }
+    }
+}
+
+// ------------------------------------------------------------------ bf16 operand loader
+// Operands are bf16 in memory; a tile row is 32 bf16 = 64 bytes in LDS (+ pad).
+template <int BR>
+struct LoaderBF16 {
+    static constexpr int NREG = BR / 8;  // bf16 values held per thread for one tile
+    const unsigned short *base;
+    long long row_stride, batch_stride;
+    int rows, hw, ones_row, vec;
+    int row0, koff, r0, m, n, t, kend;
+
+    __device__ __forceinline__ void init(const Operand &op, int tile_row0, int k0, int k1, int tid)
+    {
+        base = (const unsigned short *)op.base;
+        row_stride = op.row_stride; batch_stride = op.batch_stride;
+        rows = op.rows; hw = op.hw; ones_row = op.ones_row; vec = op.vec;
+        row0 = tile_row0; kend = k1;
+        if (vec == 4) { koff = (tid & 7) * 4; r0 = tid >> 3; }
+        else          { koff = tid & 31;      r0 = tid >> 5; }
+        m = k0 + koff;
+        n = m / hw;
+        t = m - n * hw;
+    }
+    __device__ __forceinline__ void advance()
+    {
+        m += KT; t += KT;
+        while (t >= hw) { t -= hw; ++n; }
+    }
+    __device__ __forceinline__ void load(unsigned short (&reg)[NREG]) const
+    {
+        const unsigned short one = 0x3F80;  // 1.0 in bf16
+        const long long col = (long long)n * batch_stride + t;
+        if (vec == 4) {
+#pragma unroll
+            for (int s = 0; s < BR / 32; ++s) {
+                const int row = row0 + r0 + 32 * s;
+                ushortx4 v = {0, 0, 0, 0};
+                if (row == ones_row) {
+                    v[0] = (m + 0 < kend) ? one : 0; v[1] = (m + 1 < kend) ? one : 0;
+                    v[2] = (m + 2 < kend) ? one : 0; v[3] = (m + 3 < kend) ? one : 0;
+                } else if (row < rows && m < kend) {
+                    const unsigned short *p = base + (long long)row * row_stride + col;
+                    if (m + 3 < kend) {
+                        v = *(const ushortx4 *)p;
+                    } else {
+                        v[0] = p[0];
+                        if (m + 1 < kend) v[1] = p[1];
+                        if (m + 2 < kend) v[2] = p[2];
+                    }
+                }
+                reg[4 * s + 0] = v[0]; reg[4 * s + 1] = v[1]; reg[4 * s + 2] = v[2]; reg[4 * s + 3] = v[3];
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < BR / 8; ++s) {
+                const int row = row0 + r0 + 8 * s;
+                unsigned short v = 0;
+                if (m < kend) {
+                    if (row == ones_row) v = one;
+                    else if (row < rows) v = base[(long long)row * row_stride + col];
+                }
+                reg[s] = v;
+            }
+        }
+    }
+    __device__ __forceinline__ void store_lds(const unsigned short (&reg)[NREG], unsigned short *lds) const
+    {
+        if (vec == 4) {
+#pragma unroll
+            for (int s = 0; s < BR / 32; ++s) {
+                ushortx4 v = {reg[4 * s], reg[4 * s + 1], reg[4 * s + 2], reg[4 * s + 3]};
+                *(ushortx4 *)(lds + (r0 + 32 * s) * LDH + koff) = v;
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < BR / 8; ++s) lds[(r0 + 8 * s) * LDH + koff] = reg[s];
+        }
+    }
+};
+
+// ------------------------------------------------------------------ bf16 kernel
+template <int TM, int TN>
+__global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__restrict__ probs,
+                                                           const int *__restrict__ tile_start, int n_probs)
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    __shared__ __attribute__((aligned(16))) unsigned short lds_a[BM * LDH];
+    __shared__ __attribute__((aligned(16))) unsigned short lds_b[BN * LDH];
+
+    const int wg = blockIdx.x;
+    const int pi = find_problem(tile_start, n_probs, wg);
+    const GemmProblem &P = probs[pi];
+    const int local = wg - tile_start[pi];
+    const int split = local % P.splits;
+    const int tile = local / P.splits;
+    int tm, tn;
+    if (P.flags & GEMM_SYM) tri_decode(tile, tm, tn);
+    else { tm = tile / P.tiles_n; tn = tile - tm * P.tiles_n; }
+    const int k0 = split * P.k_per_split;
+    const int k1 = min(P.K, k0 + P.k_per_split);
+    const int tid = threadIdx.x;
+
+    LoaderBF16<BM> la;
+    LoaderBF16<BN> lb;
+    la.init(P.a, tm * BM, k0, k1, tid);
+    lb.init(P.b, tn * BN, k0, k1, tid);
+    unsigned short ra[BM / 8], rb[BN / 8];
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int lane = tid & 63, wid = tid >> 6;
+    const int wave_m = wid >> 1, wave_n = wid & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    const int nk = (k1 - k0 + KT - 1) / KT;
+    if (nk > 0) { la.load(ra); lb.load(rb); }
+    for (int it = 0; it < nk; ++it) {
+        __syncthreads();
+        la.store_lds(ra, lds_a);
+        lb.store_lds(rb, lds_b);
+        __syncthreads();
+        if (it + 1 < nk) {
+            la.advance(); lb.advance();
+            la.load(ra); lb.load(rb);
+        }
+        // v_mfma_f32_32x32x16_bf16: a lane supplies 8 consecutive k of row lane%32; the two
+        // half-waves cover k groups {0..7},{8..15}.  Two issues cover the 32-wide tile:
+        // issue u uses k = 16u + 8*half + 0..7, identically for both operands.
+        ushortx8 fa[TM][2], fb[TN][2];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const unsigned short *p = lds_a + (wave_m * 32 * TM + i * 32 + l32) * LDH + half * 8;
+            fa[i][0] = *(const ushortx8 *)(p);
+            fa[i][1] = *(const ushortx8 *)(p + 16);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const unsigned short *p = lds_b + (wave_n * 32 * TN + j * 32 + l32) * LDH + half * 8;
+            fb[j][0] = *(const ushortx8 *)(p);
+            fb[j][1] = *(const ushortx8 *)(p + 16);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, fa[i][u]), __builtin_bit_cast(bf16x8, fb[j][u]), acc[i][j], 0, 0, 0);
+    }
+
+    const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
+    if (P.splits > 1) {
+        float *part = P.partial + ((long long)tile * P.splits + split) * (BM * BN);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = wave_m * 32 * TM + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                    const int c = wave_n * 32 * TN + j * 32 + l32;
+                    part[r * BN + c] = acc[i][j][v];
+                }
+    } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = tm * BM + wave_m * 32 * TM + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                    const int c = tn * BN + wave_n * 32 * TN + j * 32 + l32;
+                    store_result(P, diag_tile, r, c, acc[i][j][v]);
+                }
+    }
+}
+
+// ------------------------------------------------------------------ split-K reduction + epilogue
+// One workgroup per (problem, tile): sums the partial tiles in split order (fixed order,
+// so results are reproducible bit for bit) and applies the same epilogue.
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmProblem *__restrict__ probs,
+                                                          const int *__restrict__ red_start, int n_probs)
+{
+    const int wg = blockIdx.x;
+    const int pi = find_problem(red_start, n_probs, wg);
+    const GemmProblem &P = probs[pi];
+    if (P.splits <= 1) return;
+    const int tile = wg - red_start[pi];
+    const int B = (P.tile_cfg == 0) ? 128 : 64;
+    int tm, tn;
+    if (P.flags & GEMM_SYM) tri_decode(tile, tm, tn);
+    else { tm = tile / P.tiles_n; tn = tile - tm * P.tiles_n; }
+    const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
+    const float *part = P.partial + (long long)tile * P.splits * (B * B);
+    for (int e = threadIdx.x; e < B * B; e += 256) {
+        const int r = e / B, c = e - r * B;
+        const int i = tm * B + r, j = tn * B + c;
+        if (i >= P.M || j >= P.N) continue;
+        float s = 0.f;
+        for (int q = 0; q < P.splits; ++q) s += part[(long long)q * (B * B) + e];
+        store_result(P, diag_tile, i, j, s);
+    }
+}
+
+hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, int n_probs,
+                       int total_wgs, int tile_cfg, int dtype, hipStream_t s)
+{
+    if (total_wgs <= 0) return hipSuccess;
+    dim3 grid(total_wgs), block(256);
+    if (dtype == 0) {
+        if (tile_cfg == 0) gemm_nt_f32_kernel<2, 2><<<grid, block, 0, s>>>(probs_dev, tile_start_dev, n_probs);
+        else               gemm_nt_f32_kernel<1, 1><<<grid, block, 0, s>>>(probs_dev, tile_start_dev, n_probs);
+    } else {
+        if (tile_cfg == 0) gemm_nt_bf16_kernel<2, 2><<<grid, block, 0, s>>>(probs_dev, tile_start_dev, n_probs);
+        else               gemm_nt_bf16_kernel<1, 1><<<grid, block, 0, s>>>(probs_dev, tile_start_dev, n_probs);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_reduce(const GemmProblem *probs_dev, const int *red_start_dev, int n_probs,
+                              int total_wgs, hipStream_t s)
+{
+    if (total_wgs <= 0) return hipSuccess;
+    gemm_reduce_kernel<<<dim3(total_wgs), dim3(256), 0, s>>>(probs_dev, red_start_dev, n_probs);
+    return hipGetLastError();
+}
+
+}  // namespace kfac

@@ -1,0 +1,917 @@
+// Host side of the C ABI declared in include/kfac.h: argument validation, per-call
+// planning (which grouped launches, with which device tables and workspace slices),
+// table upload and launch.  Every step of the path runs in the HIP kernels of this
+// library; this file only decides what to launch.
+#include "../../include/kfac.h"
+#include "kfac_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+using namespace kfac;
+
+// ------------------------------------------------------------------ context
+namespace {
+
+constexpr int kSlots = 8;
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Tunables {
+    int target_wgs;      // split-K aims at this many workgroups per problem
+    int min_k_per_split; // never split below this contraction length
+    Tunables()
+    {
+        const char *e = getenv("KFAC_TARGET_WGS");
+        target_wgs = e ? std::max(1, atoi(e)) : 512;
+        e = getenv("KFAC_MIN_K_SPLIT");
+        min_k_per_split = e ? std::max(32, atoi(e) / 32 * 32) : 512;
+    }
+};
+
+}  // namespace
+
+struct kfac_ctx {
+    hipStream_t stream;
+    char *ws;
+    size_t ws_bytes;
+    // pinned staging ring for device tables
+    char *pinned[kSlots];
+    size_t pinned_bytes[kSlots];
+    hipEvent_t ev[kSlots];
+    bool ev_valid[kSlots];
+    int next_slot;
+    Tunables tun;
+};
+
+namespace {
+
+// Workspace carving. With base == nullptr it only counts bytes (dry run).
+struct Arena {
+    char *base;
+    size_t used, peak;
+    explicit Arena(char *b) : base(b), used(0), peak(0) {}
+    void *take(size_t bytes)
+    {
+        used = align_up(used, kAlign);
+        char *p = base ? base + used : (char *)nullptr + used;
+        used += bytes;
+        peak = std::max(peak, used);
+        return p;
+    }
+    // scratch taken after `mark` is dead once the launches that use it have been enqueued
+    // (everything runs in order on one stream), so later launches may reuse it
+    void release_to(size_t mark) { used = mark; }
+    void *take_tail(size_t bytes) { used = peak; return take(bytes); }
+};
+
+// Host image of the device tables of one call.
+struct Tables {
+    std::vector<char> buf;
+    size_t add(const void *data, size_t bytes)
+    {
+        size_t off = align_up(buf.size(), 16);
+        buf.resize(off + bytes);
+        if (bytes) memcpy(buf.data() + off, data, bytes);
+        return off;
+    }
+};
+
+enum LaunchKind { L_GEMM, L_REDUCE, L_PATCH, L_TRACE, L_COPY, L_LEAF, L_ZERO, L_BN, L_BNRED };
+
+struct Launch {
+    LaunchKind kind;
+    size_t off_a, off_b;   // table offsets
+    int n, total_wgs, cfg, dtype;
+    float f0, f1;
+    void *p0, *p1;
+};
+
+struct Plan {
+    Tables tab;
+    std::vector<Launch> launches;
+};
+
+bool layer_ok(const kfac_layer &L, int *dA, int *dG, int *h, int *w)
+{
+    if (L.N < 1 || L.c_in < 1 || L.c_out < 1 || L.k < 1 || L.stride < 1 || L.pad < 0 || L.h_in < 1 || L.w_in < 1)
+        return false;
+    if (L.bias != 0 && L.bias != 1) return false;
+    const long long nh = (long long)L.h_in + 2LL * L.pad - L.k, nw = (long long)L.w_in + 2LL * L.pad - L.k;
+    if (nh < 0 || nw < 0) return false;
+    const long long hh = nh / L.stride + 1, ww = nw / L.stride + 1;
+    const long long da = (long long)L.c_in * L.k * L.k + L.bias;
+    if (da > (1 << 20) || L.c_out > (1 << 20)) return false;
+    if (hh * ww > (1LL << 24) || (long long)L.N * hh * ww > (1LL << 30)) return false;
+    if ((long long)L.N * L.c_in * L.h_in * L.w_in > (1LL << 40)) return false;
+    if (dA) *dA = (int)da;
+    if (dG) *dG = L.c_out;
+    if (h) *h = (int)hh;
+    if (w) *w = (int)ww;
+    return true;
+}
+
+// ---------------------------------------------------------------- GEMM grouping
+struct GemmGroup {   // problems that go into one phase (no dependencies among them)
+    std::vector<GemmProblem> probs;
+};
+
+int tile_edge(int cfg) { return cfg == 0 ? 128 : 64; }
+
+int choose_tile_cfg(int M, int N)
+{
+    auto cost = [&](int B, double w) {
+        return (double)((M + B - 1) / B) * ((N + B - 1) / B) * B * B * w;
+    };
+    return cost(128, 1.0) <= cost(64, 1.25) ? 0 : 1;
+}
+
+void finish_problem(GemmProblem &P)
+{
+    const int B = tile_edge(P.tile_cfg);
+    P.tiles_m = (P.M + B - 1) / B;
+    P.tiles_n = (P.N + B - 1) / B;
+    P.n_tiles = (P.flags & GEMM_SYM) ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n;
+    P.splits = 1;
+    P.k_per_split = std::max(32, (P.K + 31) / 32 * 32);
+    P.partial = nullptr;
+}
+
+// Emits the launches of one phase: per tile configuration one GEMM launch, plus one
+// reduction launch if any problem was split along K.
+void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<GemmProblem> &probs,
+                     int dtype, bool allow_split)
+{
+    if (probs.empty()) return;
+    for (int cfg = 0; cfg < 2; ++cfg) {
+        std::vector<GemmProblem> sel;
+        for (auto &P : probs)
+            if (P.tile_cfg == cfg) sel.push_back(P);
+        if (sel.empty()) continue;
+        const int B = tile_edge(cfg);
+        if (allow_split) {
+            // per problem (independent of what else is in the launch, so that the workspace
+            // need of a layer list does not depend on which of its inputs are present)
+            for (auto &P : sel) {
+                const int want = (tun.target_wgs + P.n_tiles - 1) / P.n_tiles;
+                int splits = std::min(want, P.K / tun.min_k_per_split);
+                if (splits > 1) {
+                    const int kps = ((P.K + splits - 1) / splits + 31) / 32 * 32;
+                    splits = (P.K + kps - 1) / kps;
+                    if (splits > 1) {
+                        P.splits = splits;
+                        P.k_per_split = kps;
+                        P.partial = (float *)arena.take((size_t)P.n_tiles * splits * B * B * sizeof(float));
+                    }
+                }
+            }
+        }
+        // longest workgroups first
+        std::stable_sort(sel.begin(), sel.end(), [](const GemmProblem &x, const GemmProblem &y) {
+            return std::min(x.K, x.k_per_split) > std::min(y.K, y.k_per_split);
+        });
+        std::vector<int> start(sel.size() + 1, 0), rstart(sel.size() + 1, 0);
+        bool any_split = false;
+        for (size_t i = 0; i < sel.size(); ++i) {
+            start[i + 1] = start[i] + sel[i].n_tiles * sel[i].splits;
+            rstart[i + 1] = rstart[i] + (sel[i].splits > 1 ? sel[i].n_tiles : 0);
+            any_split |= sel[i].splits > 1;
+        }
+        Launch L{};
+        L.kind = L_GEMM;
+        L.off_a = plan.tab.add(sel.data(), sel.size() * sizeof(GemmProblem));
+        L.off_b = plan.tab.add(start.data(), start.size() * sizeof(int));
+        L.n = (int)sel.size();
+        L.total_wgs = start.back();
+        L.cfg = cfg;
+        L.dtype = dtype;
+        plan.launches.push_back(L);
+        if (any_split) {
+            Launch R{};
+            R.kind = L_REDUCE;
+            R.off_a = L.off_a;
+            R.off_b = plan.tab.add(rstart.data(), rstart.size() * sizeof(int));
+            R.n = (int)sel.size();
+            R.total_wgs = rstart.back();
+            plan.launches.push_back(R);
+        }
+    }
+}
+
+Operand plain_operand(const float *base, long long ld, int rows, int K)
+{
+    Operand o{};
+    o.base = base;
+    o.row_stride = ld;
+    o.batch_stride = 0;
+    o.rows = rows;
+    o.hw = std::max(K, 1) + 64;   // one run covers the whole contraction
+    o.ones_row = -1;
+    o.vec = (ld % 4 == 0 && ((uintptr_t)base % 16) == 0) ? 4 : 1;
+    return o;
+}
+
+// ---------------------------------------------------------------- stats planner
+struct StatsArgs {
+    int n_layers;
+    const kfac_layer *L;
+    kfac_dtype in;
+    const void *const *act;
+    const void *const *grad_out;
+    float decay;
+    int g_spatial_mean;
+    float *const *A_ema;
+    float *const *G_ema;
+};
+
+void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &a, bool dry)
+{
+    const int esize = a.in == KFAC_BF16 ? 2 : 4;
+    const size_t vec_align = a.in == KFAC_BF16 ? 8 : 16;
+    std::vector<PatchJob> pjobs;
+    std::vector<GemmProblem> probs;
+    int patch_wgs = 0;
+    for (int l = 0; l < a.n_layers; ++l) {
+        const kfac_layer &Ly = a.L[l];
+        int dA, dG, h, w;
+        layer_ok(Ly, &dA, &dG, &h, &w);
+        const int hw = h * w;
+        const int K = Ly.N * hw;
+        const bool want_A = dry || (a.act && a.act[l]);
+        const bool want_G = dry || (a.grad_out && a.grad_out[l]);
+        if (want_A) {
+            const int d0 = Ly.c_in * Ly.k * Ly.k;
+            Operand op{};
+            const bool direct = (Ly.k == 1 && Ly.stride == 1 && Ly.pad == 0);
+            if (direct) {
+                op.base = dry ? nullptr : a.act[l];
+                op.row_stride = hw;
+                op.batch_stride = (long long)Ly.c_in * hw;
+                op.rows = d0;
+                op.hw = hw;
+                op.vec = (hw % 4 == 0 && !dry && ((uintptr_t)op.base % vec_align) == 0) ? 4 : 1;
+            } else {
+                const long long ld = align_up((size_t)K, 32);
+                void *P = arena.take((size_t)d0 * ld * esize);
+                PatchJob J{};
+                J.src = dry ? nullptr : a.act[l];
+                J.dst = P;
+                J.ld = ld;
+                J.N = Ly.N; J.c_in = Ly.c_in; J.k = Ly.k; J.stride = Ly.stride; J.pad = Ly.pad;
+                J.h_in = Ly.h_in; J.w_in = Ly.w_in; J.h = h; J.w = w;
+                J.esize = esize;
+                J.magic_w = (hw < 65536) ? (unsigned)((1ULL << 32) / (unsigned)w + 1ULL) : 0u;
+                if (w == 1) J.magic_w = 0;   // 2^32/1 + 1 does not fit; plain division
+                J.wg_start = patch_wgs;
+                patch_wgs += ((Ly.N * Ly.c_in + 3) / 4) * ((hw + 1023) / 1024);
+                pjobs.push_back(J);
+                op.base = P;
+                op.row_stride = ld;
+                op.batch_stride = 0;
+                op.rows = d0;
+                op.hw = K + 64;
+                op.vec = 4;
+            }
+            op.ones_row = Ly.bias ? d0 : -1;
+            GemmProblem P{};
+            P.a = op; P.b = op;
+            P.C = dry ? nullptr : a.A_ema[l];
+            P.Ct = nullptr;
+            P.ldc = dA; P.ldct = 0;
+            P.M = dA; P.N = dA; P.K = K;
+            P.flags = GEMM_SYM;
+            P.tile_cfg = choose_tile_cfg(dA, dA);
+            P.alpha = (float)((1.0 - (double)a.decay) / ((double)Ly.N * (double)hw));
+            P.beta = a.decay;
+            finish_problem(P);
+            probs.push_back(P);
+        }
+        if (want_G) {
+            Operand op{};
+            op.base = dry ? nullptr : a.grad_out[l];
+            op.row_stride = hw;
+            op.batch_stride = (long long)Ly.c_out * hw;
+            op.rows = dG;
+            op.hw = hw;
+            op.ones_row = -1;
+            op.vec = (hw % 4 == 0 && !dry && ((uintptr_t)op.base % vec_align) == 0) ? 4 : 1;
+            GemmProblem P{};
+            P.a = op; P.b = op;
+            P.C = dry ? nullptr : a.G_ema[l];
+            P.ldc = dG;
+            P.M = dG; P.N = dG; P.K = K;
+            P.flags = GEMM_SYM;
+            P.tile_cfg = choose_tile_cfg(dG, dG);
+            double scale = 1.0 / (double)Ly.N;
+            if (a.g_spatial_mean) scale /= (double)hw;
+            P.alpha = (float)((1.0 - (double)a.decay) * scale);
+            P.beta = a.decay;
+            finish_problem(P);
+            probs.push_back(P);
+        }
+    }
+    if (!pjobs.empty()) {
+        Launch L{};
+        L.kind = L_PATCH;
+        L.off_a = plan.tab.add(pjobs.data(), pjobs.size() * sizeof(PatchJob));
+        L.n = (int)pjobs.size();
+        L.total_wgs = patch_wgs;
+        plan.launches.push_back(L);
+    }
+    emit_gemm_phase(plan, arena, tun, probs, a.in == KFAC_BF16 ? 1 : 0, true);
+}
+
+// ---------------------------------------------------------------- inversion planner
+struct InvMatrix {
+    const float *src;
+    float *dst;
+    int n, damp_idx, info_idx;
+};
+
+enum OpKind { OP_LEAF, OP_GEMM };
+struct InvOp {
+    int level;
+    OpKind kind;
+    LeafJob leaf;
+    GemmProblem gemm;
+};
+
+int leaf_class(int n)
+{
+    for (int c = 0; c < kNumLeafClasses; ++c)
+        if (n <= 32 * kLeafClasses[c]) return c;
+    return -1;
+}
+
+int split_point(int n)
+{
+    int n1 = ((n / 2) + 16) / 32 * 32;
+    n1 = std::max(32, std::min(n1, n - 1));
+    return n1;
+}
+
+// Recursive 2x2 block inversion through the Schur complement, in place in X (leading
+// dimension ld) on the diagonal block starting at `o` of size n.  With X = [A11 A12; A21 A22]:
+//   X11 <- A11^-1                                  (recursion)
+//   Y   = A21 X11,  W = Y^T                        (GEMM, both copies kept in scratch)
+//   X22 <- A22 - Y A21^T  = S                      (GEMM, symmetric)
+//   X22 <- S^-1                                    (recursion)
+//   X12 <- -W X22,  X21 <- X12^T                   (GEMM + transposed copy)
+//   X11 <- X11 - X12 W^T                           (GEMM, symmetric)
+// Returns the first level at which the block's inverse is complete.
+int build_inverse(std::vector<InvOp> &ops, Arena &arena, float *X, long long ld, int o, int n, int level,
+                  int info_idx)
+{
+    if (n <= kLeafMax) {
+        InvOp op{};
+        op.level = level;
+        op.kind = OP_LEAF;
+        float *v = X + (long long)o * ld + o;
+        op.leaf.src = v; op.leaf.dst = v;
+        op.leaf.lds = ld; op.leaf.ldd = ld;
+        op.leaf.n = n;
+        op.leaf.damp_idx = -1;
+        op.leaf.info_idx = info_idx;
+        op.leaf.pivot_base = o;
+        ops.push_back(op);
+        return level + 1;
+    }
+    const int n1 = split_point(n), n2 = n - n1;
+    float *X11 = X + (long long)o * ld + o;
+    float *X12 = X11 + n1;
+    float *X21 = X11 + (long long)n1 * ld;
+    float *X22 = X21 + n1;
+    const long long ldy = align_up((size_t)n1, 4), ldw = align_up((size_t)n2, 4);
+    float *Y = (float *)arena.take((size_t)n2 * ldy * sizeof(float));
+    float *W = (float *)arena.take((size_t)n1 * ldw * sizeof(float));
+
+    const int l1 = build_inverse(ops, arena, X, ld, o, n1, level, info_idx);
+    {
+        InvOp op{};
+        op.level = l1; op.kind = OP_GEMM;
+        GemmProblem &P = op.gemm;
+        P.a = plain_operand(X21, ld, n2, n1);
+        P.b = plain_operand(X11, ld, n1, n1);
+        P.C = Y; P.ldc = ldy; P.Ct = W; P.ldct = ldw;
+        P.M = n2; P.N = n1; P.K = n1; P.flags = 0;
+        P.alpha = 1.f; P.beta = 0.f;
+        P.tile_cfg = choose_tile_cfg(P.M, P.N);
+        finish_problem(P);
+        ops.push_back(op);
+    }
+    {
+        InvOp op{};
+        op.level = l1 + 1; op.kind = OP_GEMM;
+        GemmProblem &P = op.gemm;
+        P.a = plain_operand(Y, ldy, n2, n1);
+        P.b = plain_operand(X21, ld, n2, n1);
+        P.C = X22; P.ldc = ld; P.Ct = nullptr;
+        P.M = n2; P.N = n2; P.K = n1; P.flags = GEMM_SYM;
+        P.alpha = -1.f; P.beta = 1.f;
+        P.tile_cfg = choose_tile_cfg(P.M, P.N);
+        finish_problem(P);
+        ops.push_back(op);
+    }
+    const int l2 = build_inverse(ops, arena, X, ld, o + n1, n2, l1 + 2, info_idx);
+    {
+        InvOp op{};
+        op.level = l2; op.kind = OP_GEMM;
+        GemmProblem &P = op.gemm;
+        P.a = plain_operand(W, ldw, n1, n2);
+        P.b = plain_operand(X22, ld, n2, n2);
+        P.C = X12; P.ldc = ld; P.Ct = X21; P.ldct = ld;
+        P.M = n1; P.N = n2; P.K = n2; P.flags = 0;
+        P.alpha = -1.f; P.beta = 0.f;
+        P.tile_cfg = choose_tile_cfg(P.M, P.N);
+        finish_problem(P);
+        ops.push_back(op);
+    }
+    {
+        InvOp op{};
+        op.level = l2 + 1; op.kind = OP_GEMM;
+        GemmProblem &P = op.gemm;
+        P.a = plain_operand(X12, ld, n1, n2);
+        P.b = plain_operand(W, ldw, n1, n2);
+        P.C = X11; P.ldc = ld; P.Ct = nullptr;
+        P.M = n1; P.N = n1; P.K = n2; P.flags = GEMM_SYM;
+        P.alpha = -1.f; P.beta = 1.f;
+        P.tile_cfg = choose_tile_cfg(P.M, P.N);
+        finish_problem(P);
+        ops.push_back(op);
+    }
+    return l2 + 2;
+}
+
+struct InvertArgs {
+    int n_layers;
+    const kfac_layer *L;
+    const float *const *A_ema;
+    const float *const *G_ema;
+    float gamma;
+    float *const *A_inv;
+    float *const *G_inv;
+    float *pi_out;
+    int32_t *info;
+};
+
+void plan_invert(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs &a, bool dry)
+{
+    float *damp = (float *)arena.take((size_t)3 * a.n_layers * sizeof(float));
+    std::vector<TraceJob> tjobs;
+    std::vector<InvMatrix> mats;
+    for (int l = 0; l < a.n_layers; ++l) {
+        int dA, dG;
+        layer_ok(a.L[l], &dA, &dG, nullptr, nullptr);
+        TraceJob T{};
+        T.A = dry ? nullptr : a.A_ema[l];
+        T.G = dry ? nullptr : a.G_ema[l];
+        T.dA = dA; T.dG = dG;
+        tjobs.push_back(T);
+        // dry runs only need distinct, well-aligned stand-in addresses for planning
+        mats.push_back({T.A, dry ? (float *)nullptr : a.A_inv[l], dA, 3 * l + 1, 2 * l});
+        mats.push_back({T.G, dry ? (float *)nullptr : a.G_inv[l], dG, 3 * l + 2, 2 * l + 1});
+    }
+    if (a.info || dry) {
+        Launch Z{};
+        Z.kind = L_ZERO;
+        Z.p0 = a.info;
+        Z.n = 2 * a.n_layers;
+        plan.launches.push_back(Z);
+    }
+    {
+        Launch T{};
+        T.kind = L_TRACE;
+        T.off_a = plan.tab.add(tjobs.data(), tjobs.size() * sizeof(TraceJob));
+        T.n = a.n_layers;
+        T.f0 = a.gamma;
+        T.p0 = damp;
+        T.p1 = a.pi_out;
+        plan.launches.push_back(T);
+    }
+    std::vector<CopyJob> cjobs;
+    std::vector<InvOp> ops;
+    int copy_wgs = 0;
+    for (auto &m : mats) {
+        if (m.n <= kLeafMax) {
+            InvOp op{};
+            op.level = 0; op.kind = OP_LEAF;
+            op.leaf.src = m.src; op.leaf.dst = m.dst;
+            op.leaf.lds = m.n; op.leaf.ldd = m.n;
+            op.leaf.n = m.n;
+            op.leaf.damp_idx = m.damp_idx;
+            op.leaf.info_idx = m.info_idx;
+            op.leaf.pivot_base = 0;
+            ops.push_back(op);
+        } else {
+            CopyJob C{};
+            C.src = m.src; C.dst = m.dst;
+            C.lds = m.n; C.ldd = m.n; C.n = m.n;
+            C.damp_idx = m.damp_idx;
+            C.wg_start = copy_wgs;
+            copy_wgs += (m.n + 7) / 8;
+            cjobs.push_back(C);
+            build_inverse(ops, arena, m.dst, m.n, 0, m.n, 0, m.info_idx);
+        }
+    }
+    if (!cjobs.empty()) {
+        Launch C{};
+        C.kind = L_COPY;
+        C.off_a = plan.tab.add(cjobs.data(), cjobs.size() * sizeof(CopyJob));
+        C.n = (int)cjobs.size();
+        C.total_wgs = copy_wgs;
+        C.p0 = damp;
+        plan.launches.push_back(C);
+    }
+    int max_level = -1;
+    for (auto &op : ops) max_level = std::max(max_level, op.level);
+    for (int lv = 0; lv <= max_level; ++lv) {
+        for (int c = 0; c < kNumLeafClasses; ++c) {
+            std::vector<LeafJob> lj;
+            for (auto &op : ops)
+                if (op.level == lv && op.kind == OP_LEAF && leaf_class(op.leaf.n) == c) lj.push_back(op.leaf);
+            if (lj.empty()) continue;
+            Launch Lf{};
+            Lf.kind = L_LEAF;
+            Lf.off_a = plan.tab.add(lj.data(), lj.size() * sizeof(LeafJob));
+            Lf.n = (int)lj.size();
+            Lf.cfg = c;
+            Lf.p0 = damp;
+            Lf.p1 = a.info;
+            plan.launches.push_back(Lf);
+        }
+        std::vector<GemmProblem> gp;
+        for (auto &op : ops)
+            if (op.level == lv && op.kind == OP_GEMM) gp.push_back(op.gemm);
+        const size_t mark = arena.used;
+        emit_gemm_phase(plan, arena, tun, gp, 0, true);
+        arena.release_to(mark);
+    }
+}
+
+// ---------------------------------------------------------------- preconditioning planner
+struct PrecondArgs {
+    int n_layers;
+    const kfac_layer *L;
+    const float *const *G_inv;
+    const float *const *A_inv;
+    const float *const *grad_W;
+    float *const *out;
+};
+
+void plan_precondition(Plan &plan, Arena &arena, const Tunables &tun, const PrecondArgs &a, bool dry)
+{
+    // phase 1: Vt = A_inv * grad_W^T  ([dA, dG]);  phase 2: out = G_inv * Vt^T  ([dG, dA])
+    std::vector<GemmProblem> p1, p2;
+    for (int l = 0; l < a.n_layers; ++l) {
+        int dA, dG;
+        layer_ok(a.L[l], &dA, &dG, nullptr, nullptr);
+        const long long ldv = align_up((size_t)dG, 4);
+        float *Vt = (float *)arena.take((size_t)dA * ldv * sizeof(float));
+        GemmProblem P{};
+        P.a = plain_operand(dry ? nullptr : a.A_inv[l], dA, dA, dA);
+        P.b = plain_operand(dry ? nullptr : a.grad_W[l], dA, dG, dA);
+        P.C = Vt; P.ldc = ldv; P.Ct = nullptr;
+        P.M = dA; P.N = dG; P.K = dA; P.flags = 0;
+        P.alpha = 1.f; P.beta = 0.f;
+        P.tile_cfg = choose_tile_cfg(P.M, P.N);
+        finish_problem(P);
+        p1.push_back(P);
+        GemmProblem Q{};
+        Q.a = plain_operand(dry ? nullptr : a.G_inv[l], dG, dG, dG);
+        Q.b = plain_operand(Vt, ldv, dA, dG);
+        Q.C = dry ? nullptr : a.out[l]; Q.ldc = dA; Q.Ct = nullptr;
+        Q.M = dG; Q.N = dA; Q.K = dG; Q.flags = 0;
+        Q.alpha = 1.f; Q.beta = 0.f;
+        Q.tile_cfg = choose_tile_cfg(Q.M, Q.N);
+        finish_problem(Q);
+        p2.push_back(Q);
+    }
+    emit_gemm_phase(plan, arena, tun, p1, 0, true);
+    emit_gemm_phase(plan, arena, tun, p2, 0, true);
+}
+
+// ---------------------------------------------------------------- execution
+kfac_status ensure_slot(kfac_ctx *ctx, int slot, size_t bytes)
+{
+    if (ctx->ev_valid[slot]) {
+        if (hipEventSynchronize(ctx->ev[slot]) != hipSuccess) return KFAC_ERR_DEVICE;
+    } else {
+        if (hipEventCreateWithFlags(&ctx->ev[slot], hipEventDisableTiming) != hipSuccess) return KFAC_ERR_DEVICE;
+        ctx->ev_valid[slot] = true;
+    }
+    if (ctx->pinned_bytes[slot] < bytes) {
+        if (ctx->pinned[slot]) (void)hipHostFree(ctx->pinned[slot]);
+        ctx->pinned[slot] = nullptr;
+        ctx->pinned_bytes[slot] = 0;
+        size_t want = std::max(bytes, (size_t)1 << 20);
+        void *p = nullptr;
+        if (hipHostMalloc(&p, want, hipHostMallocDefault) != hipSuccess) return KFAC_ERR_DEVICE;
+        ctx->pinned[slot] = (char *)p;
+        ctx->pinned_bytes[slot] = want;
+    }
+    return KFAC_OK;
+}
+
+kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
+{
+    // tables go behind the scratch slices
+    const size_t tab_bytes = plan.tab.buf.size();
+    char *tab_dev = (char *)arena.take_tail(tab_bytes + 16);
+    if (arena.peak > ctx->ws_bytes) return KFAC_ERR_WORKSPACE;
+    hipStream_t s = ctx->stream;
+    if (tab_bytes) {
+        const int slot = ctx->next_slot;
+        ctx->next_slot = (ctx->next_slot + 1) % kSlots;
+        kfac_status st = ensure_slot(ctx, slot, tab_bytes);
+        if (st != KFAC_OK) return st;
+        memcpy(ctx->pinned[slot], plan.tab.buf.data(), tab_bytes);
+        if (hipMemcpyAsync(tab_dev, ctx->pinned[slot], tab_bytes, hipMemcpyHostToDevice, s) != hipSuccess)
+            return KFAC_ERR_DEVICE;
+        if (hipEventRecord(ctx->ev[slot], s) != hipSuccess) return KFAC_ERR_DEVICE;
+    }
+    for (auto &L : plan.launches) {
+        hipError_t e = hipSuccess;
+        switch (L.kind) {
+            case L_GEMM:
+                e = launch_gemm((const GemmProblem *)(tab_dev + L.off_a), (const int *)(tab_dev + L.off_b), L.n,
+                                L.total_wgs, L.cfg, L.dtype, s);
+                break;
+            case L_REDUCE:
+                e = launch_gemm_reduce((const GemmProblem *)(tab_dev + L.off_a), (const int *)(tab_dev + L.off_b),
+                                       L.n, L.total_wgs, s);
+                break;
+            case L_PATCH:
+                e = launch_patch((const PatchJob *)(tab_dev + L.off_a), L.n, L.total_wgs, s);
+                break;
+            case L_TRACE:
+                e = launch_trace((const TraceJob *)(tab_dev + L.off_a), L.n, L.f0, (float *)L.p0, (float *)L.p1, s);
+                break;
+            case L_COPY:
+                e = launch_copy_damp((const CopyJob *)(tab_dev + L.off_a), L.n, L.total_wgs, (const float *)L.p0, s);
+                break;
+            case L_LEAF:
+                e = launch_leaf((const LeafJob *)(tab_dev + L.off_a), L.n, L.cfg, (const float *)L.p0,
+                                (int32_t *)L.p1, s);
+                break;
+            case L_ZERO:
+                e = launch_zero_i32((int32_t *)L.p0, L.n, s);
+                break;
+            case L_BN:
+                e = launch_bn((const BnJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, L.f0, L.f1, s);
+                break;
+            case L_BNRED:
+                e = launch_bn_reduce((const BnReduceJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, s);
+                break;
+        }
+        if (e != hipSuccess) return KFAC_ERR_DEVICE;
+    }
+    return KFAC_OK;
+}
+
+bool layers_ok(const kfac_layer *L, int n)
+{
+    if (!L || n < 1 || n > 65536) return false;
+    for (int i = 0; i < n; ++i)
+        if (!layer_ok(L[i], nullptr, nullptr, nullptr, nullptr)) return false;
+    return true;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI
+extern "C" {
+
+const char *kfac_status_string(kfac_status s)
+{
+    switch (s) {
+        case KFAC_OK: return "ok";
+        case KFAC_ERR_INVALID: return "invalid argument";
+        case KFAC_ERR_WORKSPACE: return "workspace too small";
+        case KFAC_ERR_NOT_PD: return "matrix not positive definite";
+        case KFAC_ERR_DEVICE: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+kfac_status kfac_layer_dims(const kfac_layer *L, int32_t *dA, int32_t *dG, int32_t *h, int32_t *w)
+{
+    if (!L) return KFAC_ERR_INVALID;
+    int a, g, hh, ww;
+    if (!layer_ok(*L, &a, &g, &hh, &ww)) return KFAC_ERR_INVALID;
+    if (dA) *dA = a;
+    if (dG) *dG = g;
+    if (h) *h = hh;
+    if (w) *w = ww;
+    return KFAC_OK;
+}
+
+size_t kfac_workspace_bytes(const kfac_layer *L, int32_t n_layers, kfac_dtype in)
+{
+    if (!layers_ok(L, n_layers) || (in != KFAC_F32 && in != KFAC_BF16)) return 0;
+    Tunables tun;
+    size_t best = 0;
+    {
+        Plan plan; Arena arena(nullptr);
+        StatsArgs a{n_layers, L, in, nullptr, nullptr, 0.5f, 0, nullptr, nullptr};
+        plan_stats(plan, arena, tun, a, true);
+        arena.take_tail(plan.tab.buf.size() + 16);
+        best = std::max(best, arena.peak);
+    }
+    {
+        Plan plan; Arena arena(nullptr);
+        InvertArgs a{n_layers, L, nullptr, nullptr, 1e-3f, nullptr, nullptr, nullptr, nullptr};
+        plan_invert(plan, arena, tun, a, true);
+        arena.take_tail(plan.tab.buf.size() + 16);
+        best = std::max(best, arena.peak);
+    }
+    {
+        Plan plan; Arena arena(nullptr);
+        PrecondArgs a{n_layers, L, nullptr, nullptr, nullptr, nullptr};
+        plan_precondition(plan, arena, tun, a, true);
+        arena.take_tail(plan.tab.buf.size() + 16);
+        best = std::max(best, arena.peak);
+    }
+    // im2col of a single layer and the BatchNorm calls need table space only
+    best = std::max(best, (size_t)1 << 20);
+    return align_up(best + 4096, kAlign);
+}
+
+kfac_status kfac_create(kfac_ctx **out, void *hip_stream, void *workspace_dev, size_t workspace_bytes)
+{
+    if (!out) return KFAC_ERR_INVALID;
+    *out = nullptr;
+    if (!workspace_dev || workspace_bytes == 0 || ((uintptr_t)workspace_dev % kAlign) != 0) return KFAC_ERR_INVALID;
+    kfac_ctx *c = new (std::nothrow) kfac_ctx();
+    if (!c) return KFAC_ERR_DEVICE;
+    c->stream = (hipStream_t)hip_stream;
+    c->ws = (char *)workspace_dev;
+    c->ws_bytes = workspace_bytes;
+    for (int i = 0; i < kSlots; ++i) {
+        c->pinned[i] = nullptr;
+        c->pinned_bytes[i] = 0;
+        c->ev_valid[i] = false;
+    }
+    c->next_slot = 0;
+    *out = c;
+    return KFAC_OK;
+}
+
+void kfac_destroy(kfac_ctx *ctx)
+{
+    if (!ctx) return;
+    for (int i = 0; i < kSlots; ++i) {
+        if (ctx->ev_valid[i]) {
+            (void)hipEventSynchronize(ctx->ev[i]);
+            (void)hipEventDestroy(ctx->ev[i]);
+        }
+        if (ctx->pinned[i]) (void)hipHostFree(ctx->pinned[i]);
+    }
+    delete ctx;
+}
+
+kfac_status kfac_im2col(kfac_ctx *ctx, const kfac_layer *L, kfac_dtype dt, const void *act, void *patches,
+                        int64_t ld)
+{
+    if (!ctx || !L || !act || !patches) return KFAC_ERR_INVALID;
+    if (dt != KFAC_F32 && dt != KFAC_BF16) return KFAC_ERR_INVALID;
+    int dA, dG, h, w;
+    if (!layer_ok(*L, &dA, &dG, &h, &w)) return KFAC_ERR_INVALID;
+    const int hw = h * w;
+    if (ld < (int64_t)L->N * hw) return KFAC_ERR_INVALID;
+    Plan plan; Arena arena(ctx->ws);
+    PatchJob J{};
+    J.src = act; J.dst = patches; J.ld = ld;
+    J.N = L->N; J.c_in = L->c_in; J.k = L->k; J.stride = L->stride; J.pad = L->pad;
+    J.h_in = L->h_in; J.w_in = L->w_in; J.h = h; J.w = w;
+    J.esize = dt == KFAC_BF16 ? 2 : 4;
+    J.magic_w = (hw < 65536 && w > 1) ? (unsigned)((1ULL << 32) / (unsigned)w + 1ULL) : 0u;
+    J.wg_start = 0;
+    Launch Lc{};
+    Lc.kind = L_PATCH;
+    Lc.off_a = plan.tab.add(&J, sizeof(J));
+    Lc.n = 1;
+    Lc.total_wgs = ((L->N * L->c_in + 3) / 4) * ((hw + 1023) / 1024);
+    plan.launches.push_back(Lc);
+    return run_plan(ctx, plan, arena);
+}
+
+kfac_status kfac_stats(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
+                       const void *const *act, const void *const *grad_out, float decay, int32_t g_spatial_mean,
+                       float *const *A_ema, float *const *G_ema)
+{
+    if (!ctx || !layers_ok(L, n_layers)) return KFAC_ERR_INVALID;
+    if (in != KFAC_F32 && in != KFAC_BF16) return KFAC_ERR_INVALID;
+    if (!(decay >= 0.0f && decay < 1.0f)) return KFAC_ERR_INVALID;
+    if (!act && !grad_out) return KFAC_ERR_INVALID;
+    for (int l = 0; l < n_layers; ++l) {
+        if (act && act[l] && (!A_ema || !A_ema[l])) return KFAC_ERR_INVALID;
+        if (grad_out && grad_out[l] && (!G_ema || !G_ema[l])) return KFAC_ERR_INVALID;
+        const size_t es = in == KFAC_BF16 ? 2 : 4;
+        if (act && act[l] && ((uintptr_t)act[l] % es) != 0) return KFAC_ERR_INVALID;
+        if (grad_out && grad_out[l] && ((uintptr_t)grad_out[l] % es) != 0) return KFAC_ERR_INVALID;
+    }
+    Plan plan; Arena arena(ctx->ws);
+    StatsArgs a{n_layers, L, in, act, grad_out, decay, g_spatial_mean != 0, A_ema, G_ema};
+    plan_stats(plan, arena, ctx->tun, a, false);
+    return run_plan(ctx, plan, arena);
+}
+
+kfac_status kfac_invert(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, const float *const *A_ema,
+                        const float *const *G_ema, float gamma, float *const *A_inv, float *const *G_inv,
+                        float *pi_out, int32_t *info)
+{
+    if (!ctx || !layers_ok(L, n_layers)) return KFAC_ERR_INVALID;
+    if (!A_ema || !G_ema || !A_inv || !G_inv) return KFAC_ERR_INVALID;
+    if (!(gamma >= 0.0f) || !std::isfinite(gamma)) return KFAC_ERR_INVALID;
+    for (int l = 0; l < n_layers; ++l) {
+        if (!A_ema[l] || !G_ema[l] || !A_inv[l] || !G_inv[l]) return KFAC_ERR_INVALID;
+        if (A_ema[l] == A_inv[l] || G_ema[l] == G_inv[l]) return KFAC_ERR_INVALID;
+    }
+    Plan plan; Arena arena(ctx->ws);
+    InvertArgs a{n_layers, L, A_ema, G_ema, gamma, A_inv, G_inv, pi_out, info};
+    plan_invert(plan, arena, ctx->tun, a, false);
+    return run_plan(ctx, plan, arena);
+}
+
+kfac_status kfac_precondition(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, const float *const *G_inv,
+                              const float *const *A_inv, const float *const *grad_W, float *const *out)
+{
+    if (!ctx || !layers_ok(L, n_layers)) return KFAC_ERR_INVALID;
+    if (!G_inv || !A_inv || !grad_W || !out) return KFAC_ERR_INVALID;
+    for (int l = 0; l < n_layers; ++l)
+        if (!G_inv[l] || !A_inv[l] || !grad_W[l] || !out[l]) return KFAC_ERR_INVALID;
+    Plan plan; Arena arena(ctx->ws);
+    PrecondArgs a{n_layers, L, G_inv, A_inv, grad_W, out};
+    plan_precondition(plan, arena, ctx->tun, a, false);
+    return run_plan(ctx, plan, arena);
+}
+
+kfac_status bn_unitwise_precondition(kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,
+                                     const float *const *g_gamma, const float *const *g_beta, float decay,
+                                     float lambda, float *const *F_ema, float *const *out_gamma,
+                                     float *const *out_beta)
+{
+    if (!ctx || n_layers < 1 || n_layers > 65536 || N < 1 || !C) return KFAC_ERR_INVALID;
+    if (!g_gamma || !g_beta || !F_ema || !out_gamma || !out_beta) return KFAC_ERR_INVALID;
+    if (!(decay >= 0.0f && decay < 1.0f) || !(lambda >= 0.0f) || !std::isfinite(lambda)) return KFAC_ERR_INVALID;
+    std::vector<BnJob> jobs;
+    int wgs = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        if (C[l] < 1 || C[l] > (1 << 24)) return KFAC_ERR_INVALID;
+        if (!g_gamma[l] || !g_beta[l] || !F_ema[l] || !out_gamma[l] || !out_beta[l]) return KFAC_ERR_INVALID;
+        BnJob J{};
+        J.g_gamma = g_gamma[l]; J.g_beta = g_beta[l];
+        J.F_ema = F_ema[l]; J.out_gamma = out_gamma[l]; J.out_beta = out_beta[l];
+        J.C = C[l];
+        J.wg_start = wgs;
+        wgs += (C[l] + 255) / 256;
+        jobs.push_back(J);
+    }
+    Plan plan; Arena arena(ctx->ws);
+    Launch Lc{};
+    Lc.kind = L_BN;
+    Lc.off_a = plan.tab.add(jobs.data(), jobs.size() * sizeof(BnJob));
+    Lc.n = n_layers;
+    Lc.total_wgs = wgs;
+    Lc.cfg = N;
+    Lc.f0 = decay;
+    Lc.f1 = lambda;
+    plan.launches.push_back(Lc);
+    return run_plan(ctx, plan, arena);
+}
+
+kfac_status bn_unitwise_reduce_nchw(kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,
+                                    const int32_t *HW, const float *const *dy, const float *const *xhat,
+                                    float *const *g_gamma, float *const *g_beta)
+{
+    if (!ctx || n_layers < 1 || n_layers > 65536 || N < 1 || !C || !HW) return KFAC_ERR_INVALID;
+    if (!dy || !xhat || !g_gamma || !g_beta) return KFAC_ERR_INVALID;
+    std::vector<BnReduceJob> jobs;
+    long long wgs = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        if (C[l] < 1 || C[l] > (1 << 24) || HW[l] < 1 || HW[l] > (1 << 24)) return KFAC_ERR_INVALID;
+        if (!dy[l] || !xhat[l] || !g_gamma[l] || !g_beta[l]) return KFAC_ERR_INVALID;
+        BnReduceJob J{};
+        J.dy = dy[l]; J.xhat = xhat[l]; J.g_gamma = g_gamma[l]; J.g_beta = g_beta[l];
+        J.C = C[l]; J.HW = HW[l];
+        J.wg_start = (int)wgs;
+        wgs += ((long long)N * C[l] + 3) / 4;
+        if (wgs > (1LL << 30)) return KFAC_ERR_INVALID;
+        jobs.push_back(J);
+    }
+    Plan plan; Arena arena(ctx->ws);
+    Launch Lc{};
+    Lc.kind = L_BNRED;
+    Lc.off_a = plan.tab.add(jobs.data(), jobs.size() * sizeof(BnReduceJob));
+    Lc.n = n_layers;
+    Lc.total_wgs = (int)wgs;
+    Lc.cfg = N;
+    plan.launches.push_back(Lc);
+    return run_plan(ctx, plan, arena);
+}
+
+}  // extern "C"

@@ -1,0 +1,117 @@
+// Internal device-table layouts and launch entry points shared by the host planner
+// (kfac_api.hip) and the kernel files.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kfac {
+
+// ---- grouped NT GEMM -------------------------------------------------------------
+// One operand of C[i][j] = sum_m a(i, m) * b(j, m): a matrix whose rows run along the
+// contraction index m.  Element (r, m) lives at
+//     base + (m / hw) * batch_stride + r * row_stride + (m % hw)
+// so an NCHW tensor [N, rows, hw] is contracted in place over (n, t) (batch_stride =
+// rows*hw, row_stride = hw) and a plain row-major matrix is the case hw >= K.
+// Row `ones_row` (if >= 0) is virtual: it reads as 1 for every m < K (the bias row of
+// the patch matrix).  Rows >= rows (other than ones_row) read as 0.
+struct Operand {
+    const void *base;
+    long long row_stride;
+    long long batch_stride;
+    int rows;
+    int hw;
+    int ones_row;
+    int vec;  // 4: every (r, m) with m % 4 == 0 is 16-byte aligned and m..m+3 share a run; else 1
+};
+
+enum : int { GEMM_SYM = 1 };
+
+struct GemmProblem {
+    Operand a, b;
+    float *C;        // [M, N], leading dimension ldc (may be null if only Ct is wanted)
+    float *Ct;       // optional transposed copy Ct[j][i], leading dimension ldct (or null)
+    float *partial;  // split-K scratch: [tiles][splits][BM*BN] (null if splits == 1)
+    long long ldc, ldct;
+    int M, N, K;
+    int tiles_m, tiles_n, n_tiles;
+    int splits, k_per_split;  // k_per_split is a multiple of 32
+    int flags;                // GEMM_SYM: M == N, only tiles tm >= tn are computed and mirrored
+    int tile_cfg;             // 0: 128x128 tiles, 1: 64x64 tiles
+    float alpha, beta;        // C = alpha * acc + beta * C   (beta == 0: C is not read)
+};
+
+// ---- patch extraction ------------------------------------------------------------
+struct PatchJob {
+    const void *src;  // [N, c_in, h_in, w_in]
+    void *dst;        // [c_in*k*k, ld]
+    long long ld;
+    int N, c_in, k, stride, pad, h_in, w_in, h, w;
+    int esize;        // 4 (f32) or 2 (bf16)
+    unsigned magic_w; // floor(2^32 / w) + 1: t / w == mulhi(t, magic_w) for t, w < 2^16
+    int wg_start;     // first workgroup of this job in the grouped launch
+};
+
+// ---- inversion ---------------------------------------------------------------------
+struct TraceJob {   // one per layer
+    const float *A, *G;
+    int dA, dG;
+};
+
+struct CopyJob {    // dst[i][j] = src[i][j] + (i == j) * damp[damp_idx]
+    const float *src;
+    float *dst;
+    long long lds, ldd;
+    int n;
+    int damp_idx;   // index into the damping array, or -1
+    int wg_start;
+};
+
+struct LeafJob {    // dst = (src + damp I)^-1 by in-register Gauss-Jordan, n <= 288
+    const float *src;
+    float *dst;
+    long long lds, ldd;
+    int n;
+    int damp_idx;   // or -1
+    int info_idx;   // index into info (or -1), pivot indices are reported + pivot_base
+    int pivot_base;
+};
+
+// ---- BatchNorm ---------------------------------------------------------------------
+struct BnJob {
+    const float *g_gamma, *g_beta;
+    float *F_ema, *out_gamma, *out_beta;
+    int C;
+    int wg_start;
+};
+
+struct BnReduceJob {
+    const float *dy, *xhat;
+    float *g_gamma, *g_beta;
+    int C, HW;
+    int wg_start;   // one wave per (n, c) row; 4 rows per workgroup
+};
+
+// ---- launchers (implemented in the kernel files) -----------------------------------
+hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, int n_probs,
+                       int total_wgs, int tile_cfg, int dtype, hipStream_t s);
+hipError_t launch_gemm_reduce(const GemmProblem *probs_dev, const int *red_start_dev, int n_probs,
+                              int total_wgs, hipStream_t s);
+hipError_t launch_patch(const PatchJob *jobs_dev, int n_jobs, int total_wgs, hipStream_t s);
+hipError_t launch_trace(const TraceJob *jobs_dev, int n_layers, float gamma, float *damp_dev,
+                        float *pi_out, hipStream_t s);
+hipError_t launch_copy_damp(const CopyJob *jobs_dev, int n_jobs, int total_wgs, const float *damp_dev,
+                            hipStream_t s);
+hipError_t launch_leaf(const LeafJob *jobs_dev, int n_jobs, int size_class, const float *damp_dev,
+                       int32_t *info, hipStream_t s);
+hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t s);
+hipError_t launch_bn(const BnJob *jobs_dev, int n_jobs, int total_wgs, int N, float decay, float lambda,
+                     hipStream_t s);
+hipError_t launch_bn_reduce(const BnReduceJob *jobs_dev, int n_jobs, int total_wgs, int N, hipStream_t s);
+
+// leaf size classes: a class value B serves n <= 32*B
+static const int kLeafClasses[] = {2, 3, 4, 5, 7, 8, 9};
+static const int kNumLeafClasses = 7;
+static const int kLeafMax = 288;
+
+}  // namespace kfac

@@ -1,0 +1,61 @@
+// Patch extraction (Sec. 3.3, Eq. 10: M_A = im2col(A) in R^{c_in k^2 x h w}) as a grouped,
+// HBM-bound copy.  Output layout [c_in*k*k][ld] with the contraction index m = (n, y, x)
+// contiguous, which is what the factor GEMM wants.  A wavefront owns one input plane
+// (n, c): for each of the k*k taps it writes one contiguous run of h*w outputs (fully
+// coalesced 256-byte stores); the plane itself is re-read k*k times out of L1/L2.
+#include "kfac_internal.h"
+
+namespace kfac {
+
+constexpr int TCHUNK = 1024;  // output positions of one plane handled by one workgroup pass
+
+template <typename T>
+__device__ __forceinline__ void patch_plane(const PatchJob &J, int plane, int t0, int t1, int lane)
+{
+    const int n = plane / J.c_in, c = plane - n * J.c_in;
+    const T *src = (const T *)J.src + (long long)plane * J.h_in * J.w_in;
+    const int hw = J.h * J.w;
+    const int kk = J.k * J.k;
+    T *dst_row0 = (T *)J.dst + (long long)c * kk * J.ld + (long long)n * hw;
+    for (int tap = 0; tap < kk; ++tap) {
+        const int ky = tap / J.k, kx = tap - ky * J.k;
+        T *dst = dst_row0 + (long long)tap * J.ld;
+        for (int t = t0 + lane; t < t1; t += 64) {
+            const int y = J.magic_w ? (int)__umulhi((unsigned)t, J.magic_w) : t / J.w;
+            const int x = t - y * J.w;
+            const int iy = y * J.stride + ky - J.pad, ix = x * J.stride + kx - J.pad;
+            T v = (T)0;
+            if (iy >= 0 && iy < J.h_in && ix >= 0 && ix < J.w_in) v = src[iy * J.w_in + ix];
+            dst[t] = v;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void patch_kernel(const PatchJob *__restrict__ jobs, int n_jobs)
+{
+    const int wg = blockIdx.x;
+    int lo = 0, hi = n_jobs;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (jobs[mid].wg_start <= wg) lo = mid; else hi = mid;
+    }
+    const PatchJob &J = jobs[lo];
+    const int local = wg - J.wg_start;
+    const int hw = J.h * J.w;
+    const int chunks = (hw + TCHUNK - 1) / TCHUNK;
+    const int chunk = local % chunks;
+    const int plane = (local / chunks) * 4 + (threadIdx.x >> 6);
+    if (plane >= J.N * J.c_in) return;
+    const int t0 = chunk * TCHUNK, t1 = min(hw, t0 + TCHUNK);
+    if (J.esize == 4) patch_plane<float>(J, plane, t0, t1, threadIdx.x & 63);
+    else              patch_plane<unsigned short>(J, plane, t0, t1, threadIdx.x & 63);
+}
+
+hipError_t launch_patch(const PatchJob *jobs_dev, int n_jobs, int total_wgs, hipStream_t s)
+{
+    if (total_wgs <= 0) return hipSuccess;
+    patch_kernel<<<dim3(total_wgs), dim3(256), 0, s>>>(jobs_dev, n_jobs);
+    return hipGetLastError();
+}
+
+}  // namespace kfac

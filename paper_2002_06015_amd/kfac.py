@@ -1,0 +1,227 @@
+"""Python binding of the C-ABI HIP library (``include/kfac.h``): argument marshalling only.
+
+torch is used for device memory and the stream handle; every step of the path runs
+in the HIP kernels of ``libkfac_hip.so``.  There is no CPU fallback: if the library
+is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkfac_hip.so")
+
+KFAC_OK, KFAC_ERR_INVALID, KFAC_ERR_WORKSPACE, KFAC_ERR_NOT_PD, KFAC_ERR_DEVICE = range(5)
+KFAC_F32, KFAC_BF16 = 0, 1
+
+EXPORTS = [
+    "kfac_status_string", "kfac_layer_dims", "kfac_workspace_bytes", "kfac_create", "kfac_destroy",
+    "kfac_im2col", "kfac_stats", "kfac_invert", "kfac_precondition",
+    "bn_unitwise_precondition", "bn_unitwise_reduce_nchw",
+]
+
+
+class kfac_layer(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("N", "c_in", "c_out", "k", "stride", "pad", "h_in", "w_in", "bias")]
+
+
+class KfacError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (status %d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the HIP library built in-tree (``python -m paper_2002_06015_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("HIP library %s is not built; run __graft_entry__.build()" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
+        L.kfac_status_string.restype = ctypes.c_char_p
+        L.kfac_status_string.argtypes = [ctypes.c_int]
+        L.kfac_layer_dims.argtypes = [vp, vp, vp, vp, vp]
+        L.kfac_workspace_bytes.restype = ctypes.c_size_t
+        L.kfac_workspace_bytes.argtypes = [vp, i32, ctypes.c_int]
+        L.kfac_create.argtypes = [vp, vp, vp, ctypes.c_size_t]
+        L.kfac_destroy.restype = None
+        L.kfac_destroy.argtypes = [vp]
+        L.kfac_im2col.argtypes = [vp, vp, ctypes.c_int, vp, vp, ctypes.c_int64]
+        L.kfac_stats.argtypes = [vp, i32, vp, ctypes.c_int, vp, vp, f32, i32, vp, vp]
+        L.kfac_invert.argtypes = [vp, i32, vp, vp, vp, f32, vp, vp, vp, vp]
+        L.kfac_precondition.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+        L.bn_unitwise_precondition.argtypes = [vp, i32, i32, vp, vp, vp, f32, f32, vp, vp, vp]
+        L.bn_unitwise_reduce_nchw.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().kfac_status_string(int(status)).decode()
+
+
+def _layers(layers: Sequence) -> ctypes.Array:
+    arr = (kfac_layer * len(layers))()
+    for i, L in enumerate(layers):
+        arr[i] = kfac_layer(*[int(v) for v in L])
+    return arr
+
+
+def _ptrs(tensors: Optional[Sequence[Optional[torch.Tensor]]], n: int, dtype=None) -> Optional[ctypes.Array]:
+    """Host array of device pointers; None entries become NULL; None list becomes NULL."""
+    if tensors is None:
+        return None
+    if len(tensors) != n:
+        raise ValueError("expected %d tensors, got %d" % (n, len(tensors)))
+    arr = (ctypes.c_void_p * n)()
+    for i, t in enumerate(tensors):
+        if t is None:
+            arr[i] = None
+            continue
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensor %d must be a contiguous device tensor" % i)
+        if dtype is not None and t.dtype != dtype:
+            raise ValueError("tensor %d must be %s" % (i, dtype))
+        arr[i] = t.data_ptr()
+    return arr
+
+
+def _i32(values: Sequence[int]) -> ctypes.Array:
+    return (ctypes.c_int32 * len(values))(*[int(v) for v in values])
+
+
+def kfac_layer_dims(layer) -> tuple:
+    L = kfac_layer(*[int(v) for v in layer])
+    out = [ctypes.c_int32() for _ in range(4)]
+    st = lib().kfac_layer_dims(ctypes.addressof(L), *[ctypes.addressof(o) for o in out])
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_layer_dims")
+    return tuple(o.value for o in out)
+
+
+def kfac_workspace_bytes(layers: Sequence, in_dtype: int = KFAC_F32) -> int:
+    arr = _layers(layers)
+    return int(lib().kfac_workspace_bytes(ctypes.addressof(arr), len(layers), int(in_dtype)))
+
+
+class Context:
+    """kfac_create/kfac_destroy with a torch-allocated workspace on the current device and
+    torch's current stream."""
+
+    def __init__(self, layers: Sequence, in_dtype: int = KFAC_F32, extra_layer_lists: Sequence[Sequence] = (),
+                 workspace_bytes: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None):
+        need = kfac_workspace_bytes(layers, in_dtype)
+        if need == 0:
+            raise KfacError(KFAC_ERR_INVALID, "kfac_workspace_bytes")
+        for other in extra_layer_lists:
+            need = max(need, kfac_workspace_bytes(other, in_dtype))
+        if workspace_bytes is not None:
+            need = int(workspace_bytes)
+        self.workspace = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+        base = (self.workspace.data_ptr() + 255) // 256 * 256
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        handle = ctypes.c_void_p()
+        st = lib().kfac_create(ctypes.addressof(handle), ctypes.c_void_p(self.stream.cuda_stream),
+                               ctypes.c_void_p(base), need)
+        if st != KFAC_OK:
+            raise KfacError(st, "kfac_create")
+        self.handle = handle
+
+    def close(self):
+        if getattr(self, "handle", None) is not None and self.handle.value:
+            lib().kfac_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _tdtype(in_dtype: int):
+    return torch.bfloat16 if in_dtype == KFAC_BF16 else torch.float32
+
+
+def kfac_im2col(ctx: Context, layer, in_dtype: int, act: torch.Tensor, patches: torch.Tensor, ld: int) -> None:
+    L = kfac_layer(*[int(v) for v in layer])
+    if act.dtype != _tdtype(in_dtype) or patches.dtype != _tdtype(in_dtype):
+        raise ValueError("dtype mismatch")
+    st = lib().kfac_im2col(ctx.handle, ctypes.addressof(L), int(in_dtype), act.data_ptr(), patches.data_ptr(), int(ld))
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_im2col")
+
+
+def kfac_stats(ctx: Context, layers: Sequence, in_dtype: int, act, grad_out, decay: float,
+               g_spatial_mean: bool, A_ema, G_ema) -> None:
+    n = len(layers)
+    arr = _layers(layers)
+    pa, pg = _ptrs(act, n, _tdtype(in_dtype)), _ptrs(grad_out, n, _tdtype(in_dtype))
+    pA, pG = _ptrs(A_ema, n, torch.float32), _ptrs(G_ema, n, torch.float32)
+    st = lib().kfac_stats(ctx.handle, n, ctypes.addressof(arr), int(in_dtype),
+                          pa and ctypes.addressof(pa), pg and ctypes.addressof(pg),
+                          float(decay), int(bool(g_spatial_mean)),
+                          pA and ctypes.addressof(pA), pG and ctypes.addressof(pG))
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_stats")
+
+
+def kfac_invert(ctx: Context, layers: Sequence, A_ema, G_ema, gamma: float, A_inv, G_inv,
+                pi_out: Optional[torch.Tensor] = None, info: Optional[torch.Tensor] = None) -> None:
+    n = len(layers)
+    arr = _layers(layers)
+    pA, pG = _ptrs(A_ema, n, torch.float32), _ptrs(G_ema, n, torch.float32)
+    pAi, pGi = _ptrs(A_inv, n, torch.float32), _ptrs(G_inv, n, torch.float32)
+    if pi_out is not None and (pi_out.dtype != torch.float32 or pi_out.numel() < n):
+        raise ValueError("pi_out must be float32 [n_layers]")
+    if info is not None and (info.dtype != torch.int32 or info.numel() < 2 * n):
+        raise ValueError("info must be int32 [2*n_layers]")
+    st = lib().kfac_invert(ctx.handle, n, ctypes.addressof(arr),
+                           pA and ctypes.addressof(pA), pG and ctypes.addressof(pG), float(gamma),
+                           pAi and ctypes.addressof(pAi), pGi and ctypes.addressof(pGi),
+                           None if pi_out is None else pi_out.data_ptr(),
+                           None if info is None else info.data_ptr())
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_invert")
+
+
+def kfac_precondition(ctx: Context, layers: Sequence, G_inv, A_inv, grad_W, out) -> None:
+    n = len(layers)
+    arr = _layers(layers)
+    ps = [_ptrs(x, n, torch.float32) for x in (G_inv, A_inv, grad_W, out)]
+    st = lib().kfac_precondition(ctx.handle, n, ctypes.addressof(arr), *[p and ctypes.addressof(p) for p in ps])
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_precondition")
+
+
+def bn_unitwise_precondition(ctx: Context, N: int, C: Sequence[int], g_gamma, g_beta, decay: float, lam: float,
+                             F_ema, out_gamma, out_beta) -> None:
+    n = len(C)
+    cs = _i32(C)
+    ps = [_ptrs(x, n, torch.float32) for x in (g_gamma, g_beta)]
+    qs = [_ptrs(x, n, torch.float32) for x in (F_ema, out_gamma, out_beta)]
+    st = lib().bn_unitwise_precondition(ctx.handle, n, int(N), ctypes.addressof(cs),
+                                        *[p and ctypes.addressof(p) for p in ps], float(decay), float(lam),
+                                        *[p and ctypes.addressof(p) for p in qs])
+    if st != KFAC_OK:
+        raise KfacError(st, "bn_unitwise_precondition")
+
+
+def bn_unitwise_reduce_nchw(ctx: Context, N: int, C: Sequence[int], HW: Sequence[int], dy, xhat,
+                            g_gamma, g_beta) -> None:
+    n = len(C)
+    cs, hs = _i32(C), _i32(HW)
+    ps = [_ptrs(x, n, torch.float32) for x in (dy, xhat, g_gamma, g_beta)]
+    st = lib().bn_unitwise_reduce_nchw(ctx.handle, n, int(N), ctypes.addressof(cs), ctypes.addressof(hs),
+                                       *[p and ctypes.addressof(p) for p in ps])
+    if st != KFAC_OK:
+        raise KfacError(st, "bn_unitwise_reduce_nchw")

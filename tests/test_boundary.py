@@ -1,0 +1,144 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports what the header
+declares, sizes workspaces, and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2002_06015_amd import kfac, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "kfac.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(kfac_[a-z0-9_]+|bn_unitwise_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = kfac.lib()
+    declared = _declared_functions()
+    assert set(declared) == set(kfac.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    assert kfac.status_string(kfac.KFAC_OK) == "ok"
+    for s in range(5):
+        assert kfac.status_string(s)
+
+
+def test_layer_dims_and_validation():
+    assert kfac.kfac_layer_dims(wl.conv_layer(32, 64, 64, 3, 1, 1, 56)) == (577, 64, 56, 56)
+    assert kfac.kfac_layer_dims(wl.fc_layer(32, 2048, 1000)) == (2049, 1000, 1, 1)
+    assert kfac.kfac_layer_dims(wl.conv_layer(2, 3, 64, 7, 2, 3, 224)) == (148, 64, 112, 112)
+    assert kfac.kfac_layer_dims(wl.conv_layer(2, 3, 4, 3, 2, 0, 6, bias=0)) == (27, 4, 2, 2)
+    for bad in [(0, 3, 4, 3, 1, 1, 5, 5, 1), (2, 0, 4, 3, 1, 1, 5, 5, 1), (2, 3, 4, 3, 0, 1, 5, 5, 1),
+                (2, 3, 4, 7, 1, 0, 5, 5, 1), (2, 3, 4, 3, 1, -1, 5, 5, 1), (2, 3, 4, 3, 1, 1, 5, 5, 2)]:
+        with pytest.raises(kfac.KfacError):
+            kfac.kfac_layer_dims(bad)
+
+
+def test_workspace_bytes():
+    assert kfac.kfac_workspace_bytes([(0, 1, 1, 1, 1, 0, 1, 1, 1)]) == 0
+    small = kfac.kfac_workspace_bytes(wl.config_layers(1))
+    c2 = kfac.kfac_workspace_bytes(wl.config_layers(2))
+    c4 = kfac.kfac_workspace_bytes(wl.config_layers(4))
+    assert 0 < small < c2 < c4 < 16 * 2 ** 30
+    # patches of the 3x3 layer (576 x 100352 fp32) must fit
+    assert c2 >= 576 * 100352 * 4
+    assert kfac.kfac_workspace_bytes(wl.config_layers(2), kfac.KFAC_BF16) < c2
+
+
+def _fake_ctx(nbytes=1 << 20):
+    """A context on a made-up (aligned, never dereferenced) workspace address: enough to
+    exercise validation, which must fail before any GPU call."""
+    h = ctypes.c_void_p()
+    st = kfac.lib().kfac_create(ctypes.addressof(h), None, ctypes.c_void_p(0x100000), nbytes)
+    assert st == kfac.KFAC_OK
+    return h
+
+
+def test_create_rejects_bad_arguments():
+    h = ctypes.c_void_p()
+    L = kfac.lib()
+    assert L.kfac_create(None, None, ctypes.c_void_p(0x100000), 1024) == kfac.KFAC_ERR_INVALID
+    assert L.kfac_create(ctypes.addressof(h), None, None, 1024) == kfac.KFAC_ERR_INVALID
+    assert L.kfac_create(ctypes.addressof(h), None, ctypes.c_void_p(0x100001), 1024) == kfac.KFAC_ERR_INVALID
+    assert L.kfac_create(ctypes.addressof(h), None, ctypes.c_void_p(0x100000), 0) == kfac.KFAC_ERR_INVALID
+    L.kfac_destroy(None)
+
+
+def test_calls_reject_bad_arguments_without_a_gpu():
+    L = kfac.lib()
+    h = _fake_ctx()
+    lay = kfac.kfac_layer(*wl.fc_layer(4, 8, 3))
+    lp = ctypes.addressof(lay)
+    fake = (ctypes.c_void_p * 1)(0x200000)
+    fp = ctypes.addressof(fake)
+    null1 = (ctypes.c_void_p * 1)(None)
+    np_ = ctypes.addressof(null1)
+    INV = kfac.KFAC_ERR_INVALID
+    # kfac_stats
+    assert L.kfac_stats(None, 1, lp, 0, fp, fp, 0.0, 0, fp, fp) == INV
+    assert L.kfac_stats(h, 0, lp, 0, fp, fp, 0.0, 0, fp, fp) == INV
+    assert L.kfac_stats(h, 1, None, 0, fp, fp, 0.0, 0, fp, fp) == INV
+    assert L.kfac_stats(h, 1, lp, 7, fp, fp, 0.0, 0, fp, fp) == INV
+    assert L.kfac_stats(h, 1, lp, 0, fp, fp, 1.0, 0, fp, fp) == INV          # decay must be < 1
+    assert L.kfac_stats(h, 1, lp, 0, fp, fp, -0.1, 0, fp, fp) == INV
+    assert L.kfac_stats(h, 1, lp, 0, fp, fp, float("nan"), 0, fp, fp) == INV
+    assert L.kfac_stats(h, 1, lp, 0, None, None, 0.0, 0, fp, fp) == INV       # nothing to do
+    assert L.kfac_stats(h, 1, lp, 0, fp, fp, 0.0, 0, None, fp) == INV          # act given, A_ema missing
+    assert L.kfac_stats(h, 1, lp, 0, fp, fp, 0.0, 0, fp, np_) == INV
+    # kfac_invert
+    assert L.kfac_invert(h, 1, lp, fp, fp, -1.0, fp, fp, None, None) == INV
+    assert L.kfac_invert(h, 1, lp, fp, fp, 1e-3, fp, fp, None, None) == INV   # in == out
+    assert L.kfac_invert(h, 1, lp, None, fp, 1e-3, fp, fp, None, None) == INV
+    assert L.kfac_invert(h, 1, lp, np_, fp, 1e-3, fp, fp, None, None) == INV
+    # kfac_precondition
+    assert L.kfac_precondition(h, 1, lp, fp, fp, None, fp) == INV
+    assert L.kfac_precondition(h, 1, lp, fp, fp, fp, np_) == INV
+    assert L.kfac_precondition(h, -1, lp, fp, fp, fp, fp) == INV
+    # kfac_im2col
+    assert L.kfac_im2col(h, lp, 0, None, fake[0], 4) == INV
+    assert L.kfac_im2col(h, lp, 0, fake[0], fake[0], 3) == INV                 # ld < N*h*w
+    # BatchNorm
+    C = (ctypes.c_int32 * 1)(8)
+    cp = ctypes.addressof(C)
+    assert L.bn_unitwise_precondition(h, 1, 0, cp, fp, fp, 0.0, 1e-6, fp, fp, fp) == INV
+    assert L.bn_unitwise_precondition(h, 1, 4, None, fp, fp, 0.0, 1e-6, fp, fp, fp) == INV
+    assert L.bn_unitwise_precondition(h, 1, 4, cp, fp, fp, 1.5, 1e-6, fp, fp, fp) == INV
+    assert L.bn_unitwise_precondition(h, 1, 4, cp, fp, fp, 0.0, -1.0, fp, fp, fp) == INV
+    assert L.bn_unitwise_precondition(h, 1, 4, cp, fp, np_, 0.0, 1e-6, fp, fp, fp) == INV
+    Z = (ctypes.c_int32 * 1)(0)
+    assert L.bn_unitwise_reduce_nchw(h, 1, 4, cp, ctypes.addressof(Z), fp, fp, fp, fp) == INV
+    assert L.bn_unitwise_reduce_nchw(h, 1, 4, cp, None, fp, fp, fp, fp) == INV
+    L.kfac_destroy(h)
+
+
+def test_workspace_too_small_is_reported_before_launch():
+    """The 3x3 layer of configuration 2 needs a 231 MB patch buffer; a 1 MB workspace is refused."""
+    L = kfac.lib()
+    h = _fake_ctx(1 << 20)
+    lay = kfac.kfac_layer(*wl.config_layers(2)[0])
+    fake = (ctypes.c_void_p * 1)(0x200000)
+    fp = ctypes.addressof(fake)
+    st = L.kfac_stats(h, 1, ctypes.addressof(lay), 0, fp, fp, 0.0, 0, fp, fp)
+    assert st == kfac.KFAC_ERR_WORKSPACE
+    L.kfac_destroy(h)
+
+
+def test_resnet50_layer_set_matches_planned_histogram():
+    layers, bns = wl.resnet50_layers(32)
+    dims = sorted([L.dA for L in layers] + [L.dG for L in layers])
+    from collections import Counter
+    hist = Counter(dims)
+    assert hist == Counter({64: 7, 65: 5, 128: 8, 129: 4, 148: 1, 256: 16, 257: 10, 512: 11, 513: 8, 577: 3,
+                            1000: 1, 1024: 7, 1025: 7, 1153: 4, 2048: 4, 2049: 3, 2305: 6, 4609: 3})
+    assert sum(C for C, _ in bns) == 26560
+    tot = sum(sum(wl.flops(L).values()) for L in layers)
+    assert abs(tot / 1e12 - 1.396) < 0.01

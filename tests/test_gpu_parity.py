@@ -1,0 +1,363 @@
+"""GPU parity tests: the HIP path (through the C ABI) against the float64 CPU oracle,
+element by element on the same seeded inputs.
+
+Tolerances (norm-wise: max|X - X_ref| / max|X_ref|): 1e-4 for fp32 factors and
+inverses' defining property, 1e-3 for the preconditioned gradient; integer/copy work
+(patch extraction) is bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2002_06015_amd import kfac, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL_FACTOR = 1e-4
+TOL_PRECOND = 1e-3
+
+
+def relerr(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300))
+
+
+def dev(x, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    assert torch.cuda.is_available()
+    torch.cuda.set_device(0)
+    kfac.lib()
+    return torch.device("cuda")
+
+
+SMALL_LAYERS = [
+    wl.fc_layer(32, 64, 32),                       # configuration 1
+    wl.fc_layer(5, 7, 3, bias=0),
+    wl.fc_layer(1, 130, 70),
+    wl.conv_layer(2, 3, 4, 3, 1, 1, 5),
+    wl.conv_layer(3, 5, 6, 3, 2, 1, 9),
+    wl.conv_layer(2, 8, 5, 1, 1, 0, 6),            # direct (no patches), hw % 4 == 0
+    wl.conv_layer(2, 8, 5, 1, 1, 0, 7),            # direct, hw = 49 (unaligned runs)
+    wl.conv_layer(3, 6, 4, 1, 2, 0, 8, bias=0),    # strided 1x1
+    wl.conv_layer(2, 3, 8, 7, 2, 3, 30),           # 7x7 stem shape, d_A = 148
+    wl.conv_layer(4, 16, 70, 3, 1, 1, 12),         # d_A = 145: two 128-tiles with a ragged tail
+    wl.conv_layer(2, 40, 130, 3, 1, 1, 10),        # d_A = 361: several tiles, d_G = 130
+]
+
+
+def run_stats(layers, acts, grads, decay, spatial_mean, A=None, G=None, dtype=kfac.KFAC_F32, ctx=None):
+    own = ctx is None
+    if own:
+        ctx = kfac.Context(layers, dtype)
+    tdt = torch.bfloat16 if dtype == kfac.KFAC_BF16 else torch.float32
+    d_act = [None if a is None else dev(a, tdt) for a in acts]
+    d_grad = [None if g is None else dev(g, tdt) for g in grads]
+    if A is None:
+        A = [torch.full((L.dA, L.dA), float("nan"), device="cuda") for L in layers]
+    if G is None:
+        G = [torch.full((L.dG, L.dG), float("nan"), device="cuda") for L in layers]
+    kfac.kfac_stats(ctx, layers, dtype, d_act, d_grad, decay, spatial_mean, A, G)
+    torch.cuda.synchronize()
+    if own:
+        ctx.close()
+    return A, G
+
+
+# ------------------------------------------------------------------ a1: patch extraction
+@pytest.mark.parametrize("layer", [L for L in SMALL_LAYERS if L.h_in > 1] + [wl.conv_layer(2, 4, 4, 3, 1, 1, 40)])
+@pytest.mark.parametrize("dtype", [kfac.KFAC_F32, kfac.KFAC_BF16])
+def test_im2col_bit_exact(gpu, layer, dtype):
+    act = wl.make_act(layer, 11)
+    if dtype == kfac.KFAC_BF16:
+        act = wl.round_to_bf16(act)
+    tdt = torch.bfloat16 if dtype == kfac.KFAC_BF16 else torch.float32
+    ctx = kfac.Context([layer], dtype)
+    d0 = layer.c_in * layer.k ** 2
+    ld = layer.M + 5
+    P = torch.full((d0, ld), -7.0, device="cuda", dtype=tdt)
+    kfac.kfac_im2col(ctx, layer, dtype, dev(act, tdt), P, ld)
+    torch.cuda.synchronize()
+    ctx.close()
+    ref = oracle.im2col(tuple(layer), act)                      # [N, dA, hw]
+    ref = ref[:, :d0, :].transpose(1, 0, 2).reshape(d0, layer.M)
+    got = host(P)
+    assert np.array_equal(got[:, :layer.M], ref)
+    assert np.all(got[:, layer.M:] == -7.0)                      # padding columns untouched
+
+
+# ------------------------------------------------------------------ a2-a4: factors + running average
+@pytest.mark.parametrize("layer", SMALL_LAYERS)
+@pytest.mark.parametrize("spatial_mean", [False, True])
+def test_stats_two_steps(gpu, layer, spatial_mean):
+    a0, g0 = wl.make_act(layer, 21), wl.make_grad_out(layer, 21)
+    a1, g1 = wl.make_act(layer, 521), wl.make_grad_out(layer, 521)
+    A, G = run_stats([layer], [a0], [g0], 0.0, spatial_mean)                  # step 0 overwrites NaNs
+    Ar, Gr = oracle.kfac_stats(tuple(layer), a0, g0, 0.0, spatial_mean, None, None)
+    assert relerr(host(A[0]), Ar) <= TOL_FACTOR
+    assert relerr(host(G[0]), Gr) <= TOL_FACTOR
+    A, G = run_stats([layer], [a1], [g1], wl.DECAY, spatial_mean, A, G)       # step 1: running average
+    Ar, Gr = oracle.kfac_stats(tuple(layer), a1, g1, wl.DECAY, spatial_mean, Ar, Gr)
+    hA, hG = host(A[0]), host(G[0])
+    assert relerr(hA, Ar) <= TOL_FACTOR
+    assert relerr(hG, Gr) <= TOL_FACTOR
+    assert np.array_equal(hA, hA.T) and np.array_equal(hG, hG.T)              # exactly symmetric
+    if layer.bias:
+        assert abs(hA[-1, -1] - 1.0) < 1e-5
+
+
+def test_stats_grouped_and_partial_inputs(gpu):
+    """Several layers in one call; A-only and G-only forms leave the other factor alone."""
+    layers = SMALL_LAYERS[:6]
+    acts = [wl.make_act(L, 30 + i) for i, L in enumerate(layers)]
+    grads = [wl.make_grad_out(L, 30 + i) for i, L in enumerate(layers)]
+    A, G = run_stats(layers, acts, grads, 0.0, False)
+    for i, L in enumerate(layers):
+        Ar, Gr = oracle.kfac_stats(tuple(L), acts[i], grads[i], 0.0, False, None, None)
+        assert relerr(host(A[i]), Ar) <= TOL_FACTOR
+        assert relerr(host(G[i]), Gr) <= TOL_FACTOR
+    keepG = [g.clone() for g in G]
+    keepA = [a.clone() for a in A]
+    A2, G2 = run_stats(layers, acts, [None] * len(layers), 0.5, False, A, G)
+    for i in range(len(layers)):
+        assert torch.equal(G2[i], keepG[i])
+    ctx = kfac.Context(layers)
+    kfac.kfac_stats(ctx, layers, kfac.KFAC_F32, None, [dev(g) for g in grads], 0.5, False, None, G2)
+    torch.cuda.synchronize()
+    ctx.close()
+    for i, L in enumerate(layers):
+        Ar = oracle.factor_A(tuple(L), acts[i])
+        assert relerr(host(A2[i]), 0.5 * host(keepA[i]) + 0.5 * Ar) <= TOL_FACTOR
+
+
+def test_stats_split_k_is_reproducible_and_matches(gpu):
+    """Long contraction (K = 4*48*48 = 9216 >> split threshold) on few tiles: split-K path."""
+    layer = wl.conv_layer(4, 24, 20, 3, 1, 1, 48)            # d_A = 217, K = 9216
+    a, g = wl.make_act(layer, 41), wl.make_grad_out(layer, 41)
+    A1, G1 = run_stats([layer], [a], [g], 0.0, True)
+    A2, G2 = run_stats([layer], [a], [g], 0.0, True)
+    assert torch.equal(A1[0], A2[0]) and torch.equal(G1[0], G2[0])          # bitwise reproducible
+    Ar, Gr = oracle.kfac_stats(tuple(layer), a, g, 0.0, True, None, None)
+    assert relerr(host(A1[0]), Ar) <= TOL_FACTOR
+    assert relerr(host(G1[0]), Gr) <= TOL_FACTOR
+
+
+@pytest.mark.parametrize("layer", [SMALL_LAYERS[0], SMALL_LAYERS[5], SMALL_LAYERS[6], SMALL_LAYERS[9]])
+def test_stats_bf16_inputs(gpu, layer):
+    """bf16-input variant: against the oracle on the bf16-rounded inputs the bound is the
+    fp32 one (products of bf16 values are exact in fp32); against the oracle on the
+    original fp32 inputs the error is that of the input rounding (2^-9 relative per value)."""
+    a, g = wl.make_act(layer, 51), wl.make_grad_out(layer, 51)
+    ab, gb = wl.round_to_bf16(a), wl.round_to_bf16(g)
+    A, G = run_stats([layer], [ab], [gb], 0.0, True, dtype=kfac.KFAC_BF16)
+    Ar, Gr = oracle.kfac_stats(tuple(layer), ab, gb, 0.0, True, None, None)
+    assert relerr(host(A[0]), Ar) <= TOL_FACTOR
+    assert relerr(host(G[0]), Gr) <= TOL_FACTOR
+    Af, Gf = oracle.kfac_stats(tuple(layer), a, g, 0.0, True, None, None)
+    assert relerr(host(A[0]), Af) <= 8e-3
+    assert relerr(host(G[0]), Gf) <= 8e-3
+
+
+# ------------------------------------------------------------------ a5-a7: damping + inversion
+def _spd(n, seed, cond=1e3, scale=1.0):
+    rng = np.random.default_rng(seed)
+    Q, _ = np.linalg.qr(rng.standard_normal((n, n)))
+    e = np.geomspace(1.0, 1.0 / cond, n) * scale
+    M = (Q * e) @ Q.T
+    return (0.5 * (M + M.T)).astype(np.float32)
+
+
+def run_invert(layers, As, Gs, gamma):
+    ctx = kfac.Context(layers)
+    dA = [dev(a) for a in As]
+    dG = [dev(g) for g in Gs]
+    Ai = [torch.full_like(a, float("nan")) for a in dA]
+    Gi = [torch.full_like(g, float("nan")) for g in dG]
+    pi = torch.zeros(len(layers), device="cuda")
+    info = torch.full((2 * len(layers),), -5, dtype=torch.int32, device="cuda")
+    kfac.kfac_invert(ctx, layers, dA, dG, gamma, Ai, Gi, pi, info)
+    torch.cuda.synchronize()
+    ctx.close()
+    return Ai, Gi, host(pi), info.cpu().numpy()
+
+
+@pytest.mark.parametrize("dims", [(1, 1), (2, 3), (33, 17), (65, 32), (129, 64), (148, 96), (257, 160),
+                                  (224, 256), (289, 288), (577, 64), (700, 513), (1153, 321)])
+def test_invert_matches_oracle(gpu, dims):
+    dA, dG = dims
+    layer = wl.fc_layer(4, dA - 1, dG)
+    A = _spd(dA, 100 + dA, cond=300.0, scale=0.5)
+    G = _spd(dG, 200 + dG, cond=50.0, scale=1e-6)
+    gamma = 1e-3
+    Ai, Gi, pi, info = run_invert([layer], [A], [G], gamma)
+    Air, Gir, pir, infor = oracle.kfac_invert(A, G, gamma)
+    assert not info.any() and not infor.any()
+    assert abs(pi[0] - pir) <= 1e-5 * pir
+    hAi, hGi = host(Ai[0]), host(Gi[0])
+    assert relerr(hAi, Air) <= TOL_FACTOR
+    assert relerr(hGi, Gir) <= TOL_FACTOR
+    assert np.array_equal(hAi, hAi.T) and np.array_equal(hGi, hGi.T)
+    # defining property, independent of the oracle
+    da, dg = pir * gamma, gamma / pir
+    assert np.abs((A.astype(np.float64) + da * np.eye(dA)) @ hAi - np.eye(dA)).max() <= 1e-3
+    assert np.abs((G.astype(np.float64) + dg * np.eye(dG)) @ hGi - np.eye(dG)).max() <= 1e-3
+
+
+def test_invert_grouped_mixed_sizes(gpu):
+    dims = [(65, 64), (577, 64), (129, 512), (257, 128), (321, 300)]
+    layers = [wl.fc_layer(2, a - 1, g) for a, g in dims]
+    As = [_spd(a, 300 + i, 200.0, 0.5) for i, (a, g) in enumerate(dims)]
+    Gs = [_spd(g, 400 + i, 30.0, 1e-6) for i, (a, g) in enumerate(dims)]
+    Ai, Gi, pi, info = run_invert(layers, As, Gs, 1e-3)
+    assert not info.any()
+    for i in range(len(dims)):
+        Air, Gir, pir, _ = oracle.kfac_invert(As[i], Gs[i], 1e-3)
+        assert relerr(host(Ai[i]), Air) <= TOL_FACTOR
+        assert relerr(host(Gi[i]), Gir) <= TOL_FACTOR
+
+
+def test_invert_reports_non_positive_definite(gpu):
+    """gamma = 0 on a singular A (exact zero pivot) and an indefinite G inside the blocked path:
+    info names the same pivot as the oracle's Cholesky, and nothing faults."""
+    layer = wl.fc_layer(2, 39, 300)
+    A = _spd(40, 5, 10.0, 1.0)
+    A[5, :] = 0.0
+    A[:, 5] = 0.0                                          # pivot 5 is exactly zero
+    G = _spd(300, 7, 10.0, 1.0)
+    G[150, 150] = -4.0                                     # pivot 150 is negative
+    Ai, Gi, pi, info = run_invert([layer], [A], [G], 0.0)
+    _, _, _, infor = oracle.kfac_invert(A, G, 0.0)
+    assert infor[0] == 6 and infor[1] == 151
+    assert info[0] == 6 and info[1] == 151
+
+
+def test_zero_factor_gives_pi_one(gpu):
+    layer = wl.fc_layer(2, 7, 5)
+    A = np.zeros((8, 8), np.float32)
+    G = _spd(5, 9, 10.0, 1.0)
+    Ai, Gi, pi, info = run_invert([layer], [A], [G], 0.5)
+    assert pi[0] == 1.0 and not info.any()
+    np.testing.assert_allclose(host(Ai[0]), np.eye(8) / 0.5, rtol=1e-6)
+
+
+# ------------------------------------------------------------------ a8: preconditioning
+@pytest.mark.parametrize("dims", [(65, 32), (577, 64), (130, 257), (300, 1000)])
+def test_precondition_matches_oracle(gpu, dims):
+    dA, dG = dims
+    layer = wl.fc_layer(2, dA - 1, dG)
+    Ai = _spd(dA, 500 + dA, 100.0, 2.0)
+    Gi = _spd(dG, 600 + dG, 100.0, 1e3)
+    V = wl.make_grad_W(layer, 3)
+    ctx = kfac.Context([layer])
+    out = torch.full((dG, dA), float("nan"), device="cuda")
+    kfac.kfac_precondition(ctx, [layer], [dev(Gi)], [dev(Ai)], [dev(V)], [out])
+    torch.cuda.synchronize()
+    Ur = oracle.kfac_precondition(Gi, Ai, V)
+    assert relerr(host(out), Ur) <= TOL_PRECOND
+    # in place: out == grad_W
+    dV = dev(V)
+    kfac.kfac_precondition(ctx, [layer], [dev(Gi)], [dev(Ai)], [dV], [dV])
+    torch.cuda.synchronize()
+    ctx.close()
+    assert torch.equal(dV, out)
+
+
+# ------------------------------------------------------------------ a9: BatchNorm unit-wise
+def test_bn_unitwise_matches_oracle(gpu):
+    N = 32
+    Cs = [64, 256, 1, 77, 1024]
+    ctx = kfac.Context([wl.fc_layer(2, 4, 4)])
+    ggs, gbs = zip(*[wl.make_bn_grads(N, C, 60 + i) for i, C in enumerate(Cs)])
+    F = [torch.full((C, 3), float("nan"), device="cuda") for C in Cs]
+    og = [torch.empty(C, device="cuda") for C in Cs]
+    ob = [torch.empty(C, device="cuda") for C in Cs]
+    kfac.bn_unitwise_precondition(ctx, N, Cs, [dev(x) for x in ggs], [dev(x) for x in gbs], 0.0, wl.BN_LAMBDA,
+                                  F, og, ob)
+    torch.cuda.synchronize()
+    refs = [oracle.bn_unitwise_precondition(ggs[i], gbs[i], 0.0, wl.BN_LAMBDA) for i in range(len(Cs))]
+    for i in range(len(Cs)):
+        assert relerr(host(F[i]), refs[i][0]) <= TOL_FACTOR
+        assert relerr(host(og[i]), refs[i][1]) <= TOL_FACTOR
+        assert relerr(host(ob[i]), refs[i][2]) <= TOL_FACTOR
+    # second step with the running average
+    gg2, gb2 = zip(*[wl.make_bn_grads(N, C, 560 + i) for i, C in enumerate(Cs)])
+    kfac.bn_unitwise_precondition(ctx, N, Cs, [dev(x) for x in gg2], [dev(x) for x in gb2], wl.DECAY,
+                                  wl.BN_LAMBDA, F, og, ob)
+    torch.cuda.synchronize()
+    ctx.close()
+    for i in range(len(Cs)):
+        Fr, ogr, obr = oracle.bn_unitwise_precondition(gg2[i], gb2[i], wl.DECAY, wl.BN_LAMBDA, refs[i][0])
+        assert relerr(host(F[i]), Fr) <= TOL_FACTOR
+        assert relerr(host(og[i]), ogr) <= TOL_FACTOR
+        assert relerr(host(ob[i]), obr) <= TOL_FACTOR
+
+
+def test_bn_reduce_nchw_matches_oracle(gpu):
+    N = 4
+    Cs, HWs = [8, 3, 16], [196, 49, 1]
+    ctx = kfac.Context([wl.fc_layer(2, 4, 4)])
+    data = [wl.make_bn_nchw(N, C, HW, 70 + i) for i, (C, HW) in enumerate(zip(Cs, HWs))]
+    gg = [torch.empty(N, C, device="cuda") for C in Cs]
+    gb = [torch.empty(N, C, device="cuda") for C in Cs]
+    kfac.bn_unitwise_reduce_nchw(ctx, N, Cs, HWs, [dev(d[0]) for d in data], [dev(d[1]) for d in data], gg, gb)
+    torch.cuda.synchronize()
+    ctx.close()
+    for i in range(len(Cs)):
+        ggr, gbr = oracle.bn_reduce_nchw(*data[i])
+        assert relerr(host(gg[i]), ggr) <= TOL_FACTOR
+        assert relerr(host(gb[i]), gbr) <= TOL_FACTOR
+
+
+# ------------------------------------------------------------------ whole step, configurations 1 and 2
+def _full_step(layers, config, spatial_mean, steps=2):
+    ctx = kfac.Context(layers)
+    A = [torch.full((L.dA, L.dA), float("nan"), device="cuda") for L in layers]
+    G = [torch.full((L.dG, L.dG), float("nan"), device="cuda") for L in layers]
+    Ai = [torch.empty_like(x) for x in A]
+    Gi = [torch.empty_like(x) for x in G]
+    U = [torch.empty(L.dG, L.dA, device="cuda") for L in layers]
+    info = torch.zeros(2 * len(layers), dtype=torch.int32, device="cuda")
+    Ar, Gr = [None] * len(layers), [None] * len(layers)
+    worst = {"A": 0.0, "G": 0.0, "U": 0.0}
+    for step in range(steps):
+        decay = 0.0 if step == 0 else wl.DECAY
+        acts = [wl.make_act(L, wl.layer_seed(config, i, step == 1)) for i, L in enumerate(layers)]
+        grads = [wl.make_grad_out(L, wl.layer_seed(config, i, step == 1)) for i, L in enumerate(layers)]
+        gws = [wl.make_grad_W(L, wl.layer_seed(config, i, step == 1)) for i, L in enumerate(layers)]
+        kfac.kfac_stats(ctx, layers, kfac.KFAC_F32, [dev(a) for a in acts], [dev(g) for g in grads], decay,
+                        spatial_mean, A, G)
+        kfac.kfac_invert(ctx, layers, A, G, wl.GAMMA, Ai, Gi, None, info)
+        kfac.kfac_precondition(ctx, layers, Gi, Ai, [dev(g) for g in gws], U)
+        torch.cuda.synchronize()
+        assert not info.cpu().numpy().any()
+        for i, L in enumerate(layers):
+            Ar[i], Gr[i] = oracle.kfac_stats(tuple(L), acts[i], grads[i], decay, spatial_mean, Ar[i], Gr[i])
+            Air, Gir, _, _ = oracle.kfac_invert(Ar[i], Gr[i], wl.GAMMA)
+            Ur = oracle.kfac_precondition(Gir, Air, gws[i])
+            worst["A"] = max(worst["A"], relerr(host(A[i]), Ar[i]))
+            worst["G"] = max(worst["G"], relerr(host(G[i]), Gr[i]))
+            worst["U"] = max(worst["U"], relerr(host(U[i]), Ur))
+    ctx.close()
+    return worst
+
+
+def test_config1_fc_two_steps(gpu):
+    worst = _full_step(wl.config_layers(1), 1, False)
+    assert worst["A"] <= TOL_FACTOR and worst["G"] <= TOL_FACTOR and worst["U"] <= TOL_PRECOND, worst
+
+
+def test_config2_conv3x3_full_size(gpu):
+    """One ResNet-50 3x3 layer at full size (A 577x577 from 100352 patch columns); the oracle
+    rebuilds the whole factor (a few seconds)."""
+    worst = _full_step(wl.config_layers(2), 2, True, steps=1)
+    assert worst["A"] <= TOL_FACTOR and worst["G"] <= TOL_FACTOR and worst["U"] <= TOL_PRECOND, worst
