@@ -195,7 +195,7 @@ def run_invert(layers, As, Gs, gamma):
                                   (224, 256), (289, 288), (577, 64), (700, 513), (1153, 321)])
 def test_invert_matches_oracle(gpu, dims):
     dA, dG = dims
-    layer = wl.fc_layer(4, dA - 1, dG)
+    layer = wl.fc_layer(4, dA, dG, bias=0)
     A = _spd(dA, 100 + dA, cond=300.0, scale=0.5)
     G = _spd(dG, 200 + dG, cond=50.0, scale=1e-6)
     gamma = 1e-3
