@@ -1,0 +1,258 @@
+#!/usr/bin/env python3
+"""Benchmark of the K-FAC hot path on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic mini-batch: factor construction
+with running average for every Conv/FC layer, damped inversion of every factor (or of the
+seeded stale subset in configuration 5), preconditioning of every weight gradient, and the
+unit-wise BatchNorm call for all BatchNorm layers.  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--dtype f32|bf16]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
+PEAK_HBM_GBS = 8000.0
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default: full ResNet-50 set, batch 32)")
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32", help="type of activations / output gradients")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives are built); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2002_06015_amd import kfac, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    kfac.lib()
+    cfg = args.config
+    layers = wl.config_layers(cfg)
+    N = layers[0].N
+    bns = wl.resnet50_layers(N)[1] if cfg >= 4 else []
+    in_dtype = kfac.KFAC_BF16 if args.dtype == "bf16" else kfac.KFAC_F32
+    tdt = torch.bfloat16 if args.dtype == "bf16" else torch.float32
+    spatial_mean = cfg >= 2          # the conv configurations ask for spatially averaged output gradients
+    stale = cfg == 5
+    n = len(layers)
+
+    # ---------------------------------------------------------------- inputs (seeded, host -> HBM)
+    t0 = time.time()
+    acts, grads, gws = [], [], []
+    for i, L in enumerate(layers):
+        s = wl.layer_seed(cfg, i)
+        a, g = wl.make_act(L, s), wl.make_grad_out(L, s)
+        acts.append(torch.from_numpy(a).cuda().to(tdt))
+        grads.append(torch.from_numpy(g).cuda().to(tdt))
+        gws.append(torch.from_numpy(wl.make_grad_W(L, s)).cuda())
+        del a, g
+    bn_gg, bn_gb = [], []
+    for i, (C, _) in enumerate(bns):
+        gg, gb = wl.make_bn_grads(N, C, wl.layer_seed(cfg, 100 + i))
+        bn_gg.append(torch.from_numpy(gg).cuda())
+        bn_gb.append(torch.from_numpy(gb).cuda())
+    log("inputs generated and uploaded in %.1f s" % (time.time() - t0))
+
+    subset = list(wl.stale_subset(n, seed=0)) if stale else list(range(n))
+    sub_layers = [layers[i] for i in subset]
+    ctx = kfac.Context(layers, in_dtype, extra_layer_lists=[sub_layers])
+    A = [torch.zeros(L.dA, L.dA, device="cuda") for L in layers]
+    G = [torch.zeros(L.dG, L.dG, device="cuda") for L in layers]
+    Ai = [torch.zeros_like(x) for x in A]
+    Gi = [torch.zeros_like(x) for x in G]
+    U = [torch.zeros(L.dG, L.dA, device="cuda") for L in layers]
+    info = torch.zeros(2 * n, dtype=torch.int32, device="cuda")
+    Cs = [C for C, _ in bns]
+    F = [torch.zeros(C, 3, device="cuda") for C in Cs]
+    og = [torch.zeros(C, device="cuda") for C in Cs]
+    ob = [torch.zeros(C, device="cuda") for C in Cs]
+
+    def sel(xs, idx):
+        return [xs[i] for i in idx]
+
+    def stats(decay):
+        kfac.kfac_stats(ctx, layers, in_dtype, acts, grads, decay, spatial_mean, A, G)
+
+    def invert(idx):
+        kfac.kfac_invert(ctx, sel(layers, idx), sel(A, idx), sel(G, idx), wl.GAMMA, sel(Ai, idx), sel(Gi, idx),
+                         None, info)
+
+    def precond():
+        kfac.kfac_precondition(ctx, layers, Gi, Ai, gws, U)
+
+    def bn(decay):
+        if Cs:
+            kfac.bn_unitwise_precondition(ctx, N, Cs, bn_gg, bn_gb, decay, wl.BN_LAMBDA, F, og, ob)
+
+    def step(decay, idx):
+        stats(decay)
+        invert(idx)
+        precond()
+        bn(decay)
+
+    # step 0 initialises every running average and every inverse (untimed)
+    step(0.0, list(range(n)))
+    torch.cuda.synchronize()
+    assert int(info.abs().sum().item()) == 0, "a factor was not positive definite"
+    for _ in range(args.warmup):
+        step(wl.DECAY, subset)
+    torch.cuda.synchronize()
+
+    # ---------------------------------------------------------------- timed region
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        step(wl.DECAY, subset)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    assert int(info.abs().sum().item()) == 0
+    assert all(bool(torch.isfinite(u).all().item()) for u in U)
+
+    # ---------------------------------------------------------------- per-stage and per-kernel times
+    stage_ms = {"stats": 0.0, "invert": 0.0, "precondition": 0.0, "bn": 0.0}
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+    for _ in range(args.profile_steps):
+        ev[0].record(); stats(wl.DECAY)
+        ev[1].record(); invert(subset)
+        ev[2].record(); precond()
+        ev[3].record(); bn(wl.DECAY)
+        ev[4].record()
+        torch.cuda.synchronize()
+        for j, k in enumerate(stage_ms):
+            stage_ms[k] += ev[j].elapsed_time(ev[j + 1]) / args.profile_steps
+    kfac.kfac_profile_enable(ctx, True)
+    for _ in range(args.profile_steps):
+        step(wl.DECAY, subset)
+    entries = kfac.kfac_profile_read(ctx, 16384)
+    kfac.kfac_profile_enable(ctx, False)
+    kernels = {}
+    for e in entries:
+        name = e["kernel"] + ("_tile%d" % (128 if e["variant"] == 0 else 64) if e["kernel"].startswith("gemm_f") or
+                              e["kernel"] == "gemm_bf16" else "")
+        k = kernels.setdefault(name, {"launches": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
+        k["launches"] += 1
+        k["ms"] += e["ms"]
+        k["flops"] += e["flops"]
+        k["bytes"] += e["bytes"]
+    for k in kernels.values():
+        for f in ("launches", "ms", "flops", "bytes"):
+            k[f] /= args.profile_steps
+    dom_name = max(kernels, key=lambda q: kernels[q]["ms"])
+    dom = kernels[dom_name]
+    gemm_dt = "bf16" if dom_name.startswith("gemm_bf16") else "f32"
+    if dom["flops"] > 0:
+        achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+        roofline = {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_TFLOPS[gemm_dt],
+                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS[gemm_dt], 4), "traffic": None,
+                    "launches_per_step": dom["launches"], "avg_launch_ms": round(dom["ms"] / dom["launches"], 4)}
+    else:
+        achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+        roofline = {"kernel": dom_name, "bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                    "launches_per_step": dom["launches"], "avg_launch_ms": round(dom["ms"] / dom["launches"], 4)}
+
+    fl = {"stats_A": 0.0, "stats_G": 0.0, "inv": 0.0, "precond": 0.0}
+    for L in layers:
+        for k, v in wl.flops(L).items():
+            if k != "inv":
+                fl[k] += v
+    fl["inv"] = sum(wl.flops(layers[i])["inv"] for i in subset)
+    total_flops = sum(fl.values())
+    fi_flops = fl["stats_A"] + fl["stats_G"] + fl["inv"]
+    fi_ms = stage_ms["stats"] + stage_ms["invert"]
+
+    # ---------------------------------------------------------------- oracle on the host cores (bounded sample)
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        # a sample of layers whose oracle time stays within tens of seconds
+        budget_flops = 60e9
+        order = sorted(range(n), key=lambda i: sum(wl.flops(layers[i]).values()))
+        sample, acc = [], 0.0
+        for i in order:
+            f = sum(wl.flops(layers[i]).values())
+            if acc + f > budget_flops and sample:
+                break
+            sample.append(i)
+            acc += f
+        t_cpu = 0.0
+        worst = 0.0
+        for i in sample:
+            L = layers[i]
+            s = wl.layer_seed(cfg, i)
+            a, g, gw = acts[i].float().cpu().numpy(), grads[i].float().cpu().numpy(), gws[i].cpu().numpy()
+            t1 = time.perf_counter()
+            Ar, Gr = oracle.kfac_stats(tuple(L), a, g, 0.0, spatial_mean, None, None)
+            Air, Gir, _, _ = oracle.kfac_invert(Ar, Gr, wl.GAMMA)
+            oracle.kfac_precondition(Gir, Air, gw)
+            t_cpu += time.perf_counter() - t1
+        est_ms = t_cpu * 1e3 * total_flops / acc
+        cpu_baseline = {"value": round(est_ms, 1), "unit": "ms", "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": "float64 oracle on the %d cheapest layers of the set (%.1f GFLOP algorithmic, "
+                                  "%.2f s measured), scaled to the whole step by algorithmic flops (x%.1f)"
+                                  % (len(sample), acc / 1e9, t_cpu, total_flops / acc)}
+
+    out = {
+        "metric": "K-FAC step ms for ResNet-50 layer set; factor+inverse TFLOP/s vs MFMA peak",
+        "value": round(ms_per_step, 4),
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": args.dtype,
+        "data": "synthetic",
+        "config": {"workload": "config %d: %s" % (cfg, {
+            1: "single FC layer 64->32, batch 32",
+            2: "one ResNet-50 conv3x3 64->64 at 56x56, batch 32",
+            3: "largest ResNet-50 conv3x3 512->512 at 7x7 plus FC 2048->1000, batch 32",
+            4: "full ResNet-50 layer set (53 conv + 1 FC + 53 BatchNorm), batch 32",
+            5: "full ResNet-50 layer set, batch 128, inverses refreshed for a seeded 25% subset"}[cfg]),
+            "layers": n, "bn_layers": len(Cs), "batch": N, "inverted_layers": len(subset),
+            "g_spatial_mean": bool(spatial_mean)},
+        "algorithmic_gflop": {k: round(v / 1e9, 2) for k, v in fl.items()},
+        "step_tflops": round(total_flops / (ms_per_step * 1e-3) / 1e12, 3),
+        "factor_inverse_tflops": round(fi_flops / (fi_ms * 1e-3) / 1e12, 3),
+        "factor_inverse_frac_of_mfma_peak": round(fi_flops / (fi_ms * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype if args.dtype == "f32" else "f32"], 4),
+        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "kernels": {k: {"launches": v["launches"], "ms": round(v["ms"], 4),
+                        "tflops": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 3) if v["flops"] else None,
+                        "gbs": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["bytes"] else None}
+                    for k, v in sorted(kernels.items())},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -162,6 +162,32 @@ kfac_status bn_unitwise_reduce_nchw(kfac_ctx *ctx, int32_t n_layers, int32_t N, 
                                     const int32_t *HW, const float *const *dy, const float *const *xhat,
                                     float *const *g_gamma, float *const *g_beta);
 
+/*
+ * Optional per-launch timing for benchmarks (not part of the method).  While enabled,
+ * every kernel launch of this context is bracketed by HIP events on the context's stream.
+ * kfac_profile_read waits for the stream, copies up to max_entries records (in launch
+ * order) to the host array `out`, clears the log and returns the number of launches
+ * that were recorded (which may exceed max_entries), or -1 on error.
+ * flops / bytes are the algorithmic counts of the launch: K*M*(M+1) for a symmetric
+ * product, 2*M*N*K for a general one; bytes read + written for the copy-like kernels.
+ */
+typedef enum {
+    KFAC_K_GEMM_F32 = 0, KFAC_K_GEMM_BF16 = 1, KFAC_K_GEMM_REDUCE = 2, KFAC_K_PATCH = 3, KFAC_K_TRACE = 4,
+    KFAC_K_COPY_DAMP = 5, KFAC_K_LEAF_INVERSE = 6, KFAC_K_ZERO = 7, KFAC_K_BN_UNIT = 8, KFAC_K_BN_REDUCE = 9
+} kfac_kernel;
+
+typedef struct {
+    int32_t kernel;    /* kfac_kernel */
+    int32_t variant;   /* GEMM: 0 = 128x128 tiles, 1 = 64x64 tiles; leaf inverse: size class */
+    int32_t workgroups;
+    float ms;
+    double flops;
+    double bytes;
+} kfac_profile_entry;
+
+kfac_status kfac_profile_enable(kfac_ctx *ctx, int32_t on);
+int32_t kfac_profile_read(kfac_ctx *ctx, kfac_profile_entry *out, int32_t max_entries);
+
 #ifdef __cplusplus
 }
 #endif

@@ -89,6 +89,10 @@ struct LoaderF32 {
         m += KT; t += KT;
         while (t >= hw) { t -= hw; ++n; }
     }
+    // Branch-free: every slot issues its load (out-of-range slots read element 0 of the
+    // operand, which always exists) and the value is masked afterwards, so that all loads
+    // of a tile are in flight together.  With vec == 4 the four elements m..m+3 of a row are
+    // always inside the operand's allocation (its rows are padded to a multiple of 4).
     __device__ __forceinline__ void load(float (&reg)[NREG]) const
     {
         const long long col = (long long)n * batch_stride + t;
@@ -96,32 +100,25 @@ struct LoaderF32 {
 #pragma unroll
             for (int s = 0; s < BR / 32; ++s) {
                 const int row = row0 + r0 + 32 * s;
-                floatx4 v = {0.f, 0.f, 0.f, 0.f};
-                if (row == ones_row) {
-                    v[0] = (m + 0 < kend) ? 1.f : 0.f; v[1] = (m + 1 < kend) ? 1.f : 0.f;
-                    v[2] = (m + 2 < kend) ? 1.f : 0.f; v[3] = (m + 3 < kend) ? 1.f : 0.f;
-                } else if (row < rows && m < kend) {
-                    const float *p = base + (long long)row * row_stride + col;
-                    if (m + 3 < kend) {
-                        v = *(const floatx4 *)p;
-                    } else {
-                        v[0] = p[0];
-                        if (m + 1 < kend) v[1] = p[1];
-                        if (m + 2 < kend) v[2] = p[2];
-                    }
+                const bool ok = (row < rows) && (m < kend);
+                const long long off = ok ? (long long)row * row_stride + col : 0;
+                floatx4 v = *(const floatx4 *)(base + off);
+                const bool use = ok || row == ones_row;
+                const float one = (row == ones_row) ? 1.f : 0.f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float x = ok ? v[e] : one;
+                    reg[4 * s + e] = (use && m + e < kend) ? x : 0.f;
                 }
-                reg[4 * s + 0] = v[0]; reg[4 * s + 1] = v[1]; reg[4 * s + 2] = v[2]; reg[4 * s + 3] = v[3];
             }
         } else {
 #pragma unroll
             for (int s = 0; s < BR / 8; ++s) {
                 const int row = row0 + r0 + 8 * s;
-                float v = 0.f;
-                if (m < kend) {
-                    if (row == ones_row) v = 1.f;
-                    else if (row < rows) v = base[(long long)row * row_stride + col];
-                }
-                reg[s] = v;
+                const bool ok = (row < rows) && (m < kend);
+                const long long off = ok ? (long long)row * row_stride + col : 0;
+                const float v = base[off];
+                reg[s] = ok ? v : ((row == ones_row && m < kend) ? 1.f : 0.f);
             }
         }
     }
@@ -180,6 +177,12 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__r
     const int wave_m = wid >> 1, wave_n = wid & 1;
     const int l32 = lane & 31, half = lane >> 5;
 
+    // A wavefront whose whole sub-tile lies outside the matrix, or above the diagonal of a
+    // symmetric product, stores nothing: it only helps with the loads and skips the math.
+    const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
+    const int wave_r0 = tm * BM + wave_m * 32 * TM, wave_c0 = tn * BN + wave_n * 32 * TN;
+    [[maybe_unused]] const bool live = wave_r0 < P.M && wave_c0 < P.N && !(diag_tile && wave_c0 >= wave_r0 + 32 * TM);
+
     const int nk = (k1 - k0 + KT - 1) / KT;
     if (nk > 0) { la.load(ra); lb.load(rb); }
     for (int it = 0; it < nk; ++it) {
@@ -218,7 +221,6 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__r
 
     // accumulator layout of the 32x32 block: column = lane % 32,
     // row = 8 * (v / 4) + 4 * (lane / 32) + v % 4 for register v = 0..15
-    const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
     if (P.splits > 1) {
         float *part = P.partial + ((long long)tile * P.splits + split) * (BM * BN);
 #pragma unroll
@@ -272,40 +274,34 @@ struct LoaderBF16 {
         m += KT; t += KT;
         while (t >= hw) { t -= hw; ++n; }
     }
+    // Branch-free, as in the fp32 loader.
     __device__ __forceinline__ void load(unsigned short (&reg)[NREG]) const
     {
-        const unsigned short one = 0x3F80;  // 1.0 in bf16
+        const unsigned short one_bits = 0x3F80;  // 1.0 in bf16
         const long long col = (long long)n * batch_stride + t;
         if (vec == 4) {
 #pragma unroll
             for (int s = 0; s < BR / 32; ++s) {
                 const int row = row0 + r0 + 32 * s;
-                ushortx4 v = {0, 0, 0, 0};
-                if (row == ones_row) {
-                    v[0] = (m + 0 < kend) ? one : 0; v[1] = (m + 1 < kend) ? one : 0;
-                    v[2] = (m + 2 < kend) ? one : 0; v[3] = (m + 3 < kend) ? one : 0;
-                } else if (row < rows && m < kend) {
-                    const unsigned short *p = base + (long long)row * row_stride + col;
-                    if (m + 3 < kend) {
-                        v = *(const ushortx4 *)p;
-                    } else {
-                        v[0] = p[0];
-                        if (m + 1 < kend) v[1] = p[1];
-                        if (m + 2 < kend) v[2] = p[2];
-                    }
+                const bool ok = (row < rows) && (m < kend);
+                const long long off = ok ? (long long)row * row_stride + col : 0;
+                ushortx4 v = *(const ushortx4 *)(base + off);
+                const bool use = ok || row == ones_row;
+                const unsigned short one = (row == ones_row) ? one_bits : (unsigned short)0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const unsigned short x = ok ? v[e] : one;
+                    reg[4 * s + e] = (use && m + e < kend) ? x : (unsigned short)0;
                 }
-                reg[4 * s + 0] = v[0]; reg[4 * s + 1] = v[1]; reg[4 * s + 2] = v[2]; reg[4 * s + 3] = v[3];
             }
         } else {
 #pragma unroll
             for (int s = 0; s < BR / 8; ++s) {
                 const int row = row0 + r0 + 8 * s;
-                unsigned short v = 0;
-                if (m < kend) {
-                    if (row == ones_row) v = one;
-                    else if (row < rows) v = base[(long long)row * row_stride + col];
-                }
-                reg[s] = v;
+                const bool ok = (row < rows) && (m < kend);
+                const long long off = ok ? (long long)row * row_stride + col : 0;
+                const unsigned short v = base[off];
+                reg[s] = ok ? v : ((row == ones_row && m < kend) ? one_bits : (unsigned short)0);
             }
         }
     }
@@ -364,6 +360,12 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__
     const int wave_m = wid >> 1, wave_n = wid & 1;
     const int l32 = lane & 31, half = lane >> 5;
 
+    // A wavefront whose whole sub-tile lies outside the matrix, or above the diagonal of a
+    // symmetric product, stores nothing: it only helps with the loads and skips the math.
+    const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
+    const int wave_r0 = tm * BM + wave_m * 32 * TM, wave_c0 = tn * BN + wave_n * 32 * TN;
+    [[maybe_unused]] const bool live = wave_r0 < P.M && wave_c0 < P.N && !(diag_tile && wave_c0 >= wave_r0 + 32 * TM);
+
     const int nk = (k1 - k0 + KT - 1) / KT;
     if (nk > 0) { la.load(ra); lb.load(rb); }
     for (int it = 0; it < nk; ++it) {
@@ -401,7 +403,6 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__
                         __builtin_bit_cast(bf16x8, fa[i][u]), __builtin_bit_cast(bf16x8, fb[j][u]), acc[i][j], 0, 0, 0);
     }
 
-    const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
     if (P.splits > 1) {
         float *part = P.partial + ((long long)tile * P.splits + split) * (BM * BN);
 #pragma unroll
@@ -429,8 +430,9 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__
 }
 
 // ------------------------------------------------------------------ split-K reduction + epilogue
-// One workgroup per (problem, tile): sums the partial tiles in split order (fixed order,
-// so results are reproducible bit for bit) and applies the same epilogue.
+// One workgroup per 1024 consecutive elements of a partial tile (a thread owns 4 adjacent
+// columns): sums the partial tiles in split order (fixed order, so results are
+// reproducible bit for bit) and applies the same epilogue.  red_start counts these chunks.
 __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmProblem *__restrict__ probs,
                                                           const int *__restrict__ red_start, int n_probs)
 {
@@ -438,21 +440,25 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmProblem *__r
     const int pi = find_problem(red_start, n_probs, wg);
     const GemmProblem &P = probs[pi];
     if (P.splits <= 1) return;
-    const int tile = wg - red_start[pi];
     const int B = (P.tile_cfg == 0) ? 128 : 64;
+    const int chunks = B * B / 1024;
+    const int local = wg - red_start[pi];
+    const int tile = local / chunks;
+    const int e = (local - tile * chunks) * 1024 + threadIdx.x * 4;
     int tm, tn;
     if (P.flags & GEMM_SYM) tri_decode(tile, tm, tn);
     else { tm = tile / P.tiles_n; tn = tile - tm * P.tiles_n; }
     const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
-    const float *part = P.partial + (long long)tile * P.splits * (B * B);
-    for (int e = threadIdx.x; e < B * B; e += 256) {
-        const int r = e / B, c = e - r * B;
-        const int i = tm * B + r, j = tn * B + c;
-        if (i >= P.M || j >= P.N) continue;
-        float s = 0.f;
-        for (int q = 0; q < P.splits; ++q) s += part[(long long)q * (B * B) + e];
-        store_result(P, diag_tile, i, j, s);
-    }
+    const int r = e / B, c = e - r * B;
+    const int i = tm * B + r, j = tn * B + c;
+    if (i >= P.M || j >= P.N) return;
+    const float *part = P.partial + (long long)tile * P.splits * (B * B) + e;
+    floatx4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < P.splits; ++q) s += *(const floatx4 *)(part + (long long)q * (B * B));
+    store_result(P, diag_tile, i, j + 0, s[0]);
+    store_result(P, diag_tile, i, j + 1, s[1]);
+    store_result(P, diag_tile, i, j + 2, s[2]);
+    store_result(P, diag_tile, i, j + 3, s[3]);
 }
 
 hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, int n_probs,

@@ -22,14 +22,17 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Tunables {
-    int target_wgs;      // split-K aims at this many workgroups per problem
+    int target_wgs;      // split-K gives a problem at least this many workgroups (if K allows)
     int min_k_per_split; // never split below this contraction length
+    int max_k_per_wg;    // and never leaves a workgroup a longer contraction than this
     Tunables()
     {
         const char *e = getenv("KFAC_TARGET_WGS");
-        target_wgs = e ? std::max(1, atoi(e)) : 512;
+        target_wgs = e ? std::max(1, atoi(e)) : 256;
         e = getenv("KFAC_MIN_K_SPLIT");
         min_k_per_split = e ? std::max(32, atoi(e) / 32 * 32) : 512;
+        e = getenv("KFAC_MAX_K_PER_WG");
+        max_k_per_wg = e ? std::max(32, atoi(e) / 32 * 32) : 4096;
     }
 };
 
@@ -46,6 +49,10 @@ struct kfac_ctx {
     bool ev_valid[kSlots];
     int next_slot;
     Tunables tun;
+    // optional per-launch timing
+    bool profiling;
+    std::vector<hipEvent_t> ev_pool;      // pairs: [2i] start, [2i+1] stop
+    std::vector<kfac_profile_entry> prof; // one per recorded launch (ms filled at read time)
 };
 
 namespace {
@@ -89,6 +96,7 @@ struct Launch {
     int n, total_wgs, cfg, dtype;
     float f0, f1;
     void *p0, *p1;
+    double flops, bytes;   // algorithmic counts (profiling only)
 };
 
 struct Plan {
@@ -158,7 +166,8 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
             // need of a layer list does not depend on which of its inputs are present)
             for (auto &P : sel) {
                 const int want = (tun.target_wgs + P.n_tiles - 1) / P.n_tiles;
-                int splits = std::min(want, P.K / tun.min_k_per_split);
+                int splits = std::max((P.K + tun.max_k_per_wg - 1) / tun.max_k_per_wg,
+                                      std::min(want, P.K / tun.min_k_per_split));
                 if (splits > 1) {
                     const int kps = ((P.K + splits - 1) / splits + 31) / 32 * 32;
                     splits = (P.K + kps - 1) / kps;
@@ -178,11 +187,13 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
         bool any_split = false;
         for (size_t i = 0; i < sel.size(); ++i) {
             start[i + 1] = start[i] + sel[i].n_tiles * sel[i].splits;
-            rstart[i + 1] = rstart[i] + (sel[i].splits > 1 ? sel[i].n_tiles : 0);
+            rstart[i + 1] = rstart[i] + (sel[i].splits > 1 ? sel[i].n_tiles * (B * B / 1024) : 0);
             any_split |= sel[i].splits > 1;
         }
         Launch L{};
         L.kind = L_GEMM;
+        for (auto &P : sel)
+            L.flops += (P.flags & GEMM_SYM) ? (double)P.K * P.M * (P.M + 1.0) : 2.0 * P.M * (double)P.N * P.K;
         L.off_a = plan.tab.add(sel.data(), sel.size() * sizeof(GemmProblem));
         L.off_b = plan.tab.add(start.data(), start.size() * sizeof(int));
         L.n = (int)sel.size();
@@ -235,6 +246,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
     std::vector<PatchJob> pjobs;
     std::vector<GemmProblem> probs;
     int patch_wgs = 0;
+    double patch_bytes = 0;
     for (int l = 0; l < a.n_layers; ++l) {
         const kfac_layer &Ly = a.L[l];
         int dA, dG, h, w;
@@ -268,6 +280,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
                 if (w == 1) J.magic_w = 0;   // 2^32/1 + 1 does not fit; plain division
                 J.wg_start = patch_wgs;
                 patch_wgs += ((Ly.N * Ly.c_in + 3) / 4) * ((hw + 1023) / 1024);
+                patch_bytes += (double)esize * ((double)Ly.N * Ly.c_in * Ly.h_in * Ly.w_in + (double)d0 * K);
                 pjobs.push_back(J);
                 op.base = P;
                 op.row_stride = ld;
@@ -320,6 +333,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         L.off_a = plan.tab.add(pjobs.data(), pjobs.size() * sizeof(PatchJob));
         L.n = (int)pjobs.size();
         L.total_wgs = patch_wgs;
+        L.bytes = patch_bytes;
         plan.launches.push_back(L);
     }
     emit_gemm_phase(plan, arena, tun, probs, a.in == KFAC_BF16 ? 1 : 0, true);
@@ -635,6 +649,33 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
     }
     for (auto &L : plan.launches) {
         hipError_t e = hipSuccess;
+        const bool timed = ctx->profiling && L.kind != L_ZERO;
+        if (timed) {
+            const size_t idx = ctx->prof.size();
+            while (ctx->ev_pool.size() < 2 * (idx + 1)) {
+                hipEvent_t ev;
+                if (hipEventCreate(&ev) != hipSuccess) return KFAC_ERR_DEVICE;
+                ctx->ev_pool.push_back(ev);
+            }
+            kfac_profile_entry pe{};
+            switch (L.kind) {
+                case L_GEMM: pe.kernel = L.dtype == 0 ? KFAC_K_GEMM_F32 : KFAC_K_GEMM_BF16; break;
+                case L_REDUCE: pe.kernel = KFAC_K_GEMM_REDUCE; break;
+                case L_PATCH: pe.kernel = KFAC_K_PATCH; break;
+                case L_TRACE: pe.kernel = KFAC_K_TRACE; break;
+                case L_COPY: pe.kernel = KFAC_K_COPY_DAMP; break;
+                case L_LEAF: pe.kernel = KFAC_K_LEAF_INVERSE; break;
+                case L_ZERO: pe.kernel = KFAC_K_ZERO; break;
+                case L_BN: pe.kernel = KFAC_K_BN_UNIT; break;
+                case L_BNRED: pe.kernel = KFAC_K_BN_REDUCE; break;
+            }
+            pe.variant = (L.kind == L_GEMM || L.kind == L_LEAF) ? L.cfg : 0;
+            pe.workgroups = (L.kind == L_TRACE || L.kind == L_LEAF) ? L.n : L.total_wgs;
+            pe.flops = L.flops;
+            pe.bytes = L.bytes;
+            ctx->prof.push_back(pe);
+            if (hipEventRecord(ctx->ev_pool[2 * idx], s) != hipSuccess) return KFAC_ERR_DEVICE;
+        }
         switch (L.kind) {
             case L_GEMM:
                 e = launch_gemm((const GemmProblem *)(tab_dev + L.off_a), (const int *)(tab_dev + L.off_b), L.n,
@@ -668,6 +709,8 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 break;
         }
         if (e != hipSuccess) return KFAC_ERR_DEVICE;
+        if (timed && hipEventRecord(ctx->ev_pool[2 * ctx->prof.size() - 1], s) != hipSuccess)
+            return KFAC_ERR_DEVICE;
     }
     return KFAC_OK;
 }
@@ -756,6 +799,7 @@ kfac_status kfac_create(kfac_ctx **out, void *hip_stream, void *workspace_dev, s
         c->ev_valid[i] = false;
     }
     c->next_slot = 0;
+    c->profiling = false;
     *out = c;
     return KFAC_OK;
 }
@@ -770,7 +814,32 @@ void kfac_destroy(kfac_ctx *ctx)
         }
         if (ctx->pinned[i]) (void)hipHostFree(ctx->pinned[i]);
     }
+    for (auto ev : ctx->ev_pool) (void)hipEventDestroy(ev);
     delete ctx;
+}
+
+kfac_status kfac_profile_enable(kfac_ctx *ctx, int32_t on)
+{
+    if (!ctx) return KFAC_ERR_INVALID;
+    ctx->profiling = on != 0;
+    ctx->prof.clear();
+    return KFAC_OK;
+}
+
+int32_t kfac_profile_read(kfac_ctx *ctx, kfac_profile_entry *out, int32_t max_entries)
+{
+    if (!ctx || (max_entries > 0 && !out) || max_entries < 0) return -1;
+    const int32_t n = (int32_t)ctx->prof.size();
+    if (n == 0) return 0;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return -1;
+    for (int32_t i = 0; i < n; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ctx->ev_pool[2 * i], ctx->ev_pool[2 * i + 1]) != hipSuccess) return -1;
+        ctx->prof[i].ms = ms;
+        if (i < max_entries) out[i] = ctx->prof[i];
+    }
+    ctx->prof.clear();
+    return n;
 }
 
 kfac_status kfac_im2col(kfac_ctx *ctx, const kfac_layer *L, kfac_dtype dt, const void *act, void *patches,
@@ -792,6 +861,7 @@ kfac_status kfac_im2col(kfac_ctx *ctx, const kfac_layer *L, kfac_dtype dt, const
     J.wg_start = 0;
     Launch Lc{};
     Lc.kind = L_PATCH;
+    Lc.bytes = (double)J.esize * ((double)L->N * L->c_in * L->h_in * L->w_in + (double)L->c_in * L->k * L->k * L->N * hw);
     Lc.off_a = plan.tab.add(&J, sizeof(J));
     Lc.n = 1;
     Lc.total_wgs = ((L->N * L->c_in + 3) / 4) * ((hw + 1023) / 1024);
@@ -874,6 +944,7 @@ kfac_status bn_unitwise_precondition(kfac_ctx *ctx, int32_t n_layers, int32_t N,
     Plan plan; Arena arena(ctx->ws);
     Launch Lc{};
     Lc.kind = L_BN;
+    for (auto &J : jobs) Lc.bytes += 8.0 * N * J.C + 32.0 * J.C;
     Lc.off_a = plan.tab.add(jobs.data(), jobs.size() * sizeof(BnJob));
     Lc.n = n_layers;
     Lc.total_wgs = wgs;
@@ -906,6 +977,7 @@ kfac_status bn_unitwise_reduce_nchw(kfac_ctx *ctx, int32_t n_layers, int32_t N, 
     Plan plan; Arena arena(ctx->ws);
     Launch Lc{};
     Lc.kind = L_BNRED;
+    for (auto &J : jobs) Lc.bytes += 8.0 * N * J.C * J.HW + 8.0 * N * J.C;
     Lc.off_a = plan.tab.add(jobs.data(), jobs.size() * sizeof(BnReduceJob));
     Lc.n = n_layers;
     Lc.total_wgs = (int)wgs;

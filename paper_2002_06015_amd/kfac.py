@@ -21,8 +21,16 @@ KFAC_F32, KFAC_BF16 = 0, 1
 EXPORTS = [
     "kfac_status_string", "kfac_layer_dims", "kfac_workspace_bytes", "kfac_create", "kfac_destroy",
     "kfac_im2col", "kfac_stats", "kfac_invert", "kfac_precondition",
-    "bn_unitwise_precondition", "bn_unitwise_reduce_nchw",
+    "bn_unitwise_precondition", "bn_unitwise_reduce_nchw", "kfac_profile_enable", "kfac_profile_read",
 ]
+
+KERNEL_NAMES = ["gemm_f32", "gemm_bf16", "gemm_reduce", "patch", "trace", "copy_damp", "leaf_inverse", "zero",
+                "bn_unit", "bn_reduce"]
+
+
+class kfac_profile_entry(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int32), ("variant", ctypes.c_int32), ("workgroups", ctypes.c_int32),
+                ("ms", ctypes.c_float), ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
 
 
 class kfac_layer(ctypes.Structure):
@@ -61,6 +69,9 @@ def lib() -> ctypes.CDLL:
         L.kfac_precondition.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         L.bn_unitwise_precondition.argtypes = [vp, i32, i32, vp, vp, vp, f32, f32, vp, vp, vp]
         L.bn_unitwise_reduce_nchw.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
+        L.kfac_profile_enable.argtypes = [vp, i32]
+        L.kfac_profile_read.restype = i32
+        L.kfac_profile_read.argtypes = [vp, vp, i32]
         _lib = L
     return _lib
 
@@ -225,3 +236,19 @@ def bn_unitwise_reduce_nchw(ctx: Context, N: int, C: Sequence[int], HW: Sequence
                                        *[p and ctypes.addressof(p) for p in ps])
     if st != KFAC_OK:
         raise KfacError(st, "bn_unitwise_reduce_nchw")
+
+
+def kfac_profile_enable(ctx: Context, on: bool) -> None:
+    st = lib().kfac_profile_enable(ctx.handle, int(bool(on)))
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_profile_enable")
+
+
+def kfac_profile_read(ctx: Context, max_entries: int = 4096) -> list:
+    """Per-launch records since the last read: dicts with kernel, variant, workgroups, ms, flops, bytes."""
+    arr = (kfac_profile_entry * max_entries)()
+    n = lib().kfac_profile_read(ctx.handle, ctypes.addressof(arr), max_entries)
+    if n < 0:
+        raise KfacError(KFAC_ERR_DEVICE, "kfac_profile_read")
+    return [dict(kernel=KERNEL_NAMES[e.kernel], variant=e.variant, workgroups=e.workgroups, ms=e.ms,
+                 flops=e.flops, bytes=e.bytes) for e in arr[:min(n, max_entries)]]
