@@ -61,26 +61,54 @@ __device__ __forceinline__ void store_result(const GemmProblem &P, bool diag_til
 }
 
 // ------------------------------------------------------------------ operand loader (fp32)
-template <int BR>  // rows of the operand tile
-struct LoaderF32 {
-    static constexpr int NREG = BR / 8;  // floats held per thread for one tile
-    const float *base;
-    long long row_stride, batch_stride;
-    int rows, hw, ones_row, vec;
-    int row0;       // first row of the tile
-    int koff, r0;   // this thread's k offset inside the tile and first row slot
-    int m, n, t;    // current contraction index of this thread and its (batch, run) split
-    int kend;
+// A thread owns one 4-wide k chunk (kq = 4 * (tid % 8)) of the rows r0 + 32*s (r0 = tid / 8)
+// of the operand tile.  A chunk is one 16-byte load that only needs 4-byte alignment (any
+// leading dimension works); the host guarantees that the 4 elements of a chunk are adjacent
+// in memory (hw % 4 == 0 for NCHW operands).  Every load of the main loop has an
+// unconditionally valid address and is masked by value afterwards, so the loads of a whole
+// tile are issued back to back:
+//   - rows outside the operand are clamped to its last row and replaced by 0 (or by 1 for
+//     the virtual all-ones row);
+//   - the contraction range of a workgroup is cut into full 32-wide tiles; a remaining
+//     multiple of 4 is covered by one more full tile shifted back to end at the range end,
+//     whose already-counted k positions are zeroed in ONE operand;
+//   - a remaining K % 4 (only plain matrices have one) is added in the epilogue.
+// Ranges shorter than 32 take a slow, careful tile instead.
+typedef float floatx4_u __attribute__((ext_vector_type(4), aligned(4)));
+typedef const float __attribute__((address_space(1))) *gfloat_ptr;
+typedef const floatx4_u __attribute__((address_space(1))) *gfloat4_ptr;
 
-    __device__ __forceinline__ void init(const Operand &op, int tile_row0, int k0, int k1, int tid)
+template <int BR>
+struct LoaderF32 {
+    static constexpr int SLOTS = BR / 32;
+    gfloat_ptr base;
+    long long rowoff[SLOTS];   // clamped row * row_stride (loop invariant)
+    unsigned dead;             // bit s: slot row is outside the operand
+    unsigned ones;             // bit s: slot row is the virtual all-ones row
+    long long batch_stride;
+    int hw, kq, r0, m, n, t;
+    bool zero_all;             // the tile held in registers is to be stored as zeros
+
+    __device__ __forceinline__ void init(const Operand &op, int tile_row0, int tid)
     {
-        base = (const float *)op.base;
-        row_stride = op.row_stride; batch_stride = op.batch_stride;
-        rows = op.rows; hw = op.hw; ones_row = op.ones_row; vec = op.vec;
-        row0 = tile_row0; kend = k1;
-        if (vec == 4) { koff = (tid & 7) * 4; r0 = tid >> 3; }
-        else          { koff = tid & 31;      r0 = tid >> 5; }
-        m = k0 + koff;
+        base = (gfloat_ptr)op.base;
+        batch_stride = op.batch_stride;
+        hw = op.hw;
+        kq = (tid & 7) * 4; r0 = tid >> 3;
+        dead = 0; ones = 0;
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const int row = tile_row0 + r0 + 32 * s;
+            if (row >= op.rows) dead |= 1u << s;
+            if (row == op.ones_row) ones |= 1u << s;
+            rowoff[s] = (long long)min(row, op.rows - 1) * op.row_stride;
+        }
+        m = n = t = 0;
+        zero_all = false;
+    }
+    __device__ __forceinline__ void seek(int tile_k0)   // position on the tile starting at tile_k0
+    {
+        m = tile_k0 + kq;
         n = m / hw;
         t = m - n * hw;
     }
@@ -89,62 +117,142 @@ struct LoaderF32 {
         m += KT; t += KT;
         while (t >= hw) { t -= hw; ++n; }
     }
-    // Branch-free: every slot issues its load (out-of-range slots read element 0 of the
-    // operand, which always exists) and the value is masked afterwards, so that all loads
-    // of a tile are in flight together.  With vec == 4 the four elements m..m+3 of a row are
-    // always inside the operand's allocation (its rows are padded to a multiple of 4).
-    __device__ __forceinline__ void load(float (&reg)[NREG]) const
+    // Raw loads only: the masks are applied in store_lds, one iteration later, so nothing
+    // waits for the data before the matrix instructions of the current tile are issued.
+    __device__ __forceinline__ void load_full(floatx4 (&reg)[SLOTS])
     {
         const long long col = (long long)n * batch_stride + t;
-        if (vec == 4) {
 #pragma unroll
-            for (int s = 0; s < BR / 32; ++s) {
-                const int row = row0 + r0 + 32 * s;
-                const bool ok = (row < rows) && (m < kend);
-                const long long off = ok ? (long long)row * row_stride + col : 0;
-                floatx4 v = *(const floatx4 *)(base + off);
-                const bool use = ok || row == ones_row;
-                const float one = (row == ones_row) ? 1.f : 0.f;
+        for (int s = 0; s < SLOTS; ++s) reg[s] = *(gfloat4_ptr)(base + rowoff[s] + col);
+        zero_all = false;
+    }
+    // the shifted tile: k positions below mlo were already covered by the full tiles
+    __device__ __forceinline__ void zero_below(int mlo) { zero_all = m < mlo; }
+    // careful tile for short ranges: chunks at or beyond kend4 are not read
+    __device__ __forceinline__ void load_careful(floatx4 (&reg)[SLOTS], int kend4)
+    {
+        const long long col = (long long)n * batch_stride + t;
+        const bool in = m < kend4;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float x = ok ? v[e] : one;
-                    reg[4 * s + e] = (use && m + e < kend) ? x : 0.f;
-                }
-            }
-        } else {
+        for (int s = 0; s < SLOTS; ++s) {
+            floatx4 v = {0.f, 0.f, 0.f, 0.f};
+            if (in) v = *(gfloat4_ptr)(base + rowoff[s] + col);
+            reg[s] = v;
+        }
+        zero_all = !in;
+    }
+    __device__ __forceinline__ void store_lds(const floatx4 (&reg)[SLOTS], float *lds) const
+    {
 #pragma unroll
-            for (int s = 0; s < BR / 8; ++s) {
-                const int row = row0 + r0 + 8 * s;
-                const bool ok = (row < rows) && (m < kend);
-                const long long off = ok ? (long long)row * row_stride + col : 0;
-                const float v = base[off];
-                reg[s] = ok ? v : ((row == ones_row && m < kend) ? 1.f : 0.f);
-            }
+        for (int s = 0; s < SLOTS; ++s) {
+            floatx4 v = reg[s];
+            const float fill = (ones >> s) & 1 ? 1.f : 0.f;
+            if ((dead >> s) & 1) { v[0] = fill; v[1] = fill; v[2] = fill; v[3] = fill; }
+            if (zero_all) { v[0] = 0.f; v[1] = 0.f; v[2] = 0.f; v[3] = 0.f; }
+            *(floatx4 *)(lds + (r0 + 32 * s) * LDF + kq) = v;
         }
     }
-    __device__ __forceinline__ void store_lds(const float (&reg)[NREG], float *lds) const
+    // K % 4 remainder tile (plain matrices only: hw > K): thread tid < BR fills LDS row tid
+    // with the elements k4 .. kend-1 of its operand row followed by zeros
+    __device__ __forceinline__ static void fill_remainder(const Operand &op, int tile_row0, int k4, int kend,
+                                                          int tid, float *lds)
     {
-        if (vec == 4) {
-#pragma unroll
-            for (int s = 0; s < BR / 32; ++s) {
-                floatx4 v = {reg[4 * s], reg[4 * s + 1], reg[4 * s + 2], reg[4 * s + 3]};
-                *(floatx4 *)(lds + (r0 + 32 * s) * LDF + koff) = v;
-            }
-        } else {
-#pragma unroll
-            for (int s = 0; s < BR / 8; ++s) lds[(r0 + 8 * s) * LDF + koff] = reg[s];
+        if (tid >= BR) return;
+        const int row = tile_row0 + tid;
+        floatx4 x = {0.f, 0.f, 0.f, 0.f};
+        if (row == op.ones_row) {
+            for (int e = 0; e < 3; ++e)
+                if (k4 + e < kend) x[e] = 1.f;
+        } else if (row < op.rows) {
+            gfloat_ptr p = (gfloat_ptr)op.base + (long long)row * op.row_stride + k4;
+            for (int e = 0; e < 3; ++e)
+                if (k4 + e < kend) x[e] = p[e];
         }
+        float *dst = lds + tid * LDF;
+        *(floatx4 *)dst = x;
+#pragma unroll
+        for (int q = 1; q < 8; ++q) *(floatx4 *)(dst + 4 * q) = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 };
 
 // ------------------------------------------------------------------ fp32 kernel
+// Two LDS stages: iteration `it` stores the tile it already holds in registers into stage
+// it & 1, issues the global loads of tile it + 1, then (one barrier) multiplies out of stage
+// it & 1.  The stage written in iteration it + 1 was last read before the barrier of
+// iteration it + 1, which every wavefront reaches only after finishing that read.
+template <int TM, int TN, bool LIVE>
+__device__ __forceinline__ void gemm_f32_mainloop(const GemmProblem &P, int tm, int tn, int tid,
+                                                  LoaderF32<64 * TM> &la, LoaderF32<64 * TN> &lb, float *lds,
+                                                  int k0, int k1, int wave_m, int wave_n, int l32, int half,
+                                                  floatx16 (&acc)[TM][TN])
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int STAGE = (BM + BN) * LDF;
+    // [k0, k0 + klen4) is covered by vector-loaded tiles; a K % 4 remainder [k0 + klen4, k1)
+    // exists only in the last split of a plain-matrix problem and gets a tile of its own
+    const int klen = max(k1 - k0, 0);
+    const int klen4 = klen & ~3;
+    const int nfull = klen4 / KT;
+    const bool shifted = nfull > 0 && klen4 > nfull * KT;   // one more full tile ending at k0 + klen4
+    const bool careful = nfull == 0 && klen4 > 0;
+    const int nvec = nfull + ((shifted || careful) ? 1 : 0);
+    const int nk = nvec + (klen4 < klen ? 1 : 0);
+    floatx4 ra[BM / 32], rb[BN / 32];
+    la.seek(k0); lb.seek(k0);
+    if (nfull > 0) { la.load_full(ra); lb.load_full(rb); }
+    else if (careful) { la.load_careful(ra, k0 + klen4); lb.load_careful(rb, k0 + klen4); }
+    for (int it = 0; it < nk; ++it) {
+        float *sa = lds + (it & 1) * STAGE, *sb = sa + BM * LDF;
+        if (it < nvec) {
+            la.store_lds(ra, sa);
+            lb.store_lds(rb, sb);
+        } else {
+            LoaderF32<BM>::fill_remainder(P.a, tm * BM, k0 + klen4, k1, tid, sa);
+            LoaderF32<BN>::fill_remainder(P.b, tn * BN, k0 + klen4, k1, tid, sb);
+        }
+        if (it + 1 < nfull) {
+            la.advance(); lb.advance();
+            la.load_full(ra); lb.load_full(rb);
+        } else if (it + 1 < nvec) {
+            la.seek(k0 + klen4 - KT); lb.seek(k0 + klen4 - KT);
+            la.load_full(ra); lb.load_full(rb);
+            la.zero_below(k0 + nfull * KT);
+        }
+        __syncthreads();
+        if constexpr (LIVE) {
+            // each half-wave takes 16 consecutive k of the tile (the same 16 for both operands)
+            floatx4 fa[TM][4], fb[TN][4];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const float *p = sa + (wave_m * 32 * TM + i * 32 + l32) * LDF + half * 16;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) fa[i][q] = *(const floatx4 *)(p + 4 * q);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const float *p = sb + (wave_n * 32 * TN + j * 32 + l32) * LDF + half * 16;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) fb[j][q] = *(const floatx4 *)(p + 4 * q);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][q][e], fb[j][q][e], acc[i][j], 0, 0, 0);
+        }
+    }
+}
+
 template <int TM, int TN>
 __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__restrict__ probs,
                                                           const int *__restrict__ tile_start, int n_probs)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    __shared__ __attribute__((aligned(16))) float lds_a[BM * LDF];
-    __shared__ __attribute__((aligned(16))) float lds_b[BN * LDF];
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // 2 stages of (BM + BN) * LDF floats
 
     const int wg = blockIdx.x;
     const int pi = find_problem(tile_start, n_probs, wg);
@@ -161,9 +269,8 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__r
 
     LoaderF32<BM> la;
     LoaderF32<BN> lb;
-    la.init(P.a, tm * BM, k0, k1, tid);
-    lb.init(P.b, tn * BN, k0, k1, tid);
-    float ra[BM / 8], rb[BN / 8];
+    la.init(P.a, tm * BM, tid);
+    lb.init(P.b, tn * BN, tid);
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -181,43 +288,10 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__r
     // symmetric product, stores nothing: it only helps with the loads and skips the math.
     const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
     const int wave_r0 = tm * BM + wave_m * 32 * TM, wave_c0 = tn * BN + wave_n * 32 * TN;
-    [[maybe_unused]] const bool live = wave_r0 < P.M && wave_c0 < P.N && !(diag_tile && wave_c0 >= wave_r0 + 32 * TM);
+    const bool live = wave_r0 < P.M && wave_c0 < P.N && !(diag_tile && wave_c0 >= wave_r0 + 32 * TM);
 
-    const int nk = (k1 - k0 + KT - 1) / KT;
-    if (nk > 0) { la.load(ra); lb.load(rb); }
-    for (int it = 0; it < nk; ++it) {
-        __syncthreads();
-        la.store_lds(ra, lds_a);
-        lb.store_lds(rb, lds_b);
-        __syncthreads();
-        if (it + 1 < nk) {
-            la.advance(); lb.advance();
-            la.load(ra); lb.load(rb);
-        }
-        // each half-wave takes 16 consecutive k of the tile (the same 16 for both operands)
-        floatx4 fa[TM][4], fb[TN][4];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const float *p = lds_a + (wave_m * 32 * TM + i * 32 + l32) * LDF + half * 16;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) fa[i][q] = *(const floatx4 *)(p + 4 * q);
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const float *p = lds_b + (wave_n * 32 * TN + j * 32 + l32) * LDF + half * 16;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) fb[j][q] = *(const floatx4 *)(p + 4 * q);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][q][e], fb[j][q][e], acc[i][j], 0, 0, 0);
-    }
+    if (live) gemm_f32_mainloop<TM, TN, true>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc);
+    else      gemm_f32_mainloop<TM, TN, false>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc);
 
     // accumulator layout of the 32x32 block: column = lane % 32,
     // row = 8 * (v / 4) + 4 * (lane / 32) + v % 4 for register v = 0..15
@@ -233,7 +307,7 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__r
                     const int c = wave_n * 32 * TN + j * 32 + l32;
                     part[r * BN + c] = acc[i][j][v];
                 }
-    } else {
+    } else if (live) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -461,18 +535,33 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmProblem *__r
     store_result(P, diag_tile, i, j + 3, s[3]);
 }
 
+template <int TM, int TN>
+static hipError_t launch_f32(const GemmProblem *probs_dev, const int *tile_start_dev, int n_probs, int total_wgs,
+                             hipStream_t s)
+{
+    constexpr size_t lds_bytes = 2 * (64 * TM + 64 * TN) * LDF * sizeof(float);
+    static bool configured = false;   // the attribute is per function, set once per process
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_f32_kernel<TM, TN>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    gemm_nt_f32_kernel<TM, TN><<<dim3(total_wgs), dim3(256), lds_bytes, s>>>(probs_dev, tile_start_dev, n_probs);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, int n_probs,
                        int total_wgs, int tile_cfg, int dtype, hipStream_t s)
 {
     if (total_wgs <= 0) return hipSuccess;
     dim3 grid(total_wgs), block(256);
     if (dtype == 0) {
-        if (tile_cfg == 0) gemm_nt_f32_kernel<2, 2><<<grid, block, 0, s>>>(probs_dev, tile_start_dev, n_probs);
-        else               gemm_nt_f32_kernel<1, 1><<<grid, block, 0, s>>>(probs_dev, tile_start_dev, n_probs);
-    } else {
-        if (tile_cfg == 0) gemm_nt_bf16_kernel<2, 2><<<grid, block, 0, s>>>(probs_dev, tile_start_dev, n_probs);
-        else               gemm_nt_bf16_kernel<1, 1><<<grid, block, 0, s>>>(probs_dev, tile_start_dev, n_probs);
+        if (tile_cfg == 0) return launch_f32<2, 2>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
+        return launch_f32<1, 1>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
     }
+    if (tile_cfg == 0) gemm_nt_bf16_kernel<2, 2><<<grid, block, 0, s>>>(probs_dev, tile_start_dev, n_probs);
+    else               gemm_nt_bf16_kernel<1, 1><<<grid, block, 0, s>>>(probs_dev, tile_start_dev, n_probs);
     return hipGetLastError();
 }
 

@@ -222,7 +222,7 @@ Operand plain_operand(const float *base, long long ld, int rows, int K)
     o.rows = rows;
     o.hw = std::max(K, 1) + 64;   // one run covers the whole contraction
     o.ones_row = -1;
-    o.vec = (ld % 4 == 0 && ((uintptr_t)base % 16) == 0) ? 4 : 1;
+    o.vec = 4;   // unused by the fp32 kernel (any leading dimension works)
     return o;
 }
 
@@ -239,14 +239,68 @@ struct StatsArgs {
     float *const *G_ema;
 };
 
+// Workgroups of one patch / repack job.
+int patch_job_wgs(const PatchJob &J)
+{
+    const int hw = J.h * J.w;
+    if (J.flat) return J.c_in * ((J.N * hw + 255) / 256);
+    return ((J.N * J.c_in + 3) / 4) * ((hw + 1023) / 1024);
+}
+
+PatchJob make_patch_job(const void *src, void *dst, long long ld, int N, int c, int k, int stride, int pad,
+                        int h_in, int w_in, int h, int w, int esize)
+{
+    PatchJob J{};
+    J.src = src; J.dst = dst; J.ld = ld;
+    J.N = N; J.c_in = c; J.k = k; J.stride = stride; J.pad = pad;
+    J.h_in = h_in; J.w_in = w_in; J.h = h; J.w = w;
+    J.esize = esize;
+    J.flat = (k == 1 && stride == 1 && pad == 0 && h * w < 64) ? 1 : 0;
+    J.magic_w = (h * w < 65536 && w > 1) ? (unsigned)((1ULL << 32) / (unsigned)w + 1ULL) : 0u;
+    return J;
+}
+
 void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &a, bool dry)
 {
     const int esize = a.in == KFAC_BF16 ? 2 : 4;
-    const size_t vec_align = a.in == KFAC_BF16 ? 8 : 16;
+    const size_t chunk_align = a.in == KFAC_BF16 ? 8 : 4;   // alignment of a 4-element chunk
     std::vector<PatchJob> pjobs;
     std::vector<GemmProblem> probs;
     int patch_wgs = 0;
     double patch_bytes = 0;
+    // An NCHW tensor [N, c, hw] is contracted in place when its runs are whole 4-element
+    // chunks; otherwise (and for every k > 1 / strided / padded layer) it is first rewritten
+    // as [c k^2][ld] with the contraction index contiguous.
+    auto operand_for = [&](const void *src, int N, int c, int k, int stride, int pad, int h_in, int w_in, int h,
+                           int w) {
+        const int hw = h * w, K = N * hw, d0 = c * k * k;
+        Operand op{};
+        const bool direct = (k == 1 && stride == 1 && pad == 0 && hw % 4 == 0 &&
+                             (dry || ((uintptr_t)src % chunk_align) == 0));
+        if (direct) {
+            op.base = src;
+            op.row_stride = hw;
+            op.batch_stride = (long long)c * hw;
+            op.rows = d0;
+            op.hw = hw;
+        } else {
+            const long long ld = align_up((size_t)K, 32);
+            void *P = arena.take((size_t)d0 * ld * esize);
+            PatchJob J = make_patch_job(src, P, ld, N, c, k, stride, pad, h_in, w_in, h, w, esize);
+            J.wg_start = patch_wgs;
+            patch_wgs += patch_job_wgs(J);
+            patch_bytes += (double)esize * ((double)N * c * h_in * w_in + (double)d0 * K);
+            pjobs.push_back(J);
+            op.base = P;
+            op.row_stride = ld;
+            op.batch_stride = 0;
+            op.rows = d0;
+            op.hw = K + 64;
+        }
+        op.vec = 4;
+        op.ones_row = -1;
+        return op;
+    };
     for (int l = 0; l < a.n_layers; ++l) {
         const kfac_layer &Ly = a.L[l];
         int dA, dG, h, w;
@@ -256,40 +310,9 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         const bool want_A = dry || (a.act && a.act[l]);
         const bool want_G = dry || (a.grad_out && a.grad_out[l]);
         if (want_A) {
-            const int d0 = Ly.c_in * Ly.k * Ly.k;
-            Operand op{};
-            const bool direct = (Ly.k == 1 && Ly.stride == 1 && Ly.pad == 0);
-            if (direct) {
-                op.base = dry ? nullptr : a.act[l];
-                op.row_stride = hw;
-                op.batch_stride = (long long)Ly.c_in * hw;
-                op.rows = d0;
-                op.hw = hw;
-                op.vec = (hw % 4 == 0 && !dry && ((uintptr_t)op.base % vec_align) == 0) ? 4 : 1;
-            } else {
-                const long long ld = align_up((size_t)K, 32);
-                void *P = arena.take((size_t)d0 * ld * esize);
-                PatchJob J{};
-                J.src = dry ? nullptr : a.act[l];
-                J.dst = P;
-                J.ld = ld;
-                J.N = Ly.N; J.c_in = Ly.c_in; J.k = Ly.k; J.stride = Ly.stride; J.pad = Ly.pad;
-                J.h_in = Ly.h_in; J.w_in = Ly.w_in; J.h = h; J.w = w;
-                J.esize = esize;
-                J.magic_w = (hw < 65536) ? (unsigned)((1ULL << 32) / (unsigned)w + 1ULL) : 0u;
-                if (w == 1) J.magic_w = 0;   // 2^32/1 + 1 does not fit; plain division
-                J.wg_start = patch_wgs;
-                patch_wgs += ((Ly.N * Ly.c_in + 3) / 4) * ((hw + 1023) / 1024);
-                patch_bytes += (double)esize * ((double)Ly.N * Ly.c_in * Ly.h_in * Ly.w_in + (double)d0 * K);
-                pjobs.push_back(J);
-                op.base = P;
-                op.row_stride = ld;
-                op.batch_stride = 0;
-                op.rows = d0;
-                op.hw = K + 64;
-                op.vec = 4;
-            }
-            op.ones_row = Ly.bias ? d0 : -1;
+            Operand op = operand_for(dry ? nullptr : a.act[l], Ly.N, Ly.c_in, Ly.k, Ly.stride, Ly.pad, Ly.h_in,
+                                     Ly.w_in, h, w);
+            op.ones_row = Ly.bias ? op.rows : -1;
             GemmProblem P{};
             P.a = op; P.b = op;
             P.C = dry ? nullptr : a.A_ema[l];
@@ -304,14 +327,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             probs.push_back(P);
         }
         if (want_G) {
-            Operand op{};
-            op.base = dry ? nullptr : a.grad_out[l];
-            op.row_stride = hw;
-            op.batch_stride = (long long)Ly.c_out * hw;
-            op.rows = dG;
-            op.hw = hw;
-            op.ones_row = -1;
-            op.vec = (hw % 4 == 0 && !dry && ((uintptr_t)op.base % vec_align) == 0) ? 4 : 1;
+            Operand op = operand_for(dry ? nullptr : a.grad_out[l], Ly.N, Ly.c_out, 1, 1, 0, h, w, h, w);
             GemmProblem P{};
             P.a = op; P.b = op;
             P.C = dry ? nullptr : a.G_ema[l];
@@ -852,19 +868,15 @@ kfac_status kfac_im2col(kfac_ctx *ctx, const kfac_layer *L, kfac_dtype dt, const
     const int hw = h * w;
     if (ld < (int64_t)L->N * hw) return KFAC_ERR_INVALID;
     Plan plan; Arena arena(ctx->ws);
-    PatchJob J{};
-    J.src = act; J.dst = patches; J.ld = ld;
-    J.N = L->N; J.c_in = L->c_in; J.k = L->k; J.stride = L->stride; J.pad = L->pad;
-    J.h_in = L->h_in; J.w_in = L->w_in; J.h = h; J.w = w;
-    J.esize = dt == KFAC_BF16 ? 2 : 4;
-    J.magic_w = (hw < 65536 && w > 1) ? (unsigned)((1ULL << 32) / (unsigned)w + 1ULL) : 0u;
+    PatchJob J = make_patch_job(act, patches, ld, L->N, L->c_in, L->k, L->stride, L->pad, L->h_in, L->w_in, h, w,
+                                dt == KFAC_BF16 ? 2 : 4);
     J.wg_start = 0;
     Launch Lc{};
     Lc.kind = L_PATCH;
     Lc.bytes = (double)J.esize * ((double)L->N * L->c_in * L->h_in * L->w_in + (double)L->c_in * L->k * L->k * L->N * hw);
     Lc.off_a = plan.tab.add(&J, sizeof(J));
     Lc.n = 1;
-    Lc.total_wgs = ((L->N * L->c_in + 3) / 4) * ((hw + 1023) / 1024);
+    Lc.total_wgs = patch_job_wgs(J);
     plan.launches.push_back(Lc);
     return run_plan(ctx, plan, arena);
 }

@@ -22,7 +22,8 @@ struct Operand {
     int rows;
     int hw;
     int ones_row;
-    int vec;  // 4: every (r, m) with m % 4 == 0 is 16-byte aligned and m..m+3 share a run; else 1
+    int vec;  // bf16 kernel only: 4 = chunks of 4 are 8-byte aligned and share a run, else 1
+              // (fp32 operands always satisfy hw % 4 == 0 or are plain matrices)
 };
 
 enum : int { GEMM_SYM = 1 };
@@ -48,6 +49,7 @@ struct PatchJob {
     long long ld;
     int N, c_in, k, stride, pad, h_in, w_in, h, w;
     int esize;        // 4 (f32) or 2 (bf16)
+    int flat;         // 1: k == 1, stride 1, no padding, tiny planes: one thread per output element
     unsigned magic_w; // floor(2^32 / w) + 1: t / w == mulhi(t, magic_w) for t, w < 2^16
     int wg_start;     // first workgroup of this job in the grouped launch
 };

@@ -42,6 +42,21 @@ __global__ __launch_bounds__(256) void patch_kernel(const PatchJob *__restrict__
     const PatchJob &J = jobs[lo];
     const int local = wg - J.wg_start;
     const int hw = J.h * J.w;
+    if (J.flat) {
+        // pointwise layer with tiny planes (e.g. a fully-connected layer, hw = 1): one thread
+        // per output element, P[c][n*hw + t] = src[n][c][t]
+        const int M = J.N * hw;
+        const int chunks_m = (M + 255) / 256;
+        const int row = local / chunks_m;
+        const int m = (local - row * chunks_m) * 256 + (int)threadIdx.x;
+        if (m >= M) return;
+        const int n = m / hw, t = m - n * hw;
+        const long long so = ((long long)n * J.c_in + row) * hw + t;
+        const long long d = (long long)row * J.ld + m;
+        if (J.esize == 4) ((float *)J.dst)[d] = ((const float *)J.src)[so];
+        else              ((unsigned short *)J.dst)[d] = ((const unsigned short *)J.src)[so];
+        return;
+    }
     const int chunks = (hw + TCHUNK - 1) / TCHUNK;
     const int chunk = local % chunks;
     const int plane = (local / chunks) * 4 + (threadIdx.x >> 6);
