@@ -46,7 +46,8 @@ __device__ __forceinline__ void tri_decode(int t, int &tm, int &tn)
     tn = t - r * (r + 1) / 2;
 }
 
-// Final write of one element of C (and of its mirror / transposed copy).
+// Final write of one element of C and of its mirror / transposed copy (element-wise form,
+// used by the bf16 kernel).
 __device__ __forceinline__ void store_result(const GemmProblem &P, bool diag_tile, int i, int j, float acc)
 {
     if (i >= P.M || j >= P.N) return;
@@ -58,6 +59,86 @@ __device__ __forceinline__ void store_result(const GemmProblem &P, bool diag_til
     *c = v;
     if (sym && i != j) P.C[(long long)j * P.ldc + i] = v;
     if (P.Ct) P.Ct[(long long)j * P.ldct + i] = v;
+}
+
+// Final write of a ROWS x COLS slab of accumulated sums held in LDS (T[r][c] at
+// T[r * (COLS + 1) + c], global position (gi0 + r, gj0 + c)):
+//     C[i][j] = alpha * T + beta * C[i][j]
+// plus, for symmetric problems, the mirror image C[j][i] (for a tile on the diagonal only
+// j <= i is written directly and j < i mirrored, which makes the result exactly symmetric),
+// plus the optional transposed copy Ct[j][i].  Both passes write whole row segments with
+// adjacent lanes on adjacent addresses; the transposition happens in the LDS reads.
+// The mirror pass relies on the old C being exactly symmetric (it reads beta's operand at
+// the mirrored position); Ct requires beta == 0.
+typedef float floatx4_st __attribute__((ext_vector_type(4), aligned(4)));
+
+template <int ROWS, int COLS>
+__device__ __forceinline__ void store_slab(const GemmProblem &P, const float *T, int gi0, int gj0, bool diag_tile,
+                                           int tid)
+{
+    constexpr int LDT = COLS + 1;
+    const bool sym = (P.flags & GEMM_SYM) != 0;
+    const float alpha = P.alpha, beta = P.beta;
+    // direct pass: a thread owns 4 adjacent columns of one row
+    {
+        constexpr int TPR = COLS / 4, RPP = 256 / TPR;
+        const int c = (tid % TPR) * 4, rr = tid / TPR;
+        for (int r = rr; r < ROWS; r += RPP) {
+            const int i = gi0 + r, j = gj0 + c;
+            if (i >= P.M || j >= P.N) continue;
+            const int jmax = min(diag_tile ? i : P.N - 1, P.N - 1);   // last column this row may write
+            if (j > jmax) continue;
+            float *dst = P.C + (long long)i * P.ldc + j;
+            const float *t = T + r * LDT + c;
+            if (j + 3 <= jmax) {
+                floatx4 v = {alpha * t[0], alpha * t[1], alpha * t[2], alpha * t[3]};
+                if (beta != 0.0f) {
+                    const floatx4 o = *(const floatx4_st *)dst;
+                    for (int e = 0; e < 4; ++e) v[e] = fmaf(beta, o[e], v[e]);   // same rounding in every path
+                }
+                *(floatx4_st *)dst = v;
+            } else {
+                for (int e = 0; e < 4 && j + e <= jmax; ++e) {
+                    float v = alpha * t[e];
+                    if (beta != 0.0f) v = fmaf(beta, dst[e], v);
+                    dst[e] = v;
+                }
+            }
+        }
+    }
+    // mirrored / transposed pass: a thread owns 4 adjacent rows i of one column j, which are
+    // 4 adjacent addresses of row j of the mirror image
+    float *mbase = sym ? P.C : P.Ct;
+    if (mbase) {
+        const long long ldm = sym ? P.ldc : P.ldct;
+        const float mbeta = sym ? beta : 0.0f;
+        constexpr int TPR = ROWS / 4, RPP = 256 / TPR;
+        const int r = (tid % TPR) * 4, cc = tid / TPR;
+        for (int c = cc; c < COLS; c += RPP) {
+            const int i = gi0 + r, j = gj0 + c;
+            if (i >= P.M || j >= P.N) continue;
+            // rows i..i+3 that may be mirrored: i + e < M and, on a diagonal tile, j < i + e
+            const int e0 = (sym && diag_tile) ? max(0, j + 1 - i) : 0;
+            const int e1 = min(4, P.M - i);
+            if (e0 >= e1) continue;
+            float *dst = mbase + (long long)j * ldm + i;
+            const float *t = T + r * LDT + c;
+            if (e0 == 0 && e1 == 4) {
+                floatx4 v = {alpha * t[0], alpha * t[LDT], alpha * t[2 * LDT], alpha * t[3 * LDT]};
+                if (mbeta != 0.0f) {
+                    const floatx4 o = *(const floatx4_st *)dst;
+                    for (int e = 0; e < 4; ++e) v[e] = fmaf(mbeta, o[e], v[e]);
+                }
+                *(floatx4_st *)dst = v;
+            } else {
+                for (int e = e0; e < e1; ++e) {
+                    float v = alpha * t[e * LDT];
+                    if (mbeta != 0.0f) v = fmaf(mbeta, dst[e], v);
+                    dst[e] = v;
+                }
+            }
+        }
+    }
 }
 
 // ------------------------------------------------------------------ operand loader (fp32)
@@ -307,17 +388,23 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__r
                     const int c = wave_n * 32 * TN + j * 32 + l32;
                     part[r * BN + c] = acc[i][j][v];
                 }
-    } else if (live) {
+    } else {
+        // stage the tile in LDS (the operand stages are dead by now), then store whole rows
+        __syncthreads();
+        if (live) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int r = tm * BM + wave_m * 32 * TM + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                    const int c = tn * BN + wave_n * 32 * TN + j * 32 + l32;
-                    store_result(P, diag_tile, r, c, acc[i][j][v]);
-                }
+                    for (int v = 0; v < 16; ++v) {
+                        const int r = wave_m * 32 * TM + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                        const int c = wave_n * 32 * TN + j * 32 + l32;
+                        lds[r * (BN + 1) + c] = acc[i][j][v];
+                    }
+        }
+        __syncthreads();
+        store_slab<BM, BN>(P, lds, tm * BM, tn * BN, diag_tile, tid);
     }
 }
 
@@ -504,35 +591,45 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__
 }
 
 // ------------------------------------------------------------------ split-K reduction + epilogue
-// One workgroup per 1024 consecutive elements of a partial tile (a thread owns 4 adjacent
-// columns): sums the partial tiles in split order (fixed order, so results are
-// reproducible bit for bit) and applies the same epilogue.  red_start counts these chunks.
+// One workgroup per 32-row slab of a partial tile: sums the partial tiles in split order
+// (fixed order, so results are reproducible bit for bit) into LDS and applies the same
+// row-wise epilogue.  red_start counts slabs.
+template <int B>
+__device__ __forceinline__ void reduce_slab(const GemmProblem &P, int tile, int slab, int tm, int tn, float *T)
+{
+    const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
+    const float *part = P.partial + (long long)tile * P.splits * (B * B) + slab * 32 * B;
+    // 32 * B elements, 4 per thread per pass
+    for (int e = threadIdx.x * 4; e < 32 * B; e += 1024) {
+        floatx4 s = {0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < P.splits; ++q) s += *(const floatx4 *)(part + (long long)q * (B * B) + e);
+        const int r = e / B, c = e - r * B;
+        float *t = T + r * (B + 1) + c;
+        t[0] = s[0]; t[1] = s[1]; t[2] = s[2]; t[3] = s[3];
+    }
+    __syncthreads();
+    store_slab<32, B>(P, T, tm * B + slab * 32, tn * B, diag_tile, threadIdx.x);
+}
+
 __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmProblem *__restrict__ probs,
                                                           const int *__restrict__ red_start, int n_probs)
 {
+    __shared__ float T[32 * 129];
     const int wg = blockIdx.x;
     const int pi = find_problem(red_start, n_probs, wg);
     const GemmProblem &P = probs[pi];
     if (P.splits <= 1) return;
     const int B = (P.tile_cfg == 0) ? 128 : 64;
-    const int chunks = B * B / 1024;
+    const int slabs = B / 32;
     const int local = wg - red_start[pi];
-    const int tile = local / chunks;
-    const int e = (local - tile * chunks) * 1024 + threadIdx.x * 4;
+    const int tile = local / slabs;
+    const int slab = local - tile * slabs;
     int tm, tn;
     if (P.flags & GEMM_SYM) tri_decode(tile, tm, tn);
     else { tm = tile / P.tiles_n; tn = tile - tm * P.tiles_n; }
-    const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
-    const int r = e / B, c = e - r * B;
-    const int i = tm * B + r, j = tn * B + c;
-    if (i >= P.M || j >= P.N) return;
-    const float *part = P.partial + (long long)tile * P.splits * (B * B) + e;
-    floatx4 s = {0.f, 0.f, 0.f, 0.f};
-    for (int q = 0; q < P.splits; ++q) s += *(const floatx4 *)(part + (long long)q * (B * B));
-    store_result(P, diag_tile, i, j + 0, s[0]);
-    store_result(P, diag_tile, i, j + 1, s[1]);
-    store_result(P, diag_tile, i, j + 2, s[2]);
-    store_result(P, diag_tile, i, j + 3, s[3]);
+    if (tm * B + slab * 32 >= P.M) return;
+    if (B == 128) reduce_slab<128>(P, tile, slab, tm, tn, T);
+    else          reduce_slab<64>(P, tile, slab, tm, tn, T);
 }
 
 template <int TM, int TN>

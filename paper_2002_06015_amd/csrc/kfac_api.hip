@@ -25,6 +25,8 @@ struct Tunables {
     int target_wgs;      // split-K gives a problem at least this many workgroups (if K allows)
     int min_k_per_split; // never split below this contraction length
     int max_k_per_wg;    // and never leaves a workgroup a longer contraction than this
+    int inv_streams;     // independent inversion chains run on this many streams (1..4)
+    int rec_leaf;        // the blocked inversion recurses down to blocks of at most this size
     Tunables()
     {
         const char *e = getenv("KFAC_TARGET_WGS");
@@ -33,6 +35,10 @@ struct Tunables {
         min_k_per_split = e ? std::max(32, atoi(e) / 32 * 32) : 512;
         e = getenv("KFAC_MAX_K_PER_WG");
         max_k_per_wg = e ? std::max(32, atoi(e) / 32 * 32) : 4096;
+        e = getenv("KFAC_INV_STREAMS");
+        inv_streams = e ? std::min(4, std::max(1, atoi(e))) : 1;
+        e = getenv("KFAC_REC_LEAF");
+        rec_leaf = e ? std::min(kLeafMax, std::max(32, atoi(e))) : 160;
     }
 };
 
@@ -49,6 +55,10 @@ struct kfac_ctx {
     bool ev_valid[kSlots];
     int next_slot;
     Tunables tun;
+    // auxiliary streams (default priority) for independent chains of launches inside one call
+    hipStream_t aux[3];
+    hipEvent_t fork_ev, join_ev[3];
+    bool aux_valid;
     // optional per-launch timing
     bool profiling;
     std::vector<hipEvent_t> ev_pool;      // pairs: [2i] start, [2i+1] stop
@@ -97,6 +107,7 @@ struct Launch {
     float f0, f1;
     void *p0, *p1;
     double flops, bytes;   // algorithmic counts (profiling only)
+    int stream;            // 0: the context's stream; 1..3: auxiliary streams (forked/joined inside the call)
 };
 
 struct Plan {
@@ -130,12 +141,29 @@ struct GemmGroup {   // problems that go into one phase (no dependencies among t
 
 int tile_edge(int cfg) { return cfg == 0 ? 128 : 64; }
 
-int choose_tile_cfg(int M, int N)
+// Rough time model (matrix-pipe cycles) of one problem under a tile configuration: the
+// matrix instructions of the workgroups resident on a CU serialise per SIMD, and a lone
+// wavefront per SIMD cannot hide its per-tile load/barrier latency.  Small products
+// therefore prefer 64x64 tiles (4x the workgroups, a quarter of the work each).
+double tile_cfg_cost(int M, int N, int K, bool sym, int cfg)
 {
-    auto cost = [&](int B, double w) {
-        return (double)((M + B - 1) / B) * ((N + B - 1) / B) * B * B * w;
-    };
-    return cost(128, 1.0) <= cost(64, 1.25) ? 0 : 1;
+    const int B = cfg == 0 ? 128 : 64;
+    const int slots = cfg == 0 ? 2 : 4;                 // workgroups per CU (registers / LDS)
+    // cycles per wavefront per 32-wide K tile; the small tile moves twice the operand bytes
+    // per flop, which costs it some efficiency on large products
+    const double mfma = cfg == 0 ? 4096.0 : 1024.0 * 1.2;
+    const double tm = (M + B - 1) / B, tn = (N + B - 1) / B;
+    const double tiles = sym ? tm * (tm + 1) / 2 : tm * tn;
+    const double per_cu = tiles / 256.0;
+    const double resident = std::min<double>(slots, std::max(1.0, per_cu));
+    const double rounds = std::max(1.0, per_cu / slots);
+    const double ksteps = std::max(1.0, K / 32.0);
+    return rounds * ksteps * std::max(mfma * resident, mfma + 700.0) + 3000.0;
+}
+
+int choose_tile_cfg(int M, int N, int K, bool sym)
+{
+    return tile_cfg_cost(M, N, K, sym, 0) <= tile_cfg_cost(M, N, K, sym, 1) ? 0 : 1;
 }
 
 void finish_problem(GemmProblem &P)
@@ -187,7 +215,7 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
         bool any_split = false;
         for (size_t i = 0; i < sel.size(); ++i) {
             start[i + 1] = start[i] + sel[i].n_tiles * sel[i].splits;
-            rstart[i + 1] = rstart[i] + (sel[i].splits > 1 ? sel[i].n_tiles * (B * B / 1024) : 0);
+            rstart[i + 1] = rstart[i] + (sel[i].splits > 1 ? sel[i].n_tiles * (B / 32) : 0);
             any_split |= sel[i].splits > 1;
         }
         Launch L{};
@@ -320,7 +348,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             P.ldc = dA; P.ldct = 0;
             P.M = dA; P.N = dA; P.K = K;
             P.flags = GEMM_SYM;
-            P.tile_cfg = choose_tile_cfg(dA, dA);
+            P.tile_cfg = choose_tile_cfg(dA, dA, K, true);
             P.alpha = (float)((1.0 - (double)a.decay) / ((double)Ly.N * (double)hw));
             P.beta = a.decay;
             finish_problem(P);
@@ -334,7 +362,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             P.ldc = dG;
             P.M = dG; P.N = dG; P.K = K;
             P.flags = GEMM_SYM;
-            P.tile_cfg = choose_tile_cfg(dG, dG);
+            P.tile_cfg = choose_tile_cfg(dG, dG, K, true);
             double scale = 1.0 / (double)Ly.N;
             if (a.g_spatial_mean) scale /= (double)hw;
             P.alpha = (float)((1.0 - (double)a.decay) * scale);
@@ -394,9 +422,9 @@ int split_point(int n)
 //   X11 <- X11 - X12 W^T                           (GEMM, symmetric)
 // Returns the first level at which the block's inverse is complete.
 int build_inverse(std::vector<InvOp> &ops, Arena &arena, float *X, long long ld, int o, int n, int level,
-                  int info_idx)
+                  int info_idx, int rec_leaf)
 {
-    if (n <= kLeafMax) {
+    if (n <= rec_leaf) {
         InvOp op{};
         op.level = level;
         op.kind = OP_LEAF;
@@ -419,7 +447,7 @@ int build_inverse(std::vector<InvOp> &ops, Arena &arena, float *X, long long ld,
     float *Y = (float *)arena.take((size_t)n2 * ldy * sizeof(float));
     float *W = (float *)arena.take((size_t)n1 * ldw * sizeof(float));
 
-    const int l1 = build_inverse(ops, arena, X, ld, o, n1, level, info_idx);
+    const int l1 = build_inverse(ops, arena, X, ld, o, n1, level, info_idx, rec_leaf);
     {
         InvOp op{};
         op.level = l1; op.kind = OP_GEMM;
@@ -429,7 +457,7 @@ int build_inverse(std::vector<InvOp> &ops, Arena &arena, float *X, long long ld,
         P.C = Y; P.ldc = ldy; P.Ct = W; P.ldct = ldw;
         P.M = n2; P.N = n1; P.K = n1; P.flags = 0;
         P.alpha = 1.f; P.beta = 0.f;
-        P.tile_cfg = choose_tile_cfg(P.M, P.N);
+        P.tile_cfg = choose_tile_cfg(P.M, P.N, P.K, (P.flags & GEMM_SYM) != 0);
         finish_problem(P);
         ops.push_back(op);
     }
@@ -442,11 +470,11 @@ int build_inverse(std::vector<InvOp> &ops, Arena &arena, float *X, long long ld,
         P.C = X22; P.ldc = ld; P.Ct = nullptr;
         P.M = n2; P.N = n2; P.K = n1; P.flags = GEMM_SYM;
         P.alpha = -1.f; P.beta = 1.f;
-        P.tile_cfg = choose_tile_cfg(P.M, P.N);
+        P.tile_cfg = choose_tile_cfg(P.M, P.N, P.K, (P.flags & GEMM_SYM) != 0);
         finish_problem(P);
         ops.push_back(op);
     }
-    const int l2 = build_inverse(ops, arena, X, ld, o + n1, n2, l1 + 2, info_idx);
+    const int l2 = build_inverse(ops, arena, X, ld, o + n1, n2, l1 + 2, info_idx, rec_leaf);
     {
         InvOp op{};
         op.level = l2; op.kind = OP_GEMM;
@@ -456,7 +484,7 @@ int build_inverse(std::vector<InvOp> &ops, Arena &arena, float *X, long long ld,
         P.C = X12; P.ldc = ld; P.Ct = X21; P.ldct = ld;
         P.M = n1; P.N = n2; P.K = n2; P.flags = 0;
         P.alpha = -1.f; P.beta = 0.f;
-        P.tile_cfg = choose_tile_cfg(P.M, P.N);
+        P.tile_cfg = choose_tile_cfg(P.M, P.N, P.K, (P.flags & GEMM_SYM) != 0);
         finish_problem(P);
         ops.push_back(op);
     }
@@ -469,7 +497,7 @@ int build_inverse(std::vector<InvOp> &ops, Arena &arena, float *X, long long ld,
         P.C = X11; P.ldc = ld; P.Ct = nullptr;
         P.M = n1; P.N = n1; P.K = n2; P.flags = GEMM_SYM;
         P.alpha = -1.f; P.beta = 1.f;
-        P.tile_cfg = choose_tile_cfg(P.M, P.N);
+        P.tile_cfg = choose_tile_cfg(P.M, P.N, P.K, (P.flags & GEMM_SYM) != 0);
         finish_problem(P);
         ops.push_back(op);
     }
@@ -522,10 +550,29 @@ void plan_invert(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs
         T.p1 = a.pi_out;
         plan.launches.push_back(T);
     }
+    // The recursion of one matrix is a long dependent chain of small launches.  Matrices are
+    // dealt into up to inv_streams groups of similar n^3; each group has its own levelled
+    // schedule on its own stream, so the serial parts of one chain overlap the large
+    // products of another.  Group 0 runs on the context's stream.
+    const int n_groups = std::max(1, std::min(tun.inv_streams, 4));
+    std::vector<int> order(mats.size());
+    for (size_t i = 0; i < mats.size(); ++i) order[i] = (int)i;
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return mats[x].n > mats[y].n; });
+    std::vector<double> load(n_groups, 0.0);
+    std::vector<int> group_of(mats.size(), 0);
+    for (int idx : order) {
+        if (mats[idx].n <= kLeafMax) { group_of[idx] = 0; continue; }   // single launch: no chain
+        int g = 0;
+        for (int q = 1; q < n_groups; ++q)
+            if (load[q] < load[g]) g = q;
+        group_of[idx] = g;
+        load[g] += (double)mats[idx].n * mats[idx].n * mats[idx].n;
+    }
     std::vector<CopyJob> cjobs;
-    std::vector<InvOp> ops;
     int copy_wgs = 0;
-    for (auto &m : mats) {
+    std::vector<std::vector<InvOp>> ops(n_groups);
+    for (size_t i = 0; i < mats.size(); ++i) {
+        const InvMatrix &m = mats[i];
         if (m.n <= kLeafMax) {
             InvOp op{};
             op.level = 0; op.kind = OP_LEAF;
@@ -535,7 +582,7 @@ void plan_invert(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs
             op.leaf.damp_idx = m.damp_idx;
             op.leaf.info_idx = m.info_idx;
             op.leaf.pivot_base = 0;
-            ops.push_back(op);
+            ops[0].push_back(op);
         } else {
             CopyJob C{};
             C.src = m.src; C.dst = m.dst;
@@ -544,7 +591,7 @@ void plan_invert(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs
             C.wg_start = copy_wgs;
             copy_wgs += (m.n + 7) / 8;
             cjobs.push_back(C);
-            build_inverse(ops, arena, m.dst, m.n, 0, m.n, 0, m.info_idx);
+            build_inverse(ops[group_of[i]], arena, m.dst, m.n, 0, m.n, 0, m.info_idx, tun.rec_leaf);
         }
     }
     if (!cjobs.empty()) {
@@ -556,29 +603,39 @@ void plan_invert(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs
         C.p0 = damp;
         plan.launches.push_back(C);
     }
-    int max_level = -1;
-    for (auto &op : ops) max_level = std::max(max_level, op.level);
-    for (int lv = 0; lv <= max_level; ++lv) {
-        for (int c = 0; c < kNumLeafClasses; ++c) {
-            std::vector<LeafJob> lj;
-            for (auto &op : ops)
-                if (op.level == lv && op.kind == OP_LEAF && leaf_class(op.leaf.n) == c) lj.push_back(op.leaf);
-            if (lj.empty()) continue;
-            Launch Lf{};
-            Lf.kind = L_LEAF;
-            Lf.off_a = plan.tab.add(lj.data(), lj.size() * sizeof(LeafJob));
-            Lf.n = (int)lj.size();
-            Lf.cfg = c;
-            Lf.p0 = damp;
-            Lf.p1 = a.info;
-            plan.launches.push_back(Lf);
+    // auxiliary groups first, so that their launches are enqueued before the main chain's
+    for (int gi = 0; gi < n_groups; ++gi) {
+        const int g = (gi + 1) % n_groups;
+        if (ops[g].empty()) continue;
+        // split-K scratch of different groups must not overlap: they run concurrently
+        const size_t group_base = align_up(arena.peak, kAlign);
+        arena.used = group_base;
+        int max_level = -1;
+        for (auto &op : ops[g]) max_level = std::max(max_level, op.level);
+        for (int lv = 0; lv <= max_level; ++lv) {
+            const size_t first = plan.launches.size();
+            for (int c = 0; c < kNumLeafClasses; ++c) {
+                std::vector<LeafJob> lj;
+                for (auto &op : ops[g])
+                    if (op.level == lv && op.kind == OP_LEAF && leaf_class(op.leaf.n) == c) lj.push_back(op.leaf);
+                if (lj.empty()) continue;
+                Launch Lf{};
+                Lf.kind = L_LEAF;
+                Lf.off_a = plan.tab.add(lj.data(), lj.size() * sizeof(LeafJob));
+                Lf.n = (int)lj.size();
+                Lf.cfg = c;
+                Lf.p0 = damp;
+                Lf.p1 = a.info;
+                plan.launches.push_back(Lf);
+            }
+            std::vector<GemmProblem> gp;
+            for (auto &op : ops[g])
+                if (op.level == lv && op.kind == OP_GEMM) gp.push_back(op.gemm);
+            const size_t mark = arena.used;
+            emit_gemm_phase(plan, arena, tun, gp, 0, true);
+            arena.release_to(mark);
+            for (size_t q = first; q < plan.launches.size(); ++q) plan.launches[q].stream = g;
         }
-        std::vector<GemmProblem> gp;
-        for (auto &op : ops)
-            if (op.level == lv && op.kind == OP_GEMM) gp.push_back(op.gemm);
-        const size_t mark = arena.used;
-        emit_gemm_phase(plan, arena, tun, gp, 0, true);
-        arena.release_to(mark);
     }
 }
 
@@ -607,7 +664,7 @@ void plan_precondition(Plan &plan, Arena &arena, const Tunables &tun, const Prec
         P.C = Vt; P.ldc = ldv; P.Ct = nullptr;
         P.M = dA; P.N = dG; P.K = dA; P.flags = 0;
         P.alpha = 1.f; P.beta = 0.f;
-        P.tile_cfg = choose_tile_cfg(P.M, P.N);
+        P.tile_cfg = choose_tile_cfg(P.M, P.N, P.K, (P.flags & GEMM_SYM) != 0);
         finish_problem(P);
         p1.push_back(P);
         GemmProblem Q{};
@@ -616,7 +673,7 @@ void plan_precondition(Plan &plan, Arena &arena, const Tunables &tun, const Prec
         Q.C = dry ? nullptr : a.out[l]; Q.ldc = dA; Q.Ct = nullptr;
         Q.M = dG; Q.N = dA; Q.K = dG; Q.flags = 0;
         Q.alpha = 1.f; Q.beta = 0.f;
-        Q.tile_cfg = choose_tile_cfg(Q.M, Q.N);
+        Q.tile_cfg = choose_tile_cfg(Q.M, Q.N, Q.K, false);
         finish_problem(Q);
         p2.push_back(Q);
     }
@@ -663,8 +720,31 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
             return KFAC_ERR_DEVICE;
         if (hipEventRecord(ctx->ev[slot], s) != hipSuccess) return KFAC_ERR_DEVICE;
     }
+    bool forked = false;
+    bool used[4] = {true, false, false, false};
     for (auto &L : plan.launches) {
         hipError_t e = hipSuccess;
+        hipStream_t ls = s;
+        if (L.stream > 0) {
+            if (!ctx->aux_valid) {
+                for (int q = 0; q < 3; ++q) {
+                    if (hipStreamCreateWithFlags(&ctx->aux[q], hipStreamNonBlocking) != hipSuccess) return KFAC_ERR_DEVICE;
+                    if (hipEventCreateWithFlags(&ctx->join_ev[q], hipEventDisableTiming) != hipSuccess) return KFAC_ERR_DEVICE;
+                }
+                if (hipEventCreateWithFlags(&ctx->fork_ev, hipEventDisableTiming) != hipSuccess) return KFAC_ERR_DEVICE;
+                ctx->aux_valid = true;
+            }
+            if (!forked) {
+                // everything enqueued so far (tables, earlier launches) happens before the fork
+                if (hipEventRecord(ctx->fork_ev, s) != hipSuccess) return KFAC_ERR_DEVICE;
+                forked = true;
+            }
+            if (!used[L.stream]) {
+                if (hipStreamWaitEvent(ctx->aux[L.stream - 1], ctx->fork_ev, 0) != hipSuccess) return KFAC_ERR_DEVICE;
+                used[L.stream] = true;
+            }
+            ls = ctx->aux[L.stream - 1];
+        }
         const bool timed = ctx->profiling && L.kind != L_ZERO;
         if (timed) {
             const size_t idx = ctx->prof.size();
@@ -690,43 +770,49 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
             pe.flops = L.flops;
             pe.bytes = L.bytes;
             ctx->prof.push_back(pe);
-            if (hipEventRecord(ctx->ev_pool[2 * idx], s) != hipSuccess) return KFAC_ERR_DEVICE;
+            if (hipEventRecord(ctx->ev_pool[2 * idx], ls) != hipSuccess) return KFAC_ERR_DEVICE;
         }
         switch (L.kind) {
             case L_GEMM:
                 e = launch_gemm((const GemmProblem *)(tab_dev + L.off_a), (const int *)(tab_dev + L.off_b), L.n,
-                                L.total_wgs, L.cfg, L.dtype, s);
+                                L.total_wgs, L.cfg, L.dtype, ls);
                 break;
             case L_REDUCE:
                 e = launch_gemm_reduce((const GemmProblem *)(tab_dev + L.off_a), (const int *)(tab_dev + L.off_b),
-                                       L.n, L.total_wgs, s);
+                                       L.n, L.total_wgs, ls);
                 break;
             case L_PATCH:
-                e = launch_patch((const PatchJob *)(tab_dev + L.off_a), L.n, L.total_wgs, s);
+                e = launch_patch((const PatchJob *)(tab_dev + L.off_a), L.n, L.total_wgs, ls);
                 break;
             case L_TRACE:
-                e = launch_trace((const TraceJob *)(tab_dev + L.off_a), L.n, L.f0, (float *)L.p0, (float *)L.p1, s);
+                e = launch_trace((const TraceJob *)(tab_dev + L.off_a), L.n, L.f0, (float *)L.p0, (float *)L.p1, ls);
                 break;
             case L_COPY:
-                e = launch_copy_damp((const CopyJob *)(tab_dev + L.off_a), L.n, L.total_wgs, (const float *)L.p0, s);
+                e = launch_copy_damp((const CopyJob *)(tab_dev + L.off_a), L.n, L.total_wgs, (const float *)L.p0, ls);
                 break;
             case L_LEAF:
                 e = launch_leaf((const LeafJob *)(tab_dev + L.off_a), L.n, L.cfg, (const float *)L.p0,
-                                (int32_t *)L.p1, s);
+                                (int32_t *)L.p1, ls);
                 break;
             case L_ZERO:
-                e = launch_zero_i32((int32_t *)L.p0, L.n, s);
+                e = launch_zero_i32((int32_t *)L.p0, L.n, ls);
                 break;
             case L_BN:
-                e = launch_bn((const BnJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, L.f0, L.f1, s);
+                e = launch_bn((const BnJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, L.f0, L.f1, ls);
                 break;
             case L_BNRED:
-                e = launch_bn_reduce((const BnReduceJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, s);
+                e = launch_bn_reduce((const BnReduceJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, ls);
                 break;
         }
         if (e != hipSuccess) return KFAC_ERR_DEVICE;
-        if (timed && hipEventRecord(ctx->ev_pool[2 * ctx->prof.size() - 1], s) != hipSuccess)
+        if (timed && hipEventRecord(ctx->ev_pool[2 * ctx->prof.size() - 1], ls) != hipSuccess)
             return KFAC_ERR_DEVICE;
+    }
+    // join: the context's stream continues only after every auxiliary chain has finished
+    for (int q = 1; q < 4; ++q) {
+        if (!used[q]) continue;
+        if (hipEventRecord(ctx->join_ev[q - 1], ctx->aux[q - 1]) != hipSuccess) return KFAC_ERR_DEVICE;
+        if (hipStreamWaitEvent(s, ctx->join_ev[q - 1], 0) != hipSuccess) return KFAC_ERR_DEVICE;
     }
     return KFAC_OK;
 }
@@ -816,6 +902,7 @@ kfac_status kfac_create(kfac_ctx **out, void *hip_stream, void *workspace_dev, s
     }
     c->next_slot = 0;
     c->profiling = false;
+    c->aux_valid = false;
     *out = c;
     return KFAC_OK;
 }
@@ -831,6 +918,14 @@ void kfac_destroy(kfac_ctx *ctx)
         if (ctx->pinned[i]) (void)hipHostFree(ctx->pinned[i]);
     }
     for (auto ev : ctx->ev_pool) (void)hipEventDestroy(ev);
+    if (ctx->aux_valid) {
+        for (int q = 0; q < 3; ++q) {
+            (void)hipStreamSynchronize(ctx->aux[q]);
+            (void)hipStreamDestroy(ctx->aux[q]);
+            (void)hipEventDestroy(ctx->join_ev[q]);
+        }
+        (void)hipEventDestroy(ctx->fork_ev);
+    }
     delete ctx;
 }
 
