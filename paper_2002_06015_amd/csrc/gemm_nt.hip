@@ -37,6 +37,17 @@ __device__ __forceinline__ int find_problem(const int *start, int n, int wg)
     return lo;
 }
 
+// Workgroups are handed to the 8 XCDs round-robin (workgroup i runs on XCD i % 8) and each
+// XCD has its own L2.  This maps the hardware index to a logical index such that each XCD
+// works through one contiguous eighth of the logical range, so that tiles which share
+// operand panels (neighbours in the logical order) hit the same L2.  Bijective on [0, total).
+__device__ __forceinline__ int xcd_remap(int wg, int total)
+{
+    const int x = wg & 7, q = wg >> 3;
+    const int base = total >> 3, rem = total & 7;
+    return x * base + min(x, rem) + q;
+}
+
 __device__ __forceinline__ void tri_decode(int t, int &tm, int &tn)
 {
     int r = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
@@ -338,9 +349,14 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__r
     const int wg = blockIdx.x;
     const int pi = find_problem(tile_start, n_probs, wg);
     const GemmProblem &P = probs[pi];
-    const int local = wg - tile_start[pi];
-    const int split = local % P.splits;
-    const int tile = local / P.splits;
+    // every problem starts at a multiple of 8 workgroups (padded with idle ones), so the XCD
+    // of a workgroup is its local index % 8; neighbours in the logical order are
+    // neighbouring tiles of the same K range
+    const int n_local = P.n_tiles * P.splits;
+    const int local = xcd_remap(wg - tile_start[pi], (n_local + 7) & ~7);
+    if (local >= n_local) return;
+    const int split = local / P.n_tiles;
+    const int tile = local - split * P.n_tiles;
     int tm, tn;
     if (P.flags & GEMM_SYM) tri_decode(tile, tm, tn);
     else { tm = tile / P.tiles_n; tn = tile - tm * P.tiles_n; }
@@ -493,9 +509,11 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__
     const int wg = blockIdx.x;
     const int pi = find_problem(tile_start, n_probs, wg);
     const GemmProblem &P = probs[pi];
-    const int local = wg - tile_start[pi];
-    const int split = local % P.splits;
-    const int tile = local / P.splits;
+    const int n_local = P.n_tiles * P.splits;
+    const int local = xcd_remap(wg - tile_start[pi], (n_local + 7) & ~7);
+    if (local >= n_local) return;
+    const int split = local / P.n_tiles;
+    const int tile = local - split * P.n_tiles;
     int tm, tn;
     if (P.flags & GEMM_SYM) tri_decode(tile, tm, tn);
     else { tm = tile / P.tiles_n; tn = tile - tm * P.tiles_n; }
