@@ -96,12 +96,12 @@ hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t s)
 // Thread (ti, tj) of a TR x 32 thread grid holds the elements (ti + TR*bi, tj + 32*bj),
 // bi < BR, bj < BC (so n <= TR*BR = 32*BC).  Gauss-Jordan without pivoting (safe for a
 // positive definite matrix).  After pivots 0..k-1 the working matrix T has
-// T[k][j] = -T[j][k] for j < k and T[k][j] = T[j][k] for j > k, so publishing row k alone
-// also gives column k.  Step k:
+// T[k][j] = -T[j][k] for j < k and T[k][j] = T[j][k] for j > k, so publishing pivot rows
+// alone also gives the pivot columns.  A single-pivot step would be
 //     p = 1/T[k][k];  T[i][j] -= T[i][k] p T[k][j]  (i, j != k);
-//     T[k][j] *= p;   T[i][k] *= -p;   T[k][k] = p.
-// One barrier per step (the pivot row buffer is double-buffered).  A non-positive pivot is
-// reported through info.
+//     T[k][j] *= p;   T[i][k] *= -p;   T[k][k] = p;
+// the kernel takes the pivots in pairs (see the loop).  One barrier per pair (the pivot row
+// buffer is double-buffered).  A non-positive pivot is reported through info.
 // f(integral_constant<int, I>) for I = 0..N-1, unrolled at compile time.
 template <int I, int N, typename F>
 __device__ __forceinline__ void static_for(F &&f)
@@ -119,13 +119,13 @@ __global__ __launch_bounds__(TR * 32) void leaf_inverse_kernel(const LeafJob *__
 {
     static_assert(TR * BR == 32 * BC, "row and column coverage must agree");
     static_assert(TR == 32 || TR == 16, "thread grid is 32x32 or 16x32");
-    __shared__ float rowbuf[2][32 * BC];
-    __shared__ int bad;
+    static_assert((TR * BR) % 2 == 0, "pivots are taken in pairs");
+    __shared__ float rowbuf[2][2][32 * BC];
+    int bad = 0;
     const LeafJob J = jobs[blockIdx.x];
     const int n = J.n;
     const int tj = threadIdx.x & 31, ti = threadIdx.x >> 5;
     const float d = (J.damp_idx >= 0) ? damp[J.damp_idx] : 0.f;
-    if (threadIdx.x == 0) bad = 0;
 
     // 32-bit element offsets from the (uniform) base keep one address register per access
     const unsigned lds = (unsigned)J.lds, ldd = (unsigned)J.ldd;
@@ -145,53 +145,74 @@ __global__ __launch_bounds__(TR * 32) void leaf_inverse_kernel(const LeafJob *__
     }
     __syncthreads();
 
-    // The pivot loop is split into BR compile-time blocks of TR pivots, so that the register
-    // row (KBR) and register column (KBC) that hold pivot row/column k are compile-time
-    // constants and the matrix never leaves its registers.
+    // Two pivots per step (one barrier and one LDS round trip for both): with the pivot rows
+    // R = T[{k,k+1}, :], the 2x2 pivot block P and Q = P^-1, a block Gauss-Jordan step is
+    //     T[i][j] -= C[i,:] Q R[:,j],  T[K,j] = Q R[:,j],  T[i,K] = -C[i,:] Q,  T[K,K] = Q,
+    // where the pivot columns follow from the rows: C[i,:] = s_i R[:,i]^T, s_i = -1 for
+    // already eliminated i < k and +1 otherwise.  The owners of rows/columns k, k+1 clear
+    // their old values and patch their multipliers so that the same two fused multiply-adds
+    // produce exactly those special results.  The pivot loop is split into BR compile-time
+    // blocks of TR pivots, so that the register row (KBR) and column (KBC) holding the pivot
+    // rows/columns are compile-time constants and the matrix never leaves its registers.
+    // An odd n takes the identity padding row n as its last second pivot.
+    const int n_even = n + (n & 1);
     static_for<0, BR>([&](auto KB) {
         constexpr int KBR = decltype(KB)::value;
         constexpr int KBC = (KBR * TR) / 32;
-        const int kend = min(n, (KBR + 1) * TR);
-        for (int k = KBR * TR; k < kend; ++k) {
-            const int ktr = k - KBR * TR;   // row k lives in threads ti == ktr, register row KBR
-            const int ktc = k & 31;         // column k lives in threads tj == ktc, register column KBC
-            float *rb = rowbuf[k & 1];
+        const int kend = min(n_even, (KBR + 1) * TR);
+        for (int k = KBR * TR; k < kend; k += 2) {
+            const int ktr = k - KBR * TR;   // rows k, k+1 live in threads ti == ktr, ktr+1, register row KBR
+            const int ktc = k & 31;         // columns k, k+1 live in threads tj == ktc, ktc+1, register column KBC
+            float *rb0 = rowbuf[(k >> 1) & 1][0], *rb1 = rowbuf[(k >> 1) & 1][1];
             if (ti == ktr) {
 #pragma unroll
-                for (int bj = 0; bj < BC; ++bj) rb[tj + 32 * bj] = a[KBR][bj];
+                for (int bj = 0; bj < BC; ++bj) rb0[tj + 32 * bj] = a[KBR][bj];
+            }
+            if (ti == ktr + 1) {
+#pragma unroll
+                for (int bj = 0; bj < BC; ++bj) rb1[tj + 32 * bj] = a[KBR][bj];
             }
             __syncthreads();
-            const float pivot = rb[k];
-            // a non-positive pivot is recorded (first one wins); the elimination goes on and
-            // its (meaningless) result is still written: no early exit keeps the loop simple
-            if (!(pivot > 0.f) && threadIdx.x == 0 && bad == 0) bad = k + 1;
-            const float p = 1.0f / pivot;
-            float rj[BC], ci[BR];
+            const float pa = rb0[k], pb = rb0[k + 1], pd = rb1[k + 1];
+            const float det = fmaf(pa, pd, -pb * pb);
+            // non-positive pivots (the second one is det / pa) are recorded, first one wins,
+            // tracked in a register by every thread alike; the elimination goes on and its
+            // (meaningless) result is still written: no early exit, no branch
+            const int badk = !(pa > 0.f) ? k + 1 : (!(det > 0.f) ? k + 2 : 0);
+            bad = (bad == 0) ? badk : bad;
+            const float idet = __builtin_amdgcn_rcpf(det);
+            const float q00 = pd * idet, q01 = -pb * idet, q11 = pa * idet;
+            float t0[BC], t1[BC], c0[BR], c1[BR];
 #pragma unroll
-            for (int bj = 0; bj < BC; ++bj) rj[bj] = rb[tj + 32 * bj];
+            for (int bj = 0; bj < BC; ++bj) {
+                const float r0 = rb0[tj + 32 * bj], r1 = rb1[tj + 32 * bj];
+                t0[bj] = fmaf(q00, r0, q01 * r1);
+                t1[bj] = fmaf(q01, r0, q11 * r1);
+            }
 #pragma unroll
             for (int bi = 0; bi < BR; ++bi) {
                 const int i = ti + TR * bi;
-                const float r = rb[i];
-                ci[bi] = ((i < k) ? -r : r) * p;
+                const float r0 = rb0[i], r1 = rb1[i];
+                c0[bi] = (i < k) ? -r0 : r0;
+                c1[bi] = (i < k) ? -r1 : r1;
             }
-            // Row k and column k are special (T[k][j] <- p T[k][j], T[i][k] <- -p T[i][k],
-            // T[k][k] <- p).  Their owners clear the old values and patch their multipliers
-            // so that the one fused multiply-add below produces exactly those results.
-            if (ti == ktr) {
+            if (ti == ktr || ti == ktr + 1) {
 #pragma unroll
                 for (int bj = 0; bj < BC; ++bj) a[KBR][bj] = 0.f;
-                ci[KBR] = -p;
+                c0[KBR] = (ti == ktr) ? -1.f : 0.f;
+                c1[KBR] = (ti == ktr) ? 0.f : -1.f;
             }
-            if (tj == ktc) {
+            if (tj == ktc || tj == ktc + 1) {
 #pragma unroll
                 for (int bi = 0; bi < BR; ++bi) a[bi][KBC] = 0.f;
-                rj[KBC] = 1.f;
+                t0[KBC] = (tj == ktc) ? q00 : q01;
+                t1[KBC] = (tj == ktc) ? q01 : q11;
             }
 #pragma unroll
             for (int bi = 0; bi < BR; ++bi)
 #pragma unroll
-                for (int bj = 0; bj < BC; ++bj) a[bi][bj] = fmaf(-ci[bi], rj[bj], a[bi][bj]);
+                for (int bj = 0; bj < BC; ++bj)
+                    a[bi][bj] = fmaf(-c1[bi], t1[bj], fmaf(-c0[bi], t0[bj], a[bi][bj]));
         }
     });
     __syncthreads();
@@ -219,9 +240,9 @@ hipError_t launch_leaf(const LeafJob *jobs_dev, int n_jobs, int size_class, cons
     dim3 grid(n_jobs);
     switch (kLeafClasses[size_class]) {   // class value = n_max / 32
         case 2: leaf_inverse_kernel<2, 2, 32><<<grid, dim3(1024), 0, s>>>(jobs_dev, damp_dev, info); break;
-        case 3: leaf_inverse_kernel<3, 3, 32><<<grid, dim3(1024), 0, s>>>(jobs_dev, damp_dev, info); break;
-        case 4: leaf_inverse_kernel<4, 4, 32><<<grid, dim3(1024), 0, s>>>(jobs_dev, damp_dev, info); break;
-        case 5: leaf_inverse_kernel<5, 5, 32><<<grid, dim3(1024), 0, s>>>(jobs_dev, damp_dev, info); break;
+        case 3: leaf_inverse_kernel<6, 3, 16><<<grid, dim3(512), 0, s>>>(jobs_dev, damp_dev, info); break;
+        case 4: leaf_inverse_kernel<8, 4, 16><<<grid, dim3(512), 0, s>>>(jobs_dev, damp_dev, info); break;
+        case 5: leaf_inverse_kernel<10, 5, 16><<<grid, dim3(512), 0, s>>>(jobs_dev, damp_dev, info); break;
         case 7: leaf_inverse_kernel<14, 7, 16><<<grid, dim3(512), 0, s>>>(jobs_dev, damp_dev, info); break;
         case 8: leaf_inverse_kernel<16, 8, 16><<<grid, dim3(512), 0, s>>>(jobs_dev, damp_dev, info); break;
         case 9: leaf_inverse_kernel<18, 9, 16><<<grid, dim3(512), 0, s>>>(jobs_dev, damp_dev, info); break;

@@ -180,7 +180,7 @@ void finish_problem(GemmProblem &P)
 // Emits the launches of one phase: per tile configuration one GEMM launch, plus one
 // reduction launch if any problem was split along K.
 void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<GemmProblem> &probs,
-                     int dtype, bool allow_split)
+                     int dtype, bool allow_split, bool phase_boost = false)
 {
     if (probs.empty()) return;
     // Tile configuration per problem.  When the phase as a whole fills the GPU with 128x128
@@ -214,10 +214,19 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
         if (sel.empty()) continue;
         const int B = tile_edge(cfg);
         if (allow_split) {
-            // per problem (independent of what else is in the launch, so that the workspace
-            // need of a layer list does not depend on which of its inputs are present)
+            // A heavy phase with only a few rounds of workgroups (512 run at a time) loses a
+            // large fraction of its last round; splitting every problem a little further
+            // evens that out.  Only for phases whose problem set is fixed by the layer list.
+            int boost = 1;
+            if (phase_boost) {
+                double tiles = 0, ksteps = 0;
+                for (auto &P : sel) { tiles += P.n_tiles; ksteps += (double)P.n_tiles * ((P.K + 31) / 32); }
+                if (tiles < 2048 && ksteps >= 512.0 * 48) boost = (int)((2048 + tiles - 1) / tiles);
+            }
+            // otherwise per problem (independent of what else is in the launch, so that the
+            // workspace need of a layer list does not depend on which of its inputs are present)
             for (auto &P : sel) {
-                const int want = (tun.target_wgs + P.n_tiles - 1) / P.n_tiles;
+                const int want = std::max(boost, (tun.target_wgs + P.n_tiles - 1) / P.n_tiles);
                 int splits = std::max((P.K + tun.max_k_per_wg - 1) / tun.max_k_per_wg,
                                       std::min(want, P.K / tun.min_k_per_split));
                 if (splits > 1) {
@@ -656,7 +665,7 @@ void plan_invert(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs
             for (auto &op : ops[g])
                 if (op.level == lv && op.kind == OP_GEMM) gp.push_back(op.gemm);
             const size_t mark = arena.used;
-            emit_gemm_phase(plan, arena, tun, gp, 0, true);
+            emit_gemm_phase(plan, arena, tun, gp, 0, true, true);
             arena.release_to(mark);
             for (size_t q = first; q < plan.launches.size(); ++q) plan.launches[q].stream = g;
         }
@@ -701,8 +710,8 @@ void plan_precondition(Plan &plan, Arena &arena, const Tunables &tun, const Prec
         finish_problem(Q);
         p2.push_back(Q);
     }
-    emit_gemm_phase(plan, arena, tun, p1, 0, true);
-    emit_gemm_phase(plan, arena, tun, p2, 0, true);
+    emit_gemm_phase(plan, arena, tun, p1, 0, true, true);
+    emit_gemm_phase(plan, arena, tun, p2, 0, true, true);
 }
 
 // ---------------------------------------------------------------- execution
