@@ -25,7 +25,6 @@ typedef unsigned short ushortx4 __attribute__((ext_vector_type(4)));
 
 constexpr int KT = 32;      // contraction tile
 constexpr int LDF = 36;     // LDS row length in floats (32 + 4 pad: conflict-free 16-byte reads)
-constexpr int LDH = 40;     // LDS row length in bf16 (32 + 8 pad)
 
 __device__ __forceinline__ int find_problem(const int *start, int n, int wg)
 {
@@ -55,21 +54,6 @@ __device__ __forceinline__ void tri_decode(int t, int &tm, int &tn)
     while ((r + 1) * (r + 2) / 2 <= t) ++r;
     tm = r;
     tn = t - r * (r + 1) / 2;
-}
-
-// Final write of one element of C and of its mirror / transposed copy (element-wise form,
-// used by the bf16 kernel).
-__device__ __forceinline__ void store_result(const GemmProblem &P, bool diag_tile, int i, int j, float acc)
-{
-    if (i >= P.M || j >= P.N) return;
-    const bool sym = (P.flags & GEMM_SYM) != 0;
-    if (sym && diag_tile && j > i) return;  // the mirror of (j, i) writes this one
-    float *c = P.C + (long long)i * P.ldc + j;
-    float v = P.alpha * acc;
-    if (P.beta != 0.0f) v += P.beta * (*c);
-    *c = v;
-    if (sym && i != j) P.C[(long long)j * P.ldc + i] = v;
-    if (P.Ct) P.Ct[(long long)j * P.ldct + i] = v;
 }
 
 // Final write of a ROWS x COLS slab of accumulated sums held in LDS (T[r][c] at
@@ -425,86 +409,174 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__r
 }
 
 // ------------------------------------------------------------------ bf16 operand loader
-// Operands are bf16 in memory; a tile row is 32 bf16 = 64 bytes in LDS (+ pad).
+// Same scheme as the fp32 loader with 64-wide K tiles: a thread owns one chunk of 8 bf16
+// (16 bytes, 16-byte aligned: the host only contracts NCHW tensors in place when
+// hw % 8 == 0 and the base is aligned; everything else goes through the repack kernel,
+// whose rows are padded) of the rows r0 + 32*s.
+constexpr int KTH = 64;     // contraction tile of the bf16 kernel
+constexpr int LDH = 72;     // LDS row length in bf16 (64 + 8 pad: 144-byte rows, conflict-free 16-byte reads)
+typedef const unsigned short __attribute__((address_space(1))) *gushort_ptr;
+typedef const ushortx8 __attribute__((address_space(1))) *gushort8_ptr;
+
 template <int BR>
 struct LoaderBF16 {
-    static constexpr int NREG = BR / 8;  // bf16 values held per thread for one tile
-    const unsigned short *base;
-    long long row_stride, batch_stride;
-    int rows, hw, ones_row, vec;
-    int row0, koff, r0, m, n, t, kend;
+    static constexpr int SLOTS = BR / 32;
+    gushort_ptr base;
+    long long rowoff[SLOTS];
+    unsigned dead, ones;
+    long long batch_stride;
+    int hw, kq, r0, m, n, t;
+    bool zero_all;
 
-    __device__ __forceinline__ void init(const Operand &op, int tile_row0, int k0, int k1, int tid)
+    __device__ __forceinline__ void init(const Operand &op, int tile_row0, int tid)
     {
-        base = (const unsigned short *)op.base;
-        row_stride = op.row_stride; batch_stride = op.batch_stride;
-        rows = op.rows; hw = op.hw; ones_row = op.ones_row; vec = op.vec;
-        row0 = tile_row0; kend = k1;
-        if (vec == 4) { koff = (tid & 7) * 4; r0 = tid >> 3; }
-        else          { koff = tid & 31;      r0 = tid >> 5; }
-        m = k0 + koff;
+        base = (gushort_ptr)op.base;
+        batch_stride = op.batch_stride;
+        hw = op.hw;
+        kq = (tid & 7) * 8; r0 = tid >> 3;
+        dead = 0; ones = 0;
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const int row = tile_row0 + r0 + 32 * s;
+            if (row >= op.rows) dead |= 1u << s;
+            if (row == op.ones_row) ones |= 1u << s;
+            rowoff[s] = (long long)min(row, op.rows - 1) * op.row_stride;
+        }
+        m = n = t = 0;
+        zero_all = false;
+    }
+    __device__ __forceinline__ void seek(int tile_k0)
+    {
+        m = tile_k0 + kq;
         n = m / hw;
         t = m - n * hw;
     }
     __device__ __forceinline__ void advance()
     {
-        m += KT; t += KT;
+        m += KTH; t += KTH;
         while (t >= hw) { t -= hw; ++n; }
     }
-    // Branch-free, as in the fp32 loader.
-    __device__ __forceinline__ void load(unsigned short (&reg)[NREG]) const
+    __device__ __forceinline__ void load_full(ushortx8 (&reg)[SLOTS])
     {
-        const unsigned short one_bits = 0x3F80;  // 1.0 in bf16
         const long long col = (long long)n * batch_stride + t;
-        if (vec == 4) {
 #pragma unroll
-            for (int s = 0; s < BR / 32; ++s) {
-                const int row = row0 + r0 + 32 * s;
-                const bool ok = (row < rows) && (m < kend);
-                const long long off = ok ? (long long)row * row_stride + col : 0;
-                ushortx4 v = *(const ushortx4 *)(base + off);
-                const bool use = ok || row == ones_row;
-                const unsigned short one = (row == ones_row) ? one_bits : (unsigned short)0;
+        for (int s = 0; s < SLOTS; ++s) reg[s] = *(gushort8_ptr)(base + rowoff[s] + col);
+        zero_all = false;
+    }
+    __device__ __forceinline__ void zero_below(int mlo) { zero_all = m < mlo; }
+    __device__ __forceinline__ void load_careful(ushortx8 (&reg)[SLOTS], int kend8)
+    {
+        const long long col = (long long)n * batch_stride + t;
+        const bool in = m < kend8;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const unsigned short x = ok ? v[e] : one;
-                    reg[4 * s + e] = (use && m + e < kend) ? x : (unsigned short)0;
-                }
-            }
-        } else {
+        for (int s = 0; s < SLOTS; ++s) {
+            ushortx8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (in) v = *(gushort8_ptr)(base + rowoff[s] + col);
+            reg[s] = v;
+        }
+        zero_all = !in;
+    }
+    __device__ __forceinline__ void store_lds(const ushortx8 (&reg)[SLOTS], unsigned short *lds) const
+    {
 #pragma unroll
-            for (int s = 0; s < BR / 8; ++s) {
-                const int row = row0 + r0 + 8 * s;
-                const bool ok = (row < rows) && (m < kend);
-                const long long off = ok ? (long long)row * row_stride + col : 0;
-                const unsigned short v = base[off];
-                reg[s] = ok ? v : ((row == ones_row && m < kend) ? one_bits : (unsigned short)0);
-            }
+        for (int s = 0; s < SLOTS; ++s) {
+            ushortx8 v = reg[s];
+            const unsigned short fill = (ones >> s) & 1 ? (unsigned short)0x3F80 : (unsigned short)0;   // 1.0
+            if ((dead >> s) & 1) v = ushortx8{fill, fill, fill, fill, fill, fill, fill, fill};
+            if (zero_all) v = ushortx8{0, 0, 0, 0, 0, 0, 0, 0};
+            *(ushortx8 *)(lds + (r0 + 32 * s) * LDH + kq) = v;
         }
     }
-    __device__ __forceinline__ void store_lds(const unsigned short (&reg)[NREG], unsigned short *lds) const
+    // K % 8 remainder tile (repacked operands only): thread tid < BR fills LDS row tid
+    __device__ __forceinline__ static void fill_remainder(const Operand &op, int tile_row0, int k8, int kend,
+                                                          int tid, unsigned short *lds)
     {
-        if (vec == 4) {
-#pragma unroll
-            for (int s = 0; s < BR / 32; ++s) {
-                ushortx4 v = {reg[4 * s], reg[4 * s + 1], reg[4 * s + 2], reg[4 * s + 3]};
-                *(ushortx4 *)(lds + (r0 + 32 * s) * LDH + koff) = v;
-            }
-        } else {
-#pragma unroll
-            for (int s = 0; s < BR / 8; ++s) lds[(r0 + 8 * s) * LDH + koff] = reg[s];
+        if (tid >= BR) return;
+        const int row = tile_row0 + tid;
+        ushortx8 x = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (row == op.ones_row) {
+            for (int e = 0; e < 7; ++e)
+                if (k8 + e < kend) x[e] = 0x3F80;
+        } else if (row < op.rows) {
+            gushort_ptr p = (gushort_ptr)op.base + (long long)row * op.row_stride + k8;
+            for (int e = 0; e < 7; ++e)
+                if (k8 + e < kend) x[e] = p[e];
         }
+        unsigned short *dst = lds + tid * LDH;
+        *(ushortx8 *)dst = x;
+#pragma unroll
+        for (int q = 1; q < 8; ++q) *(ushortx8 *)(dst + 8 * q) = ushortx8{0, 0, 0, 0, 0, 0, 0, 0};
     }
 };
 
 // ------------------------------------------------------------------ bf16 kernel
+template <int TM, int TN, bool LIVE>
+__device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm, int tn, int tid,
+                                                   LoaderBF16<64 * TM> &la, LoaderBF16<64 * TN> &lb,
+                                                   unsigned short *lds, int k0, int k1, int wave_m, int wave_n,
+                                                   int l32, int half, floatx16 (&acc)[TM][TN])
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int STAGE = (BM + BN) * LDH;
+    const int klen = max(k1 - k0, 0);
+    const int klen8 = klen & ~7;
+    const int nfull = klen8 / KTH;
+    const bool shifted = nfull > 0 && klen8 > nfull * KTH;
+    const bool careful = nfull == 0 && klen8 > 0;
+    const int nvec = nfull + ((shifted || careful) ? 1 : 0);
+    const int nk = nvec + (klen8 < klen ? 1 : 0);
+    ushortx8 ra[BM / 32], rb[BN / 32];
+    la.seek(k0); lb.seek(k0);
+    if (nfull > 0) { la.load_full(ra); lb.load_full(rb); }
+    else if (careful) { la.load_careful(ra, k0 + klen8); lb.load_careful(rb, k0 + klen8); }
+    for (int it = 0; it < nk; ++it) {
+        unsigned short *sa = lds + (it & 1) * STAGE, *sb = sa + BM * LDH;
+        if (it < nvec) {
+            la.store_lds(ra, sa);
+            lb.store_lds(rb, sb);
+        } else {
+            LoaderBF16<BM>::fill_remainder(P.a, tm * BM, k0 + klen8, k1, tid, sa);
+            LoaderBF16<BN>::fill_remainder(P.b, tn * BN, k0 + klen8, k1, tid, sb);
+        }
+        if (it + 1 < nfull) {
+            la.advance(); lb.advance();
+            la.load_full(ra); lb.load_full(rb);
+        } else if (it + 1 < nvec) {
+            la.seek(k0 + klen8 - KTH); lb.seek(k0 + klen8 - KTH);
+            la.load_full(ra); lb.load_full(rb);
+            la.zero_below(k0 + nfull * KTH);
+        }
+        __syncthreads();
+        if constexpr (LIVE) {
+            // v_mfma_f32_32x32x16_bf16: a lane supplies 8 consecutive k of row lane % 32, the two
+            // half-waves supply two different k groups.  Issue u of the 64-wide tile uses
+            // k = 16u + 8*half + 0..7, identically for both operands.
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                ushortx8 fa[TM], fb[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    fa[i] = *(const ushortx8 *)(sa + (wave_m * 32 * TM + i * 32 + l32) * LDH + 16 * u + 8 * half);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    fb[j] = *(const ushortx8 *)(sb + (wave_n * 32 * TN + j * 32 + l32) * LDH + 16 * u + 8 * half);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, fa[i]), __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
+            }
+        }
+    }
+}
+
 template <int TM, int TN>
 __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__restrict__ probs,
                                                            const int *__restrict__ tile_start, int n_probs)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    __shared__ __attribute__((aligned(16))) unsigned short lds_a[BM * LDH];
-    __shared__ __attribute__((aligned(16))) unsigned short lds_b[BN * LDH];
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // operand stages, then the output tile
 
     const int wg = blockIdx.x;
     const int pi = find_problem(tile_start, n_probs, wg);
@@ -523,9 +595,8 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__
 
     LoaderBF16<BM> la;
     LoaderBF16<BN> lb;
-    la.init(P.a, tm * BM, k0, k1, tid);
-    lb.init(P.b, tn * BN, k0, k1, tid);
-    unsigned short ra[BM / 8], rb[BN / 8];
+    la.init(P.a, tm * BM, tid);
+    lb.init(P.b, tn * BN, tid);
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -538,49 +609,13 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__
     const int lane = tid & 63, wid = tid >> 6;
     const int wave_m = wid >> 1, wave_n = wid & 1;
     const int l32 = lane & 31, half = lane >> 5;
-
-    // A wavefront whose whole sub-tile lies outside the matrix, or above the diagonal of a
-    // symmetric product, stores nothing: it only helps with the loads and skips the math.
     const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
     const int wave_r0 = tm * BM + wave_m * 32 * TM, wave_c0 = tn * BN + wave_n * 32 * TN;
-    [[maybe_unused]] const bool live = wave_r0 < P.M && wave_c0 < P.N && !(diag_tile && wave_c0 >= wave_r0 + 32 * TM);
+    const bool live = wave_r0 < P.M && wave_c0 < P.N && !(diag_tile && wave_c0 >= wave_r0 + 32 * TM);
 
-    const int nk = (k1 - k0 + KT - 1) / KT;
-    if (nk > 0) { la.load(ra); lb.load(rb); }
-    for (int it = 0; it < nk; ++it) {
-        __syncthreads();
-        la.store_lds(ra, lds_a);
-        lb.store_lds(rb, lds_b);
-        __syncthreads();
-        if (it + 1 < nk) {
-            la.advance(); lb.advance();
-            la.load(ra); lb.load(rb);
-        }
-        // v_mfma_f32_32x32x16_bf16: a lane supplies 8 consecutive k of row lane%32; the two
-        // half-waves cover k groups {0..7},{8..15}.  Two issues cover the 32-wide tile:
-        // issue u uses k = 16u + 8*half + 0..7, identically for both operands.
-        ushortx8 fa[TM][2], fb[TN][2];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const unsigned short *p = lds_a + (wave_m * 32 * TM + i * 32 + l32) * LDH + half * 8;
-            fa[i][0] = *(const ushortx8 *)(p);
-            fa[i][1] = *(const ushortx8 *)(p + 16);
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const unsigned short *p = lds_b + (wave_n * 32 * TN + j * 32 + l32) * LDH + half * 8;
-            fb[j][0] = *(const ushortx8 *)(p);
-            fb[j][1] = *(const ushortx8 *)(p + 16);
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8, fa[i][u]), __builtin_bit_cast(bf16x8, fb[j][u]), acc[i][j], 0, 0, 0);
-    }
+    unsigned short *lds16 = (unsigned short *)lds;
+    if (live) gemm_bf16_mainloop<TM, TN, true>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc);
+    else      gemm_bf16_mainloop<TM, TN, false>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc);
 
     if (P.splits > 1) {
         float *part = P.partial + ((long long)tile * P.splits + split) * (BM * BN);
@@ -595,16 +630,21 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__
                     part[r * BN + c] = acc[i][j][v];
                 }
     } else {
+        __syncthreads();
+        if (live) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int r = tm * BM + wave_m * 32 * TM + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                    const int c = tn * BN + wave_n * 32 * TN + j * 32 + l32;
-                    store_result(P, diag_tile, r, c, acc[i][j][v]);
-                }
+                    for (int v = 0; v < 16; ++v) {
+                        const int r = wave_m * 32 * TM + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                        const int c = wave_n * 32 * TN + j * 32 + l32;
+                        lds[r * (BN + 1) + c] = acc[i][j][v];
+                    }
+        }
+        __syncthreads();
+        store_slab<BM, BN>(P, lds, tm * BM, tn * BN, diag_tile, tid);
     }
 }
 
@@ -650,19 +690,30 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmProblem *__r
     else          reduce_slab<64>(P, tile, slab, tm, tn, T);
 }
 
+// LDS per workgroup: two operand stages, reused for the (BM x BN+1) fp32 output tile.
 template <int TM, int TN>
-static hipError_t launch_f32(const GemmProblem *probs_dev, const int *tile_start_dev, int n_probs, int total_wgs,
+constexpr size_t gemm_lds_bytes()
+{
+    const size_t stages = 2 * (64 * TM + 64 * TN) * LDF * sizeof(float);   // same size for LDH bf16 rows
+    const size_t tile = (size_t)(64 * TM) * (64 * TN + 1) * sizeof(float);
+    return stages > tile ? stages : tile;
+}
+
+template <int TM, int TN, int DT>
+static hipError_t launch_one(const GemmProblem *probs_dev, const int *tile_start_dev, int n_probs, int total_wgs,
                              hipStream_t s)
 {
-    constexpr size_t lds_bytes = 2 * (64 * TM + 64 * TN) * LDF * sizeof(float);
+    static_assert(2 * LDH == 4 * LDF, "bf16 and fp32 stages have the same size");
+    constexpr size_t lds_bytes = gemm_lds_bytes<TM, TN>();
+    auto kernel = DT == 0 ? gemm_nt_f32_kernel<TM, TN> : gemm_nt_bf16_kernel<TM, TN>;
     static bool configured = false;   // the attribute is per function, set once per process
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_f32_kernel<TM, TN>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds_bytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    gemm_nt_f32_kernel<TM, TN><<<dim3(total_wgs), dim3(256), lds_bytes, s>>>(probs_dev, tile_start_dev, n_probs);
+    kernel<<<dim3(total_wgs), dim3(256), lds_bytes, s>>>(probs_dev, tile_start_dev, n_probs);
     return hipGetLastError();
 }
 
@@ -670,14 +721,12 @@ hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, 
                        int total_wgs, int tile_cfg, int dtype, hipStream_t s)
 {
     if (total_wgs <= 0) return hipSuccess;
-    dim3 grid(total_wgs), block(256);
     if (dtype == 0) {
-        if (tile_cfg == 0) return launch_f32<2, 2>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
-        return launch_f32<1, 1>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
+        if (tile_cfg == 0) return launch_one<2, 2, 0>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
+        return launch_one<1, 1, 0>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
     }
-    if (tile_cfg == 0) gemm_nt_bf16_kernel<2, 2><<<grid, block, 0, s>>>(probs_dev, tile_start_dev, n_probs);
-    else               gemm_nt_bf16_kernel<1, 1><<<grid, block, 0, s>>>(probs_dev, tile_start_dev, n_probs);
-    return hipGetLastError();
+    if (tile_cfg == 0) return launch_one<2, 2, 1>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
+    return launch_one<1, 1, 1>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
 }
 
 hipError_t launch_gemm_reduce(const GemmProblem *probs_dev, const int *red_start_dev, int n_probs,

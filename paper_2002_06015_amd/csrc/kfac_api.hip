@@ -283,7 +283,6 @@ Operand plain_operand(const float *base, long long ld, int rows, int K)
     o.rows = rows;
     o.hw = std::max(K, 1) + 64;   // one run covers the whole contraction
     o.ones_row = -1;
-    o.vec = 4;   // unused by the fp32 kernel (any leading dimension works)
     return o;
 }
 
@@ -324,19 +323,20 @@ PatchJob make_patch_job(const void *src, void *dst, long long ld, int N, int c, 
 void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &a, bool dry)
 {
     const int esize = a.in == KFAC_BF16 ? 2 : 4;
-    const size_t chunk_align = a.in == KFAC_BF16 ? 8 : 4;   // alignment of a 4-element chunk
+    // a thread loads 16-byte chunks: 4 fp32 (element alignment is enough) or 8 bf16 (16-byte aligned)
+    const int chunk = a.in == KFAC_BF16 ? 8 : 4;
+    const size_t chunk_align = a.in == KFAC_BF16 ? 16 : 4;
     std::vector<PatchJob> pjobs;
     std::vector<GemmProblem> probs;
     int patch_wgs = 0;
     double patch_bytes = 0;
-    // An NCHW tensor [N, c, hw] is contracted in place when its runs are whole 4-element
-    // chunks; otherwise (and for every k > 1 / strided / padded layer) it is first rewritten
+    // An NCHW tensor [N, c, hw] is contracted in place when its runs are whole chunks; otherwise (and for every k > 1 / strided / padded layer) it is first rewritten
     // as [c k^2][ld] with the contraction index contiguous.
     auto operand_for = [&](const void *src, int N, int c, int k, int stride, int pad, int h_in, int w_in, int h,
                            int w) {
         const int hw = h * w, K = N * hw, d0 = c * k * k;
         Operand op{};
-        const bool direct = (k == 1 && stride == 1 && pad == 0 && hw % 4 == 0 &&
+        const bool direct = (k == 1 && stride == 1 && pad == 0 && hw % chunk == 0 &&
                              (dry || ((uintptr_t)src % chunk_align) == 0));
         if (direct) {
             op.base = src;
@@ -358,7 +358,6 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             op.rows = d0;
             op.hw = K + 64;
         }
-        op.vec = 4;
         op.ones_row = -1;
         return op;
     };

@@ -15,6 +15,9 @@ namespace kfac {
 // rows*hw, row_stride = hw) and a plain row-major matrix is the case hw >= K.
 // Row `ones_row` (if >= 0) is virtual: it reads as 1 for every m < K (the bias row of
 // the patch matrix).  Rows >= rows (other than ones_row) read as 0.
+// A thread loads 16-byte chunks along m: fp32 operands need hw % 4 == 0 (or a plain
+// matrix, any leading dimension); bf16 operands need hw % 8 == 0 or a plain matrix, and
+// base, row_stride and batch_stride that keep every chunk 16-byte aligned.
 struct Operand {
     const void *base;
     long long row_stride;
@@ -22,8 +25,6 @@ struct Operand {
     int rows;
     int hw;
     int ones_row;
-    int vec;  // bf16 kernel only: 4 = chunks of 4 are 8-byte aligned and share a run, else 1
-              // (fp32 operands always satisfy hw % 4 == 0 or are plain matrices)
 };
 
 enum : int { GEMM_SYM = 1 };
