@@ -136,6 +136,24 @@ __device__ __forceinline__ void store_slab(const GemmProblem &P, const float *T,
     }
 }
 
+// Border of a GEMM_BORDER problem: entry `row` of the extra row / column from the row sum
+// of the operand, and the corner from the contraction length.
+__device__ __forceinline__ void store_border(const GemmProblem &P, int row, float sum)
+{
+    float *pr = P.C + (long long)P.M * P.ldc + row;
+    float v = P.alpha * sum;
+    if (P.beta != 0.0f) v = fmaf(P.beta, *pr, v);
+    *pr = v;
+    P.C[(long long)row * P.ldc + P.M] = v;
+}
+__device__ __forceinline__ void store_corner(const GemmProblem &P)
+{
+    float *pc = P.C + (long long)P.M * P.ldc + P.M;
+    float v = P.alpha * (float)P.K;
+    if (P.beta != 0.0f) v = fmaf(P.beta, *pc, v);
+    *pc = v;
+}
+
 // ------------------------------------------------------------------ operand loader (fp32)
 // A thread owns one 4-wide k chunk (kq = 4 * (tid % 8)) of the rows r0 + 32*s (r0 = tid / 8)
 // of the operand tile.  A chunk is one 16-byte load that only needs 4-byte alignment (any
@@ -143,8 +161,7 @@ __device__ __forceinline__ void store_slab(const GemmProblem &P, const float *T,
 // in memory (hw % 4 == 0 for NCHW operands).  Every load of the main loop has an
 // unconditionally valid address and is masked by value afterwards, so the loads of a whole
 // tile are issued back to back:
-//   - rows outside the operand are clamped to its last row and replaced by 0 (or by 1 for
-//     the virtual all-ones row);
+//   - rows outside the operand are clamped to its last row and replaced by 0;
 //   - the contraction range of a workgroup is cut into full 32-wide tiles; a remaining
 //     multiple of 4 is covered by one more full tile shifted back to end at the range end,
 //     whose already-counted k positions are zeroed in ONE operand;
@@ -160,7 +177,6 @@ struct LoaderF32 {
     gfloat_ptr base;
     long long rowoff[SLOTS];   // clamped row * row_stride (loop invariant)
     unsigned dead;             // bit s: slot row is outside the operand
-    unsigned ones;             // bit s: slot row is the virtual all-ones row
     long long batch_stride;
     int hw, kq, r0, m, n, t;
     bool zero_all;             // the tile held in registers is to be stored as zeros
@@ -171,12 +187,11 @@ struct LoaderF32 {
         batch_stride = op.batch_stride;
         hw = op.hw;
         kq = (tid & 7) * 4; r0 = tid >> 3;
-        dead = 0; ones = 0;
+        dead = 0;
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const int row = tile_row0 + r0 + 32 * s;
             if (row >= op.rows) dead |= 1u << s;
-            if (row == op.ones_row) ones |= 1u << s;
             rowoff[s] = (long long)min(row, op.rows - 1) * op.row_stride;
         }
         m = n = t = 0;
@@ -217,29 +232,27 @@ struct LoaderF32 {
         }
         zero_all = !in;
     }
-    __device__ __forceinline__ void store_lds(const floatx4 (&reg)[SLOTS], float *lds) const
+    // RS: also add what is stored to the running row sums rs[s] of the rows r0 + 32*s
+    template <bool RS>
+    __device__ __forceinline__ void store_lds(const floatx4 (&reg)[SLOTS], float *lds, float (&rs)[SLOTS]) const
     {
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             floatx4 v = reg[s];
-            const float fill = (ones >> s) & 1 ? 1.f : 0.f;
-            if ((dead >> s) & 1) { v[0] = fill; v[1] = fill; v[2] = fill; v[3] = fill; }
-            if (zero_all) { v[0] = 0.f; v[1] = 0.f; v[2] = 0.f; v[3] = 0.f; }
+            if (((dead >> s) & 1) || zero_all) { v[0] = 0.f; v[1] = 0.f; v[2] = 0.f; v[3] = 0.f; }
+            if constexpr (RS) rs[s] += (v[0] + v[1]) + (v[2] + v[3]);
             *(floatx4 *)(lds + (r0 + 32 * s) * LDF + kq) = v;
         }
     }
     // K % 4 remainder tile (plain matrices only: hw > K): thread tid < BR fills LDS row tid
-    // with the elements k4 .. kend-1 of its operand row followed by zeros
-    __device__ __forceinline__ static void fill_remainder(const Operand &op, int tile_row0, int k4, int kend,
-                                                          int tid, float *lds)
+    // with the elements k4 .. kend-1 of its operand row followed by zeros; returns their sum
+    __device__ __forceinline__ static float fill_remainder(const Operand &op, int tile_row0, int k4, int kend,
+                                                           int tid, float *lds)
     {
-        if (tid >= BR) return;
+        if (tid >= BR) return 0.f;
         const int row = tile_row0 + tid;
         floatx4 x = {0.f, 0.f, 0.f, 0.f};
-        if (row == op.ones_row) {
-            for (int e = 0; e < 3; ++e)
-                if (k4 + e < kend) x[e] = 1.f;
-        } else if (row < op.rows) {
+        if (row < op.rows) {
             gfloat_ptr p = (gfloat_ptr)op.base + (long long)row * op.row_stride + k4;
             for (int e = 0; e < 3; ++e)
                 if (k4 + e < kend) x[e] = p[e];
@@ -248,19 +261,53 @@ struct LoaderF32 {
         *(floatx4 *)dst = x;
 #pragma unroll
         for (int q = 1; q < 8; ++q) *(floatx4 *)(dst + 4 * q) = floatx4{0.f, 0.f, 0.f, 0.f};
+        return x[0] + x[1] + x[2];
     }
 };
+
+// Finishes the border row sums of a diagonal tile: adds up the 8 lanes that share a row,
+// then either stores the border entries (splits == 1) or this split's partial sums.
+// Uses the first BM floats of LDS; all 256 threads call it, between barriers of its own.
+template <int BM>
+__device__ __forceinline__ void finish_row_sums(const GemmProblem &P, float *lds, int tm, int tile, int split,
+                                                int tid, float (&rs)[BM / 32], float rs_rem)
+{
+#pragma unroll
+    for (int s = 0; s < BM / 32; ++s) {
+        float v = rs[s];
+        v += __shfl_xor(v, 1);
+        v += __shfl_xor(v, 2);
+        v += __shfl_xor(v, 4);
+        rs[s] = v;
+    }
+    __syncthreads();   // the operand stages are dead
+    if ((tid & 7) == 0) {
+#pragma unroll
+        for (int s = 0; s < BM / 32; ++s) lds[(tid >> 3) + 32 * s] = rs[s];
+    }
+    __syncthreads();
+    if (tid < BM) {
+        const float total = lds[tid] + rs_rem;
+        const int row = tm * BM + tid;
+        if (P.splits > 1) P.partial_rs[((long long)tm * P.splits + split) * BM + tid] = total;
+        else if (row < P.M) store_border(P, row, total);
+    }
+    if (tile == 0 && tid == 0 && P.splits == 1) store_corner(P);
+    __syncthreads();
+}
 
 // ------------------------------------------------------------------ fp32 kernel
 // Two LDS stages: iteration `it` stores the tile it already holds in registers into stage
 // it & 1, issues the global loads of tile it + 1, then (one barrier) multiplies out of stage
 // it & 1.  The stage written in iteration it + 1 was last read before the barrier of
 // iteration it + 1, which every wavefront reaches only after finishing that read.
-template <int TM, int TN, bool LIVE>
+// RS: the row sums of the a-operand tile are accumulated on the side (rs: rows r0 + 32*s of
+// the vector-loaded part, rs_rem: row tid of the K % 4 remainder).
+template <int TM, int TN, bool LIVE, bool RS>
 __device__ __forceinline__ void gemm_f32_mainloop(const GemmProblem &P, int tm, int tn, int tid,
                                                   LoaderF32<64 * TM> &la, LoaderF32<64 * TN> &lb, float *lds,
                                                   int k0, int k1, int wave_m, int wave_n, int l32, int half,
-                                                  floatx16 (&acc)[TM][TN])
+                                                  floatx16 (&acc)[TM][TN], float (&rs)[2 * TM], float &rs_rem)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     constexpr int STAGE = (BM + BN) * LDF;
@@ -280,10 +327,11 @@ __device__ __forceinline__ void gemm_f32_mainloop(const GemmProblem &P, int tm, 
     for (int it = 0; it < nk; ++it) {
         float *sa = lds + (it & 1) * STAGE, *sb = sa + BM * LDF;
         if (it < nvec) {
-            la.store_lds(ra, sa);
-            lb.store_lds(rb, sb);
+            float unused[BN / 32];
+            la.template store_lds<RS>(ra, sa, rs);
+            lb.template store_lds<false>(rb, sb, unused);
         } else {
-            LoaderF32<BM>::fill_remainder(P.a, tm * BM, k0 + klen4, k1, tid, sa);
+            rs_rem = LoaderF32<BM>::fill_remainder(P.a, tm * BM, k0 + klen4, k1, tid, sa);
             LoaderF32<BN>::fill_remainder(P.b, tn * BN, k0 + klen4, k1, tid, sb);
         }
         if (it + 1 < nfull) {
@@ -371,8 +419,19 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__r
     const int wave_r0 = tm * BM + wave_m * 32 * TM, wave_c0 = tn * BN + wave_n * 32 * TN;
     const bool live = wave_r0 < P.M && wave_c0 < P.N && !(diag_tile && wave_c0 >= wave_r0 + 32 * TM);
 
-    if (live) gemm_f32_mainloop<TM, TN, true>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc);
-    else      gemm_f32_mainloop<TM, TN, false>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc);
+    // The diagonal tiles of a bordered problem also take the row sums of their operand rows.
+    const bool border = diag_tile && (P.flags & GEMM_BORDER);
+    float rs[BM / 32], rs_rem = 0.f;
+#pragma unroll
+    for (int s = 0; s < BM / 32; ++s) rs[s] = 0.f;
+    if (border) {
+        if (live) gemm_f32_mainloop<TM, TN, true, true>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        else      gemm_f32_mainloop<TM, TN, false, true>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        finish_row_sums<BM>(P, lds, tm, tile, split, tid, rs, rs_rem);
+    } else {
+        if (live) gemm_f32_mainloop<TM, TN, true, false>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        else      gemm_f32_mainloop<TM, TN, false, false>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+    }
 
     // accumulator layout of the 32x32 block: column = lane % 32,
     // row = 8 * (v / 4) + 4 * (lane / 32) + v % 4 for register v = 0..15
@@ -423,7 +482,7 @@ struct LoaderBF16 {
     static constexpr int SLOTS = BR / 32;
     gushort_ptr base;
     long long rowoff[SLOTS];
-    unsigned dead, ones;
+    unsigned dead;
     long long batch_stride;
     int hw, kq, r0, m, n, t;
     bool zero_all;
@@ -434,12 +493,11 @@ struct LoaderBF16 {
         batch_stride = op.batch_stride;
         hw = op.hw;
         kq = (tid & 7) * 8; r0 = tid >> 3;
-        dead = 0; ones = 0;
+        dead = 0;
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const int row = tile_row0 + r0 + 32 * s;
             if (row >= op.rows) dead |= 1u << s;
-            if (row == op.ones_row) ones |= 1u << s;
             rowoff[s] = (long long)min(row, op.rows - 1) * op.row_stride;
         }
         m = n = t = 0;
@@ -476,28 +534,28 @@ struct LoaderBF16 {
         }
         zero_all = !in;
     }
-    __device__ __forceinline__ void store_lds(const ushortx8 (&reg)[SLOTS], unsigned short *lds) const
+    static __device__ __forceinline__ float widen(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
+    template <bool RS>
+    __device__ __forceinline__ void store_lds(const ushortx8 (&reg)[SLOTS], unsigned short *lds, float (&rs)[SLOTS]) const
     {
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             ushortx8 v = reg[s];
-            const unsigned short fill = (ones >> s) & 1 ? (unsigned short)0x3F80 : (unsigned short)0;   // 1.0
-            if ((dead >> s) & 1) v = ushortx8{fill, fill, fill, fill, fill, fill, fill, fill};
-            if (zero_all) v = ushortx8{0, 0, 0, 0, 0, 0, 0, 0};
+            if (((dead >> s) & 1) || zero_all) v = ushortx8{0, 0, 0, 0, 0, 0, 0, 0};
+            if constexpr (RS)
+                rs[s] += ((widen(v[0]) + widen(v[1])) + (widen(v[2]) + widen(v[3]))) +
+                         ((widen(v[4]) + widen(v[5])) + (widen(v[6]) + widen(v[7])));
             *(ushortx8 *)(lds + (r0 + 32 * s) * LDH + kq) = v;
         }
     }
     // K % 8 remainder tile (repacked operands only): thread tid < BR fills LDS row tid
-    __device__ __forceinline__ static void fill_remainder(const Operand &op, int tile_row0, int k8, int kend,
-                                                          int tid, unsigned short *lds)
+    __device__ __forceinline__ static float fill_remainder(const Operand &op, int tile_row0, int k8, int kend,
+                                                           int tid, unsigned short *lds)
     {
-        if (tid >= BR) return;
+        if (tid >= BR) return 0.f;
         const int row = tile_row0 + tid;
         ushortx8 x = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (row == op.ones_row) {
-            for (int e = 0; e < 7; ++e)
-                if (k8 + e < kend) x[e] = 0x3F80;
-        } else if (row < op.rows) {
+        if (row < op.rows) {
             gushort_ptr p = (gushort_ptr)op.base + (long long)row * op.row_stride + k8;
             for (int e = 0; e < 7; ++e)
                 if (k8 + e < kend) x[e] = p[e];
@@ -506,15 +564,19 @@ struct LoaderBF16 {
         *(ushortx8 *)dst = x;
 #pragma unroll
         for (int q = 1; q < 8; ++q) *(ushortx8 *)(dst + 8 * q) = ushortx8{0, 0, 0, 0, 0, 0, 0, 0};
+        float sum = 0.f;
+        for (int e = 0; e < 7; ++e) sum += widen(x[e]);
+        return sum;
     }
 };
 
 // ------------------------------------------------------------------ bf16 kernel
-template <int TM, int TN, bool LIVE>
+template <int TM, int TN, bool LIVE, bool RS>
 __device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm, int tn, int tid,
                                                    LoaderBF16<64 * TM> &la, LoaderBF16<64 * TN> &lb,
                                                    unsigned short *lds, int k0, int k1, int wave_m, int wave_n,
-                                                   int l32, int half, floatx16 (&acc)[TM][TN])
+                                                   int l32, int half, floatx16 (&acc)[TM][TN], float (&rs)[2 * TM],
+                                                   float &rs_rem)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     constexpr int STAGE = (BM + BN) * LDH;
@@ -532,10 +594,11 @@ __device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm,
     for (int it = 0; it < nk; ++it) {
         unsigned short *sa = lds + (it & 1) * STAGE, *sb = sa + BM * LDH;
         if (it < nvec) {
-            la.store_lds(ra, sa);
-            lb.store_lds(rb, sb);
+            float unused[BN / 32];
+            la.template store_lds<RS>(ra, sa, rs);
+            lb.template store_lds<false>(rb, sb, unused);
         } else {
-            LoaderBF16<BM>::fill_remainder(P.a, tm * BM, k0 + klen8, k1, tid, sa);
+            rs_rem = LoaderBF16<BM>::fill_remainder(P.a, tm * BM, k0 + klen8, k1, tid, sa);
             LoaderBF16<BN>::fill_remainder(P.b, tn * BN, k0 + klen8, k1, tid, sb);
         }
         if (it + 1 < nfull) {
@@ -614,8 +677,18 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__
     const bool live = wave_r0 < P.M && wave_c0 < P.N && !(diag_tile && wave_c0 >= wave_r0 + 32 * TM);
 
     unsigned short *lds16 = (unsigned short *)lds;
-    if (live) gemm_bf16_mainloop<TM, TN, true>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc);
-    else      gemm_bf16_mainloop<TM, TN, false>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc);
+    const bool border = diag_tile && (P.flags & GEMM_BORDER);
+    float rs[BM / 32], rs_rem = 0.f;
+#pragma unroll
+    for (int s = 0; s < BM / 32; ++s) rs[s] = 0.f;
+    if (border) {
+        if (live) gemm_bf16_mainloop<TM, TN, true, true>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        else      gemm_bf16_mainloop<TM, TN, false, true>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        finish_row_sums<BM>(P, lds, tm, tile, split, tid, rs, rs_rem);
+    } else {
+        if (live) gemm_bf16_mainloop<TM, TN, true, false>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        else      gemm_bf16_mainloop<TM, TN, false, false>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+    }
 
     if (P.splits > 1) {
         float *part = P.partial + ((long long)tile * P.splits + split) * (BM * BN);
@@ -667,6 +740,16 @@ __device__ __forceinline__ void reduce_slab(const GemmProblem &P, int tile, int 
     }
     __syncthreads();
     store_slab<32, B>(P, T, tm * B + slab * 32, tn * B, diag_tile, threadIdx.x);
+    if (diag_tile && (P.flags & GEMM_BORDER)) {
+        const int row = tm * B + slab * 32 + threadIdx.x;
+        if (threadIdx.x < 32 && row < P.M) {
+            const float *prs = P.partial_rs + (long long)tm * P.splits * B + slab * 32 + threadIdx.x;
+            float sum = 0.f;
+            for (int q = 0; q < P.splits; ++q) sum += prs[(long long)q * B];
+            store_border(P, row, sum);
+        }
+        if (tile == 0 && slab == 0 && threadIdx.x == 0) store_corner(P);
+    }
 }
 
 __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmProblem *__restrict__ probs,

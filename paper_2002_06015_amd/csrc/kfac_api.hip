@@ -27,6 +27,9 @@ struct Tunables {
     int max_k_per_wg;    // and never leaves a workgroup a longer contraction than this
     int inv_streams;     // independent inversion chains run on this many streams (1..4)
     int rec_leaf;        // the blocked inversion recurses down to blocks of at most this size
+    int slots;           // staging slots in use (2..kSlots): a call waits until the device has started the
+                         // call `slots` calls back.  Measured: letting the host run further ahead than a
+                         // couple of calls makes the chains of small launches slower, not faster.
     Tunables()
     {
         const char *e = getenv("KFAC_TARGET_WGS");
@@ -36,9 +39,11 @@ struct Tunables {
         e = getenv("KFAC_MAX_K_PER_WG");
         max_k_per_wg = e ? std::max(32, atoi(e) / 32 * 32) : 4096;
         e = getenv("KFAC_INV_STREAMS");
-        inv_streams = e ? std::min(4, std::max(1, atoi(e))) : 1;
+        inv_streams = e ? std::min(4, std::max(1, atoi(e))) : 4;
         e = getenv("KFAC_REC_LEAF");
         rec_leaf = e ? std::min(kLeafMax, std::max(32, atoi(e))) : 160;
+        e = getenv("KFAC_STAGING_SLOTS");
+        slots = e ? std::min(kSlots, std::max(2, atoi(e))) : 2;
     }
 };
 
@@ -175,6 +180,7 @@ void finish_problem(GemmProblem &P)
     P.splits = 1;
     P.k_per_split = std::max(32, (P.K + 31) / 32 * 32);
     P.partial = nullptr;
+    P.partial_rs = nullptr;
 }
 
 // Emits the launches of one phase: per tile configuration one GEMM launch, plus one
@@ -236,6 +242,8 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
                         P.splits = splits;
                         P.k_per_split = kps;
                         P.partial = (float *)arena.take((size_t)P.n_tiles * splits * B * B * sizeof(float));
+                        if (P.flags & GEMM_BORDER)
+                            P.partial_rs = (float *)arena.take((size_t)P.tiles_m * splits * B * sizeof(float));
                     }
                 }
             }
@@ -254,7 +262,12 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
         Launch L{};
         L.kind = L_GEMM;
         for (auto &P : sel)
-            L.flops += (P.flags & GEMM_SYM) ? (double)P.K * P.M * (P.M + 1.0) : 2.0 * P.M * (double)P.N * P.K;
+            if (P.flags & GEMM_SYM) {
+                const double d = P.M + ((P.flags & GEMM_BORDER) ? 1.0 : 0.0);
+                L.flops += (double)P.K * d * (d + 1.0);
+            } else {
+                L.flops += 2.0 * P.M * (double)P.N * P.K;
+            }
         L.off_a = plan.tab.add(sel.data(), sel.size() * sizeof(GemmProblem));
         L.off_b = plan.tab.add(start.data(), start.size() * sizeof(int));
         L.n = (int)sel.size();
@@ -282,7 +295,6 @@ Operand plain_operand(const float *base, long long ld, int rows, int K)
     o.batch_stride = 0;
     o.rows = rows;
     o.hw = std::max(K, 1) + 64;   // one run covers the whole contraction
-    o.ones_row = -1;
     return o;
 }
 
@@ -358,7 +370,6 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             op.rows = d0;
             op.hw = K + 64;
         }
-        op.ones_row = -1;
         return op;
     };
     for (int l = 0; l < a.n_layers; ++l) {
@@ -372,15 +383,16 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         if (want_A) {
             Operand op = operand_for(dry ? nullptr : a.act[l], Ly.N, Ly.c_in, Ly.k, Ly.stride, Ly.pad, Ly.h_in,
                                      Ly.w_in, h, w);
-            op.ones_row = Ly.bias ? op.rows : -1;
+            // the bias row of the patch matrix is not multiplied out: the border of A comes
+            // from row sums (GEMM_BORDER), which keeps c_in k^2 a whole number of tiles
             GemmProblem P{};
             P.a = op; P.b = op;
             P.C = dry ? nullptr : a.A_ema[l];
             P.Ct = nullptr;
             P.ldc = dA; P.ldct = 0;
-            P.M = dA; P.N = dA; P.K = K;
-            P.flags = GEMM_SYM;
-            P.tile_cfg = choose_tile_cfg(dA, dA, K, true);
+            P.M = op.rows; P.N = op.rows; P.K = K;
+            P.flags = GEMM_SYM | (Ly.bias ? GEMM_BORDER : 0);
+            P.tile_cfg = choose_tile_cfg(P.M, P.N, K, true);
             P.alpha = (float)((1.0 - (double)a.decay) / ((double)Ly.N * (double)hw));
             P.beta = a.decay;
             finish_problem(P);
@@ -744,7 +756,7 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
     hipStream_t s = ctx->stream;
     if (tab_bytes) {
         const int slot = ctx->next_slot;
-        ctx->next_slot = (ctx->next_slot + 1) % kSlots;
+        ctx->next_slot = (ctx->next_slot + 1) % ctx->tun.slots;
         kfac_status st = ensure_slot(ctx, slot, tab_bytes);
         if (st != KFAC_OK) return st;
         memcpy(ctx->pinned[slot], plan.tab.buf.data(), tab_bytes);

@@ -13,8 +13,7 @@ namespace kfac {
 //     base + (m / hw) * batch_stride + r * row_stride + (m % hw)
 // so an NCHW tensor [N, rows, hw] is contracted in place over (n, t) (batch_stride =
 // rows*hw, row_stride = hw) and a plain row-major matrix is the case hw >= K.
-// Row `ones_row` (if >= 0) is virtual: it reads as 1 for every m < K (the bias row of
-// the patch matrix).  Rows >= rows (other than ones_row) read as 0.
+// Rows >= rows read as 0.
 // A thread loads 16-byte chunks along m: fp32 operands need hw % 4 == 0 (or a plain
 // matrix, any leading dimension); bf16 operands need hw % 8 == 0 or a plain matrix, and
 // base, row_stride and batch_stride that keep every chunk 16-byte aligned.
@@ -24,21 +23,27 @@ struct Operand {
     long long batch_stride;
     int rows;
     int hw;
-    int ones_row;
 };
 
-enum : int { GEMM_SYM = 1 };
+// GEMM_SYM:    M == N and a == b; only tiles tm >= tn are computed and mirrored.
+// GEMM_BORDER: (with GEMM_SYM) C is (M+1) x (M+1): the product of the operand extended by
+//              an all-ones row (the bias row of the patch matrix, Sec. 3.3).  The border is
+//              not multiplied out: C[i][M] = C[M][i] = alpha * sum_m a(i, m) + beta * old
+//              comes from row sums taken while the diagonal tiles stage their operand,
+//              and C[M][M] = alpha * K + beta * old.
+enum : int { GEMM_SYM = 1, GEMM_BORDER = 2 };
 
 struct GemmProblem {
     Operand a, b;
     float *C;        // [M, N], leading dimension ldc (may be null if only Ct is wanted)
     float *Ct;       // optional transposed copy Ct[j][i], leading dimension ldct (or null)
     float *partial;  // split-K scratch: [tiles][splits][BM*BN] (null if splits == 1)
+    float *partial_rs;  // split-K scratch of the border row sums: [tiles_m][splits][BM] (GEMM_BORDER, splits > 1)
     long long ldc, ldct;
     int M, N, K;
     int tiles_m, tiles_n, n_tiles;
     int splits, k_per_split;  // k_per_split is a multiple of 32
-    int flags;                // GEMM_SYM: M == N, only tiles tm >= tn are computed and mirrored
+    int flags;
     int tile_cfg;             // 0: 128x128 tiles, 1: 64x64 tiles
     float alpha, beta;        // C = alpha * acc + beta * C   (beta == 0: C is not read)
 };
