@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32", help="type of activations / output gradients")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=2)
+    ap.add_argument("--schedule", choices=["fused", "staged"], default="fused",
+                    help="fused: one kfac_step call per step (factors, inverses and preconditioning planned as one "
+                         "graph); staged: kfac_stats, kfac_invert, kfac_precondition one after the other")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are built); use --gpus 1", file=sys.stderr)
@@ -108,9 +111,16 @@ def main():
             kfac.bn_unitwise_precondition(ctx, N, Cs, bn_gg, bn_gb, decay, wl.BN_LAMBDA, F, og, ob)
 
     def step(decay, idx):
-        stats(decay)
-        invert(idx)
-        precond()
+        if args.schedule == "fused":
+            mask = [False] * n
+            for i in idx:
+                mask[i] = True
+            kfac.kfac_step(ctx, layers, in_dtype, acts, grads, decay, spatial_mean, A, G, mask, wl.GAMMA, Ai, Gi,
+                           None, info, gws, U)
+        else:
+            stats(decay)
+            invert(idx)
+            precond()
         bn(decay)
 
     # step 0 initialises every running average and every inverse (untimed)
@@ -134,8 +144,11 @@ def main():
     assert all(bool(torch.isfinite(u).all().item()) for u in U)
 
     # ---------------------------------------------------------------- per-stage and per-kernel times
+    # (the stages one after the other, whatever the schedule of the timed region: with the fused
+    # schedule they overlap and have no separate durations)
     stage_ms = {"stats": 0.0, "invert": 0.0, "precondition": 0.0, "bn": 0.0}
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+    args.profile_steps = max(1, args.profile_steps)
     for _ in range(args.profile_steps):
         ev[0].record(); stats(wl.DECAY)
         ev[1].record(); invert(subset)
@@ -237,12 +250,13 @@ def main():
             4: "full ResNet-50 layer set (53 conv + 1 FC + 53 BatchNorm), batch 32",
             5: "full ResNet-50 layer set, batch 128, inverses refreshed for a seeded 25% subset"}[cfg]),
             "layers": n, "bn_layers": len(Cs), "batch": N, "inverted_layers": len(subset),
-            "g_spatial_mean": bool(spatial_mean)},
+            "g_spatial_mean": bool(spatial_mean), "schedule": args.schedule},
         "algorithmic_gflop": {k: round(v / 1e9, 2) for k, v in fl.items()},
         "step_tflops": round(total_flops / (ms_per_step * 1e-3) / 1e12, 3),
         "factor_inverse_tflops": round(fi_flops / (fi_ms * 1e-3) / 1e12, 3),
         "factor_inverse_frac_of_mfma_peak": round(fi_flops / (fi_ms * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype if args.dtype == "f32" else "f32"], 4),
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "stage_ms_note": "stages run one after the other (separate calls); the fused schedule overlaps them",
         "kernels": {k: {"launches": v["launches"], "ms": round(v["ms"], 4),
                         "tflops": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 3) if v["flops"] else None,
                         "gbs": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["bytes"] else None}

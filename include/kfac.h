@@ -140,6 +140,31 @@ kfac_status kfac_precondition(kfac_ctx *ctx, int32_t n_layers, const kfac_layer 
                               const float *const *grad_W, float *const *out);
 
 /*
+ * One whole step for a layer list (Algorithm 1, one iteration on one GPU): exactly
+ *   kfac_stats(all layers) -> kfac_invert(layers with invert_mask[l] != 0)
+ *   -> kfac_precondition(all layers, with the inverses then stored in A_inv / G_inv)
+ * with the same arguments and the same results up to the rounding order of the
+ * contractions, but planned as one dependency graph: the factors of the layers
+ * with the largest matrices are built first and their inversions (long chains of
+ * small launches) run on internal streams underneath the remaining factor
+ * contractions.  Use it when nothing else has to happen between the three stages
+ * (a multi-GPU caller that reduces the factors between stages uses the separate
+ * calls).  invert_mask: host uint8 [n_layers] or NULL (invert every layer); layers
+ * not inverted keep the inverses their buffers hold (stale statistics, Sec. 4.3).
+ * pi_out: dev [n_layers] or NULL, info: dev int32 [2*n_layers] or NULL, both
+ * indexed by position in the layer list; entries of layers not inverted: pi_out
+ * untouched, info 0.  No argument may be NULL otherwise.  On return every stream
+ * the call used internally has been joined into the context's stream.
+ */
+kfac_status kfac_step(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
+                      const void *const *act, const void *const *grad_out,
+                      float decay, int32_t g_spatial_mean,
+                      float *const *A_ema, float *const *G_ema,
+                      const uint8_t *invert_mask, float gamma,
+                      float *const *A_inv, float *const *G_inv, float *pi_out, int32_t *info,
+                      const float *const *grad_W, float *const *out);
+
+/*
  * Unit-wise natural gradient for BatchNorm, Sec. 4.2 Eq. 15-17.  Per layer l
  * and channel i, with per-sample gradients gg = g_gamma[l][n, i], gb = g_beta[l][n, i]:
  *   F_batch = mean_n (gg^2, gg*gb, gb^2);  F_ema[l][i, 0..2] <- decay F_ema + (1-decay) F_batch
@@ -183,6 +208,8 @@ typedef struct {
     float ms;
     double flops;
     double bytes;
+    float start_ms;    /* start of the launch, measured from the start of the first recorded launch */
+    int32_t stream;    /* 0: the context's stream, 1..3: internal streams */
 } kfac_profile_entry;
 
 kfac_status kfac_profile_enable(kfac_ctx *ctx, int32_t on);

@@ -33,10 +33,10 @@ __global__ __launch_bounds__(256) void trace_kernel(const TraceJob *__restrict__
         const double trA = red[0][0], trG = red[1][0];
         double pi = 1.0;
         if (trA > 0.0 && trG > 0.0) pi = sqrt((trA / J.dA) / (trG / J.dG));
-        damp[3 * blockIdx.x + 0] = (float)pi;
-        damp[3 * blockIdx.x + 1] = (float)(pi * (double)gamma);   // added to A
-        damp[3 * blockIdx.x + 2] = (float)((double)gamma / pi);   // added to G
-        if (pi_out) pi_out[blockIdx.x] = (float)pi;
+        damp[3 * J.idx + 0] = (float)pi;
+        damp[3 * J.idx + 1] = (float)(pi * (double)gamma);   // added to A
+        damp[3 * J.idx + 2] = (float)((double)gamma / pi);   // added to G
+        if (pi_out) pi_out[J.idx] = (float)pi;
     }
 }
 

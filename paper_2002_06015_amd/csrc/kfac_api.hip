@@ -17,6 +17,7 @@ using namespace kfac;
 namespace {
 
 constexpr int kSlots = 8;
+constexpr int kSyncEvents = 8;   // events that order the streams of one call among each other
 constexpr size_t kAlign = 256;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -27,6 +28,8 @@ struct Tunables {
     int max_k_per_wg;    // and never leaves a workgroup a longer contraction than this
     int inv_streams;     // independent inversion chains run on this many streams (1..4)
     int rec_leaf;        // the blocked inversion recurses down to blocks of at most this size
+    int early_n;         // fused step: layers with a factor of at least this size are built first so
+                         // that their inversion chains start while the other factors are still being built
     int slots;           // staging slots in use (2..kSlots): a call waits until the device has started the
                          // call `slots` calls back.  Measured: letting the host run further ahead than a
                          // couple of calls makes the chains of small launches slower, not faster.
@@ -42,6 +45,8 @@ struct Tunables {
         inv_streams = e ? std::min(4, std::max(1, atoi(e))) : 4;
         e = getenv("KFAC_REC_LEAF");
         rec_leaf = e ? std::min(kLeafMax, std::max(32, atoi(e))) : 160;
+        e = getenv("KFAC_EARLY_N");
+        early_n = e ? std::max(1, atoi(e)) : 2048;
         e = getenv("KFAC_STAGING_SLOTS");
         slots = e ? std::min(kSlots, std::max(2, atoi(e))) : 2;
     }
@@ -62,7 +67,7 @@ struct kfac_ctx {
     Tunables tun;
     // auxiliary streams (default priority) for independent chains of launches inside one call
     hipStream_t aux[3];
-    hipEvent_t fork_ev, join_ev[3];
+    hipEvent_t sync_ev[kSyncEvents];
     bool aux_valid;
     // optional per-launch timing
     bool profiling;
@@ -103,7 +108,8 @@ struct Tables {
     }
 };
 
-enum LaunchKind { L_GEMM, L_REDUCE, L_PATCH, L_TRACE, L_COPY, L_LEAF, L_ZERO, L_BN, L_BNRED };
+enum LaunchKind { L_GEMM, L_REDUCE, L_PATCH, L_TRACE, L_COPY, L_LEAF, L_ZERO, L_BN, L_BNRED,
+                  L_RECORD, L_WAIT };   // stream ordering: record / wait for sync event `n` on `stream`
 
 struct Launch {
     LaunchKind kind;
@@ -112,12 +118,22 @@ struct Launch {
     float f0, f1;
     void *p0, *p1;
     double flops, bytes;   // algorithmic counts (profiling only)
-    int stream;            // 0: the context's stream; 1..3: auxiliary streams (forked/joined inside the call)
+    int stream;            // 0: the context's stream; 1..3: auxiliary streams (ordered by L_RECORD / L_WAIT)
 };
 
 struct Plan {
     Tables tab;
     std::vector<Launch> launches;
+    void sync(LaunchKind kind, int event, int stream)
+    {
+        Launch L{};
+        L.kind = kind; L.n = event; L.stream = stream;
+        launches.push_back(L);
+    }
+    void set_stream(size_t first, int stream)
+    {
+        for (size_t q = first; q < launches.size(); ++q) launches[q].stream = stream;
+    }
 };
 
 bool layer_ok(const kfac_layer &L, int *dA, int *dG, int *h, int *w)
@@ -332,7 +348,9 @@ PatchJob make_patch_job(const void *src, void *dst, long long ld, int N, int c, 
     return J;
 }
 
-void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &a, bool dry)
+// `subset` (or null for all): the layers of `a` to build factors for.
+void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &a, bool dry,
+                const std::vector<int> *subset = nullptr)
 {
     const int esize = a.in == KFAC_BF16 ? 2 : 4;
     // a thread loads 16-byte chunks: 4 fp32 (element alignment is enough) or 8 bf16 (16-byte aligned)
@@ -372,7 +390,9 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         }
         return op;
     };
-    for (int l = 0; l < a.n_layers; ++l) {
+    const int n_sel = subset ? (int)subset->size() : a.n_layers;
+    for (int q = 0; q < n_sel; ++q) {
+        const int l = subset ? (*subset)[q] : q;
         const kfac_layer &Ly = a.L[l];
         int dA, dG, h, w;
         layer_ok(Ly, &dA, &dG, &h, &w);
@@ -560,63 +580,43 @@ struct InvertArgs {
     int32_t *info;
 };
 
-void plan_invert(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs &a, bool dry)
+// Inversion of both factors of the layers `ids` as one chain of launches on `stream`:
+// traces / damping, the damped copies, then the recursion of every matrix with the launches
+// of equal depth merged.  damp: [3 * n_layers] floats shared by all groups of the call.
+void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs &a, bool dry,
+                       const std::vector<int> &ids, float *damp, int stream)
 {
-    float *damp = (float *)arena.take((size_t)3 * a.n_layers * sizeof(float));
+    if (ids.empty()) return;
+    const size_t first_launch = plan.launches.size();
     std::vector<TraceJob> tjobs;
     std::vector<InvMatrix> mats;
-    for (int l = 0; l < a.n_layers; ++l) {
+    for (int l : ids) {
         int dA, dG;
         layer_ok(a.L[l], &dA, &dG, nullptr, nullptr);
         TraceJob T{};
         T.A = dry ? nullptr : a.A_ema[l];
         T.G = dry ? nullptr : a.G_ema[l];
         T.dA = dA; T.dG = dG;
+        T.idx = l;
         tjobs.push_back(T);
         // dry runs only need distinct, well-aligned stand-in addresses for planning
         mats.push_back({T.A, dry ? (float *)nullptr : a.A_inv[l], dA, 3 * l + 1, 2 * l});
         mats.push_back({T.G, dry ? (float *)nullptr : a.G_inv[l], dG, 3 * l + 2, 2 * l + 1});
     }
-    if (a.info || dry) {
-        Launch Z{};
-        Z.kind = L_ZERO;
-        Z.p0 = a.info;
-        Z.n = 2 * a.n_layers;
-        plan.launches.push_back(Z);
-    }
     {
         Launch T{};
         T.kind = L_TRACE;
         T.off_a = plan.tab.add(tjobs.data(), tjobs.size() * sizeof(TraceJob));
-        T.n = a.n_layers;
+        T.n = (int)tjobs.size();
         T.f0 = a.gamma;
         T.p0 = damp;
         T.p1 = a.pi_out;
         plan.launches.push_back(T);
     }
-    // The recursion of one matrix is a long dependent chain of small launches.  Matrices are
-    // dealt into up to inv_streams groups of similar n^3; each group has its own levelled
-    // schedule on its own stream, so the serial parts of one chain overlap the large
-    // products of another.  Group 0 runs on the context's stream.
-    const int n_groups = std::max(1, std::min(tun.inv_streams, 4));
-    std::vector<int> order(mats.size());
-    for (size_t i = 0; i < mats.size(); ++i) order[i] = (int)i;
-    std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return mats[x].n > mats[y].n; });
-    std::vector<double> load(n_groups, 0.0);
-    std::vector<int> group_of(mats.size(), 0);
-    for (int idx : order) {
-        if (mats[idx].n <= kLeafMax) { group_of[idx] = 0; continue; }   // single launch: no chain
-        int g = 0;
-        for (int q = 1; q < n_groups; ++q)
-            if (load[q] < load[g]) g = q;
-        group_of[idx] = g;
-        load[g] += (double)mats[idx].n * mats[idx].n * mats[idx].n;
-    }
     std::vector<CopyJob> cjobs;
     int copy_wgs = 0;
-    std::vector<std::vector<InvOp>> ops(n_groups);
-    for (size_t i = 0; i < mats.size(); ++i) {
-        const InvMatrix &m = mats[i];
+    std::vector<InvOp> ops;
+    for (const InvMatrix &m : mats) {
         if (m.n <= kLeafMax) {
             InvOp op{};
             op.level = 0; op.kind = OP_LEAF;
@@ -626,7 +626,7 @@ void plan_invert(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs
             op.leaf.damp_idx = m.damp_idx;
             op.leaf.info_idx = m.info_idx;
             op.leaf.pivot_base = 0;
-            ops[0].push_back(op);
+            ops.push_back(op);
         } else {
             CopyJob C{};
             C.src = m.src; C.dst = m.dst;
@@ -635,7 +635,7 @@ void plan_invert(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs
             C.wg_start = copy_wgs;
             copy_wgs += (m.n + 7) / 8;
             cjobs.push_back(C);
-            build_inverse(ops[group_of[i]], arena, m.dst, m.n, 0, m.n, 0, m.info_idx, tun.rec_leaf);
+            build_inverse(ops, arena, m.dst, m.n, 0, m.n, 0, m.info_idx, tun.rec_leaf);
         }
     }
     if (!cjobs.empty()) {
@@ -647,40 +647,94 @@ void plan_invert(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs
         C.p0 = damp;
         plan.launches.push_back(C);
     }
+    int max_level = -1;
+    for (auto &op : ops) max_level = std::max(max_level, op.level);
+    for (int lv = 0; lv <= max_level; ++lv) {
+        for (int c = 0; c < kNumLeafClasses; ++c) {
+            std::vector<LeafJob> lj;
+            for (auto &op : ops)
+                if (op.level == lv && op.kind == OP_LEAF && leaf_class(op.leaf.n) == c) lj.push_back(op.leaf);
+            if (lj.empty()) continue;
+            Launch Lf{};
+            Lf.kind = L_LEAF;
+            Lf.off_a = plan.tab.add(lj.data(), lj.size() * sizeof(LeafJob));
+            Lf.n = (int)lj.size();
+            Lf.cfg = c;
+            Lf.p0 = damp;
+            Lf.p1 = a.info;
+            plan.launches.push_back(Lf);
+        }
+        std::vector<GemmProblem> gp;
+        for (auto &op : ops)
+            if (op.level == lv && op.kind == OP_GEMM) gp.push_back(op.gemm);
+        // split-K scratch of one level is dead once the level's launches are enqueued (in order)
+        const size_t mark = arena.used;
+        emit_gemm_phase(plan, arena, tun, gp, 0, true, true);
+        arena.release_to(mark);
+    }
+    plan.set_stream(first_launch, stream);
+}
+
+double chain_load(const kfac_layer &L)
+{
+    int dA, dG;
+    layer_ok(L, &dA, &dG, nullptr, nullptr);
+    auto cube = [](int n) { return n > kLeafMax ? (double)n * n * n : 0.0; };
+    return cube(dA) + cube(dG);
+}
+
+// Deals layers (largest chains first) into n_groups groups of similar total n^3.
+std::vector<std::vector<int>> deal_layers(const kfac_layer *L, std::vector<int> ids, int n_groups, int first_group)
+{
+    std::vector<std::vector<int>> groups(n_groups);
+    std::stable_sort(ids.begin(), ids.end(), [&](int x, int y) { return chain_load(L[x]) > chain_load(L[y]); });
+    std::vector<double> load(n_groups, 0.0);
+    for (int l : ids) {
+        int g = first_group;
+        if (chain_load(L[l]) > 0.0)
+            for (int q = first_group; q < n_groups; ++q)
+                if (load[q] < load[g]) g = q;
+        groups[g].push_back(l);
+        load[g] += chain_load(L[l]);
+    }
+    return groups;
+}
+
+// The recursion of one matrix is a long dependent chain of small launches.  Layers are dealt
+// into up to inv_streams groups; each group has its own levelled schedule on its own stream,
+// so the serial parts of one chain overlap the large products of another.  Group 0 runs on the
+// context's stream; the others start after everything enqueued before (sync event 0) and are
+// joined at the end (events 1..3).  Scratch of different groups never overlaps.
+void plan_invert(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs &a, bool dry)
+{
+    float *damp = (float *)arena.take((size_t)3 * a.n_layers * sizeof(float));
+    if (a.info || dry) {
+        Launch Z{};
+        Z.kind = L_ZERO;
+        Z.p0 = a.info;
+        Z.n = 2 * a.n_layers;
+        plan.launches.push_back(Z);
+    }
+    const int n_groups = std::max(1, std::min(tun.inv_streams, 4));
+    std::vector<int> all(a.n_layers);
+    for (int l = 0; l < a.n_layers; ++l) all[l] = l;
+    std::vector<std::vector<int>> groups = deal_layers(a.L, all, n_groups, 0);
+    bool forked = false;
     // auxiliary groups first, so that their launches are enqueued before the main chain's
     for (int gi = 0; gi < n_groups; ++gi) {
         const int g = (gi + 1) % n_groups;
-        if (ops[g].empty()) continue;
-        // split-K scratch of different groups must not overlap: they run concurrently
-        const size_t group_base = align_up(arena.peak, kAlign);
-        arena.used = group_base;
-        int max_level = -1;
-        for (auto &op : ops[g]) max_level = std::max(max_level, op.level);
-        for (int lv = 0; lv <= max_level; ++lv) {
-            const size_t first = plan.launches.size();
-            for (int c = 0; c < kNumLeafClasses; ++c) {
-                std::vector<LeafJob> lj;
-                for (auto &op : ops[g])
-                    if (op.level == lv && op.kind == OP_LEAF && leaf_class(op.leaf.n) == c) lj.push_back(op.leaf);
-                if (lj.empty()) continue;
-                Launch Lf{};
-                Lf.kind = L_LEAF;
-                Lf.off_a = plan.tab.add(lj.data(), lj.size() * sizeof(LeafJob));
-                Lf.n = (int)lj.size();
-                Lf.cfg = c;
-                Lf.p0 = damp;
-                Lf.p1 = a.info;
-                plan.launches.push_back(Lf);
-            }
-            std::vector<GemmProblem> gp;
-            for (auto &op : ops[g])
-                if (op.level == lv && op.kind == OP_GEMM) gp.push_back(op.gemm);
-            const size_t mark = arena.used;
-            emit_gemm_phase(plan, arena, tun, gp, 0, true, true);
-            arena.release_to(mark);
-            for (size_t q = first; q < plan.launches.size(); ++q) plan.launches[q].stream = g;
+        if (groups[g].empty()) continue;
+        if (g > 0) {
+            if (!forked) plan.sync(L_RECORD, 0, 0);
+            forked = true;
+            plan.sync(L_WAIT, 0, g);
         }
+        arena.used = align_up(arena.peak, kAlign);
+        plan_invert_group(plan, arena, tun, a, dry, groups[g], damp, g);
+        if (g > 0) plan.sync(L_RECORD, g, g);
     }
+    for (int g = 1; g < n_groups; ++g)
+        if (!groups[g].empty()) plan.sync(L_WAIT, g, 0);
 }
 
 // ---------------------------------------------------------------- preconditioning planner
@@ -725,6 +779,86 @@ void plan_precondition(Plan &plan, Arena &arena, const Tunables &tun, const Prec
     emit_gemm_phase(plan, arena, tun, p2, 0, true, true);
 }
 
+// ---------------------------------------------------------------- fused step planner
+// One K-FAC step as a single dependency graph: factors of every layer, inverses of the
+// layers selected by `mask` (null: all), preconditioned gradients of every layer.  The
+// results are those of the three separate calls; the difference is the schedule.  The
+// inversion of a large factor is a long chain of mostly small launches that leaves the GPU
+// idle, while the factor contractions are throughput bound.  So the layers are built in
+// classes, longest chains first:
+//   class 0: a factor of at least 2 * early_n   (event 4)
+//   class 1: a factor of at least early_n       (event 5)
+//   rest
+// all on the context's stream, and the chains of a class start on auxiliary streams as soon
+// as its factors exist.  (A grid of thousands of matrix-kernel workgroups leaves no compute
+// unit with room for another workgroup, so the chains mostly advance between the big
+// launches, not underneath them; what this order buys is that the longest chains are not also
+// the last to start.)  The rest is inverted on the context's stream.
+void plan_step(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &st, const InvertArgs &inv,
+               const uint8_t *mask, const PrecondArgs &pc, bool dry)
+{
+    const int n = st.n_layers;
+    float *damp = (float *)arena.take((size_t)3 * n * sizeof(float));
+    if (inv.info || dry) {
+        Launch Z{};
+        Z.kind = L_ZERO;
+        Z.p0 = inv.info;
+        Z.n = 2 * n;
+        plan.launches.push_back(Z);
+    }
+    const int n_aux = std::max(0, std::min(tun.inv_streams, 4) - 1);
+    std::vector<int> cls[2], late, late_inv;
+    for (int l = 0; l < n; ++l) {
+        int dA, dG;
+        layer_ok(st.L[l], &dA, &dG, nullptr, nullptr);
+        const bool inverted = !mask || mask[l];
+        const int big = std::max(dA, dG);
+        if (inverted && n_aux > 0 && big >= tun.early_n) cls[big >= 2 * tun.early_n ? 0 : 1].push_back(l);
+        else {
+            late.push_back(l);
+            if (inverted) late_inv.push_back(l);
+        }
+    }
+    if (cls[0].empty()) std::swap(cls[0], cls[1]);
+    // auxiliary streams per class: with two classes the first (few, longest chains) gets one
+    int aux_of[2][2] = {{1, n_aux}, {0, -1}};   // [class][first, last]
+    if (!cls[1].empty()) {
+        if (n_aux >= 2) { aux_of[0][1] = 1; aux_of[1][0] = 2; aux_of[1][1] = n_aux; }
+        else { cls[0].insert(cls[0].end(), cls[1].begin(), cls[1].end()); cls[1].clear(); }
+    }
+    const size_t mark0 = arena.used;
+    auto factor_phase = [&](const std::vector<int> &ids, int event) {
+        if (ids.empty()) return;
+        arena.release_to(mark0);   // each phase starts after the previous one has finished
+        plan_stats(plan, arena, tun, st, dry, &ids);
+        if (event >= 0) plan.sync(L_RECORD, event, 0);
+    };
+    factor_phase(cls[0], 4);
+    factor_phase(cls[1], 5);
+    factor_phase(late, -1);
+    bool joined[4] = {false, false, false, false};
+    for (int c = 0; c < 2; ++c) {
+        if (cls[c].empty()) continue;
+        const int g0 = aux_of[c][0], g1 = aux_of[c][1];
+        std::vector<std::vector<int>> groups = deal_layers(st.L, cls[c], g1 + 1, g0);
+        for (int g = g0; g <= g1; ++g) {
+            if (groups[g].empty()) continue;
+            plan.sync(L_WAIT, 4 + c, g);
+            arena.used = align_up(arena.peak, kAlign);   // concurrent with everything else: own scratch
+            plan_invert_group(plan, arena, tun, inv, dry, groups[g], damp, g);
+            plan.sync(L_RECORD, g, g);
+            joined[g] = true;
+        }
+    }
+    arena.used = align_up(arena.peak, kAlign);
+    plan_invert_group(plan, arena, tun, inv, dry, late_inv, damp, 0);
+    for (int g = 1; g < 4; ++g)
+        if (joined[g]) plan.sync(L_WAIT, g, 0);
+    // everything above has finished (in stream order) when these run: reuse the scratch
+    arena.release_to(mark0);
+    plan_precondition(plan, arena, tun, pc, dry);
+}
+
 // ---------------------------------------------------------------- execution
 kfac_status ensure_slot(kfac_ctx *ctx, int slot, size_t bytes)
 {
@@ -764,30 +898,28 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
             return KFAC_ERR_DEVICE;
         if (hipEventRecord(ctx->ev[slot], s) != hipSuccess) return KFAC_ERR_DEVICE;
     }
-    bool forked = false;
-    bool used[4] = {true, false, false, false};
     for (auto &L : plan.launches) {
         hipError_t e = hipSuccess;
         hipStream_t ls = s;
-        if (L.stream > 0) {
+        if (L.stream > 0 || L.kind == L_RECORD || L.kind == L_WAIT) {
             if (!ctx->aux_valid) {
-                for (int q = 0; q < 3; ++q) {
+                for (int q = 0; q < 3; ++q)
                     if (hipStreamCreateWithFlags(&ctx->aux[q], hipStreamNonBlocking) != hipSuccess) return KFAC_ERR_DEVICE;
-                    if (hipEventCreateWithFlags(&ctx->join_ev[q], hipEventDisableTiming) != hipSuccess) return KFAC_ERR_DEVICE;
-                }
-                if (hipEventCreateWithFlags(&ctx->fork_ev, hipEventDisableTiming) != hipSuccess) return KFAC_ERR_DEVICE;
+                for (int q = 0; q < kSyncEvents; ++q)
+                    if (hipEventCreateWithFlags(&ctx->sync_ev[q], hipEventDisableTiming) != hipSuccess) return KFAC_ERR_DEVICE;
                 ctx->aux_valid = true;
             }
-            if (!forked) {
-                // everything enqueued so far (tables, earlier launches) happens before the fork
-                if (hipEventRecord(ctx->fork_ev, s) != hipSuccess) return KFAC_ERR_DEVICE;
-                forked = true;
+            if (L.stream > 0) {
+                ls = ctx->aux[L.stream - 1];
             }
-            if (!used[L.stream]) {
-                if (hipStreamWaitEvent(ctx->aux[L.stream - 1], ctx->fork_ev, 0) != hipSuccess) return KFAC_ERR_DEVICE;
-                used[L.stream] = true;
-            }
-            ls = ctx->aux[L.stream - 1];
+        }
+        if (L.kind == L_RECORD) {
+            if (hipEventRecord(ctx->sync_ev[L.n], ls) != hipSuccess) return KFAC_ERR_DEVICE;
+            continue;
+        }
+        if (L.kind == L_WAIT) {
+            if (hipStreamWaitEvent(ls, ctx->sync_ev[L.n], 0) != hipSuccess) return KFAC_ERR_DEVICE;
+            continue;
         }
         const bool timed = ctx->profiling && L.kind != L_ZERO;
         if (timed) {
@@ -808,11 +940,13 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 case L_ZERO: pe.kernel = KFAC_K_ZERO; break;
                 case L_BN: pe.kernel = KFAC_K_BN_UNIT; break;
                 case L_BNRED: pe.kernel = KFAC_K_BN_REDUCE; break;
+                case L_RECORD: case L_WAIT: break;
             }
             pe.variant = (L.kind == L_GEMM || L.kind == L_LEAF) ? L.cfg : 0;
             pe.workgroups = (L.kind == L_TRACE || L.kind == L_LEAF) ? L.n : L.total_wgs;
             pe.flops = L.flops;
             pe.bytes = L.bytes;
+            pe.stream = L.stream;
             ctx->prof.push_back(pe);
             if (hipEventRecord(ctx->ev_pool[2 * idx], ls) != hipSuccess) return KFAC_ERR_DEVICE;
         }
@@ -847,16 +981,11 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
             case L_BNRED:
                 e = launch_bn_reduce((const BnReduceJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, ls);
                 break;
+            case L_RECORD: case L_WAIT: break;
         }
         if (e != hipSuccess) return KFAC_ERR_DEVICE;
         if (timed && hipEventRecord(ctx->ev_pool[2 * ctx->prof.size() - 1], ls) != hipSuccess)
             return KFAC_ERR_DEVICE;
-    }
-    // join: the context's stream continues only after every auxiliary chain has finished
-    for (int q = 1; q < 4; ++q) {
-        if (!used[q]) continue;
-        if (hipEventRecord(ctx->join_ev[q - 1], ctx->aux[q - 1]) != hipSuccess) return KFAC_ERR_DEVICE;
-        if (hipStreamWaitEvent(s, ctx->join_ev[q - 1], 0) != hipSuccess) return KFAC_ERR_DEVICE;
     }
     return KFAC_OK;
 }
@@ -902,13 +1031,14 @@ size_t kfac_workspace_bytes(const kfac_layer *L, int32_t n_layers, kfac_dtype in
 {
     if (!layers_ok(L, n_layers) || (in != KFAC_F32 && in != KFAC_BF16)) return 0;
     Tunables tun;
-    size_t best = 0;
+    size_t best = 0, sum_peaks = 0;
     {
         Plan plan; Arena arena(nullptr);
         StatsArgs a{n_layers, L, in, nullptr, nullptr, 0.5f, 0, nullptr, nullptr};
         plan_stats(plan, arena, tun, a, true);
         arena.take_tail(plan.tab.buf.size() + 16);
         best = std::max(best, arena.peak);
+        sum_peaks += arena.peak;
     }
     {
         Plan plan; Arena arena(nullptr);
@@ -916,6 +1046,7 @@ size_t kfac_workspace_bytes(const kfac_layer *L, int32_t n_layers, kfac_dtype in
         plan_invert(plan, arena, tun, a, true);
         arena.take_tail(plan.tab.buf.size() + 16);
         best = std::max(best, arena.peak);
+        sum_peaks += arena.peak;
     }
     {
         Plan plan; Arena arena(nullptr);
@@ -923,6 +1054,17 @@ size_t kfac_workspace_bytes(const kfac_layer *L, int32_t n_layers, kfac_dtype in
         plan_precondition(plan, arena, tun, a, true);
         arena.take_tail(plan.tab.buf.size() + 16);
         best = std::max(best, arena.peak);
+    }
+    {
+        // fused step, all layers inverted; a partial mask moves layers between the two factor
+        // phases and the inversion groups, which the sum of the separate peaks covers
+        Plan plan; Arena arena(nullptr);
+        StatsArgs st{n_layers, L, in, nullptr, nullptr, 0.5f, 0, nullptr, nullptr};
+        InvertArgs iv{n_layers, L, nullptr, nullptr, 1e-3f, nullptr, nullptr, nullptr, nullptr};
+        PrecondArgs pc{n_layers, L, nullptr, nullptr, nullptr, nullptr};
+        plan_step(plan, arena, tun, st, iv, nullptr, pc, true);
+        arena.take_tail(plan.tab.buf.size() + 16);
+        best = std::max(best, std::max(arena.peak, sum_peaks + sum_peaks / 8));
     }
     // im2col of a single layer and the BatchNorm calls need table space only
     best = std::max(best, (size_t)1 << 20);
@@ -966,9 +1108,8 @@ void kfac_destroy(kfac_ctx *ctx)
         for (int q = 0; q < 3; ++q) {
             (void)hipStreamSynchronize(ctx->aux[q]);
             (void)hipStreamDestroy(ctx->aux[q]);
-            (void)hipEventDestroy(ctx->join_ev[q]);
         }
-        (void)hipEventDestroy(ctx->fork_ev);
+        for (int q = 0; q < kSyncEvents; ++q) (void)hipEventDestroy(ctx->sync_ev[q]);
     }
     delete ctx;
 }
@@ -991,6 +1132,9 @@ int32_t kfac_profile_read(kfac_ctx *ctx, kfac_profile_entry *out, int32_t max_en
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, ctx->ev_pool[2 * i], ctx->ev_pool[2 * i + 1]) != hipSuccess) return -1;
         ctx->prof[i].ms = ms;
+        float t0 = 0.f;
+        if (i > 0 && hipEventElapsedTime(&t0, ctx->ev_pool[0], ctx->ev_pool[2 * i]) != hipSuccess) return -1;
+        ctx->prof[i].start_ms = t0;
         if (i < max_entries) out[i] = ctx->prof[i];
     }
     ctx->prof.clear();
@@ -1068,6 +1212,32 @@ kfac_status kfac_precondition(kfac_ctx *ctx, int32_t n_layers, const kfac_layer 
     Plan plan; Arena arena(ctx->ws);
     PrecondArgs a{n_layers, L, G_inv, A_inv, grad_W, out};
     plan_precondition(plan, arena, ctx->tun, a, false);
+    return run_plan(ctx, plan, arena);
+}
+
+kfac_status kfac_step(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
+                      const void *const *act, const void *const *grad_out, float decay, int32_t g_spatial_mean,
+                      float *const *A_ema, float *const *G_ema, const uint8_t *invert_mask, float gamma,
+                      float *const *A_inv, float *const *G_inv, float *pi_out, int32_t *info,
+                      const float *const *grad_W, float *const *out)
+{
+    if (!ctx || !layers_ok(L, n_layers)) return KFAC_ERR_INVALID;
+    if (in != KFAC_F32 && in != KFAC_BF16) return KFAC_ERR_INVALID;
+    if (!(decay >= 0.0f && decay < 1.0f)) return KFAC_ERR_INVALID;
+    if (!(gamma >= 0.0f) || !std::isfinite(gamma)) return KFAC_ERR_INVALID;
+    if (!act || !grad_out || !A_ema || !G_ema || !A_inv || !G_inv || !grad_W || !out) return KFAC_ERR_INVALID;
+    const size_t es = in == KFAC_BF16 ? 2 : 4;
+    for (int l = 0; l < n_layers; ++l) {
+        if (!act[l] || !grad_out[l] || !A_ema[l] || !G_ema[l] || !A_inv[l] || !G_inv[l] || !grad_W[l] || !out[l])
+            return KFAC_ERR_INVALID;
+        if (((uintptr_t)act[l] % es) != 0 || ((uintptr_t)grad_out[l] % es) != 0) return KFAC_ERR_INVALID;
+        if (A_ema[l] == A_inv[l] || G_ema[l] == G_inv[l]) return KFAC_ERR_INVALID;
+    }
+    Plan plan; Arena arena(ctx->ws);
+    StatsArgs st{n_layers, L, in, act, grad_out, decay, g_spatial_mean != 0, A_ema, G_ema};
+    InvertArgs iv{n_layers, L, A_ema, G_ema, gamma, A_inv, G_inv, pi_out, info};
+    PrecondArgs pc{n_layers, L, G_inv, A_inv, grad_W, out};
+    plan_step(plan, arena, ctx->tun, st, iv, invert_mask, pc, false);
     return run_plan(ctx, plan, arena);
 }
 

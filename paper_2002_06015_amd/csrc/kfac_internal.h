@@ -64,6 +64,7 @@ struct PatchJob {
 struct TraceJob {   // one per layer
     const float *A, *G;
     int dA, dG;
+    int idx;        // layer index: damp[3*idx .. 3*idx+2] and pi_out[idx] are written
 };
 
 struct CopyJob {    // dst[i][j] = src[i][j] + (i == j) * damp[damp_idx]

@@ -20,7 +20,7 @@ KFAC_F32, KFAC_BF16 = 0, 1
 
 EXPORTS = [
     "kfac_status_string", "kfac_layer_dims", "kfac_workspace_bytes", "kfac_create", "kfac_destroy",
-    "kfac_im2col", "kfac_stats", "kfac_invert", "kfac_precondition",
+    "kfac_im2col", "kfac_stats", "kfac_invert", "kfac_precondition", "kfac_step",
     "bn_unitwise_precondition", "bn_unitwise_reduce_nchw", "kfac_profile_enable", "kfac_profile_read",
 ]
 
@@ -30,7 +30,8 @@ KERNEL_NAMES = ["gemm_f32", "gemm_bf16", "gemm_reduce", "patch", "trace", "copy_
 
 class kfac_profile_entry(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int32), ("variant", ctypes.c_int32), ("workgroups", ctypes.c_int32),
-                ("ms", ctypes.c_float), ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
+                ("ms", ctypes.c_float), ("flops", ctypes.c_double), ("bytes", ctypes.c_double),
+                ("start_ms", ctypes.c_float), ("stream", ctypes.c_int32)]
 
 
 class kfac_layer(ctypes.Structure):
@@ -67,6 +68,7 @@ def lib() -> ctypes.CDLL:
         L.kfac_stats.argtypes = [vp, i32, vp, ctypes.c_int, vp, vp, f32, i32, vp, vp]
         L.kfac_invert.argtypes = [vp, i32, vp, vp, vp, f32, vp, vp, vp, vp]
         L.kfac_precondition.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+        L.kfac_step.argtypes = [vp, i32, vp, ctypes.c_int, vp, vp, f32, i32, vp, vp, vp, f32, vp, vp, vp, vp, vp, vp]
         L.bn_unitwise_precondition.argtypes = [vp, i32, i32, vp, vp, vp, f32, f32, vp, vp, vp]
         L.bn_unitwise_reduce_nchw.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
         L.kfac_profile_enable.argtypes = [vp, i32]
@@ -214,6 +216,31 @@ def kfac_precondition(ctx: Context, layers: Sequence, G_inv, A_inv, grad_W, out)
         raise KfacError(st, "kfac_precondition")
 
 
+def kfac_step(ctx: Context, layers: Sequence, in_dtype: int, act, grad_out, decay: float, g_spatial_mean: bool,
+              A_ema, G_ema, invert_mask: Optional[Sequence[bool]], gamma: float, A_inv, G_inv,
+              pi_out: Optional[torch.Tensor], info: Optional[torch.Tensor], grad_W, out) -> None:
+    n = len(layers)
+    arr = _layers(layers)
+    ps = [_ptrs(act, n, _tdtype(in_dtype)), _ptrs(grad_out, n, _tdtype(in_dtype))]
+    ps += [_ptrs(x, n, torch.float32) for x in (A_ema, G_ema, A_inv, G_inv, grad_W, out)]
+    pa, pg, pA, pG, pAi, pGi, pW, pO = [p and ctypes.addressof(p) for p in ps]
+    mask = None
+    if invert_mask is not None:
+        if len(invert_mask) != n:
+            raise ValueError("invert_mask must have one entry per layer")
+        mask = (ctypes.c_uint8 * n)(*[1 if m else 0 for m in invert_mask])
+    if pi_out is not None and (pi_out.dtype != torch.float32 or pi_out.numel() < n):
+        raise ValueError("pi_out must be float32 [n_layers]")
+    if info is not None and (info.dtype != torch.int32 or info.numel() < 2 * n):
+        raise ValueError("info must be int32 [2*n_layers]")
+    st = lib().kfac_step(ctx.handle, n, ctypes.addressof(arr), int(in_dtype), pa, pg, float(decay),
+                         int(bool(g_spatial_mean)), pA, pG, mask and ctypes.addressof(mask), float(gamma),
+                         pAi, pGi, None if pi_out is None else pi_out.data_ptr(),
+                         None if info is None else info.data_ptr(), pW, pO)
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_step")
+
+
 def bn_unitwise_precondition(ctx: Context, N: int, C: Sequence[int], g_gamma, g_beta, decay: float, lam: float,
                              F_ema, out_gamma, out_beta) -> None:
     n = len(C)
@@ -245,10 +272,12 @@ def kfac_profile_enable(ctx: Context, on: bool) -> None:
 
 
 def kfac_profile_read(ctx: Context, max_entries: int = 4096) -> list:
-    """Per-launch records since the last read: dicts with kernel, variant, workgroups, ms, flops, bytes."""
+    """Per-launch records since the last read: dicts with kernel, variant, workgroups, ms, flops, bytes,
+    start_ms (from the start of the first recorded launch) and stream."""
     arr = (kfac_profile_entry * max_entries)()
     n = lib().kfac_profile_read(ctx.handle, ctypes.addressof(arr), max_entries)
     if n < 0:
         raise KfacError(KFAC_ERR_DEVICE, "kfac_profile_read")
     return [dict(kernel=KERNEL_NAMES[e.kernel], variant=e.variant, workgroups=e.workgroups, ms=e.ms,
-                 flops=e.flops, bytes=e.bytes) for e in arr[:min(n, max_entries)]]
+                 flops=e.flops, bytes=e.bytes, start_ms=e.start_ms, stream=e.stream)
+            for e in arr[:min(n, max_entries)]]

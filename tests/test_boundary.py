@@ -103,6 +103,31 @@ def test_calls_reject_bad_arguments_without_a_gpu():
     assert L.kfac_precondition(h, 1, lp, fp, fp, None, fp) == INV
     assert L.kfac_precondition(h, 1, lp, fp, fp, fp, np_) == INV
     assert L.kfac_precondition(h, -1, lp, fp, fp, fp, fp) == INV
+    # kfac_step: the union of the three checks
+    ok = [h, 1, lp, 0, fp, fp, 0.0, 0, fp, fp, None, 1e-3, fp, fp, None, None, fp, fp]
+    other = (ctypes.c_void_p * 1)(0x400000)
+    op = ctypes.addressof(other)
+
+    def step_with(**kw):
+        a = list(ok)
+        a[12], a[13] = op, op                      # inverses distinct from the factors
+        names = ["ctx", "n", "L", "in", "act", "grad_out", "decay", "gsm", "A", "G", "mask", "gamma", "Ai", "Gi",
+                 "pi", "info", "gW", "out"]
+        for k, v in kw.items():
+            a[names.index(k)] = v
+        return L.kfac_step(*a)
+
+    assert L.kfac_step(*ok) == INV                 # A_inv aliases A_ema
+    assert step_with(ctx=None) == INV
+    assert step_with(n=0) == INV
+    assert step_with(decay=1.0) == INV
+    assert step_with(gamma=-1.0) == INV
+    assert step_with(gamma=float("inf")) == INV
+    assert step_with(act=None) == INV
+    assert step_with(grad_out=np_) == INV
+    assert step_with(gW=None) == INV
+    assert step_with(out=np_) == INV
+    assert step_with(**{"in": 5}) == INV
     # kfac_im2col
     assert L.kfac_im2col(h, lp, 0, None, fake[0], 4) == INV
     assert L.kfac_im2col(h, lp, 0, fake[0], fake[0], 3) == INV                 # ld < N*h*w

@@ -40,7 +40,7 @@ def gpu():
     return torch.device("cuda")
 
 
-def _run_step(layers, config, in_dtype, invert_idx=None, decay=0.0):
+def _run_step(layers, config, in_dtype, invert_idx=None, decay=0.0, fused=False):
     n = len(layers)
     tdt = torch.bfloat16 if in_dtype == kfac.KFAC_BF16 else torch.float32
     acts, grads, gws = [], [], []
@@ -64,14 +64,23 @@ def _run_step(layers, config, in_dtype, invert_idx=None, decay=0.0):
     U = [torch.zeros(L.dG, L.dA, device="cuda") for L in layers]
     pi = torch.zeros(n, device="cuda")
     info = torch.zeros(2 * n, dtype=torch.int32, device="cuda")
-    kfac.kfac_stats(ctx, layers, in_dtype, d_act, d_grad, decay, True, A, G)
     sel = lambda xs: [xs[i] for i in idx]
-    kfac.kfac_invert(ctx, sel(layers), sel(A), sel(G), wl.GAMMA, sel(Ai), sel(Gi), pi, info)
-    kfac.kfac_precondition(ctx, sel(layers), sel(Gi), sel(Ai), sel(d_gw), sel(U))
-    torch.cuda.synchronize()
+    if fused:
+        # one call; pi / info are indexed by layer, the preconditioning covers every layer
+        mask = [i in idx for i in range(n)]
+        kfac.kfac_step(ctx, layers, in_dtype, d_act, d_grad, decay, True, A, G, mask, wl.GAMMA, Ai, Gi, pi, info,
+                       d_gw, U)
+        torch.cuda.synchronize()
+        pi_h = host(pi)[idx]
+    else:
+        kfac.kfac_stats(ctx, layers, in_dtype, d_act, d_grad, decay, True, A, G)
+        kfac.kfac_invert(ctx, sel(layers), sel(A), sel(G), wl.GAMMA, sel(Ai), sel(Gi), pi, info)
+        kfac.kfac_precondition(ctx, sel(layers), sel(Gi), sel(Ai), sel(d_gw), sel(U))
+        torch.cuda.synchronize()
+        pi_h = host(pi)
     ctx.close()
     assert not info.cpu().numpy().any()
-    return dict(acts=acts, grads=grads, gws=gws, A=A, G=G, Ai=Ai, Gi=Gi, U=U, pi=host(pi), idx=idx)
+    return dict(acts=acts, grads=grads, gws=gws, A=A, G=G, Ai=Ai, Gi=Gi, U=U, pi=pi_h, idx=idx)
 
 
 @pytest.mark.timeout(600)
@@ -127,9 +136,10 @@ def _check_sampled(layers, r, rng, check_layers, n_pairs=48, n_cols=24):
 
 
 @pytest.mark.timeout(600)
-def test_config4_full_resnet50_set_sampled(gpu):
+@pytest.mark.parametrize("fused", [False, True])
+def test_config4_full_resnet50_set_sampled(gpu, fused):
     layers = wl.config_layers(4)
-    r = _run_step(layers, 4, kfac.KFAC_F32)
+    r = _run_step(layers, 4, kfac.KFAC_F32, fused=fused)
     rng = np.random.default_rng(4)
     worst = _check_sampled(layers, r, rng, range(len(layers)))
     assert worst["A"] <= TOL_FACTOR and worst["G"] <= TOL_FACTOR, worst
@@ -137,12 +147,13 @@ def test_config4_full_resnet50_set_sampled(gpu):
 
 
 @pytest.mark.timeout(900)
-def test_config5_batch128_stale_subset_sampled(gpu):
+@pytest.mark.parametrize("fused", [False, True])
+def test_config5_batch128_stale_subset_sampled(gpu, fused):
     """Batch 128, statistics for every layer, inverses only for the seeded 25 % subset.
     Sampled checks on the subset plus a few of the largest layers."""
     layers = wl.config_layers(5)
     subset = [int(i) for i in wl.stale_subset(len(layers), seed=0)]
-    r = _run_step(layers, 5, kfac.KFAC_F32, invert_idx=subset)
+    r = _run_step(layers, 5, kfac.KFAC_F32, invert_idx=subset, fused=fused)
     rng = np.random.default_rng(5)
     check = sorted(set(subset) | {0, 2, 46, 53})
     worst = _check_sampled(layers, r, rng, check, n_pairs=24, n_cols=16)

@@ -361,3 +361,81 @@ def test_config2_conv3x3_full_size(gpu):
     rebuilds the whole factor (a few seconds)."""
     worst = _full_step(wl.config_layers(2), 2, True, steps=1)
     assert worst["A"] <= TOL_FACTOR and worst["G"] <= TOL_FACTOR and worst["U"] <= TOL_PRECOND, worst
+
+
+# ------------------------------------------------------------------ fused step
+def _fused_vs_separate(layers, mask, early_n, monkeypatch):
+    """kfac_step against the oracle and against the three separate calls, two steps (the
+    second with the running average and, if a mask is given, stale inverses for the rest)."""
+    monkeypatch.setenv("KFAC_EARLY_N", str(early_n))   # read when the context is created
+    ctx = kfac.Context(layers)
+    n = len(layers)
+    mk = lambda: ([torch.full((L.dA, L.dA), float("nan"), device="cuda") for L in layers],
+                  [torch.full((L.dG, L.dG), float("nan"), device="cuda") for L in layers])
+    A, G = mk()
+    A2, G2 = mk()
+    Ai, Gi = [torch.zeros_like(x) for x in A], [torch.zeros_like(x) for x in G]
+    Ai2, Gi2 = [torch.zeros_like(x) for x in A], [torch.zeros_like(x) for x in G]
+    U = [torch.zeros(L.dG, L.dA, device="cuda") for L in layers]
+    U2 = [torch.zeros_like(x) for x in U]
+    pi = torch.full((n,), -1.0, device="cuda")
+    info = torch.full((2 * n,), 7, dtype=torch.int32, device="cuda")
+    info2 = torch.zeros(2 * n, dtype=torch.int32, device="cuda")
+    Ar, Gr = [None] * n, [None] * n
+    Air, Gir = [None] * n, [None] * n
+    for step in range(2):
+        decay = 0.0 if step == 0 else wl.DECAY
+        m = None if step == 0 else mask       # the first step gives every layer an inverse
+        acts = [wl.make_act(L, wl.layer_seed(9, i, step == 1)) for i, L in enumerate(layers)]
+        grads = [wl.make_grad_out(L, wl.layer_seed(9, i, step == 1)) for i, L in enumerate(layers)]
+        gws = [wl.make_grad_W(L, wl.layer_seed(9, i, step == 1)) for i, L in enumerate(layers)]
+        d_a, d_g, d_w = [dev(a) for a in acts], [dev(g) for g in grads], [dev(g) for g in gws]
+        kfac.kfac_step(ctx, layers, kfac.KFAC_F32, d_a, d_g, decay, True, A, G, m, wl.GAMMA, Ai, Gi, pi, info, d_w, U)
+        idx = [i for i in range(n) if m is None or m[i]]
+        sel = lambda xs: [xs[i] for i in idx]
+        kfac.kfac_stats(ctx, layers, kfac.KFAC_F32, d_a, d_g, decay, True, A2, G2)
+        if idx:
+            kfac.kfac_invert(ctx, sel(layers), sel(A2), sel(G2), wl.GAMMA, sel(Ai2), sel(Gi2), None, info2)
+        kfac.kfac_precondition(ctx, layers, Gi2, Ai2, d_w, U2)
+        torch.cuda.synchronize()
+        assert not info.cpu().numpy().any() and not info2.cpu().numpy().any()
+        for i, L in enumerate(layers):
+            Ar[i], Gr[i] = oracle.kfac_stats(tuple(L), acts[i], grads[i], decay, True, Ar[i], Gr[i])
+            if i in idx:
+                Air[i], Gir[i], pir, _ = oracle.kfac_invert(Ar[i], Gr[i], wl.GAMMA)
+                assert abs(float(pi[i]) - pir) <= 1e-4 * pir
+            Ur = oracle.kfac_precondition(Gir[i], Air[i], gws[i])
+            assert relerr(host(A[i]), Ar[i]) <= TOL_FACTOR and relerr(host(G[i]), Gr[i]) <= TOL_FACTOR
+            assert relerr(host(Ai[i]), Air[i]) <= TOL_PRECOND and relerr(host(Gi[i]), Gir[i]) <= TOL_PRECOND
+            assert relerr(host(U[i]), Ur) <= TOL_PRECOND
+            # same results as the separate calls up to the rounding order of the contractions
+            assert relerr(host(A[i]), host(A2[i])) <= 1e-5 and relerr(host(U[i]), host(U2[i])) <= 1e-4
+            if i not in idx:
+                assert float(pi[i]) == pi_before[i]          # untouched
+        pi_before = pi.cpu().numpy().copy()
+    ctx.close()
+
+
+FUSED_LAYERS = [
+    wl.conv_layer(2, 40, 130, 3, 1, 1, 10),        # d_A = 361 (recursion), d_G = 130
+    wl.fc_layer(32, 64, 32),
+    wl.conv_layer(4, 16, 70, 3, 1, 1, 12),         # d_A = 145
+    wl.conv_layer(2, 8, 5, 1, 1, 0, 6),
+    wl.fc_layer(16, 300, 310),                     # d_A = 301, d_G = 310: both recursive
+    wl.conv_layer(3, 5, 6, 3, 2, 1, 9, bias=0),
+]
+
+
+@pytest.mark.parametrize("early_n", [100, 300, 100000])
+def test_fused_step_all_layers(gpu, monkeypatch, early_n):
+    """early_n = 100: five layers take the early path on the auxiliary streams; 300: two;
+    100000: none (everything in order on the context's stream)."""
+    _fused_vs_separate(FUSED_LAYERS, None, early_n, monkeypatch)
+
+
+def test_fused_step_stale_subset(gpu, monkeypatch):
+    _fused_vs_separate(FUSED_LAYERS, [True, False, False, True, True, False], 100, monkeypatch)
+
+
+def test_fused_step_nothing_inverted(gpu, monkeypatch):
+    _fused_vs_separate(FUSED_LAYERS, [False] * len(FUSED_LAYERS), 100, monkeypatch)
