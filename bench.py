@@ -158,9 +158,15 @@ def main():
         torch.cuda.synchronize()
         for j, k in enumerate(stage_ms):
             stage_ms[k] += ev[j].elapsed_time(ev[j + 1]) / args.profile_steps
+    # per-kernel durations (HIP events around every launch, on the launch's own stream), also
+    # taken with the stages one after the other: under the fused schedule launches of different
+    # streams wait for each other's compute units and an event pair then brackets the wait too
     kfac.kfac_profile_enable(ctx, True)
     for _ in range(args.profile_steps):
-        step(wl.DECAY, subset)
+        stats(wl.DECAY)
+        invert(subset)
+        precond()
+        bn(wl.DECAY)
     entries = kfac.kfac_profile_read(ctx, 16384)
     kfac.kfac_profile_enable(ctx, False)
     kernels = {}
@@ -175,18 +181,34 @@ def main():
     for k in kernels.values():
         for f in ("launches", "ms", "flops", "bytes"):
             k[f] /= args.profile_steps
-    dom_name = max(kernels, key=lambda q: kernels[q]["ms"])
+    # the dominant kernel: the one that carries most of the step's arithmetic (if none has any,
+    # the one that takes most of the time)
+    if any(k["flops"] > 0 for k in kernels.values()):
+        dom_name = max(kernels, key=lambda q: kernels[q]["flops"])
+    else:
+        dom_name = max(kernels, key=lambda q: kernels[q]["ms"])
     dom = kernels[dom_name]
+    # HBM traffic per launch of that kernel: measured separately with rocprofv3 --pmc (FETCH_SIZE
+    # and WRITE_SIZE, scaled by what they read for the plain copy kernel of the same run) and
+    # kept with the profile summaries; null if no measurement covers this configuration
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "pmc_traffic.json")) as f:
+            for rec in json.load(f)["records"]:
+                if rec["config"] == cfg and rec["dtype"] == args.dtype and rec["kernel"] == dom_name:
+                    traffic = rec["bytes_per_launch"]
+    except (OSError, ValueError, KeyError):
+        traffic = None
     gemm_dt = "bf16" if dom_name.startswith("gemm_bf16") else "f32"
     if dom["flops"] > 0:
         achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
         roofline = {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_TFLOPS[gemm_dt],
-                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS[gemm_dt], 4), "traffic": None,
+                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS[gemm_dt], 4), "traffic": traffic,
                     "launches_per_step": dom["launches"], "avg_launch_ms": round(dom["ms"] / dom["launches"], 4)}
     else:
         achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
         roofline = {"kernel": dom_name, "bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": traffic,
                     "launches_per_step": dom["launches"], "avg_launch_ms": round(dom["ms"] / dom["launches"], 4)}
 
     fl = {"stats_A": 0.0, "stats_G": 0.0, "inv": 0.0, "precond": 0.0}

@@ -205,20 +205,20 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
                      int dtype, bool allow_split, bool phase_boost = false)
 {
     if (probs.empty()) return;
-    // Tile configuration per problem.  When the phase as a whole fills the GPU with 128x128
+    // Tile configuration per problem.  When the phase as a whole keeps the GPU busy with 128x128
     // tiles, each problem takes the configuration with less padded work (the big tile moves
     // half the operand bytes per flop, worth ~15 %); otherwise the latency model decides.
-    double tiles128 = 0;
+    double tile_steps128 = 0;   // 128x128 tiles times 32-wide K steps: the work of the phase
     for (auto &P : probs) {
         const double tm = (P.M + 127) / 128, tn = (P.N + 127) / 128;
-        tiles128 += (P.flags & GEMM_SYM) ? tm * (tm + 1) / 2 : tm * tn;
+        tile_steps128 += ((P.flags & GEMM_SYM) ? tm * (tm + 1) / 2 : tm * tn) * ((P.K + 31) / 32);
     }
     for (auto &P : probs) {
         const bool sym = (P.flags & GEMM_SYM) != 0;
         static const char *force = getenv("KFAC_FORCE_TILE");
         if (force && *force) {
             P.tile_cfg = atoi(force) == 64 ? 1 : 0;
-        } else if (tiles128 >= 1024) {
+        } else if (tile_steps128 >= 512.0 * 64) {   // every workgroup slot of the GPU busy for 64 steps
             auto work = [&](int B) {
                 const double tm = (P.M + B - 1) / B, tn = (P.N + B - 1) / B;
                 return (sym ? tm * (tm + 1) / 2 : tm * tn) * B * B;
