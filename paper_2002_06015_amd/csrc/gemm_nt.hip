@@ -732,8 +732,18 @@ __device__ __forceinline__ void reduce_slab(const GemmProblem &P, int tile, int 
     const float *part = P.partial + (long long)tile * P.splits * (B * B) + slab * 32 * B;
     // 32 * B elements, 4 per thread per pass
     for (int e = threadIdx.x * 4; e < 32 * B; e += 1024) {
-        floatx4 s = {0.f, 0.f, 0.f, 0.f};
-        for (int q = 0; q < P.splits; ++q) s += *(const floatx4 *)(part + (long long)q * (B * B) + e);
+        // four interleaved partial sums (splits q = 0, 4, 8, ... etc.), combined in a fixed order:
+        // as reproducible as one running sum, with four loads in flight instead of one
+        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, s2 = s0, s3 = s0;
+        int q = 0;
+        for (; q + 3 < P.splits; q += 4) {
+            s0 += *(const floatx4 *)(part + (long long)q * (B * B) + e);
+            s1 += *(const floatx4 *)(part + (long long)(q + 1) * (B * B) + e);
+            s2 += *(const floatx4 *)(part + (long long)(q + 2) * (B * B) + e);
+            s3 += *(const floatx4 *)(part + (long long)(q + 3) * (B * B) + e);
+        }
+        for (; q < P.splits; ++q) s0 += *(const floatx4 *)(part + (long long)q * (B * B) + e);
+        const floatx4 s = (s0 + s1) + (s2 + s3);
         const int r = e / B, c = e - r * B;
         float *t = T + r * (B + 1) + c;
         t[0] = s[0]; t[1] = s[1]; t[2] = s[2]; t[3] = s[3];

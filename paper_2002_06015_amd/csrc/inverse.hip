@@ -1,12 +1,11 @@
 // Kernels of the damped inversion (Sec. 3.3, Eq. 12) other than the GEMMs:
 //   - trace_kernel:  pi^2 = (tr A / dA) / (tr G / dG) and the two damping values per layer;
 //   - copy_damp_kernel: dst = src + damp * I (start of the blocked inversion);
-//   - leaf_inverse_kernel: (X + damp I)^-1 for n <= 288 by Gauss-Jordan elimination held
-//     entirely in registers of one 512- or 1024-thread workgroup (one matrix per workgroup, many
-//     matrices per launch); only the pivot row goes through LDS.
+//   - leaf_block_kernel: (X + damp I)^-1 for n <= 288 by a blocked symmetric sweep held in the
+//     registers of one 1024-thread workgroup, block products on the matrix cores (one matrix per
+//     workgroup, many matrices per launch).
 #include "kfac_internal.h"
 
-#include <type_traits>
 
 namespace kfac {
 
@@ -92,163 +91,234 @@ hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t s)
     return hipGetLastError();
 }
 
-// ------------------------------------------------------------------ in-register Gauss-Jordan
-// Thread (ti, tj) of a TR x 32 thread grid holds the elements (ti + TR*bi, tj + 32*bj),
-// bi < BR, bj < BC (so n <= TR*BR = 32*BC).  Gauss-Jordan without pivoting (safe for a
-// positive definite matrix).  After pivots 0..k-1 the working matrix T has
-// T[k][j] = -T[j][k] for j < k and T[k][j] = T[j][k] for j > k, so publishing pivot rows
-// alone also gives the pivot columns.  A single-pivot step would be
-//     p = 1/T[k][k];  T[i][j] -= T[i][k] p T[k][j]  (i, j != k);
-//     T[k][j] *= p;   T[i][k] *= -p;   T[k][k] = p;
-// the kernel takes the pivots in pairs (see the loop).  One barrier per pair (the pivot row
-// buffer is double-buffered).  A non-positive pivot is reported through info.
-// f(integral_constant<int, I>) for I = 0..N-1, unrolled at compile time.
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F &&f)
+// ------------------------------------------------------------------ blocked leaf inverse on the matrix cores
+// (X + damp I)^-1 for n <= 288 by one 1024-thread workgroup, as a symmetric block sweep with
+// 32x32 blocks.  The matrix is first scaled to unit diagonal (s_i = 1/sqrt(x_ii), undone at
+// the end), which makes every pivot of the elimination lie in (0, 1].  The workgroup holds
+// N = -(scaled matrix), lower-triangle 32x32 tiles only, each tile in the accumulator layout of
+// v_mfma_f32_32x32x2_f32 in the registers of one wavefront (tile t -> wavefront t % 16).
+// Sweeping block k (all i, j != k; D = (-N_kk)^-1; the column panel R_i = N_ik, taken from
+// tile (i,k) for i > k and from the transpose of tile (k,i) for i < k):
+//     P_i   = R_i D             ->  new N_ik (and N_ki = P_i^T)
+//     N_ij += P_i R_j^T         (symmetric: tiles i >= j only)
+//     N_kk  = D
+// After all blocks N = X^-1 (the usual sweep operator, written for -X so that every update
+// is an accumulation).  R and P go through LDS; the products are MFMA.
+// D comes from a scalar sweep of the 32x32 diagonal tile inside its owner wavefront, also on
+// the matrix core: pivot p is the rank-1 update S += a b^T with b = row p (one accumulator
+// register across the lanes) and a = -row p / d (the tile is symmetric), patched so that the
+// same update leaves column p = old column / d (b_p = d - 1; no cancellation because d <= 1);
+// row p and the pivot itself are overwritten directly.  A non-positive pivot is reported.
+typedef float lb_floatx16 __attribute__((ext_vector_type(16)));
+typedef float lb_floatx4 __attribute__((ext_vector_type(4)));
+constexpr int LB_LD = 36;          // LDS row length of the panels (floats): conflict-free 16-byte reads
+constexpr int LB_MAXN = 288;
+
+__device__ __forceinline__ float lb_readlane(float x, int lane)
 {
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
+}
+
+// 16 products of a 32x32x32 block product: rows of `pa` (A operand) and `pb` (B operand, NT
+// form) are LDS panel rows; each half-wave takes 16 of the 32 k (the same for both operands).
+__device__ __forceinline__ void lb_mma32(lb_floatx16 &acc, const float *pa, const float *pb)
+{
+    lb_floatx4 fa[4], fb[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        fa[q] = *(const lb_floatx4 *)(pa + 4 * q);
+        fb[q] = *(const lb_floatx4 *)(pb + 4 * q);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[q][e], fb[q][e], acc, 0, 0, 0);
+}
+
+template <int NSLOT>
+__global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restrict__ jobs,
+                                                          const float *__restrict__ damp,
+                                                          int32_t *__restrict__ info)
+{
+    extern __shared__ __attribute__((aligned(16))) float lb_lds[];
+    float *Rp = lb_lds;                         // [LB_MAXN][LB_LD] column panel R
+    float *Pp = Rp + LB_MAXN * LB_LD;           // [LB_MAXN][LB_LD] P = R D
+    float *Dl = Pp + LB_MAXN * LB_LD;           // [32][LB_LD]      D
+    float *sc = Dl + 32 * LB_LD;                // [LB_MAXN]        diagonal scaling
+    __shared__ int bad_s;
+
+    const LeafJob J = jobs[blockIdx.x];
+    const int n = J.n;
+    const int T = (n + 31) >> 5;
+    const int ntiles = T * (T + 1) / 2;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int l32_ = lane & 31, h_ = lane >> 5;
+    const float d = (J.damp_idx >= 0) ? damp[J.damp_idx] : 0.f;
+    const unsigned lds = (unsigned)J.lds, ldd = (unsigned)J.ldd;
+
+    if (tid < 32 * T) {
+        float v = 1.f;
+        if (tid < n) {
+            const float a = J.src[(unsigned)tid * lds + (unsigned)tid] + d;
+            v = a > 0.f ? rsqrtf(a) : 1.f;   // a non-positive diagonal shows up as a non-positive pivot
+        }
+        sc[tid] = v;
+    }
+    if (tid == 0) bad_s = 0;
+    __syncthreads();
+
+    // my tiles: tile t = w + 16 s is block (ti, tj), ti >= tj, in row-major order of the lower triangle
+    lb_floatx16 acc[NSLOT];
+    int ti[NSLOT], tj[NSLOT];
+#pragma unroll
+    for (int s = 0; s < NSLOT; ++s) {
+        const int t = w + 16 * s;
+        int r = 0;
+        while ((r + 1) * (r + 2) / 2 <= t) ++r;
+        ti[s] = t < ntiles ? r : -1;
+        tj[s] = t - r * (r + 1) / 2;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = 32 * r + 8 * (v >> 2) + 4 * h_ + (v & 3), j = 32 * tj[s] + l32_;
+            float x = (i == j) ? -1.f : 0.f;
+            if (t < ntiles && i < n && j < n) {
+                x = J.src[(unsigned)i * lds + (unsigned)j];
+                if (i == j) x += d;
+                x = -x * sc[i] * sc[j];
+            }
+            acc[s][v] = x;
+        }
+    }
+
+    for (int k = 0; k < T; ++k) {
+        // (per-step copies of the lane coordinates: as loop invariants, the 32 lane masks of the
+        // sweep and the LDS addresses below would be hoisted and kept live across the whole loop)
+        int l32 = l32_, h = h_;
+        asm volatile("" : "+v"(l32), "+v"(h));
+        // ---- column panel R into LDS; the diagonal tile's owner sweeps it meanwhile
+        const int tkk = k * (k + 1) / 2 + k;
+#pragma unroll
+        for (int s = 0; s < NSLOT; ++s) {
+            if (ti[s] < 0) continue;
+            if (tj[s] == k && ti[s] > k) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    Rp[(32 * ti[s] + 8 * (v >> 2) + 4 * h + (v & 3)) * LB_LD + l32] = acc[s][v];
+            } else if (ti[s] == k && tj[s] < k) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    Rp[(32 * tj[s] + l32) * LB_LD + 8 * (v >> 2) + 4 * h + (v & 3)] = acc[s][v];
+            }
+        }
+        if (w == (tkk & 15)) {
+            const int slot = tkk >> 4;
+            lb_floatx16 sg;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float x = acc[0][v];
+#pragma unroll
+                for (int s = 1; s < NSLOT; ++s) x = (slot == s) ? acc[s][v] : x;
+                sg[v] = -x;
+            }
+            int badl = 0;
+#pragma unroll
+            for (int p = 0; p < 32; ++p) {
+                const int vp = 4 * (p >> 3) + (p & 3), hp = (p >> 2) & 1;
+                const float x = sg[vp];
+                const float dp = lb_readlane(x, p + 32 * hp);
+                badl = (badl == 0 && !(dp > 0.f)) ? 32 * k + p + 1 : badl;
+                const float rinv = __builtin_amdgcn_rcpf(dp);
+                const bool mine = h == hp, isp = l32 == p;
+                const float xr = x * rinv;
+                const float a = (mine && !isp) ? -xr : 0.f;
+                const float b = mine ? (isp ? dp - 1.f : x) : 0.f;
+                sg = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, sg, 0, 0, 0);
+                sg[vp] = mine ? (isp ? -rinv : xr) : sg[vp];
+            }
+            // sg = -(that tile)^-1 = -D
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float x = -sg[v];
+                Dl[(8 * (v >> 2) + 4 * h + (v & 3)) * LB_LD + l32] = x;
+#pragma unroll
+                for (int s = 0; s < NSLOT; ++s) acc[s][v] = (slot == s) ? x : acc[s][v];
+            }
+            if (badl != 0 && lane == 0 && bad_s == 0) bad_s = badl;   // blocks are swept in order: the first one stays
+        }
+        __syncthreads();
+        // ---- P_i = R_i D for the T - 1 row blocks i != k, one per wavefront
+        if (w < T - 1) {
+            const int i = w < k ? w : w + 1;
+            lb_floatx16 pt;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) pt[v] = 0.f;
+            lb_mma32(pt, Rp + (32 * i + l32) * LB_LD + 16 * h, Dl + l32 * LB_LD + 16 * h);   // D is symmetric
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Pp[(32 * i + 8 * (v >> 2) + 4 * h + (v & 3)) * LB_LD + l32] = pt[v];
+        }
+        __syncthreads();
+        // ---- row / column k take P, every other tile N_ij += P_i R_j^T
+#pragma unroll
+        for (int s = 0; s < NSLOT; ++s) {
+            if (ti[s] < 0) continue;
+            const int i = ti[s], j = tj[s];
+            if (i == k && j == k) continue;
+            if (j == k) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[s][v] = Pp[(32 * i + 8 * (v >> 2) + 4 * h + (v & 3)) * LB_LD + l32];
+            } else if (i == k) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[s][v] = Pp[(32 * j + l32) * LB_LD + 8 * (v >> 2) + 4 * h + (v & 3)];
+            } else {
+                lb_mma32(acc[s], Pp + (32 * i + l32) * LB_LD + 16 * h, Rp + (32 * j + l32) * LB_LD + 16 * h);
+            }
+        }
+        __syncthreads();
+    }
+    if (tid == 0 && bad_s != 0 && info && J.info_idx >= 0) atomicCAS(&info[J.info_idx], 0, J.pivot_base + bad_s);
+
+    // undo the scaling; the lower triangle is written and mirrored, so the result is exactly symmetric
+#pragma unroll
+    for (int s = 0; s < NSLOT; ++s) {
+        if (ti[s] < 0) continue;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = 32 * ti[s] + 8 * (v >> 2) + 4 * h_ + (v & 3), j = 32 * tj[s] + l32_;
+            if (i < n && j <= i) {
+                const float x = acc[s][v] * sc[i] * sc[j];
+                J.dst[(unsigned)i * ldd + (unsigned)j] = x;
+                if (j != i) J.dst[(unsigned)j * ldd + (unsigned)i] = x;
+            }
+        }
     }
 }
 
-template <int BR, int BC, int TR>
-__global__ __launch_bounds__(TR * 32) void leaf_inverse_kernel(const LeafJob *__restrict__ jobs,
-                                                               const float *__restrict__ damp,
-                                                               int32_t *__restrict__ info)
+template <int NSLOT>
+static hipError_t launch_leaf_block(const LeafJob *jobs_dev, int n_jobs, const float *damp_dev, int32_t *info,
+                                    hipStream_t s)
 {
-    static_assert(TR * BR == 32 * BC, "row and column coverage must agree");
-    static_assert(TR == 32 || TR == 16, "thread grid is 32x32 or 16x32");
-    static_assert((TR * BR) % 2 == 0, "pivots are taken in pairs");
-    __shared__ float rowbuf[2][2][32 * BC];
-    int bad = 0;
-    const LeafJob J = jobs[blockIdx.x];
-    const int n = J.n;
-    const int tj = threadIdx.x & 31, ti = threadIdx.x >> 5;
-    const float d = (J.damp_idx >= 0) ? damp[J.damp_idx] : 0.f;
-
-    // 32-bit element offsets from the (uniform) base keep one address register per access
-    const unsigned lds = (unsigned)J.lds, ldd = (unsigned)J.ldd;
-    float a[BR][BC];
-#pragma unroll
-    for (int bi = 0; bi < BR; ++bi) {
-#pragma unroll
-        for (int bj = 0; bj < BC; ++bj) {
-            const int i = ti + TR * bi, j = tj + 32 * bj;
-            float v = (i == j) ? 1.f : 0.f;
-            if (i < n && j < n) {
-                v = J.src[(unsigned)i * lds + (unsigned)j];
-                if (i == j) v += d;
-            }
-            a[bi][bj] = v;
-        }
+    constexpr size_t lds_bytes = (size_t)(2 * LB_MAXN * LB_LD + 32 * LB_LD + LB_MAXN) * sizeof(float);
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)leaf_block_kernel<NSLOT>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        configured = true;
     }
-    __syncthreads();
-
-    // Two pivots per step (one barrier and one LDS round trip for both): with the pivot rows
-    // R = T[{k,k+1}, :], the 2x2 pivot block P and Q = P^-1, a block Gauss-Jordan step is
-    //     T[i][j] -= C[i,:] Q R[:,j],  T[K,j] = Q R[:,j],  T[i,K] = -C[i,:] Q,  T[K,K] = Q,
-    // where the pivot columns follow from the rows: C[i,:] = s_i R[:,i]^T, s_i = -1 for
-    // already eliminated i < k and +1 otherwise.  The owners of rows/columns k, k+1 clear
-    // their old values and patch their multipliers so that the same two fused multiply-adds
-    // produce exactly those special results.  The pivot loop is split into BR compile-time
-    // blocks of TR pivots, so that the register row (KBR) and column (KBC) holding the pivot
-    // rows/columns are compile-time constants and the matrix never leaves its registers.
-    // An odd n takes the identity padding row n as its last second pivot.
-    const int n_even = n + (n & 1);
-    static_for<0, BR>([&](auto KB) {
-        constexpr int KBR = decltype(KB)::value;
-        constexpr int KBC = (KBR * TR) / 32;
-        const int kend = min(n_even, (KBR + 1) * TR);
-        for (int k = KBR * TR; k < kend; k += 2) {
-            const int ktr = k - KBR * TR;   // rows k, k+1 live in threads ti == ktr, ktr+1, register row KBR
-            const int ktc = k & 31;         // columns k, k+1 live in threads tj == ktc, ktc+1, register column KBC
-            float *rb0 = rowbuf[(k >> 1) & 1][0], *rb1 = rowbuf[(k >> 1) & 1][1];
-            if (ti == ktr) {
-#pragma unroll
-                for (int bj = 0; bj < BC; ++bj) rb0[tj + 32 * bj] = a[KBR][bj];
-            }
-            if (ti == ktr + 1) {
-#pragma unroll
-                for (int bj = 0; bj < BC; ++bj) rb1[tj + 32 * bj] = a[KBR][bj];
-            }
-            __syncthreads();
-            const float pa = rb0[k], pb = rb0[k + 1], pd = rb1[k + 1];
-            const float det = fmaf(pa, pd, -pb * pb);
-            // non-positive pivots (the second one is det / pa) are recorded, first one wins,
-            // tracked in a register by every thread alike; the elimination goes on and its
-            // (meaningless) result is still written: no early exit, no branch
-            const int badk = !(pa > 0.f) ? k + 1 : (!(det > 0.f) ? k + 2 : 0);
-            bad = (bad == 0) ? badk : bad;
-            const float idet = __builtin_amdgcn_rcpf(det);
-            const float q00 = pd * idet, q01 = -pb * idet, q11 = pa * idet;
-            float t0[BC], t1[BC], c0[BR], c1[BR];
-#pragma unroll
-            for (int bj = 0; bj < BC; ++bj) {
-                const float r0 = rb0[tj + 32 * bj], r1 = rb1[tj + 32 * bj];
-                t0[bj] = fmaf(q00, r0, q01 * r1);
-                t1[bj] = fmaf(q01, r0, q11 * r1);
-            }
-#pragma unroll
-            for (int bi = 0; bi < BR; ++bi) {
-                const int i = ti + TR * bi;
-                const float r0 = rb0[i], r1 = rb1[i];
-                c0[bi] = (i < k) ? -r0 : r0;
-                c1[bi] = (i < k) ? -r1 : r1;
-            }
-            if (ti == ktr || ti == ktr + 1) {
-#pragma unroll
-                for (int bj = 0; bj < BC; ++bj) a[KBR][bj] = 0.f;
-                c0[KBR] = (ti == ktr) ? -1.f : 0.f;
-                c1[KBR] = (ti == ktr) ? 0.f : -1.f;
-            }
-            if (tj == ktc || tj == ktc + 1) {
-#pragma unroll
-                for (int bi = 0; bi < BR; ++bi) a[bi][KBC] = 0.f;
-                t0[KBC] = (tj == ktc) ? q00 : q01;
-                t1[KBC] = (tj == ktc) ? q01 : q11;
-            }
-#pragma unroll
-            for (int bi = 0; bi < BR; ++bi)
-#pragma unroll
-                for (int bj = 0; bj < BC; ++bj)
-                    a[bi][bj] = fmaf(-c1[bi], t1[bj], fmaf(-c0[bi], t0[bj], a[bi][bj]));
-        }
-    });
-    __syncthreads();
-    if (threadIdx.x == 0 && bad != 0 && info && J.info_idx >= 0)
-        atomicCAS(&info[J.info_idx], 0, J.pivot_base + bad);
-
-    // the lower triangle is written and mirrored, so the result is exactly symmetric
-#pragma unroll
-    for (int bi = 0; bi < BR; ++bi) {
-#pragma unroll
-        for (int bj = 0; bj < BC; ++bj) {
-            const int i = ti + TR * bi, j = tj + 32 * bj;
-            if (i < n && j <= i) {
-                J.dst[(unsigned)i * ldd + (unsigned)j] = a[bi][bj];
-                if (j != i) J.dst[(unsigned)j * ldd + (unsigned)i] = a[bi][bj];
-            }
-        }
-    }
+    leaf_block_kernel<NSLOT><<<dim3(n_jobs), dim3(1024), lds_bytes, s>>>(jobs_dev, damp_dev, info);
+    return hipGetLastError();
 }
 
 hipError_t launch_leaf(const LeafJob *jobs_dev, int n_jobs, int size_class, const float *damp_dev,
                        int32_t *info, hipStream_t s)
 {
     if (n_jobs <= 0) return hipSuccess;
-    dim3 grid(n_jobs);
-    switch (kLeafClasses[size_class]) {   // class value = n_max / 32
-        case 2: leaf_inverse_kernel<2, 2, 32><<<grid, dim3(1024), 0, s>>>(jobs_dev, damp_dev, info); break;
-        case 3: leaf_inverse_kernel<6, 3, 16><<<grid, dim3(512), 0, s>>>(jobs_dev, damp_dev, info); break;
-        case 4: leaf_inverse_kernel<8, 4, 16><<<grid, dim3(512), 0, s>>>(jobs_dev, damp_dev, info); break;
-        case 5: leaf_inverse_kernel<10, 5, 16><<<grid, dim3(512), 0, s>>>(jobs_dev, damp_dev, info); break;
-        case 7: leaf_inverse_kernel<14, 7, 16><<<grid, dim3(512), 0, s>>>(jobs_dev, damp_dev, info); break;
-        case 8: leaf_inverse_kernel<16, 8, 16><<<grid, dim3(512), 0, s>>>(jobs_dev, damp_dev, info); break;
-        case 9: leaf_inverse_kernel<18, 9, 16><<<grid, dim3(512), 0, s>>>(jobs_dev, damp_dev, info); break;
+    switch (kLeafClasses[size_class]) {   // class value = n_max / 32: 16, 32 or 48 tile slots
+        case 5: return launch_leaf_block<1>(jobs_dev, n_jobs, damp_dev, info, s);
+        case 7: return launch_leaf_block<2>(jobs_dev, n_jobs, damp_dev, info, s);
+        case 9: return launch_leaf_block<3>(jobs_dev, n_jobs, damp_dev, info, s);
         default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 }  // namespace kfac

@@ -44,7 +44,7 @@ struct Tunables {
         e = getenv("KFAC_INV_STREAMS");
         inv_streams = e ? std::min(4, std::max(1, atoi(e))) : 4;
         e = getenv("KFAC_REC_LEAF");
-        rec_leaf = e ? std::min(kLeafMax, std::max(32, atoi(e))) : 160;
+        rec_leaf = e ? std::min(kLeafMax, std::max(32, atoi(e))) : 288;
         e = getenv("KFAC_EARLY_N");
         early_n = e ? std::max(1, atoi(e)) : 2048;
         e = getenv("KFAC_STAGING_SLOTS");

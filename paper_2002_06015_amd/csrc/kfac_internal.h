@@ -76,7 +76,7 @@ struct CopyJob {    // dst[i][j] = src[i][j] + (i == j) * damp[damp_idx]
     int wg_start;
 };
 
-struct LeafJob {    // dst = (src + damp I)^-1 by in-register Gauss-Jordan, n <= 288
+struct LeafJob {    // dst = (src + damp I)^-1 inside one workgroup, n <= 288
     const float *src;
     float *dst;
     long long lds, ldd;
@@ -118,9 +118,9 @@ hipError_t launch_bn(const BnJob *jobs_dev, int n_jobs, int total_wgs, int N, fl
                      hipStream_t s);
 hipError_t launch_bn_reduce(const BnReduceJob *jobs_dev, int n_jobs, int total_wgs, int N, hipStream_t s);
 
-// leaf size classes: a class value B serves n <= 32*B
-static const int kLeafClasses[] = {2, 3, 4, 5, 7, 8, 9};
-static const int kNumLeafClasses = 7;
+// leaf size classes: a class value B serves n <= 32*B (one launch per class and level)
+static const int kLeafClasses[] = {5, 7, 9};
+static const int kNumLeafClasses = 3;
 static const int kLeafMax = 288;
 
 }  // namespace kfac

@@ -31,6 +31,43 @@ __device__ __forceinline__ void patch_plane(const PatchJob &J, int plane, int t0
     }
 }
 
+// The same with four outputs per lane and one 16-byte (fp32) or 8-byte (bf16) store: needs
+// h*w % 4 == 0 (so that a group of four starts aligned and stays inside the plane) and w >= 4
+// (so that it wraps to the next output row at most once).  ld is a multiple of 32.
+template <typename T>
+__device__ __forceinline__ void patch_plane_vec4(const PatchJob &J, int plane, int t0, int t1, int lane)
+{
+    typedef T vec4 __attribute__((ext_vector_type(4)));
+    const int n = plane / J.c_in, c = plane - n * J.c_in;
+    const T *src = (const T *)J.src + (long long)plane * J.h_in * J.w_in;
+    const int hw = J.h * J.w;
+    const int kk = J.k * J.k;
+    T *dst_row0 = (T *)J.dst + (long long)c * kk * J.ld + (long long)n * hw;
+    for (int t = t0 + 4 * lane; t < t1; t += 256) {
+        const int y0 = J.magic_w ? (int)__umulhi((unsigned)t, J.magic_w) : t / J.w;
+        const int x0 = t - y0 * J.w;
+        int iy[4], ix[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool wrap = x0 + e >= J.w;
+            iy[e] = (y0 + (wrap ? 1 : 0)) * J.stride - J.pad;
+            ix[e] = (x0 + e - (wrap ? J.w : 0)) * J.stride - J.pad;
+        }
+        for (int ky = 0; ky < J.k; ++ky)
+            for (int kx = 0; kx < J.k; ++kx) {
+                vec4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int yy = iy[e] + ky, xx = ix[e] + kx;
+                    T u = (T)0;
+                    if (yy >= 0 && yy < J.h_in && xx >= 0 && xx < J.w_in) u = src[yy * J.w_in + xx];
+                    v[e] = u;
+                }
+                __builtin_nontemporal_store(v, (vec4 *)(dst_row0 + (long long)(ky * J.k + kx) * J.ld + t));
+            }
+    }
+}
+
 __global__ __launch_bounds__(256) void patch_kernel(const PatchJob *__restrict__ jobs, int n_jobs)
 {
     const int wg = blockIdx.x;
@@ -62,8 +99,14 @@ __global__ __launch_bounds__(256) void patch_kernel(const PatchJob *__restrict__
     const int plane = (local / chunks) * 4 + (threadIdx.x >> 6);
     if (plane >= J.N * J.c_in) return;
     const int t0 = chunk * TCHUNK, t1 = min(hw, t0 + TCHUNK);
-    if (J.esize == 4) patch_plane<float>(J, plane, t0, t1, threadIdx.x & 63);
-    else              patch_plane<unsigned short>(J, plane, t0, t1, threadIdx.x & 63);
+    const bool vec = (hw & 3) == 0 && J.w >= 4 && (((uintptr_t)J.dst) & 15) == 0;   // TCHUNK is a multiple of 4
+    if (J.esize == 4) {
+        if (vec) patch_plane_vec4<float>(J, plane, t0, t1, threadIdx.x & 63);
+        else     patch_plane<float>(J, plane, t0, t1, threadIdx.x & 63);
+    } else {
+        if (vec) patch_plane_vec4<unsigned short>(J, plane, t0, t1, threadIdx.x & 63);
+        else     patch_plane<unsigned short>(J, plane, t0, t1, threadIdx.x & 63);
+    }
 }
 
 hipError_t launch_patch(const PatchJob *jobs_dev, int n_jobs, int total_wgs, hipStream_t s)
