@@ -192,7 +192,7 @@ def run_invert(layers, As, Gs, gamma):
 
 
 @pytest.mark.parametrize("dims", [(1, 1), (2, 3), (33, 17), (65, 32), (129, 64), (148, 96), (257, 160),
-                                  (224, 256), (289, 288), (577, 64), (700, 513), (1153, 321)])
+                                  (224, 256), (31, 161), (225, 32), (289, 288), (577, 64), (700, 513), (1153, 321)])
 def test_invert_matches_oracle(gpu, dims):
     dA, dG = dims
     layer = wl.fc_layer(4, dA, dG, bias=0)
@@ -211,6 +211,23 @@ def test_invert_matches_oracle(gpu, dims):
     da, dg = pir * gamma, gamma / pir
     assert np.abs((A.astype(np.float64) + da * np.eye(dA)) @ hAi - np.eye(dA)).max() <= 1e-3
     assert np.abs((G.astype(np.float64) + dg * np.eye(dG)) @ hGi - np.eye(dG)).max() <= 1e-3
+
+
+def test_invert_badly_scaled_diagonal(gpu):
+    """Rows/columns scaled over eight orders of magnitude: D X D with a well-conditioned X.
+    The inverse is D^-1 X^-1 D^-1; compared entry-wise after undoing the scaling."""
+    n = 200
+    rng = np.random.default_rng(77)
+    X = _spd(n, 901, cond=50.0, scale=1.0).astype(np.float64)
+    dsc = 10.0 ** rng.uniform(-4, 4, n)
+    A = (X * dsc[:, None] * dsc[None, :]).astype(np.float32)
+    G = _spd(64, 902, cond=10.0, scale=1.0)
+    layer = wl.fc_layer(4, n, 64, bias=0)
+    Ai, Gi, pi, info = run_invert([layer], [A], [G], 0.0)
+    assert not info.any()
+    ref = np.linalg.inv(A.astype(np.float64))
+    got = host(Ai[0])
+    assert relerr(got * dsc[:, None] * dsc[None, :], ref * dsc[:, None] * dsc[None, :]) <= 1e-3
 
 
 def test_invert_grouped_mixed_sizes(gpu):
