@@ -36,7 +36,7 @@ struct Tunables {
     Tunables()
     {
         const char *e = getenv("KFAC_TARGET_WGS");
-        target_wgs = e ? std::max(1, atoi(e)) : 256;
+        target_wgs = e ? std::max(1, atoi(e)) : 128;
         e = getenv("KFAC_MIN_K_SPLIT");
         min_k_per_split = e ? std::max(32, atoi(e) / 32 * 32) : 512;
         e = getenv("KFAC_MAX_K_PER_WG");
