@@ -1,0 +1,172 @@
+// The A factor of a 3x3 / stride 1 / pad 1 convolution without the patch matrix (Sec. 3.3,
+// Eq. 10 and 11 define A = 1/(N hw) sum_n M_A M_A^T with M_A = im2col).  Entry
+// ((c,ky,kx), (c',ky',kx')) of the sum is
+//     sum_n sum_{(y,x)} a_c(n, y+ky-1, x+kx-1) a_c'(n, y+ky'-1, x+kx'-1)     (a = 0 outside)
+// and, with u = (y+ky-1, x+kx-1) and D = (ky'-ky, kx'-kx), equals the full spatial
+// cross-correlation  C_D[c,c'] = sum_n sum_u a_c(n,u) a_c'(n,u+D)  except that
+//     ky = ky' = 2 leaves out the image row u_y = 0,   ky = ky' = 0 the row u_y = H-1,
+//     kx = kx' = 2 leaves out the column u_x = 0,      kx = kx' = 0 the column u_x = W-1
+// (every other bound on u coincides with u and u+D lying in the image).  So instead of the
+// 81 C^2 products of the patch Gram matrix, 13 displacements D (the other 12 are transposes)
+// are contracted over the image, plus corrections from the four border lines (1-D
+// correlations) and the four corners (inclusion-exclusion), all by the grouped GEMM kernel:
+//   - pad_kernel rewrites the activations as planes of (H+2) x (W+2) with two zero rows on
+//     top and two zero columns on the left of each plane.  Because the planes follow each
+//     other in memory, every position just outside an image (up to 2 away) is a zero of the
+//     same or the next plane, and a(n, u+D) is simply the element dy*(W+2)+dx further on: a
+//     shifted operand is the same buffer with an offset base pointer, no masks.
+//     It also extracts the border lines [C][N][L+pad] and corners [C][N] for the corrections.
+//   - assemble_kernel combines the 13 + 12 + 4 small Gram matrices into A (with the running
+//     average and the bias border, whose sums come from the GEMM_BORDER row sums).
+#include "kfac_internal.h"
+
+namespace kfac {
+
+typedef float corr_floatx4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void pad_kernel(const PadJob *__restrict__ jobs, int n_jobs)
+{
+    const int wg = blockIdx.x;
+    int lo = 0, hi = n_jobs;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (jobs[mid].wg_start <= wg) lo = mid; else hi = mid;
+    }
+    const PadJob &J = jobs[lo];
+    const long long idx = (long long)(wg - J.wg_start) * 256 + threadIdx.x;
+    const int H = J.H, W = J.W, Wp = W + 2, PP = (H + 2) * Wp;
+    const long long planes = (long long)J.N * J.C;
+    // part 1: the padded tensor including its zero slack in front and behind, 4 elements per thread
+    const long long n4 = J.padded_floats / 4;
+    if (idx < n4) {
+        corr_floatx4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const long long g = idx * 4 + e - J.front_slack;
+            float x = 0.f;
+            if (g >= 0 && g < planes * PP) {
+                const long long plane = g / PP;
+                const int r = (int)(g - plane * PP);
+                const int yp = r / Wp, xp = r - yp * Wp;
+                if (yp >= 2 && xp >= 2) x = J.src[plane * H * W + (long long)(yp - 2) * W + (xp - 2)];
+            }
+            v[e] = x;
+        }
+        *(corr_floatx4 *)(J.padded + idx * 4) = v;
+        return;
+    }
+    // part 2: border rows (top, bottom) [2][C][N][Lw], border columns (left, right) [2][C][N][Lh],
+    // corners [4][C][N]; every line is followed by at least two zeros
+    long long k = idx - n4;
+    const long long row_elems = (long long)J.C * J.N * J.Lw, col_elems = (long long)J.C * J.N * J.Lh;
+    if (k < 2 * row_elems + 4) {
+        float x = 0.f;
+        if (k < 2 * row_elems) {
+            const int which = (int)(k / row_elems);
+            const long long r = k - which * row_elems;
+            const int q = (int)(r % J.Lw);
+            const long long cn = r / J.Lw;
+            const int n = (int)(cn % J.N), c = (int)(cn / J.N);
+            if (q < W) x = J.src[((long long)n * J.C + c) * H * W + (long long)(which ? H - 1 : 0) * W + q];
+        }
+        J.rows[k] = x;
+        return;
+    }
+    k -= 2 * row_elems + 4;
+    if (k < 2 * col_elems + 4) {
+        float x = 0.f;
+        if (k < 2 * col_elems) {
+            const int which = (int)(k / col_elems);
+            const long long r = k - which * col_elems;
+            const int p = (int)(r % J.Lh);
+            const long long cn = r / J.Lh;
+            const int n = (int)(cn % J.N), c = (int)(cn / J.N);
+            if (p < H) x = J.src[((long long)n * J.C + c) * H * W + (long long)p * W + (which ? W - 1 : 0)];
+        }
+        J.cols[k] = x;
+        return;
+    }
+    k -= 2 * col_elems + 4;
+    if (k < 4LL * J.C * J.N) {
+        const int which = (int)(k / ((long long)J.C * J.N));
+        const long long r = k - (long long)which * J.C * J.N;
+        const int n = (int)(r % J.N), c = (int)(r / J.N);
+        const int p = (which & 2) ? H - 1 : 0, q = (which & 1) ? W - 1 : 0;
+        J.corners[k] = J.src[((long long)n * J.C + c) * H * W + (long long)p * W + q];
+    }
+}
+
+hipError_t launch_pad(const PadJob *jobs_dev, int n_jobs, int total_wgs, hipStream_t s)
+{
+    if (total_wgs <= 0) return hipSuccess;
+    pad_kernel<<<dim3(total_wgs), dim3(256), 0, s>>>(jobs_dev, n_jobs);
+    return hipGetLastError();
+}
+
+// Reads entry [c][c'] of the Gram matrix of displacement d >= 0 stored in g[d] (or, for
+// d < 0, entry [c'][c] of g[-d]: the correlation at -d is the transpose).
+__device__ __forceinline__ float corr_line(const float *const *g, const int *ld, int d, int c, int cp)
+{
+    return d >= 0 ? g[d][(long long)c * ld[d] + cp] : g[-d][(long long)cp * ld[-d] + c];
+}
+
+__global__ __launch_bounds__(256) void assemble_kernel(const AssembleJob *__restrict__ jobs, int n_jobs)
+{
+    const int wg = blockIdx.x;
+    int lo = 0, hi = n_jobs;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (jobs[mid].wg_start <= wg) lo = mid; else hi = mid;
+    }
+    const AssembleJob &J = jobs[lo];
+    const int d0 = 9 * J.C, dA = d0 + J.bias;
+    const long long idx = (long long)(wg - J.wg_start) * 256 + threadIdx.x;
+    if (idx >= (long long)dA * dA) return;
+    const int i = (int)(idx / dA), j = (int)(idx - (long long)i * dA);
+    float v;
+    if (i < d0 && j < d0) {
+        const int c = i / 9, k = i - 9 * c, ky = k / 3, kx = k - 3 * ky;
+        const int cp = j / 9, kp = j - 9 * cp, kyp = kp / 3, kxp = kp - 3 * kyp;
+        int dy = kyp - ky, dx = kxp - kx;
+        // full correlation: stored for dy > 0, or dy == 0 and dx >= 0
+        {
+            const bool fwd = dy > 0 || (dy == 0 && dx >= 0);
+            const int ey = fwd ? dy : -dy, ex = fwd ? dx : -dx;
+            const int slot = ey == 0 ? ex : 3 + (ey - 1) * 5 + (ex + 2);
+            const int a = fwd ? c : cp, b = fwd ? cp : c;
+            v = J.full[slot][(long long)a * J.ld_full[slot] + b];
+        }
+        const int row_out = (ky == kyp) ? (ky == 2 ? 0 : (ky == 0 ? 1 : -1)) : -1;   // 0: top row left out, 1: bottom
+        const int col_out = (kx == kxp) ? (kx == 2 ? 0 : (kx == 0 ? 1 : -1)) : -1;   // 0: left column, 1: right
+        if (row_out >= 0) v -= corr_line(J.rows[row_out], J.ld_rows[row_out], dx, c, cp);
+        if (col_out >= 0) v -= corr_line(J.cols[col_out], J.ld_cols[col_out], dy, c, cp);
+        if (row_out >= 0 && col_out >= 0) {
+            const int w = 2 * row_out + col_out;
+            v += J.corners[w][(long long)c * J.ld_corner + cp];
+        }
+    } else if (i == d0 && j == d0) {
+        v = J.count;
+    } else {
+        // bias border: the sum of the patch row (c, ky, kx) over all positions
+        const int r = i < d0 ? i : j;
+        const int c = r / 9, k = r - 9 * c, ky = k / 3, kx = k - 3 * ky;
+        const int row_out = ky == 2 ? 0 : (ky == 0 ? 1 : -1), col_out = kx == 2 ? 0 : (kx == 0 ? 1 : -1);
+        v = J.full[0][(long long)c * J.ld_full[0] + J.C];
+        if (row_out >= 0) v -= J.rows[row_out][0][(long long)c * J.ld_rows[row_out][0] + J.C];
+        if (col_out >= 0) v -= J.cols[col_out][0][(long long)c * J.ld_cols[col_out][0] + J.C];
+        if (row_out >= 0 && col_out >= 0) v += J.corners[2 * row_out + col_out][(long long)c * J.ld_corner + J.C];
+    }
+    float *out = J.A + (long long)i * J.ldA + j;
+    float r = J.alpha * v;
+    if (J.beta != 0.f) r = fmaf(J.beta, *out, r);
+    *out = r;
+}
+
+hipError_t launch_assemble(const AssembleJob *jobs_dev, int n_jobs, int total_wgs, hipStream_t s)
+{
+    if (total_wgs <= 0) return hipSuccess;
+    assemble_kernel<<<dim3(total_wgs), dim3(256), 0, s>>>(jobs_dev, n_jobs);
+    return hipGetLastError();
+}
+
+}  // namespace kfac

@@ -30,6 +30,7 @@ struct Tunables {
     int rec_leaf;        // the blocked inversion recurses down to blocks of at most this size
     int early_n;         // fused step: layers with a factor of at least this size are built first so
                          // that their inversion chains start while the other factors are still being built
+    int corr;            // 1: A factors of 3x3 / stride 1 / pad 1 convolutions through spatial correlations
     int slots;           // staging slots in use (2..kSlots): a call waits until the device has started the
                          // call `slots` calls back.  Measured: letting the host run further ahead than a
                          // couple of calls makes the chains of small launches slower, not faster.
@@ -47,6 +48,8 @@ struct Tunables {
         rec_leaf = e ? std::min(kLeafMax, std::max(32, atoi(e))) : 288;
         e = getenv("KFAC_EARLY_N");
         early_n = e ? std::max(1, atoi(e)) : 2048;
+        e = getenv("KFAC_CORR");
+        corr = e ? (atoi(e) != 0) : 1;
         e = getenv("KFAC_STAGING_SLOTS");
         slots = e ? std::min(kSlots, std::max(2, atoi(e))) : 2;
     }
@@ -108,7 +111,7 @@ struct Tables {
     }
 };
 
-enum LaunchKind { L_GEMM, L_REDUCE, L_PATCH, L_TRACE, L_COPY, L_LEAF, L_ZERO, L_BN, L_BNRED,
+enum LaunchKind { L_GEMM, L_REDUCE, L_PATCH, L_TRACE, L_COPY, L_LEAF, L_ZERO, L_BN, L_BNRED, L_PAD, L_ASSEMBLE,
                   L_RECORD, L_WAIT };   // stream ordering: record / wait for sync event `n` on `stream`
 
 struct Launch {
@@ -357,9 +360,11 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
     const int chunk = a.in == KFAC_BF16 ? 8 : 4;
     const size_t chunk_align = a.in == KFAC_BF16 ? 16 : 4;
     std::vector<PatchJob> pjobs;
+    std::vector<PadJob> padjobs;
+    std::vector<AssembleJob> asmjobs;
     std::vector<GemmProblem> probs;
-    int patch_wgs = 0;
-    double patch_bytes = 0;
+    int patch_wgs = 0, pad_wgs = 0, asm_wgs = 0;
+    double patch_bytes = 0, pad_bytes = 0;
     // An NCHW tensor [N, c, hw] is contracted in place when its runs are whole chunks; otherwise (and for every k > 1 / strided / padded layer) it is first rewritten
     // as [c k^2][ld] with the contraction index contiguous.
     auto operand_for = [&](const void *src, int N, int c, int k, int stride, int pad, int h_in, int w_in, int h,
@@ -400,7 +405,76 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         const int K = Ly.N * hw;
         const bool want_A = dry || (a.act && a.act[l]);
         const bool want_G = dry || (a.grad_out && a.grad_out[l]);
-        if (want_A) {
+        // 3x3 / stride 1 / pad 1 in fp32: 13 displaced correlations of the zero-padded image instead
+        // of the 81 C^2 products of the patch Gram matrix, if the padding does not eat the gain
+        const bool corr = tun.corr && a.in == KFAC_F32 && Ly.k == 3 && Ly.stride == 1 && Ly.pad == 1 && h >= 3 &&
+                          w >= 3 && ((h + 2) * (w + 2)) % 4 == 0 && 2 * (h + 2) * (w + 2) <= 3 * hw;
+        if (want_A && corr) {
+            const int C = Ly.c_in, N = Ly.N, Wp = w + 2, PP = (h + 2) * Wp;
+            const int Lw = (int)align_up((size_t)w + 2, 4), Lh = (int)align_up((size_t)h + 2, 4);
+            PadJob J{};
+            J.src = dry ? nullptr : (const float *)a.act[l];
+            J.front_slack = (int)align_up((size_t)2 * Wp + 2, 4);
+            J.padded_floats = (long long)J.front_slack + (long long)N * C * PP + (long long)align_up((size_t)2 * Wp + 2, 4) + 4;
+            J.padded = (float *)arena.take((size_t)J.padded_floats * sizeof(float));
+            J.rows = (float *)arena.take(((size_t)2 * C * N * Lw + 4) * sizeof(float));
+            J.cols = (float *)arena.take(((size_t)2 * C * N * Lh + 4) * sizeof(float));
+            J.corners = (float *)arena.take(((size_t)4 * C * N + 4) * sizeof(float));
+            J.N = N; J.C = C; J.H = h; J.W = w; J.Lw = Lw; J.Lh = Lh;
+            J.wg_start = pad_wgs;
+            const long long threads = J.padded_floats / 4 + (2LL * C * N * Lw + 4) + (2LL * C * N * Lh + 4) + 4LL * C * N;
+            pad_wgs += (int)((threads + 255) / 256);
+            pad_bytes += 4.0 * ((double)N * C * hw + (double)J.padded_floats);
+            padjobs.push_back(J);
+
+            AssembleJob S{};
+            S.A = dry ? nullptr : a.A_ema[l];
+            S.ldA = dA; S.C = C; S.bias = Ly.bias;
+            S.alpha = (float)((1.0 - (double)a.decay) / ((double)N * (double)hw));
+            S.beta = a.decay;
+            S.count = (float)((double)N * (double)hw);
+            S.wg_start = asm_wgs;
+            asm_wgs += (int)(((long long)dA * dA + 255) / 256);
+            // one Gram matrix per contraction; those with displacement 0 are symmetric and carry the row sums
+            auto gram = [&](const Operand &oa, const Operand &ob, int K, bool zero_shift, const float **out, int *ld) {
+                GemmProblem P{};
+                P.a = oa; P.b = ob;
+                const int ldc = zero_shift ? C + 1 : C;
+                P.C = (float *)arena.take((size_t)ldc * ldc * sizeof(float));
+                P.Ct = nullptr; P.ldc = ldc;
+                P.M = C; P.N = C; P.K = K;
+                P.flags = zero_shift ? (GEMM_SYM | GEMM_BORDER) : 0;
+                P.alpha = 1.f; P.beta = 0.f;
+                P.tile_cfg = choose_tile_cfg(C, C, K, zero_shift);
+                finish_problem(P);
+                probs.push_back(P);
+                *out = P.C; *ld = ldc;
+            };
+            Operand img{};
+            img.base = J.padded + J.front_slack;
+            img.row_stride = PP; img.batch_stride = (long long)C * PP; img.rows = C; img.hw = PP;
+            for (int slot = 0; slot < 13; ++slot) {
+                const int dy = slot < 3 ? 0 : (slot - 3) / 5 + 1, dx = slot < 3 ? slot : (slot - 3) % 5 - 2;
+                Operand sh = img;
+                sh.base = (const float *)img.base + dy * Wp + dx;
+                gram(img, sh, N * PP, slot == 0, &S.full[slot], &S.ld_full[slot]);
+            }
+            for (int which = 0; which < 2; ++which)
+                for (int d = 0; d < 3; ++d) {
+                    const float *rb = J.rows + (size_t)which * C * N * Lw, *cb = J.cols + (size_t)which * C * N * Lh;
+                    gram(plain_operand(rb, (long long)N * Lw, C, N * Lw), plain_operand(rb + d, (long long)N * Lw, C, N * Lw),
+                         N * Lw, d == 0, &S.rows[which][d], &S.ld_rows[which][d]);
+                    gram(plain_operand(cb, (long long)N * Lh, C, N * Lh), plain_operand(cb + d, (long long)N * Lh, C, N * Lh),
+                         N * Lh, d == 0, &S.cols[which][d], &S.ld_cols[which][d]);
+                }
+            for (int wc = 0; wc < 4; ++wc) {
+                const float *kb = J.corners + (size_t)wc * C * N;
+                int ld = 0;
+                gram(plain_operand(kb, N, C, N), plain_operand(kb, N, C, N), N, true, &S.corners[wc], &ld);
+                S.ld_corner = ld;
+            }
+            asmjobs.push_back(S);
+        } else if (want_A) {
             Operand op = operand_for(dry ? nullptr : a.act[l], Ly.N, Ly.c_in, Ly.k, Ly.stride, Ly.pad, Ly.h_in,
                                      Ly.w_in, h, w);
             // the bias row of the patch matrix is not multiplied out: the border of A comes
@@ -444,7 +518,24 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         L.bytes = patch_bytes;
         plan.launches.push_back(L);
     }
+    if (!padjobs.empty()) {
+        Launch L{};
+        L.kind = L_PAD;
+        L.off_a = plan.tab.add(padjobs.data(), padjobs.size() * sizeof(PadJob));
+        L.n = (int)padjobs.size();
+        L.total_wgs = pad_wgs;
+        L.bytes = pad_bytes;
+        plan.launches.push_back(L);
+    }
     emit_gemm_phase(plan, arena, tun, probs, a.in == KFAC_BF16 ? 1 : 0, true);
+    if (!asmjobs.empty()) {
+        Launch L{};
+        L.kind = L_ASSEMBLE;
+        L.off_a = plan.tab.add(asmjobs.data(), asmjobs.size() * sizeof(AssembleJob));
+        L.n = (int)asmjobs.size();
+        L.total_wgs = asm_wgs;
+        plan.launches.push_back(L);
+    }
 }
 
 // ---------------------------------------------------------------- inversion planner
@@ -940,6 +1031,8 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 case L_ZERO: pe.kernel = KFAC_K_ZERO; break;
                 case L_BN: pe.kernel = KFAC_K_BN_UNIT; break;
                 case L_BNRED: pe.kernel = KFAC_K_BN_REDUCE; break;
+                case L_PAD: pe.kernel = KFAC_K_PAD; break;
+                case L_ASSEMBLE: pe.kernel = KFAC_K_ASSEMBLE; break;
                 case L_RECORD: case L_WAIT: break;
             }
             pe.variant = (L.kind == L_GEMM || L.kind == L_LEAF) ? L.cfg : 0;
@@ -961,6 +1054,12 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 break;
             case L_PATCH:
                 e = launch_patch((const PatchJob *)(tab_dev + L.off_a), L.n, L.total_wgs, ls);
+                break;
+            case L_PAD:
+                e = launch_pad((const PadJob *)(tab_dev + L.off_a), L.n, L.total_wgs, ls);
+                break;
+            case L_ASSEMBLE:
+                e = launch_assemble((const AssembleJob *)(tab_dev + L.off_a), L.n, L.total_wgs, ls);
                 break;
             case L_TRACE:
                 e = launch_trace((const TraceJob *)(tab_dev + L.off_a), L.n, L.f0, (float *)L.p0, (float *)L.p1, ls);

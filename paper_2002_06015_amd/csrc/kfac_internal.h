@@ -60,6 +60,38 @@ struct PatchJob {
     int wg_start;     // first workgroup of this job in the grouped launch
 };
 
+// ---- A factor of 3x3 convolutions through spatial correlations (corr.hip) -------------
+struct PadJob {
+    const float *src;        // [N, C, H, W]
+    float *padded;           // start of the allocation: front slack, N*C planes of (H+2)*(W+2), back slack
+    long long padded_floats; // size of that allocation (multiple of 4)
+    int front_slack;         // floats before the first plane (multiple of 4)
+    float *rows;             // [2][C][N][Lw] top / bottom image row, then 4 zeros
+    float *cols;             // [2][C][N][Lh] left / right image column, then 4 zeros
+    float *corners;          // [4][C][N]: (top,left), (top,right), (bottom,left), (bottom,right)
+    int N, C, H, W, Lw, Lh;
+    int wg_start;
+};
+
+struct AssembleJob {
+    // Gram matrices of the contractions, [c][c'] with the leading dimensions given; those of
+    // displacement 0 carry the GEMM_BORDER column (row sums) at index C
+    const float *full[13];   // displacement (dy,dx): slot dx for dy = 0 (dx = 0..2), 3 + 5(dy-1) + dx+2 for dy = 1, 2
+    int ld_full[13];
+    const float *rows[2][3]; // [top, bottom][dx = 0..2]
+    int ld_rows[2][3];
+    const float *cols[2][3]; // [left, right][dy = 0..2]
+    int ld_cols[2][3];
+    const float *corners[4]; // all with the border column
+    int ld_corner;
+    float *A;                // [9C + bias][ldA]
+    long long ldA;
+    int C, bias;
+    float alpha, beta;       // A = alpha * sums + beta * A
+    float count;             // N * h * w: the sum of the all-ones bias row with itself
+    int wg_start;
+};
+
 // ---- inversion ---------------------------------------------------------------------
 struct TraceJob {   // one per layer
     const float *A, *G;
@@ -107,6 +139,8 @@ hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, 
 hipError_t launch_gemm_reduce(const GemmProblem *probs_dev, const int *red_start_dev, int n_probs,
                               int total_wgs, hipStream_t s);
 hipError_t launch_patch(const PatchJob *jobs_dev, int n_jobs, int total_wgs, hipStream_t s);
+hipError_t launch_pad(const PadJob *jobs_dev, int n_jobs, int total_wgs, hipStream_t s);
+hipError_t launch_assemble(const AssembleJob *jobs_dev, int n_jobs, int total_wgs, hipStream_t s);
 hipError_t launch_trace(const TraceJob *jobs_dev, int n_layers, float gamma, float *damp_dev,
                         float *pi_out, hipStream_t s);
 hipError_t launch_copy_damp(const CopyJob *jobs_dev, int n_jobs, int total_wgs, const float *damp_dev,

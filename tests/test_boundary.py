@@ -49,9 +49,10 @@ def test_workspace_bytes():
     c2 = kfac.kfac_workspace_bytes(wl.config_layers(2))
     c4 = kfac.kfac_workspace_bytes(wl.config_layers(4))
     assert 0 < small < c2 < c4 < 16 * 2 ** 30
-    # patches of the 3x3 layer (576 x 100352 fp32) must fit
-    assert c2 >= 576 * 100352 * 4
-    assert kfac.kfac_workspace_bytes(wl.config_layers(2), kfac.KFAC_BF16) < c2
+    # fp32: the zero-padded image of the 3x3 layer (32 x 64 planes of 58 x 58) must fit; the
+    # patch matrix is not built.  bf16: patches (576 x 100352 bf16) must fit
+    assert 32 * 64 * 58 * 58 * 4 <= c2 < 576 * 100352 * 4
+    assert kfac.kfac_workspace_bytes(wl.config_layers(2), kfac.KFAC_BF16) >= 576 * 100352 * 2
 
 
 def _fake_ctx(nbytes=1 << 20):
@@ -146,7 +147,7 @@ def test_calls_reject_bad_arguments_without_a_gpu():
 
 
 def test_workspace_too_small_is_reported_before_launch():
-    """The 3x3 layer of configuration 2 needs a 231 MB patch buffer; a 1 MB workspace is refused."""
+    """The 3x3 layer of configuration 2 needs tens of MB of scratch; a 1 MB workspace is refused."""
     L = kfac.lib()
     h = _fake_ctx(1 << 20)
     lay = kfac.kfac_layer(*wl.config_layers(2)[0])
