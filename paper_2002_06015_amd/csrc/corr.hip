@@ -10,10 +10,10 @@
 // 81 C^2 products of the patch Gram matrix, 13 displacements D (the other 12 are transposes)
 // are contracted over the image, plus corrections from the four border lines (1-D
 // correlations) and the four corners (inclusion-exclusion), all by the grouped GEMM kernel:
-//   - pad_kernel rewrites the activations as planes of (H+2) x (W+2) with two zero rows on
+//   - pad_kernel rewrites the activations as planes of Hp x Wp with (at least) two zero rows on
 //     top and two zero columns on the left of each plane.  Because the planes follow each
 //     other in memory, every position just outside an image (up to 2 away) is a zero of the
-//     same or the next plane, and a(n, u+D) is simply the element dy*(W+2)+dx further on: a
+//     same or the next plane, and a(n, u+D) is simply the element dy*Wp+dx further on: a
 //     shifted operand is the same buffer with an offset base pointer, no masks.
 //     It also extracts the border lines [C][N][L+pad] and corners [C][N] for the corrections.
 //   - assemble_kernel combines the 13 + 12 + 4 small Gram matrices into A (with the running
@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void pad_kernel(const PadJob *__restrict__ job
     }
     const PadJob &J = jobs[lo];
     const long long idx = (long long)(wg - J.wg_start) * 256 + threadIdx.x;
-    const int H = J.H, W = J.W, Wp = W + 2, PP = (H + 2) * Wp;
+    const int H = J.H, W = J.W, Wp = J.Wp, PP = J.Hp * Wp, y0 = J.Hp - H, x0 = Wp - W;
     const long long planes = (long long)J.N * J.C;
     // part 1: the padded tensor including its zero slack in front and behind, 4 elements per thread
     const long long n4 = J.padded_floats / 4;
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256) void pad_kernel(const PadJob *__restrict__ job
                 const long long plane = g / PP;
                 const int r = (int)(g - plane * PP);
                 const int yp = r / Wp, xp = r - yp * Wp;
-                if (yp >= 2 && xp >= 2) x = J.src[plane * H * W + (long long)(yp - 2) * W + (xp - 2)];
+                if (yp >= y0 && xp >= x0) x = J.src[plane * H * W + (long long)(yp - y0) * W + (xp - x0)];
             }
             v[e] = x;
         }
@@ -103,11 +103,57 @@ hipError_t launch_pad(const PadJob *jobs_dev, int n_jobs, int total_wgs, hipStre
     return hipGetLastError();
 }
 
-// Reads entry [c][c'] of the Gram matrix of displacement d >= 0 stored in g[d] (or, for
-// d < 0, entry [c'][c] of g[-d]: the correlation at -d is the transpose).
-__device__ __forceinline__ float corr_line(const float *const *g, const int *ld, int d, int c, int cp)
+// One workgroup per row i = (c, ky, kx) of A (plus one for the bias row), threads along the row.
+// Which Gram matrices entry (c', ky', kx') comes from depends only on (ky, kx, ky', kx'): the
+// workgroup first builds that table of 9 entries.  A displacement that is stored the other way
+// round is read from the transposed copy the GEMM wrote alongside, so every read is along a
+// row of a Gram matrix and every write along the row of A.
+struct CorrSource {
+    const float *full, *row, *col, *corner;   // row / col / corner: null if no such correction
+    int ld_full, ld_row, ld_col;
+};
+
+__device__ __forceinline__ CorrSource corr_source(const AssembleJob &J, int ky, int kx, int kyp, int kxp)
 {
-    return d >= 0 ? g[d][(long long)c * ld[d] + cp] : g[-d][(long long)cp * ld[-d] + c];
+    CorrSource S{};
+    const int dy = kyp - ky, dx = kxp - kx;
+    const bool fwd = dy > 0 || (dy == 0 && dx >= 0);
+    const int ey = fwd ? dy : -dy, ex = fwd ? dx : -dx;
+    const int slot = ey == 0 ? ex : 3 + (ey - 1) * 5 + (ex + 2);
+    S.full = fwd ? J.full[slot] : J.full_t[slot];
+    S.ld_full = J.ld_full[slot];
+    const int row_out = (ky == kyp) ? (ky == 2 ? 0 : (ky == 0 ? 1 : -1)) : -1;   // 0: top row left out, 1: bottom
+    const int col_out = (kx == kxp) ? (kx == 2 ? 0 : (kx == 0 ? 1 : -1)) : -1;   // 0: left column, 1: right
+    if (row_out >= 0) {
+        const int d = dx >= 0 ? dx : -dx;
+        S.row = dx >= 0 ? J.rows[row_out][d] : J.rows_t[row_out][d];
+        S.ld_row = J.ld_rows[row_out][d];
+    }
+    if (col_out >= 0) {
+        const int d = dy >= 0 ? dy : -dy;
+        S.col = dy >= 0 ? J.cols[col_out][d] : J.cols_t[col_out][d];
+        S.ld_col = J.ld_cols[col_out][d];
+    }
+    if (row_out >= 0 && col_out >= 0) S.corner = J.corners[2 * row_out + col_out];
+    return S;
+}
+
+// sum of the patch row (c, ky, kx) over all positions: the bias border
+__device__ __forceinline__ float corr_row_sum(const AssembleJob &J, int c, int ky, int kx)
+{
+    const int row_out = ky == 2 ? 0 : (ky == 0 ? 1 : -1), col_out = kx == 2 ? 0 : (kx == 0 ? 1 : -1);
+    float v = J.full[0][(long long)c * J.ld_full[0] + J.C];
+    if (row_out >= 0) v -= J.rows[row_out][0][(long long)c * J.ld_rows[row_out][0] + J.C];
+    if (col_out >= 0) v -= J.cols[col_out][0][(long long)c * J.ld_cols[col_out][0] + J.C];
+    if (row_out >= 0 && col_out >= 0) v += J.corners[2 * row_out + col_out][(long long)c * J.ld_corner + J.C];
+    return v;
+}
+
+__device__ __forceinline__ void corr_store(const AssembleJob &J, float *out, float v)
+{
+    float r = J.alpha * v;
+    if (J.beta != 0.f) r = fmaf(J.beta, *out, r);
+    *out = r;
 }
 
 __global__ __launch_bounds__(256) void assemble_kernel(const AssembleJob *__restrict__ jobs, int n_jobs)
@@ -119,47 +165,31 @@ __global__ __launch_bounds__(256) void assemble_kernel(const AssembleJob *__rest
         if (jobs[mid].wg_start <= wg) lo = mid; else hi = mid;
     }
     const AssembleJob &J = jobs[lo];
-    const int d0 = 9 * J.C, dA = d0 + J.bias;
-    const long long idx = (long long)(wg - J.wg_start) * 256 + threadIdx.x;
-    if (idx >= (long long)dA * dA) return;
-    const int i = (int)(idx / dA), j = (int)(idx - (long long)i * dA);
-    float v;
-    if (i < d0 && j < d0) {
+    const int d0 = 9 * J.C;
+    const int i = wg - J.wg_start;          // row of A
+    float *out_row = J.A + (long long)i * J.ldA;
+    if (i < d0) {
         const int c = i / 9, k = i - 9 * c, ky = k / 3, kx = k - 3 * ky;
-        const int cp = j / 9, kp = j - 9 * cp, kyp = kp / 3, kxp = kp - 3 * kyp;
-        int dy = kyp - ky, dx = kxp - kx;
-        // full correlation: stored for dy > 0, or dy == 0 and dx >= 0
-        {
-            const bool fwd = dy > 0 || (dy == 0 && dx >= 0);
-            const int ey = fwd ? dy : -dy, ex = fwd ? dx : -dx;
-            const int slot = ey == 0 ? ex : 3 + (ey - 1) * 5 + (ex + 2);
-            const int a = fwd ? c : cp, b = fwd ? cp : c;
-            v = J.full[slot][(long long)a * J.ld_full[slot] + b];
+        __shared__ CorrSource src[9];
+        if (threadIdx.x < 9) src[threadIdx.x] = corr_source(J, ky, kx, threadIdx.x / 3, threadIdx.x % 3);
+        __syncthreads();
+        for (int j = threadIdx.x; j < d0; j += 256) {
+            const int cp = j / 9, kp = j - 9 * cp;
+            const CorrSource S = src[kp];
+            float v = S.full[(long long)c * S.ld_full + cp];
+            if (S.row) v -= S.row[(long long)c * S.ld_row + cp];
+            if (S.col) v -= S.col[(long long)c * S.ld_col + cp];
+            if (S.corner) v += S.corner[(long long)c * J.ld_corner + cp];
+            corr_store(J, out_row + j, v);
         }
-        const int row_out = (ky == kyp) ? (ky == 2 ? 0 : (ky == 0 ? 1 : -1)) : -1;   // 0: top row left out, 1: bottom
-        const int col_out = (kx == kxp) ? (kx == 2 ? 0 : (kx == 0 ? 1 : -1)) : -1;   // 0: left column, 1: right
-        if (row_out >= 0) v -= corr_line(J.rows[row_out], J.ld_rows[row_out], dx, c, cp);
-        if (col_out >= 0) v -= corr_line(J.cols[col_out], J.ld_cols[col_out], dy, c, cp);
-        if (row_out >= 0 && col_out >= 0) {
-            const int w = 2 * row_out + col_out;
-            v += J.corners[w][(long long)c * J.ld_corner + cp];
-        }
-    } else if (i == d0 && j == d0) {
-        v = J.count;
+        if (J.bias && threadIdx.x == 0) corr_store(J, out_row + d0, corr_row_sum(J, c, ky, kx));
     } else {
-        // bias border: the sum of the patch row (c, ky, kx) over all positions
-        const int r = i < d0 ? i : j;
-        const int c = r / 9, k = r - 9 * c, ky = k / 3, kx = k - 3 * ky;
-        const int row_out = ky == 2 ? 0 : (ky == 0 ? 1 : -1), col_out = kx == 2 ? 0 : (kx == 0 ? 1 : -1);
-        v = J.full[0][(long long)c * J.ld_full[0] + J.C];
-        if (row_out >= 0) v -= J.rows[row_out][0][(long long)c * J.ld_rows[row_out][0] + J.C];
-        if (col_out >= 0) v -= J.cols[col_out][0][(long long)c * J.ld_cols[col_out][0] + J.C];
-        if (row_out >= 0 && col_out >= 0) v += J.corners[2 * row_out + col_out][(long long)c * J.ld_corner + J.C];
+        // the bias row
+        for (int j = threadIdx.x; j <= d0; j += 256) {
+            const int c = j / 9, k = j - 9 * c;
+            corr_store(J, out_row + j, j < d0 ? corr_row_sum(J, c, k / 3, k % 3) : J.count);
+        }
     }
-    float *out = J.A + (long long)i * J.ldA + j;
-    float r = J.alpha * v;
-    if (J.beta != 0.f) r = fmaf(J.beta, *out, r);
-    *out = r;
 }
 
 hipError_t launch_assemble(const AssembleJob *jobs_dev, int n_jobs, int total_wgs, hipStream_t s)

@@ -407,10 +407,16 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         const bool want_G = dry || (a.grad_out && a.grad_out[l]);
         // 3x3 / stride 1 / pad 1 in fp32: 13 displaced correlations of the zero-padded image instead
         // of the 81 C^2 products of the patch Gram matrix, if the padding does not eat the gain
+        // (at least two zero rows above and two zero columns left of every image; a few more if that
+        // is what makes the padded plane a whole number of 16-byte chunks; 26 PP < 81 hw flops-wise)
+        int Hp = 0, Wp = 0;
+        for (int eh = 2; eh <= 5; ++eh)
+            for (int ew = 2; ew <= 5; ++ew)
+                if (((h + eh) * (w + ew)) % 4 == 0 && (Hp == 0 || (h + eh) * (w + ew) < Hp * Wp)) { Hp = h + eh; Wp = w + ew; }
         const bool corr = tun.corr && a.in == KFAC_F32 && Ly.k == 3 && Ly.stride == 1 && Ly.pad == 1 && h >= 3 &&
-                          w >= 3 && ((h + 2) * (w + 2)) % 4 == 0 && 2 * (h + 2) * (w + 2) <= 3 * hw;
+                          w >= 3 && 2 * Hp * Wp <= 5 * hw;
         if (want_A && corr) {
-            const int C = Ly.c_in, N = Ly.N, Wp = w + 2, PP = (h + 2) * Wp;
+            const int C = Ly.c_in, N = Ly.N, PP = Hp * Wp;
             const int Lw = (int)align_up((size_t)w + 2, 4), Lh = (int)align_up((size_t)h + 2, 4);
             PadJob J{};
             J.src = dry ? nullptr : (const float *)a.act[l];
@@ -420,7 +426,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             J.rows = (float *)arena.take(((size_t)2 * C * N * Lw + 4) * sizeof(float));
             J.cols = (float *)arena.take(((size_t)2 * C * N * Lh + 4) * sizeof(float));
             J.corners = (float *)arena.take(((size_t)4 * C * N + 4) * sizeof(float));
-            J.N = N; J.C = C; J.H = h; J.W = w; J.Lw = Lw; J.Lh = Lh;
+            J.N = N; J.C = C; J.H = h; J.W = w; J.Hp = Hp; J.Wp = Wp; J.Lw = Lw; J.Lh = Lh;
             J.wg_start = pad_wgs;
             const long long threads = J.padded_floats / 4 + (2LL * C * N * Lw + 4) + (2LL * C * N * Lh + 4) + 4LL * C * N;
             pad_wgs += (int)((threads + 255) / 256);
@@ -434,14 +440,17 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             S.beta = a.decay;
             S.count = (float)((double)N * (double)hw);
             S.wg_start = asm_wgs;
-            asm_wgs += (int)(((long long)dA * dA + 255) / 256);
+            asm_wgs += dA;   // one workgroup per row of A
             // one Gram matrix per contraction; those with displacement 0 are symmetric and carry the row sums
-            auto gram = [&](const Operand &oa, const Operand &ob, int K, bool zero_shift, const float **out, int *ld) {
+            auto gram = [&](const Operand &oa, const Operand &ob, int K, bool zero_shift, const float **out,
+                            const float **out_t, int *ld) {
                 GemmProblem P{};
                 P.a = oa; P.b = ob;
                 const int ldc = zero_shift ? C + 1 : C;
                 P.C = (float *)arena.take((size_t)ldc * ldc * sizeof(float));
-                P.Ct = nullptr; P.ldc = ldc;
+                P.ldc = ldc;
+                P.Ct = zero_shift ? nullptr : (float *)arena.take((size_t)ldc * ldc * sizeof(float));
+                P.ldct = ldc;
                 P.M = C; P.N = C; P.K = K;
                 P.flags = zero_shift ? (GEMM_SYM | GEMM_BORDER) : 0;
                 P.alpha = 1.f; P.beta = 0.f;
@@ -449,6 +458,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
                 finish_problem(P);
                 probs.push_back(P);
                 *out = P.C; *ld = ldc;
+                if (out_t) *out_t = zero_shift ? P.C : P.Ct;
             };
             Operand img{};
             img.base = J.padded + J.front_slack;
@@ -457,20 +467,20 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
                 const int dy = slot < 3 ? 0 : (slot - 3) / 5 + 1, dx = slot < 3 ? slot : (slot - 3) % 5 - 2;
                 Operand sh = img;
                 sh.base = (const float *)img.base + dy * Wp + dx;
-                gram(img, sh, N * PP, slot == 0, &S.full[slot], &S.ld_full[slot]);
+                gram(img, sh, N * PP, slot == 0, &S.full[slot], &S.full_t[slot], &S.ld_full[slot]);
             }
             for (int which = 0; which < 2; ++which)
                 for (int d = 0; d < 3; ++d) {
                     const float *rb = J.rows + (size_t)which * C * N * Lw, *cb = J.cols + (size_t)which * C * N * Lh;
                     gram(plain_operand(rb, (long long)N * Lw, C, N * Lw), plain_operand(rb + d, (long long)N * Lw, C, N * Lw),
-                         N * Lw, d == 0, &S.rows[which][d], &S.ld_rows[which][d]);
+                         N * Lw, d == 0, &S.rows[which][d], &S.rows_t[which][d], &S.ld_rows[which][d]);
                     gram(plain_operand(cb, (long long)N * Lh, C, N * Lh), plain_operand(cb + d, (long long)N * Lh, C, N * Lh),
-                         N * Lh, d == 0, &S.cols[which][d], &S.ld_cols[which][d]);
+                         N * Lh, d == 0, &S.cols[which][d], &S.cols_t[which][d], &S.ld_cols[which][d]);
                 }
             for (int wc = 0; wc < 4; ++wc) {
                 const float *kb = J.corners + (size_t)wc * C * N;
                 int ld = 0;
-                gram(plain_operand(kb, N, C, N), plain_operand(kb, N, C, N), N, true, &S.corners[wc], &ld);
+                gram(plain_operand(kb, N, C, N), plain_operand(kb, N, C, N), N, true, &S.corners[wc], nullptr, &ld);
                 S.ld_corner = ld;
             }
             asmjobs.push_back(S);

@@ -63,24 +63,30 @@ struct PatchJob {
 // ---- A factor of 3x3 convolutions through spatial correlations (corr.hip) -------------
 struct PadJob {
     const float *src;        // [N, C, H, W]
-    float *padded;           // start of the allocation: front slack, N*C planes of (H+2)*(W+2), back slack
+    float *padded;           // start of the allocation: front slack, N*C planes of Hp*Wp, back slack
     long long padded_floats; // size of that allocation (multiple of 4)
     int front_slack;         // floats before the first plane (multiple of 4)
     float *rows;             // [2][C][N][Lw] top / bottom image row, then 4 zeros
     float *cols;             // [2][C][N][Lh] left / right image column, then 4 zeros
     float *corners;          // [4][C][N]: (top,left), (top,right), (bottom,left), (bottom,right)
     int N, C, H, W, Lw, Lh;
+    int Hp, Wp;              // padded plane: Hp - H >= 2 zero rows on top, Wp - W >= 2 zero columns on the left
     int wg_start;
 };
 
 struct AssembleJob {
     // Gram matrices of the contractions, [c][c'] with the leading dimensions given; those of
     // displacement 0 carry the GEMM_BORDER column (row sums) at index C
+    // (the *_t pointers are the transposed copies, same leading dimensions; for displacement 0
+    // they are the matrices themselves)
     const float *full[13];   // displacement (dy,dx): slot dx for dy = 0 (dx = 0..2), 3 + 5(dy-1) + dx+2 for dy = 1, 2
+    const float *full_t[13];
     int ld_full[13];
     const float *rows[2][3]; // [top, bottom][dx = 0..2]
+    const float *rows_t[2][3];
     int ld_rows[2][3];
     const float *cols[2][3]; // [left, right][dy = 0..2]
+    const float *cols_t[2][3];
     int ld_cols[2][3];
     const float *corners[4]; // all with the border column
     int ld_corner;
