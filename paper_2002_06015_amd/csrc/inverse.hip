@@ -123,16 +123,53 @@ __device__ __forceinline__ float lb_readlane(float x, int lane)
 // form) are LDS panel rows; each half-wave takes 16 of the 32 k (the same for both operands).
 __device__ __forceinline__ void lb_mma32(lb_floatx16 &acc, const float *pa, const float *pb)
 {
-    lb_floatx4 fa[4], fb[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        fa[q] = *(const lb_floatx4 *)(pa + 4 * q);
-        fb[q] = *(const lb_floatx4 *)(pb + 4 * q);
+        const lb_floatx4 fa = *(const lb_floatx4 *)(pa + 4 * q);
+        const lb_floatx4 fb = *(const lb_floatx4 *)(pb + 4 * q);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[e], fb[e], acc, 0, 0, 0);
     }
+}
+
+// Scalar sweep of the 32x32 diagonal tile of block k inside the wavefront that holds it
+// (register slot `slot`): leaves D = (-N_kk)^-1 in the slot and in Dl.  Returns the 1-based
+// index (within the matrix) of the first non-positive pivot, or 0.
+template <int NSLOT>
+__device__ __forceinline__ int lb_sweep_diag(lb_floatx16 (&acc)[NSLOT], int slot, int k, int l32, int h, float *Dl)
+{
+    lb_floatx16 sg;
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+    for (int v = 0; v < 16; ++v) {
+        float x = acc[0][v];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[q][e], fb[q][e], acc, 0, 0, 0);
+        for (int s = 1; s < NSLOT; ++s) x = (slot == s) ? acc[s][v] : x;
+        sg[v] = -x;
+    }
+    int badl = 0;
+#pragma unroll
+    for (int p = 0; p < 32; ++p) {
+        const int vp = 4 * (p >> 3) + (p & 3), hp = (p >> 2) & 1;
+        const float x = sg[vp];
+        const float dp = lb_readlane(x, p + 32 * hp);
+        badl = (badl == 0 && !(dp > 0.f)) ? 32 * k + p + 1 : badl;
+        const float rinv = __builtin_amdgcn_rcpf(dp);
+        const bool mine = h == hp, isp = l32 == p;
+        const float xr = x * rinv;
+        const float a = (mine && !isp) ? -xr : 0.f;
+        const float b = mine ? (isp ? dp - 1.f : x) : 0.f;
+        sg = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, sg, 0, 0, 0);
+        sg[vp] = mine ? (isp ? -rinv : xr) : sg[vp];
+    }
+    // sg = -(that tile)^-1 = -D
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const float x = -sg[v];
+        Dl[(8 * (v >> 2) + 4 * h + (v & 3)) * LB_LD + l32] = x;
+#pragma unroll
+        for (int s = 0; s < NSLOT; ++s) acc[s][v] = (slot == s) ? x : acc[s][v];
+    }
+    return badl;
 }
 
 template <int NSLOT>
@@ -156,18 +193,8 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
     const float d = (J.damp_idx >= 0) ? damp[J.damp_idx] : 0.f;
     const unsigned lds = (unsigned)J.lds, ldd = (unsigned)J.ldd;
 
-    if (tid < 32 * T) {
-        float v = 1.f;
-        if (tid < n) {
-            const float a = J.src[(unsigned)tid * lds + (unsigned)tid] + d;
-            v = a > 0.f ? rsqrtf(a) : 1.f;   // a non-positive diagonal shows up as a non-positive pivot
-        }
-        sc[tid] = v;
-    }
-    if (tid == 0) bad_s = 0;
-    __syncthreads();
-
-    // my tiles: tile t = w + 16 s is block (ti, tj), ti >= tj, in row-major order of the lower triangle
+    // my tiles: tile t = w + 16 s is block (ti, tj), ti >= tj, in row-major order of the lower triangle.
+    // The raw loads are issued first; the scaling needs the diagonal (through LDS) and comes after.
     lb_floatx16 acc[NSLOT];
     int ti[NSLOT], tj[NSLOT];
 #pragma unroll
@@ -180,23 +207,48 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int i = 32 * r + 8 * (v >> 2) + 4 * h_ + (v & 3), j = 32 * tj[s] + l32_;
-            float x = (i == j) ? -1.f : 0.f;
-            if (t < ntiles && i < n && j < n) {
-                x = J.src[(unsigned)i * lds + (unsigned)j];
-                if (i == j) x += d;
-                x = -x * sc[i] * sc[j];
-            }
+            float x = 0.f;
+            if (t < ntiles && i < n && j < n) x = J.src[(unsigned)i * lds + (unsigned)j];
+            acc[s][v] = x;
+        }
+    }
+    if (tid < 32 * T) {
+        float v = 1.f;
+        if (tid < n) {
+            const float a = J.src[(unsigned)tid * lds + (unsigned)tid] + d;
+            v = a > 0.f ? rsqrtf(a) : 1.f;   // a non-positive diagonal shows up as a non-positive pivot
+        }
+        sc[tid] = v;
+    }
+    if (tid == 0) bad_s = 0;
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < NSLOT; ++s) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = 32 * ti[s] + 8 * (v >> 2) + 4 * h_ + (v & 3), j = 32 * tj[s] + l32_;
+            float x = acc[s][v];
+            if (ti[s] >= 0 && i < n && j < n) x = -(x + (i == j ? d : 0.f)) * sc[i] * sc[j];
+            else x = (i == j) ? -1.f : 0.f;     // identity padding (of -X)
             acc[s][v] = x;
         }
     }
 
+    // The diagonal tile of block k + 1 is swept by its owner during the trailing update of
+    // block k (right after the owner has brought that tile up to date), so that the serial
+    // sweep runs beside the other wavefronts' products instead of in front of them.
+    if (w == 0) {
+        int l32 = l32_, h = h_;
+        asm volatile("" : "+v"(l32), "+v"(h));
+        const int badl = lb_sweep_diag<NSLOT>(acc, 0, 0, l32, h, Dl);
+        if (badl != 0 && lane == 0) bad_s = badl;
+    }
     for (int k = 0; k < T; ++k) {
         // (per-step copies of the lane coordinates: as loop invariants, the 32 lane masks of the
         // sweep and the LDS addresses below would be hoisted and kept live across the whole loop)
         int l32 = l32_, h = h_;
         asm volatile("" : "+v"(l32), "+v"(h));
-        // ---- column panel R into LDS; the diagonal tile's owner sweeps it meanwhile
-        const int tkk = k * (k + 1) / 2 + k;
+        // ---- column panel R of block k into LDS
 #pragma unroll
         for (int s = 0; s < NSLOT; ++s) {
             if (ti[s] < 0) continue;
@@ -210,42 +262,7 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
                     Rp[(32 * tj[s] + l32) * LB_LD + 8 * (v >> 2) + 4 * h + (v & 3)] = acc[s][v];
             }
         }
-        if (w == (tkk & 15)) {
-            const int slot = tkk >> 4;
-            lb_floatx16 sg;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float x = acc[0][v];
-#pragma unroll
-                for (int s = 1; s < NSLOT; ++s) x = (slot == s) ? acc[s][v] : x;
-                sg[v] = -x;
-            }
-            int badl = 0;
-#pragma unroll
-            for (int p = 0; p < 32; ++p) {
-                const int vp = 4 * (p >> 3) + (p & 3), hp = (p >> 2) & 1;
-                const float x = sg[vp];
-                const float dp = lb_readlane(x, p + 32 * hp);
-                badl = (badl == 0 && !(dp > 0.f)) ? 32 * k + p + 1 : badl;
-                const float rinv = __builtin_amdgcn_rcpf(dp);
-                const bool mine = h == hp, isp = l32 == p;
-                const float xr = x * rinv;
-                const float a = (mine && !isp) ? -xr : 0.f;
-                const float b = mine ? (isp ? dp - 1.f : x) : 0.f;
-                sg = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, sg, 0, 0, 0);
-                sg[vp] = mine ? (isp ? -rinv : xr) : sg[vp];
-            }
-            // sg = -(that tile)^-1 = -D
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float x = -sg[v];
-                Dl[(8 * (v >> 2) + 4 * h + (v & 3)) * LB_LD + l32] = x;
-#pragma unroll
-                for (int s = 0; s < NSLOT; ++s) acc[s][v] = (slot == s) ? x : acc[s][v];
-            }
-            if (badl != 0 && lane == 0 && bad_s == 0) bad_s = badl;   // blocks are swept in order: the first one stays
-        }
-        __syncthreads();
+        __syncthreads();   // R and (from the previous step or the prologue) D of block k are in LDS
         // ---- P_i = R_i D for the T - 1 row blocks i != k, one per wavefront
         if (w < T - 1) {
             const int i = w < k ? w : w + 1;
@@ -256,13 +273,28 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
 #pragma unroll
             for (int v = 0; v < 16; ++v) Pp[(32 * i + 8 * (v >> 2) + 4 * h + (v & 3)) * LB_LD + l32] = pt[v];
         }
-        __syncthreads();
+        __syncthreads();   // P is in LDS; D of block k is no longer needed
         // ---- row / column k take P, every other tile N_ij += P_i R_j^T
+        const int tnext = (k + 1) * (k + 2) / 2 + (k + 1);   // diagonal tile of block k + 1
+        const bool sweeps_next = k + 1 < T && w == (tnext & 15);
+        if (sweeps_next) {
+            const int slot = tnext >> 4;
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s)
+                if (s == slot)
+                    lb_mma32(acc[s], Pp + (32 * (k + 1) + l32) * LB_LD + 16 * h, Rp + (32 * (k + 1) + l32) * LB_LD + 16 * h);
+            // the sweep is one long dependent chain: let it issue ahead of the other wavefronts' products
+            __builtin_amdgcn_s_setprio(3);
+            const int badl = lb_sweep_diag<NSLOT>(acc, slot, k + 1, l32, h, Dl);
+            __builtin_amdgcn_s_setprio(0);
+            if (badl != 0 && lane == 0 && bad_s == 0) bad_s = badl;   // blocks are swept in order: the first one stays
+        }
 #pragma unroll
         for (int s = 0; s < NSLOT; ++s) {
             if (ti[s] < 0) continue;
             const int i = ti[s], j = tj[s];
             if (i == k && j == k) continue;
+            if (sweeps_next && i == k + 1 && j == k + 1) continue;
             if (j == k) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[s][v] = Pp[(32 * i + 8 * (v >> 2) + 4 * h + (v & 3)) * LB_LD + l32];
@@ -277,18 +309,28 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
     }
     if (tid == 0 && bad_s != 0 && info && J.info_idx >= 0) atomicCAS(&info[J.info_idx], 0, J.pivot_base + bad_s);
 
-    // undo the scaling; the lower triangle is written and mirrored, so the result is exactly symmetric
+    // undo the scaling; the lower triangle is written and mirrored, so the result is exactly
+    // symmetric.  The mirror image goes through a per-wavefront 32x33 LDS tile (the panels are
+    // dead by now) so that it is written along rows as well.
+    float *stage = lb_lds + w * (32 * 33);
 #pragma unroll
     for (int s = 0; s < NSLOT; ++s) {
         if (ti[s] < 0) continue;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int i = 32 * ti[s] + 8 * (v >> 2) + 4 * h_ + (v & 3), j = 32 * tj[s] + l32_;
-            if (i < n && j <= i) {
-                const float x = acc[s][v] * sc[i] * sc[j];
-                J.dst[(unsigned)i * ldd + (unsigned)j] = x;
-                if (j != i) J.dst[(unsigned)j * ldd + (unsigned)i] = x;
-            }
+            const int r = 8 * (v >> 2) + 4 * h_ + (v & 3);
+            const int i = 32 * ti[s] + r, j = 32 * tj[s] + l32_;
+            float x = 0.f;
+            if (i < n && j < n) x = acc[s][v] * sc[i] * sc[j];
+            if (i < n && j <= i) J.dst[(unsigned)i * ldd + (unsigned)j] = x;
+            stage[l32_ * 33 + r] = x;          // transposed
+        }
+        // rows of the transposed tile: element (r, c) is X[32 ti + c][32 tj + r], goes to dst[32 tj + r][32 ti + c]
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 8 * (v >> 2) + 4 * h_ + (v & 3);
+            const int i = 32 * ti[s] + l32_, j = 32 * tj[s] + r;
+            if (i < n && j < i) J.dst[(unsigned)j * ldd + (unsigned)i] = stage[r * 33 + l32_];
         }
     }
 }
