@@ -292,6 +292,9 @@ def main():
         "factor_inverse_frac_of_mfma_peak": round(fi_flops / (fi_ms * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype if args.dtype == "f32" else "f32"], 4),
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
         "stage_ms_note": "stages run one after the other (separate calls); the fused schedule overlaps them",
+        "flops_note": "algorithmic_gflop, step_tflops and factor_inverse_tflops count the flops of the definitions "
+                      "(patch Gram matrices, n^3 per inverse); kernels[..].tflops and roofline count the flops the "
+                      "launches execute (3x3 layers use 13 displaced correlations instead of the patch Gram matrix)",
         "kernels": {k: {"launches": v["launches"], "ms": round(v["ms"], 4),
                         "tflops": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 3) if v["flops"] else None,
                         "gbs": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["bytes"] else None}
