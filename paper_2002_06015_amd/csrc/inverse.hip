@@ -1,6 +1,8 @@
 // Kernels of the damped inversion (Sec. 3.3, Eq. 12) other than the GEMMs:
 //   - trace_kernel:  pi^2 = (tr A / dA) / (tr G / dG) and the two damping values per layer;
-//   - copy_damp_kernel: dst = src + damp * I (start of the blocked inversion);
+//   - copy_damp_kernel: dst = src + damp * I (start of the blocked inversion), optionally with the
+//     bias border of an A factor eliminated on the way (Schur complement), and border_kernel,
+//     which puts the border back into the finished inverse;
 //   - leaf_block_kernel: (X + damp I)^-1 for n <= 288 by a blocked symmetric sweep held in the
 //     registers of one 1024-thread workgroup, block products on the matrix cores (one matrix per
 //     workgroup, many matrices per launch).
@@ -62,12 +64,17 @@ __global__ __launch_bounds__(256) void copy_damp_kernel(const CopyJob *__restric
     const CopyJob J = jobs[lo];
     const float d = (J.damp_idx >= 0) ? damp[J.damp_idx] : 0.f;
     const int r0 = (wg - J.wg_start) * COPY_ROWS;
-    for (int r = r0; r < min(J.n, r0 + COPY_ROWS); ++r)
+    const float *last = J.src + (long long)J.n * J.lds;   // the border row u^T, c (if any)
+    const float ic = J.border ? 1.f / (last[J.n] + d) : 0.f;
+    for (int r = r0; r < min(J.n, r0 + COPY_ROWS); ++r) {
+        const float ur = J.border ? last[r] * ic : 0.f;
         for (int c = threadIdx.x; c < J.n; c += 256) {
             float v = J.src[(long long)r * J.lds + c];
             if (r == c) v += d;
+            if (J.border) v = fmaf(-ur, last[c], v);
             J.dst[(long long)r * J.ldd + c] = v;
         }
+    }
 }
 
 hipError_t launch_copy_damp(const CopyJob *jobs_dev, int n_jobs, int total_wgs, const float *damp_dev,
@@ -75,6 +82,63 @@ hipError_t launch_copy_damp(const CopyJob *jobs_dev, int n_jobs, int total_wgs, 
 {
     if (total_wgs <= 0) return hipSuccess;
     copy_damp_kernel<<<dim3(total_wgs), dim3(256), 0, s>>>(jobs_dev, n_jobs, damp_dev);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ border of a bordered inverse
+__global__ __launch_bounds__(256) void border_kernel(const BorderJob *__restrict__ jobs, int n_jobs, int pass,
+                                                     const float *__restrict__ damp, int32_t *__restrict__ info)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (pass == 0) {
+        // one wavefront per row i: w_i = sum_j X[i][j] u_j
+        const int wg = blockIdx.x;
+        int lo = 0, hi = n_jobs;
+        while (hi - lo > 1) {
+            int mid = (lo + hi) >> 1;
+            if (jobs[mid].wg_start <= wg) lo = mid; else hi = mid;
+        }
+        const BorderJob J = jobs[lo];
+        const int i = (wg - J.wg_start) * 4 + wave;
+        if (i >= J.n) return;
+        const float *u = J.src + (long long)J.n * J.lds;
+        const float *x = J.X + (long long)i * J.ldx;
+        float acc = 0.f;
+        for (int j = lane; j < J.n; j += 64) acc = fmaf(x[j], u[j], acc);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+        if (lane == 0) {
+            const float c = u[J.n] + ((J.damp_idx >= 0) ? damp[J.damp_idx] : 0.f);
+            const float v = -acc / c;
+            J.X[(long long)i * J.ldx + J.n] = v;
+            J.X[(long long)J.n * J.ldx + i] = v;
+        }
+        return;
+    }
+    // corner: X[n][n] = (1 - sum_i u_i X[n][i]) / c   (X[n][i] = -w_i / c from pass 0)
+    __shared__ float red[4];
+    const BorderJob J = jobs[blockIdx.x];
+    const float *u = J.src + (long long)J.n * J.lds;
+    const float *xr = J.X + (long long)J.n * J.ldx;
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < J.n; i += 256) acc = fmaf(u[i], xr[i], acc);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == 0) red[wave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float c = u[J.n] + ((J.damp_idx >= 0) ? damp[J.damp_idx] : 0.f);
+        const float q = (red[0] + red[1]) + (red[2] + red[3]);
+        J.X[(long long)J.n * J.ldx + J.n] = (1.f - q) / c;
+        if (!(c > 0.f) && info && J.info_idx >= 0) atomicCAS(&info[J.info_idx], 0, J.n + 1);
+    }
+}
+
+hipError_t launch_border(const BorderJob *jobs_dev, int n_jobs, int total_wgs, int pass, const float *damp_dev,
+                         int32_t *info, hipStream_t s)
+{
+    if (n_jobs <= 0) return hipSuccess;
+    border_kernel<<<dim3(pass == 0 ? total_wgs : n_jobs), dim3(256), 0, s>>>(jobs_dev, n_jobs, pass, damp_dev, info);
     return hipGetLastError();
 }
 

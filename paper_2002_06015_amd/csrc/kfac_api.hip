@@ -111,7 +111,7 @@ struct Tables {
     }
 };
 
-enum LaunchKind { L_GEMM, L_REDUCE, L_PATCH, L_TRACE, L_COPY, L_LEAF, L_ZERO, L_BN, L_BNRED, L_PAD, L_ASSEMBLE,
+enum LaunchKind { L_GEMM, L_REDUCE, L_PATCH, L_TRACE, L_COPY, L_LEAF, L_ZERO, L_BN, L_BNRED, L_PAD, L_ASSEMBLE, L_BORDER,
                   L_RECORD, L_WAIT };   // stream ordering: record / wait for sync event `n` on `stream`
 
 struct Launch {
@@ -239,31 +239,57 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
         if (sel.empty()) continue;
         const int B = tile_edge(cfg);
         if (allow_split) {
-            // A heavy phase with only a few rounds of workgroups (512 run at a time) loses a
-            // large fraction of its last round; splitting every problem a little further
-            // evens that out.  Only for phases whose problem set is fixed by the layer list.
-            int boost = 1;
-            if (phase_boost) {
-                double tiles = 0, ksteps = 0;
-                for (auto &P : sel) { tiles += P.n_tiles; ksteps += (double)P.n_tiles * ((P.K + 31) / 32); }
-                if (tiles < 2048 && ksteps >= 512.0 * 48) boost = (int)((2048 + tiles - 1) / tiles);
-            }
-            // otherwise per problem (independent of what else is in the launch, so that the
-            // workspace need of a layer list does not depend on which of its inputs are present)
-            for (auto &P : sel) {
+            // Per problem (independent of what else is in the launch, so that the workspace need of
+            // a layer list does not depend on which of its inputs are present): enough splits for
+            // target_wgs workgroups and at most max_k_per_wg of contraction each.
+            auto splits_for = [&](const GemmProblem &P, int boost, int *kps_out) {
                 const int want = std::max(boost, (tun.target_wgs + P.n_tiles - 1) / P.n_tiles);
                 int splits = std::max((P.K + tun.max_k_per_wg - 1) / tun.max_k_per_wg,
                                       std::min(want, P.K / tun.min_k_per_split));
+                int kps = std::max(32, (P.K + 31) / 32 * 32);
                 if (splits > 1) {
-                    const int kps = ((P.K + splits - 1) / splits + 31) / 32 * 32;
+                    kps = ((P.K + splits - 1) / splits + 31) / 32 * 32;
                     splits = (P.K + kps - 1) / kps;
-                    if (splits > 1) {
-                        P.splits = splits;
-                        P.k_per_split = kps;
-                        P.partial = (float *)arena.take((size_t)P.n_tiles * splits * B * B * sizeof(float));
-                        if (P.flags & GEMM_BORDER)
-                            P.partial_rs = (float *)arena.take((size_t)P.tiles_m * splits * B * sizeof(float));
+                }
+                *kps_out = kps;
+                return std::max(1, splits);
+            };
+            // A heavy phase with only a few rounds of workgroups (a CU holds two 128x128 or four
+            // 64x64 workgroups) loses a large part of its last round: 1026 equal tiles on 512 slots
+            // take 3 rounds, not 2.004.  Splitting every problem `boost` times further shortens the
+            // rounds; the boost with the shortest modelled makespan wins (each extra split charged
+            // 2 % for the partial tiles and their reduction).  Only for phases whose problem set is
+            // fixed by the layer list.
+            int boost = 1;
+            if (phase_boost) {
+                const double slots = cfg == 0 ? 512.0 : 1024.0;
+                double ksteps = 0;
+                for (auto &P : sel) ksteps += (double)P.n_tiles * ((P.K + 31) / 32);
+                if (ksteps >= slots * 48) {
+                    double best = 0;
+                    for (int cand = 1; cand <= 8; ++cand) {
+                        double work = 0, longest = 0;
+                        for (auto &P : sel) {
+                            int kps;
+                            const int sp = splits_for(P, cand, &kps);
+                            const double len = kps / 32 + 6.0;   // K steps plus the fixed part of a workgroup
+                            work += (double)P.n_tiles * sp * len;
+                            longest = std::max(longest, len);
+                        }
+                        const double makespan = std::ceil(work / (longest * slots)) * longest * (1.0 + 0.02 * (cand - 1));
+                        if (cand == 1 || makespan < best) { best = makespan; boost = cand; }
                     }
+                }
+            }
+            for (auto &P : sel) {
+                int kps;
+                const int splits = splits_for(P, boost, &kps);
+                if (splits > 1) {
+                    P.splits = splits;
+                    P.k_per_split = kps;
+                    P.partial = (float *)arena.take((size_t)P.n_tiles * splits * B * B * sizeof(float));
+                    if (P.flags & GEMM_BORDER)
+                        P.partial_rs = (float *)arena.take((size_t)P.tiles_m * splits * B * sizeof(float));
                 }
             }
         }
@@ -553,6 +579,7 @@ struct InvMatrix {
     const float *src;
     float *dst;
     int n, damp_idx, info_idx;
+    bool bias;   // an A factor whose last row/column is the bias border
 };
 
 enum OpKind { OP_LEAF, OP_GEMM };
@@ -701,8 +728,8 @@ void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const Inve
         T.idx = l;
         tjobs.push_back(T);
         // dry runs only need distinct, well-aligned stand-in addresses for planning
-        mats.push_back({T.A, dry ? (float *)nullptr : a.A_inv[l], dA, 3 * l + 1, 2 * l});
-        mats.push_back({T.G, dry ? (float *)nullptr : a.G_inv[l], dG, 3 * l + 2, 2 * l + 1});
+        mats.push_back({T.A, dry ? (float *)nullptr : a.A_inv[l], dA, 3 * l + 1, 2 * l, a.L[l].bias != 0});
+        mats.push_back({T.G, dry ? (float *)nullptr : a.G_inv[l], dG, 3 * l + 2, 2 * l + 1, false});
     }
     {
         Launch T{};
@@ -715,7 +742,8 @@ void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const Inve
         plan.launches.push_back(T);
     }
     std::vector<CopyJob> cjobs;
-    int copy_wgs = 0;
+    std::vector<BorderJob> bjobs;
+    int copy_wgs = 0, border_wgs = 0;
     std::vector<InvOp> ops;
     for (const InvMatrix &m : mats) {
         if (m.n <= kLeafMax) {
@@ -729,14 +757,28 @@ void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const Inve
             op.leaf.pivot_base = 0;
             ops.push_back(op);
         } else {
+            // The bias border (c_in k^2 + 1) would make every block of the recursion one row larger
+            // than a whole number of tiles.  It is eliminated first instead, inside the copy (Schur
+            // complement of the 1x1 corner), and put back into the finished inverse at the end.
+            const int core = m.bias ? m.n - 1 : m.n;
             CopyJob C{};
             C.src = m.src; C.dst = m.dst;
-            C.lds = m.n; C.ldd = m.n; C.n = m.n;
+            C.lds = m.n; C.ldd = m.n; C.n = core;
             C.damp_idx = m.damp_idx;
+            C.border = m.bias ? 1 : 0;
             C.wg_start = copy_wgs;
-            copy_wgs += (m.n + 7) / 8;
+            copy_wgs += (core + 7) / 8;
             cjobs.push_back(C);
-            build_inverse(ops, arena, m.dst, m.n, 0, m.n, 0, m.info_idx, tun.rec_leaf);
+            build_inverse(ops, arena, m.dst, m.n, 0, core, 0, m.info_idx, tun.rec_leaf);
+            if (m.bias) {
+                BorderJob B{};
+                B.src = m.src; B.X = m.dst;
+                B.lds = m.n; B.ldx = m.n; B.n = core;
+                B.damp_idx = m.damp_idx; B.info_idx = m.info_idx;
+                B.wg_start = border_wgs;
+                border_wgs += (core + 3) / 4;
+                bjobs.push_back(B);
+            }
         }
     }
     if (!cjobs.empty()) {
@@ -772,6 +814,20 @@ void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const Inve
         const size_t mark = arena.used;
         emit_gemm_phase(plan, arena, tun, gp, 0, true, true);
         arena.release_to(mark);
+    }
+    if (!bjobs.empty()) {
+        const size_t off = plan.tab.add(bjobs.data(), bjobs.size() * sizeof(BorderJob));
+        for (int pass = 0; pass < 2; ++pass) {
+            Launch B{};
+            B.kind = L_BORDER;
+            B.off_a = off;
+            B.n = (int)bjobs.size();
+            B.total_wgs = border_wgs;
+            B.cfg = pass;
+            B.p0 = damp;
+            B.p1 = a.info;
+            plan.launches.push_back(B);
+        }
     }
     plan.set_stream(first_launch, stream);
 }
@@ -1043,6 +1099,7 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 case L_BNRED: pe.kernel = KFAC_K_BN_REDUCE; break;
                 case L_PAD: pe.kernel = KFAC_K_PAD; break;
                 case L_ASSEMBLE: pe.kernel = KFAC_K_ASSEMBLE; break;
+                case L_BORDER: pe.kernel = KFAC_K_BORDER; break;
                 case L_RECORD: case L_WAIT: break;
             }
             pe.variant = (L.kind == L_GEMM || L.kind == L_LEAF) ? L.cfg : 0;
@@ -1070,6 +1127,10 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 break;
             case L_ASSEMBLE:
                 e = launch_assemble((const AssembleJob *)(tab_dev + L.off_a), L.n, L.total_wgs, ls);
+                break;
+            case L_BORDER:
+                e = launch_border((const BorderJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, (const float *)L.p0,
+                                  (int32_t *)L.p1, ls);
                 break;
             case L_TRACE:
                 e = launch_trace((const TraceJob *)(tab_dev + L.off_a), L.n, L.f0, (float *)L.p0, (float *)L.p1, ls);

@@ -105,13 +105,29 @@ struct TraceJob {   // one per layer
     int idx;        // layer index: damp[3*idx .. 3*idx+2] and pi_out[idx] are written
 };
 
-struct CopyJob {    // dst[i][j] = src[i][j] + (i == j) * damp[damp_idx]
+struct CopyJob {    // dst[i][j] = src[i][j] + (i == j) * damp[damp_idx]   (i, j < n)
     const float *src;
     float *dst;
     long long lds, ldd;
     int n;
     int damp_idx;   // index into the damping array, or -1
+    int border;     // 1: src is (n+1) x (n+1); its last row/column (the bias border of an A factor) is
+                    // eliminated on the fly: with u = src[0:n, n], c = src[n][n] + damp the copy is
+                    // the Schur complement  src[0:n,0:n] + damp I - u u^T / c
     int wg_start;
+};
+
+// Completes the inverse of a bordered matrix [[B, u], [u^T, c]] whose Schur complement
+// S = B - u u^T / c has been inverted into X[0:n, 0:n]:
+//   X[0:n, n] = X[n, 0:n] = -(X u) / c,   X[n][n] = 1/c + u^T X u / c^2.
+struct BorderJob {
+    const float *src;   // the (n+1) x (n+1) factor (u = its last row), leading dimension lds
+    float *X;           // (n+1) x (n+1), leading dimension ldx
+    long long lds, ldx;
+    int n;
+    int damp_idx;       // or -1
+    int info_idx;       // or -1: a non-positive c is reported as pivot n + 1
+    int wg_start;       // pass 0: one workgroup per 4 rows
 };
 
 struct LeafJob {    // dst = (src + damp I)^-1 inside one workgroup, n <= 288
@@ -151,6 +167,9 @@ hipError_t launch_trace(const TraceJob *jobs_dev, int n_layers, float gamma, flo
                         float *pi_out, hipStream_t s);
 hipError_t launch_copy_damp(const CopyJob *jobs_dev, int n_jobs, int total_wgs, const float *damp_dev,
                             hipStream_t s);
+// pass 0: the border row/column (total_wgs workgroups); pass 1: the corner (one workgroup per job)
+hipError_t launch_border(const BorderJob *jobs_dev, int n_jobs, int total_wgs, int pass, const float *damp_dev,
+                         int32_t *info, hipStream_t s);
 hipError_t launch_leaf(const LeafJob *jobs_dev, int n_jobs, int size_class, const float *damp_dev,
                        int32_t *info, hipStream_t s);
 hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t s);

@@ -25,7 +25,7 @@ EXPORTS = [
 ]
 
 KERNEL_NAMES = ["gemm_f32", "gemm_bf16", "gemm_reduce", "patch", "trace", "copy_damp", "leaf_inverse", "zero",
-                "bn_unit", "bn_reduce", "pad", "assemble"]
+                "bn_unit", "bn_reduce", "pad", "assemble", "border"]
 
 
 class kfac_profile_entry(ctypes.Structure):
