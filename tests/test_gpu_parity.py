@@ -53,6 +53,9 @@ SMALL_LAYERS = [
     wl.conv_layer(2, 3, 8, 7, 2, 3, 30),           # 7x7 stem shape, d_A = 148
     wl.conv_layer(4, 16, 70, 3, 1, 1, 12),         # d_A = 145: two 128-tiles with a ragged tail
     wl.conv_layer(2, 40, 130, 3, 1, 1, 10),        # d_A = 361: several tiles, d_G = 130
+    wl.Layer(2, 5, 6, 3, 1, 1, 10, 14, 1),         # 3x3 on a non-square image (correlation form, padded 12 x 16)
+    wl.Layer(3, 4, 5, 3, 1, 1, 7, 7, 0),           # 3x3 on 7x7 without bias (correlation form, padded 10 x 10)
+    wl.Layer(2, 6, 4, 1, 1, 0, 6, 10, 1),          # 1x1 on a non-square image
 ]
 
 
