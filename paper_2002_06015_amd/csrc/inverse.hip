@@ -210,20 +210,37 @@ __device__ __forceinline__ int lb_sweep_diag(lb_floatx16 (&acc)[NSLOT], int slot
         for (int s = 1; s < NSLOT; ++s) x = (slot == s) ? acc[s][v] : x;
         sg[v] = -x;
     }
+    // Pivot p is one rank-2 MFMA.  Its k = 0 slot (lanes 0..31) carries the rank-1 update
+    //     a_i = -x_i / d (i != p),  a_p = 1/d - 1;    b_j = x_j (j != p),  b_p = d - 1
+    // with x = row p and d = x_p: besides S_ij -= x_i x_j / d this leaves row and column p
+    // multiplied by 1/d (sums of equal-signed terms, because d <= 1) and S_pp = 2 - 1/d; the
+    // k = 1 slot (lanes 32..63) adds -2 at (p, p), which makes it -1/d.  Nothing is written to
+    // the tile between the MFMAs, so they follow each other through the accumulator, and the
+    // row of the next pivot is obtained ahead of the MFMA from the tile as it was before:
+    //     x'_j = S_{p+1,j} + a_{p+1} b_j.
     int badl = 0;
+    float xcur = sg[0];                 // row 0, valid in the half-wave that holds it
 #pragma unroll
     for (int p = 0; p < 32; ++p) {
-        const int vp = 4 * (p >> 3) + (p & 3), hp = (p >> 2) & 1;
-        const float x = sg[vp];
-        const float dp = lb_readlane(x, p + 32 * hp);
+        const int hp = (p >> 2) & 1;    // half-wave holding row p
+        const auto both = __builtin_amdgcn_permlane32_swap(__float_as_uint(xcur), __float_as_uint(xcur), false, false);
+        const float xb = __uint_as_float(hp == 0 ? both[0] : both[1]);   // row p in both half-waves
+        const float dp = lb_readlane(xb, p);
         badl = (badl == 0 && !(dp > 0.f)) ? 32 * k + p + 1 : badl;
         const float rinv = __builtin_amdgcn_rcpf(dp);
-        const bool mine = h == hp, isp = l32 == p;
-        const float xr = x * rinv;
-        const float a = (mine && !isp) ? -xr : 0.f;
-        const float b = mine ? (isp ? dp - 1.f : x) : 0.f;
+        const bool isp = l32 == p, k0 = h == 0;
+        const float xr = xb * rinv;
+        const float b0 = isp ? dp - 1.f : xb;
+        const float a = k0 ? (isp ? rinv - 1.f : -xr) : (isp ? -2.f : 0.f);
+        const float b = k0 ? b0 : (isp ? 1.f : 0.f);
+        float xnext = 0.f;
+        if (p < 31) {
+            const int vn = 4 * ((p + 1) >> 3) + ((p + 1) & 3);
+            const float alpha = lb_readlane(xr, p + 1);
+            xnext = fmaf(-alpha, b0, sg[vn]);
+        }
         sg = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, sg, 0, 0, 0);
-        sg[vp] = mine ? (isp ? -rinv : xr) : sg[vp];
+        xcur = xnext;
     }
     // sg = -(that tile)^-1 = -D
 #pragma unroll
