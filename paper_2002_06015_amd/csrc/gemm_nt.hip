@@ -178,6 +178,7 @@ struct LoaderF32 {
     long long rowoff[SLOTS];   // clamped row * row_stride (loop invariant)
     unsigned dead;             // bit s: slot row is outside the operand
     long long batch_stride;
+    long long col;             // offset of the thread's chunk within a row: n * batch_stride + t
     int hw, kq, r0, m, n, t;
     bool zero_all;             // the tile held in registers is to be stored as zeros
 
@@ -195,6 +196,7 @@ struct LoaderF32 {
             rowoff[s] = (long long)min(row, op.rows - 1) * op.row_stride;
         }
         m = n = t = 0;
+        col = 0;
         zero_all = false;
     }
     __device__ __forceinline__ void seek(int tile_k0)   // position on the tile starting at tile_k0
@@ -202,17 +204,17 @@ struct LoaderF32 {
         m = tile_k0 + kq;
         n = m / hw;
         t = m - n * hw;
+        col = (long long)n * batch_stride + t;
     }
     __device__ __forceinline__ void advance()
     {
-        m += KT; t += KT;
-        while (t >= hw) { t -= hw; ++n; }
+        m += KT; t += KT; col += KT;
+        while (t >= hw) { t -= hw; col += batch_stride - hw; }
     }
     // Raw loads only: the masks are applied in store_lds, one iteration later, so nothing
     // waits for the data before the matrix instructions of the current tile are issued.
     __device__ __forceinline__ void load_full(floatx4 (&reg)[SLOTS])
     {
-        const long long col = (long long)n * batch_stride + t;
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) reg[s] = *(gfloat4_ptr)(base + rowoff[s] + col);
         zero_all = false;
@@ -222,7 +224,6 @@ struct LoaderF32 {
     // careful tile for short ranges: chunks at or beyond kend4 are not read
     __device__ __forceinline__ void load_careful(floatx4 (&reg)[SLOTS], int kend4)
     {
-        const long long col = (long long)n * batch_stride + t;
         const bool in = m < kend4;
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
