@@ -904,11 +904,15 @@ struct PrecondArgs {
     float *const *out;
 };
 
-void plan_precondition(Plan &plan, Arena &arena, const Tunables &tun, const PrecondArgs &a, bool dry)
+// `subset` (or null for all): the layers of `a` to precondition.
+void plan_precondition(Plan &plan, Arena &arena, const Tunables &tun, const PrecondArgs &a, bool dry,
+                       const std::vector<int> *subset = nullptr)
 {
     // phase 1: Vt = A_inv * grad_W^T  ([dA, dG]);  phase 2: out = G_inv * Vt^T  ([dG, dA])
     std::vector<GemmProblem> p1, p2;
-    for (int l = 0; l < a.n_layers; ++l) {
+    const int n_sel = subset ? (int)subset->size() : a.n_layers;
+    for (int q = 0; q < n_sel; ++q) {
+        const int l = subset ? (*subset)[q] : q;
         int dA, dG;
         layer_ok(a.L[l], &dA, &dG, nullptr, nullptr);
         const long long ldv = align_up((size_t)dG, 4);
@@ -994,6 +998,7 @@ void plan_step(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &s
     factor_phase(cls[1], 5);
     factor_phase(late, -1);
     bool joined[4] = {false, false, false, false};
+    const int early_classes = (cls[0].empty() ? 0 : 1) + (cls[1].empty() ? 0 : 1);
     for (int c = 0; c < 2; ++c) {
         if (cls[c].empty()) continue;
         const int g0 = aux_of[c][0], g1 = aux_of[c][1];
@@ -1009,11 +1014,19 @@ void plan_step(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &s
     }
     arena.used = align_up(arena.peak, kAlign);
     plan_invert_group(plan, arena, tun, inv, dry, late_inv, damp, 0);
-    for (int g = 1; g < 4; ++g)
-        if (joined[g]) plan.sync(L_WAIT, g, 0);
-    // everything above has finished (in stream order) when these run: reuse the scratch
-    arena.release_to(mark0);
-    plan_precondition(plan, arena, tun, pc, dry);
+    // Preconditioning in the order in which the inverses arrive: the layers inverted on this
+    // stream first, then each class once its chains have been joined, so that these products
+    // fill the time in which only the longest chain is still running.  (Scratch beyond
+    // everything handed out so far: chains on other streams are still using theirs.)
+    if (early_classes == 0) arena.release_to(mark0);   // nothing else is running: reuse the scratch
+    else arena.used = align_up(arena.peak, kAlign);
+    if (!late.empty()) plan_precondition(plan, arena, tun, pc, dry, &late);
+    for (int c = 1; c >= 0; --c) {
+        if (cls[c].empty()) continue;
+        for (int g = aux_of[c][0]; g <= aux_of[c][1]; ++g)
+            if (joined[g]) plan.sync(L_WAIT, g, 0);
+        plan_precondition(plan, arena, tun, pc, dry, &cls[c]);
+    }
 }
 
 // ---------------------------------------------------------------- execution
