@@ -12,8 +12,9 @@
 // Tiling: a 256-thread workgroup (2x2 wavefronts of 64) owns a BM x BN tile; each
 // wavefront owns TM x TN blocks of 32x32 computed with v_mfma_f32_32x32x2_f32 (fp32)
 // or v_mfma_f32_32x32x16_bf16.  The contraction runs in tiles of 32 staged through LDS
-// (one stage in LDS, the next one in flight in registers).
+// (two stages in LDS, a third tile in flight in registers).
 #include "kfac_internal.h"
+#include <type_traits>
 
 namespace kfac {
 
@@ -211,6 +212,14 @@ struct LoaderF32 {
         m += KT; t += KT; col += KT;
         while (t >= hw) { t -= hw; col += batch_stride - hw; }
     }
+    // the same for runs of at least one tile (hw >= KT): at most one wrap, no branch
+    __device__ __forceinline__ void advance_once()
+    {
+        m += KT; t += KT; col += KT;
+        const bool wrap = t >= hw;
+        t -= wrap ? hw : 0;
+        col += wrap ? batch_stride - hw : 0;
+    }
     // Raw loads only: the masks are applied in store_lds, one iteration later, so nothing
     // waits for the data before the matrix instructions of the current tile are issued.
     __device__ __forceinline__ void load_full(floatx4 (&reg)[SLOTS])
@@ -244,6 +253,18 @@ struct LoaderF32 {
             if constexpr (RS) rs[s] += (v[0] + v[1]) + (v[2] + v[3]);
             *(floatx4 *)(lds + (r0 + 32 * s) * LDF + kq) = v;
         }
+    }
+    // one slot of a tile without masked rows (dead == 0, not zero_all)
+    template <bool RS>
+    __device__ __forceinline__ void store_slot(const floatx4 (&reg)[SLOTS], float *lds, float (&rs)[SLOTS], int s) const
+    {
+        const floatx4 v = reg[s];
+        if constexpr (RS) rs[s] += (v[0] + v[1]) + (v[2] + v[3]);
+        *(floatx4 *)(lds + (r0 + 32 * s) * LDF + kq) = v;
+    }
+    __device__ __forceinline__ void load_slot(floatx4 (&reg)[SLOTS], int s)
+    {
+        reg[s] = *(gfloat4_ptr)(base + rowoff[s] + col);
     }
     // K % 4 remainder tile (plain matrices only: hw > K): thread tid < BR fills LDS row tid
     // with the elements k4 .. kend-1 of its operand row followed by zeros; returns their sum
@@ -298,12 +319,43 @@ __device__ __forceinline__ void finish_row_sums(const GemmProblem &P, float *lds
 }
 
 // ------------------------------------------------------------------ fp32 kernel
-// Two LDS stages: iteration `it` stores the tile it already holds in registers into stage
-// it & 1, issues the global loads of tile it + 1, then (one barrier) multiplies out of stage
-// it & 1.  The stage written in iteration it + 1 was last read before the barrier of
-// iteration it + 1, which every wavefront reaches only after finishing that read.
+// Software pipeline over the K tiles, two LDS stages, one barrier per tile.  While the matrix
+// instructions of tile `it` run out of stage it & 1, the same wavefront
+//   - stores tile it + 1 (held in registers since the previous iteration) into the other stage,
+//   - issues the global loads of tile it + 2 into those registers,
+//   - reads its operand fragments a quarter tile ahead of the matrix instructions,
+// so that no wavefront depends on another one sharing its SIMD to keep the matrix pipe busy.
+// The barrier sits before the last quarter: after it every wavefront has finished reading
+// stage it & 1 up to the fragments it already holds, and has stored its part of tile it + 1,
+// whose first fragments are read during the last quarter.
 // RS: the row sums of the a-operand tile are accumulated on the side (rs: rows r0 + 32*s of
 // the vector-loaded part, rs_rem: row tid of the K % 4 remainder).
+template <int TM, int TN>
+struct FragF32 {
+    floatx4 a[TM], b[TN];
+};
+
+template <int TM, int TN>
+__device__ __forceinline__ void read_frag(FragF32<TM, TN> &f, const float *pa, const float *pb, int q)
+{
+#pragma unroll
+    for (int i = 0; i < TM; ++i) f.a[i] = *(const floatx4 *)(pa + i * 32 * LDF + 4 * q);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) f.b[j] = *(const floatx4 *)(pb + j * 32 * LDF + 4 * q);
+}
+
+template <int TM, int TN>
+__device__ __forceinline__ void mma_frag(const FragF32<TM, TN> &f, floatx16 (&acc)[TM][TN])
+{
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[i][e], f.b[j][e], acc[i][j], 0, 0, 0);
+}
+
 template <int TM, int TN, bool LIVE, bool RS>
 __device__ __forceinline__ void gemm_f32_mainloop(const GemmProblem &P, int tm, int tn, int tid,
                                                   LoaderF32<64 * TM> &la, LoaderF32<64 * TN> &lb, float *lds,
@@ -321,11 +373,26 @@ __device__ __forceinline__ void gemm_f32_mainloop(const GemmProblem &P, int tm, 
     const bool careful = nfull == 0 && klen4 > 0;
     const int nvec = nfull + ((shifted || careful) ? 1 : 0);
     const int nk = nvec + (klen4 < klen ? 1 : 0);
+    if (nk == 0) return;
     floatx4 ra[BM / 32], rb[BN / 32];
-    la.seek(k0); lb.seek(k0);
-    if (nfull > 0) { la.load_full(ra); lb.load_full(rb); }
-    else if (careful) { la.load_careful(ra, k0 + klen4); lb.load_careful(rb, k0 + klen4); }
-    for (int it = 0; it < nk; ++it) {
+
+    // global loads of tile `it` into the staging registers (nothing beyond the vector tiles)
+    auto load_tile = [&](int it) {
+        if (it < nfull) {
+            if (it > 0) { la.advance(); lb.advance(); }
+            la.load_full(ra); lb.load_full(rb);
+        } else if (it < nvec) {
+            if (careful) {
+                la.load_careful(ra, k0 + klen4); lb.load_careful(rb, k0 + klen4);
+            } else {
+                la.seek(k0 + klen4 - KT); lb.seek(k0 + klen4 - KT);
+                la.load_full(ra); lb.load_full(rb);
+                la.zero_below(k0 + nfull * KT);
+            }
+        }
+    };
+    // tile `it` (< nk) into its LDS stage: from the staging registers, or the K % 4 remainder
+    auto store_tile = [&](int it) {
         float *sa = lds + (it & 1) * STAGE, *sb = sa + BM * LDF;
         if (it < nvec) {
             float unused[BN / 32];
@@ -335,41 +402,101 @@ __device__ __forceinline__ void gemm_f32_mainloop(const GemmProblem &P, int tm, 
             rs_rem = LoaderF32<BM>::fill_remainder(P.a, tm * BM, k0 + klen4, k1, tid, sa);
             LoaderF32<BN>::fill_remainder(P.b, tn * BN, k0 + klen4, k1, tid, sb);
         }
-        if (it + 1 < nfull) {
-            la.advance(); lb.advance();
-            la.load_full(ra); lb.load_full(rb);
-        } else if (it + 1 < nvec) {
-            la.seek(k0 + klen4 - KT); lb.seek(k0 + klen4 - KT);
-            la.load_full(ra); lb.load_full(rb);
-            la.zero_below(k0 + nfull * KT);
-        }
+    };
+    // each half-wave takes 16 consecutive k of the tile (the same 16 for both operands)
+    const int off_a = (wave_m * 32 * TM + l32) * LDF + half * 16;
+    const int off_b = BM * LDF + (wave_n * 32 * TN + l32) * LDF + half * 16;
+
+    la.seek(k0); lb.seek(k0);
+    load_tile(0);
+    store_tile(0);
+    load_tile(1);
+    __syncthreads();
+    FragF32<TM, TN> f0, f1;
+    if constexpr (LIVE) read_frag<TM, TN>(f0, lds + off_a, lds + off_b, 0);
+
+    // One iteration of the general form: any kind of tile, stores and loads as blocks.
+    auto step = [&](int it) {
+        const float *cur = lds + (it & 1) * STAGE;
+        const float *nxt = lds + ((it + 1) & 1) * STAGE;
+        if constexpr (LIVE) read_frag<TM, TN>(f1, cur + off_a, cur + off_b, 1);
+        if (it + 1 < nk) store_tile(it + 1);
+        if constexpr (LIVE) mma_frag<TM, TN>(f0, acc);
+        if constexpr (LIVE) read_frag<TM, TN>(f0, cur + off_a, cur + off_b, 2);
+        load_tile(it + 2);
+        if constexpr (LIVE) mma_frag<TM, TN>(f1, acc);
+        if constexpr (LIVE) read_frag<TM, TN>(f1, cur + off_a, cur + off_b, 3);
+        if constexpr (LIVE) mma_frag<TM, TN>(f0, acc);
         __syncthreads();
         if constexpr (LIVE) {
-            // each half-wave takes 16 consecutive k of the tile (the same 16 for both operands)
-            floatx4 fa[TM][4], fb[TN][4];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const float *p = sa + (wave_m * 32 * TM + i * 32 + l32) * LDF + half * 16;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) fa[i][q] = *(const floatx4 *)(p + 4 * q);
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const float *p = sb + (wave_n * 32 * TN + j * 32 + l32) * LDF + half * 16;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) fb[j][q] = *(const floatx4 *)(p + 4 * q);
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][q][e], fb[j][q][e], acc[i][j], 0, 0, 0);
+            if (it + 1 < nk) read_frag<TM, TN>(f0, nxt + off_a, nxt + off_b, 0);
+            mma_frag<TM, TN>(f1, acc);
         }
-    }
+    };
+    // The steady state: tile it + 1 is a vector tile without masked rows and tile it + 2 a full
+    // one reached by a single wrap of the position.  Straight-line code in a fixed order (the
+    // scheduling barriers keep the compiler from regrouping it): the stores of tile it + 1 and
+    // the loads of tile it + 2 are dealt out one by one behind the matrix instructions of the
+    // first quarter, in whose shadow they issue; the loads then have the rest of the tile to
+    // arrive, and every fragment read has a quarter.
+    auto fast_step = [&](int it) {
+        const float *cur = lds + (it & 1) * STAGE;
+        float *nxt = lds + ((it + 1) & 1) * STAGE;
+        constexpr int SA = BM / 32, SB = BN / 32, NOPS = 2 * (SA + SB);
+        constexpr int NMMA = LIVE ? 4 * TM * TN : 1;
+        constexpr int PER = (NOPS + NMMA - 1) / NMMA;
+        auto side_op = [&](int k) {   // k-th of: stores of a, stores of b, loads of a, loads of b
+            if (k < SA) {
+                la.template store_slot<RS>(ra, nxt, rs, k);
+            } else if (k < SA + SB) {
+                float unused[SB];
+                lb.template store_slot<false>(rb, nxt + BM * LDF, unused, k - SA);
+            } else if (k < 2 * SA + SB) {
+                if (k == SA + SB) { la.advance_once(); lb.advance_once(); }
+                la.load_slot(ra, k - SA - SB);
+            } else if (k < NOPS) {
+                lb.load_slot(rb, k - 2 * SA - SB);
+            }
+        };
+        if constexpr (LIVE) {
+            read_frag<TM, TN>(f1, cur + off_a, cur + off_b, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            int n = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f0.a[i][e], f0.b[j][e], acc[i][j], 0, 0, 0);
+#pragma unroll
+                        for (int u = 0; u < PER; ++u) side_op(n * PER + u);
+                        ++n;
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+            read_frag<TM, TN>(f0, cur + off_a, cur + off_b, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_frag<TM, TN>(f1, acc);
+            __builtin_amdgcn_sched_barrier(0);
+            read_frag<TM, TN>(f1, cur + off_a, cur + off_b, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_frag<TM, TN>(f0, acc);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            read_frag<TM, TN>(f0, nxt + off_a, nxt + off_b, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_frag<TM, TN>(f1, acc);
+        } else {
+#pragma unroll
+            for (int k = 0; k < NOPS; ++k) side_op(k);
+            __syncthreads();
+        }
+    };
+    int it = 0;
+    // (a condition the whole workgroup agrees on: every row of both operand tiles exists)
+    if (la.hw >= KT && lb.hw >= KT && (tm + 1) * BM <= P.a.rows && (tn + 1) * BN <= P.b.rows)
+        for (; it + 2 < nfull; ++it) fast_step(it);
+    for (; it < nk; ++it) step(it);
 }
 
 template <int TM, int TN>
