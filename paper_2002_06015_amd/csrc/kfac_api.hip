@@ -17,7 +17,7 @@ using namespace kfac;
 namespace {
 
 constexpr int kSlots = 8;
-constexpr int kSyncEvents = 8;   // events that order the streams of one call among each other
+constexpr int kSyncEvents = 12;  // events that order the streams of one call among each other
 constexpr size_t kAlign = 256;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -34,6 +34,8 @@ struct Tunables {
     int slots;           // staging slots in use (2..kSlots): a call waits until the device has started the
                          // call `slots` calls back.  Measured: letting the host run further ahead than a
                          // couple of calls makes the chains of small launches slower, not faster.
+    int pipe;            // fused step: 1 spreads each factor phase over streams (rewrites of the next phase and
+                         // reductions of the previous one under the matrix launches of the current one)
     Tunables()
     {
         const char *e = getenv("KFAC_TARGET_WGS");
@@ -52,6 +54,8 @@ struct Tunables {
         corr = e ? (atoi(e) != 0) : 1;
         e = getenv("KFAC_STAGING_SLOTS");
         slots = e ? std::min(kSlots, std::max(2, atoi(e))) : 2;
+        e = getenv("KFAC_PIPE");
+        pipe = e ? (atoi(e) != 0) : 1;
     }
 };
 
@@ -203,9 +207,10 @@ void finish_problem(GemmProblem &P)
 }
 
 // Emits the launches of one phase: per tile configuration one GEMM launch, plus one
-// reduction launch if any problem was split along K.
+// reduction launch if any problem was split along K (appended to `deferred` instead, if given:
+// the caller then places the reductions after all the matrix launches, on a stream it chooses).
 void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<GemmProblem> &probs,
-                     int dtype, bool allow_split, bool phase_boost = false)
+                     int dtype, bool allow_split, bool phase_boost = false, std::vector<Launch> *deferred = nullptr)
 {
     if (probs.empty()) return;
     // Tile configuration per problem.  When the phase as a whole keeps the GPU busy with 128x128
@@ -327,7 +332,8 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
             R.off_b = plan.tab.add(rstart.data(), rstart.size() * sizeof(int));
             R.n = (int)sel.size();
             R.total_wgs = rstart.back();
-            plan.launches.push_back(R);
+            if (deferred) deferred->push_back(R);
+            else plan.launches.push_back(R);
         }
     }
 }
@@ -378,8 +384,18 @@ PatchJob make_patch_job(const void *src, void *dst, long long ld, int N, int c, 
 }
 
 // `subset` (or null for all): the layers of `a` to build factors for.
+// Where the parts of one factor phase run when it is spread over streams: the operand
+// rewrites (patch extraction, zero padding) ahead of the matrix launches on `pre_stream`, the
+// matrix launches on the context's stream, what follows them (split-K reductions, assembly of
+// the correlation form) on `post_stream`, which is where the phase's factors are complete.
+// A stream of 0 keeps that part on the context's stream.
+struct StatsSplit {
+    int pre_stream, ev_pre;     // event recorded when the rewrites are done
+    int post_stream, ev_gemm;   // event recorded when the matrix launches are done
+};
+
 void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &a, bool dry,
-                const std::vector<int> *subset = nullptr)
+                const std::vector<int> *subset = nullptr, const StatsSplit *split = nullptr)
 {
     const int esize = a.in == KFAC_BF16 ? 2 : 4;
     // a thread loads 16-byte chunks: 4 fp32 (element alignment is enough) or 8 bf16 (16-byte aligned)
@@ -545,6 +561,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             probs.push_back(P);
         }
     }
+    const size_t first_pre = plan.launches.size();
     if (!pjobs.empty()) {
         Launch L{};
         L.kind = L_PATCH;
@@ -563,13 +580,29 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         L.bytes = pad_bytes;
         plan.launches.push_back(L);
     }
-    emit_gemm_phase(plan, arena, tun, probs, a.in == KFAC_BF16 ? 1 : 0, true);
+    if (split && split->pre_stream > 0 && plan.launches.size() > first_pre) {
+        plan.set_stream(first_pre, split->pre_stream);
+        plan.sync(L_RECORD, split->ev_pre, split->pre_stream);
+        plan.sync(L_WAIT, split->ev_pre, 0);
+    }
+    const int post = split ? split->post_stream : 0;
+    std::vector<Launch> reductions;
+    emit_gemm_phase(plan, arena, tun, probs, a.in == KFAC_BF16 ? 1 : 0, true, false, post > 0 ? &reductions : nullptr);
+    if (post > 0) {
+        plan.sync(L_RECORD, split->ev_gemm, 0);
+        plan.sync(L_WAIT, split->ev_gemm, post);
+        for (auto &R : reductions) {
+            R.stream = post;
+            plan.launches.push_back(R);
+        }
+    }
     if (!asmjobs.empty()) {
         Launch L{};
         L.kind = L_ASSEMBLE;
         L.off_a = plan.tab.add(asmjobs.data(), asmjobs.size() * sizeof(AssembleJob));
         L.n = (int)asmjobs.size();
         L.total_wgs = asm_wgs;
+        L.stream = post;
         plan.launches.push_back(L);
     }
 }
@@ -988,15 +1021,37 @@ void plan_step(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &s
         else { cls[0].insert(cls[0].end(), cls[1].begin(), cls[1].end()); cls[1].clear(); }
     }
     const size_t mark0 = arena.used;
-    auto factor_phase = [&](const std::vector<int> &ids, int event) {
-        if (ids.empty()) return;
-        arena.release_to(mark0);   // each phase starts after the previous one has finished
-        plan_stats(plan, arena, tun, st, dry, &ids);
-        if (event >= 0) plan.sync(L_RECORD, event, 0);
-    };
-    factor_phase(cls[0], 4);
-    factor_phase(cls[1], 5);
-    factor_phase(late, -1);
+    // Factor phases in class order.  With auxiliary streams the phases are pipelined: the
+    // operand rewrites of the next phase run (on the last auxiliary stream, idle until its chain
+    // starts) under the matrix launches of the current one, and what follows the matrix launches
+    // of a class runs at the head of the first stream of its chains, under the matrix launches
+    // of the next phase.  Each phase then needs scratch of its own.
+    //   event 6: the call's tables are on the device (recorded first on the context's stream)
+    //   events 7, 8: rewrites of the second / third phase done
+    //   events 9 + c: matrix launches of class c done;  events 4 + c: factors of class c complete
+    const std::vector<int> *phases[3] = {&cls[0], &cls[1], &late};
+    const bool pipe = n_aux > 0 && tun.pipe;
+    if (pipe) plan.sync(L_RECORD, 6, 0);
+    bool pre_waited = false;
+    int n_phase = 0;
+    for (int ph = 0; ph < 3; ++ph) {
+        if (phases[ph]->empty()) continue;
+        StatsSplit sp{0, 0, 0, 0};
+        if (pipe) {
+            if (n_phase > 0) {
+                sp.pre_stream = n_aux;
+                sp.ev_pre = 6 + n_phase;
+                if (!pre_waited) plan.sync(L_WAIT, 6, n_aux);
+                pre_waited = true;
+            }
+            if (ph < 2) { sp.post_stream = aux_of[ph][0]; sp.ev_gemm = 9 + ph; }
+        } else {
+            arena.release_to(mark0);   // one stream: each phase starts after the previous one has finished
+        }
+        plan_stats(plan, arena, tun, st, dry, phases[ph], &sp);
+        if (ph < 2) plan.sync(L_RECORD, 4 + ph, pipe ? aux_of[ph][0] : 0);
+        ++n_phase;
+    }
     bool joined[4] = {false, false, false, false};
     const int early_classes = (cls[0].empty() ? 0 : 1) + (cls[1].empty() ? 0 : 1);
     for (int c = 0; c < 2; ++c) {
@@ -1004,8 +1059,8 @@ void plan_step(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &s
         const int g0 = aux_of[c][0], g1 = aux_of[c][1];
         std::vector<std::vector<int>> groups = deal_layers(st.L, cls[c], g1 + 1, g0);
         for (int g = g0; g <= g1; ++g) {
-            if (groups[g].empty()) continue;
-            plan.sync(L_WAIT, 4 + c, g);
+            if (groups[g].empty() && g != g0) continue;
+            if (g != g0 || !pipe) plan.sync(L_WAIT, 4 + c, g);   // (pipelined: the first stream of the class completed the factors itself)
             arena.used = align_up(arena.peak, kAlign);   // concurrent with everything else: own scratch
             plan_invert_group(plan, arena, tun, inv, dry, groups[g], damp, g);
             plan.sync(L_RECORD, g, g);
