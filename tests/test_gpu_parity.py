@@ -56,6 +56,11 @@ SMALL_LAYERS = [
     wl.Layer(2, 5, 6, 3, 1, 1, 10, 14, 1),         # 3x3 on a non-square image (correlation form, padded 12 x 16)
     wl.Layer(3, 4, 5, 3, 1, 1, 7, 7, 0),           # 3x3 on 7x7 without bias (correlation form, padded 10 x 10)
     wl.Layer(2, 6, 4, 1, 1, 0, 6, 10, 1),          # 1x1 on a non-square image
+    # contractions long enough for the steady-state K loop of the GEMM (>= 3 full tiles of 32)
+    wl.conv_layer(8, 8, 5, 1, 1, 0, 7),            # direct, runs of 49: every thread wraps at a different tile
+    wl.conv_layer(8, 8, 5, 1, 1, 0, 6),            # direct, runs of 36
+    wl.conv_layer(16, 8, 5, 1, 1, 0, 4),           # direct, runs of 16: several wraps per tile (general loop)
+    wl.conv_layer(4, 160, 130, 1, 1, 0, 8),        # an interior tile row (steady-state loop) and a ragged one
 ]
 
 
