@@ -612,6 +612,7 @@ struct LoaderBF16 {
     long long rowoff[SLOTS];
     unsigned dead;
     long long batch_stride;
+    long long col;             // offset of the thread's chunk within a row: n * batch_stride + t
     int hw, kq, r0, m, n, t;
     bool zero_all;
 
@@ -629,6 +630,7 @@ struct LoaderBF16 {
             rowoff[s] = (long long)min(row, op.rows - 1) * op.row_stride;
         }
         m = n = t = 0;
+        col = 0;
         zero_all = false;
     }
     __device__ __forceinline__ void seek(int tile_k0)
@@ -636,15 +638,23 @@ struct LoaderBF16 {
         m = tile_k0 + kq;
         n = m / hw;
         t = m - n * hw;
+        col = (long long)n * batch_stride + t;
     }
     __device__ __forceinline__ void advance()
     {
-        m += KTH; t += KTH;
-        while (t >= hw) { t -= hw; ++n; }
+        m += KTH; t += KTH; col += KTH;
+        while (t >= hw) { t -= hw; col += batch_stride - hw; }
+    }
+    // the same for runs of at least one tile (hw >= KTH): at most one wrap, no branch
+    __device__ __forceinline__ void advance_once()
+    {
+        m += KTH; t += KTH; col += KTH;
+        const bool wrap = t >= hw;
+        t -= wrap ? hw : 0;
+        col += wrap ? batch_stride - hw : 0;
     }
     __device__ __forceinline__ void load_full(ushortx8 (&reg)[SLOTS])
     {
-        const long long col = (long long)n * batch_stride + t;
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) reg[s] = *(gushort8_ptr)(base + rowoff[s] + col);
         zero_all = false;
@@ -652,7 +662,6 @@ struct LoaderBF16 {
     __device__ __forceinline__ void zero_below(int mlo) { zero_all = m < mlo; }
     __device__ __forceinline__ void load_careful(ushortx8 (&reg)[SLOTS], int kend8)
     {
-        const long long col = (long long)n * batch_stride + t;
         const bool in = m < kend8;
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
@@ -675,6 +684,20 @@ struct LoaderBF16 {
                          ((widen(v[4]) + widen(v[5])) + (widen(v[6]) + widen(v[7])));
             *(ushortx8 *)(lds + (r0 + 32 * s) * LDH + kq) = v;
         }
+    }
+    // one slot of a tile without masked rows (dead == 0, not zero_all)
+    template <bool RS>
+    __device__ __forceinline__ void store_slot(const ushortx8 (&reg)[SLOTS], unsigned short *lds, float (&rs)[SLOTS], int s) const
+    {
+        const ushortx8 v = reg[s];
+        if constexpr (RS)
+            rs[s] += ((widen(v[0]) + widen(v[1])) + (widen(v[2]) + widen(v[3]))) +
+                     ((widen(v[4]) + widen(v[5])) + (widen(v[6]) + widen(v[7])));
+        *(ushortx8 *)(lds + (r0 + 32 * s) * LDH + kq) = v;
+    }
+    __device__ __forceinline__ void load_slot(ushortx8 (&reg)[SLOTS], int s)
+    {
+        reg[s] = *(gushort8_ptr)(base + rowoff[s] + col);
     }
     // K % 8 remainder tile (repacked operands only): thread tid < BR fills LDS row tid
     __device__ __forceinline__ static float fill_remainder(const Operand &op, int tile_row0, int k8, int kend,
@@ -699,6 +722,36 @@ struct LoaderBF16 {
 };
 
 // ------------------------------------------------------------------ bf16 kernel
+// The software pipeline of the fp32 kernel with 64-wide K tiles.  v_mfma_f32_32x32x16_bf16: a
+// lane supplies 8 consecutive k of row lane % 32, the two half-waves supply two different k
+// groups; step u (0..3) of a tile uses k = 16u + 8*half + 0..7, identically for both operands.
+// A matrix instruction takes a quarter of the time of the fp32 one while a tile moves the same
+// number of bytes, so the stores and loads are dealt out over the first three steps.
+template <int TM, int TN>
+struct FragBF16 {
+    ushortx8 a[TM], b[TN];
+};
+
+template <int TM, int TN>
+__device__ __forceinline__ void read_frag16(FragBF16<TM, TN> &f, const unsigned short *pa, const unsigned short *pb, int u)
+{
+#pragma unroll
+    for (int i = 0; i < TM; ++i) f.a[i] = *(const ushortx8 *)(pa + i * 32 * LDH + 16 * u);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) f.b[j] = *(const ushortx8 *)(pb + j * 32 * LDH + 16 * u);
+}
+
+template <int TM, int TN>
+__device__ __forceinline__ void mma_frag16(const FragBF16<TM, TN> &f, floatx16 (&acc)[TM][TN])
+{
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i]),
+                                                                __builtin_bit_cast(bf16x8, f.b[j]), acc[i][j], 0, 0, 0);
+}
+
 template <int TM, int TN, bool LIVE, bool RS>
 __device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm, int tn, int tid,
                                                    LoaderBF16<64 * TM> &la, LoaderBF16<64 * TN> &lb,
@@ -715,11 +768,24 @@ __device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm,
     const bool careful = nfull == 0 && klen8 > 0;
     const int nvec = nfull + ((shifted || careful) ? 1 : 0);
     const int nk = nvec + (klen8 < klen ? 1 : 0);
+    if (nk == 0) return;
     ushortx8 ra[BM / 32], rb[BN / 32];
-    la.seek(k0); lb.seek(k0);
-    if (nfull > 0) { la.load_full(ra); lb.load_full(rb); }
-    else if (careful) { la.load_careful(ra, k0 + klen8); lb.load_careful(rb, k0 + klen8); }
-    for (int it = 0; it < nk; ++it) {
+
+    auto load_tile = [&](int it) {
+        if (it < nfull) {
+            if (it > 0) { la.advance(); lb.advance(); }
+            la.load_full(ra); lb.load_full(rb);
+        } else if (it < nvec) {
+            if (careful) {
+                la.load_careful(ra, k0 + klen8); lb.load_careful(rb, k0 + klen8);
+            } else {
+                la.seek(k0 + klen8 - KTH); lb.seek(k0 + klen8 - KTH);
+                la.load_full(ra); lb.load_full(rb);
+                la.zero_below(k0 + nfull * KTH);
+            }
+        }
+    };
+    auto store_tile = [&](int it) {
         unsigned short *sa = lds + (it & 1) * STAGE, *sb = sa + BM * LDH;
         if (it < nvec) {
             float unused[BN / 32];
@@ -729,37 +795,91 @@ __device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm,
             rs_rem = LoaderBF16<BM>::fill_remainder(P.a, tm * BM, k0 + klen8, k1, tid, sa);
             LoaderBF16<BN>::fill_remainder(P.b, tn * BN, k0 + klen8, k1, tid, sb);
         }
-        if (it + 1 < nfull) {
-            la.advance(); lb.advance();
-            la.load_full(ra); lb.load_full(rb);
-        } else if (it + 1 < nvec) {
-            la.seek(k0 + klen8 - KTH); lb.seek(k0 + klen8 - KTH);
-            la.load_full(ra); lb.load_full(rb);
-            la.zero_below(k0 + nfull * KTH);
-        }
+    };
+    const int off_a = (wave_m * 32 * TM + l32) * LDH + 8 * half;
+    const int off_b = BM * LDH + (wave_n * 32 * TN + l32) * LDH + 8 * half;
+
+    la.seek(k0); lb.seek(k0);
+    load_tile(0);
+    store_tile(0);
+    load_tile(1);
+    __syncthreads();
+    FragBF16<TM, TN> f0, f1;
+    if constexpr (LIVE) read_frag16<TM, TN>(f0, lds + off_a, lds + off_b, 0);
+
+    auto step = [&](int it) {
+        const unsigned short *cur = lds + (it & 1) * STAGE;
+        const unsigned short *nxt = lds + ((it + 1) & 1) * STAGE;
+        if constexpr (LIVE) read_frag16<TM, TN>(f1, cur + off_a, cur + off_b, 1);
+        if (it + 1 < nk) store_tile(it + 1);
+        if constexpr (LIVE) mma_frag16<TM, TN>(f0, acc);
+        if constexpr (LIVE) read_frag16<TM, TN>(f0, cur + off_a, cur + off_b, 2);
+        load_tile(it + 2);
+        if constexpr (LIVE) mma_frag16<TM, TN>(f1, acc);
+        if constexpr (LIVE) read_frag16<TM, TN>(f1, cur + off_a, cur + off_b, 3);
+        if constexpr (LIVE) mma_frag16<TM, TN>(f0, acc);
         __syncthreads();
         if constexpr (LIVE) {
-            // v_mfma_f32_32x32x16_bf16: a lane supplies 8 consecutive k of row lane % 32, the two
-            // half-waves supply two different k groups.  Issue u of the 64-wide tile uses
-            // k = 16u + 8*half + 0..7, identically for both operands.
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                ushortx8 fa[TM], fb[TN];
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    fa[i] = *(const ushortx8 *)(sa + (wave_m * 32 * TM + i * 32 + l32) * LDH + 16 * u + 8 * half);
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    fb[j] = *(const ushortx8 *)(sb + (wave_n * 32 * TN + j * 32 + l32) * LDH + 16 * u + 8 * half);
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, fa[i]), __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
-            }
+            if (it + 1 < nk) read_frag16<TM, TN>(f0, nxt + off_a, nxt + off_b, 0);
+            mma_frag16<TM, TN>(f1, acc);
         }
-    }
+    };
+    auto fast_step = [&](int it) {
+        const unsigned short *cur = lds + (it & 1) * STAGE;
+        unsigned short *nxt = lds + ((it + 1) & 1) * STAGE;
+        constexpr int SA = BM / 32, SB = BN / 32, NOPS = 2 * (SA + SB);
+        constexpr int NMMA = LIVE ? 3 * TM * TN : 1;   // matrix instructions ahead of the barrier
+        constexpr int PER = (NOPS + NMMA - 1) / NMMA;
+        auto side_op = [&](int k) {   // k-th of: stores of a, stores of b, loads of a, loads of b
+            if (k < SA) {
+                la.template store_slot<RS>(ra, nxt, rs, k);
+            } else if (k < SA + SB) {
+                float unused[SB];
+                lb.template store_slot<false>(rb, nxt + BM * LDH, unused, k - SA);
+            } else if (k < 2 * SA + SB) {
+                if (k == SA + SB) { la.advance_once(); lb.advance_once(); }
+                la.load_slot(ra, k - SA - SB);
+            } else if (k < NOPS) {
+                lb.load_slot(rb, k - 2 * SA - SB);
+            }
+        };
+        if constexpr (LIVE) {
+            int n = 0;
+            // step u multiplies the fragments read during step u - 1 and reads those of step u + 1
+            auto group = [&](FragBF16<TM, TN> &use, FragBF16<TM, TN> &fill, int u_fill) {
+                read_frag16<TM, TN>(fill, cur + off_a, cur + off_b, u_fill);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, use.a[i]),
+                                                                            __builtin_bit_cast(bf16x8, use.b[j]),
+                                                                            acc[i][j], 0, 0, 0);
+#pragma unroll
+                        for (int q = 0; q < PER; ++q) side_op(n * PER + q);
+                        ++n;
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+            };
+            group(f0, f1, 1);
+            group(f1, f0, 2);
+            group(f0, f1, 3);
+            __syncthreads();
+            read_frag16<TM, TN>(f0, nxt + off_a, nxt + off_b, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_frag16<TM, TN>(f1, acc);
+        } else {
+#pragma unroll
+            for (int k = 0; k < NOPS; ++k) side_op(k);
+            __syncthreads();
+        }
+    };
+    int it = 0;
+    // (a condition the whole workgroup agrees on: every row of both operand tiles exists)
+    if (la.hw >= KTH && lb.hw >= KTH && (tm + 1) * BM <= P.a.rows && (tn + 1) * BN <= P.b.rows)
+        for (; it + 2 < nfull; ++it) fast_step(it);
+    for (; it < nk; ++it) step(it);
 }
 
 template <int TM, int TN>
