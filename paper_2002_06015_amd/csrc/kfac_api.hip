@@ -270,7 +270,7 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
                 const double slots = cfg == 0 ? 512.0 : 1024.0;
                 double ksteps = 0;
                 for (auto &P : sel) ksteps += (double)P.n_tiles * ((P.K + 31) / 32);
-                if (ksteps >= slots * 48) {
+                if (ksteps >= slots * 24) {
                     double best = 0;
                     for (int cand = 1; cand <= 8; ++cand) {
                         double work = 0, longest = 0;
