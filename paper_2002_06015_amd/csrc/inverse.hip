@@ -66,9 +66,35 @@ __global__ __launch_bounds__(256) void copy_damp_kernel(const CopyJob *__restric
     const int r0 = (wg - J.wg_start) * COPY_ROWS;
     const float *last = J.src + (long long)J.n * J.lds;   // the border row u^T, c (if any)
     const float ic = J.border ? 1.f / (last[J.n] + d) : 0.f;
-    for (int r = r0; r < min(J.n, r0 + COPY_ROWS); ++r) {
+    const int r1 = min(J.n, r0 + COPY_ROWS);
+    // four adjacent columns per thread (16-byte accesses that only need element alignment: the
+    // leading dimensions are odd for bordered factors), all rows of the workgroup in flight at once
+    typedef float vec4 __attribute__((ext_vector_type(4), aligned(4)));
+    const int n4 = J.n & ~3;
+    for (int c = 4 * (int)threadIdx.x; c < n4; c += 1024) {
+        vec4 v[COPY_ROWS];
+#pragma unroll
+        for (int q = 0; q < COPY_ROWS; ++q)
+            if (r0 + q < r1) v[q] = *(const vec4 *)(J.src + (long long)(r0 + q) * J.lds + c);
+        vec4 u = {0.f, 0.f, 0.f, 0.f};
+        if (J.border) u = *(const vec4 *)(last + c);
+#pragma unroll
+        for (int q = 0; q < COPY_ROWS; ++q) {
+            const int r = r0 + q;
+            if (r >= r1) break;
+            vec4 x = v[q];
+            if (r >= c && r < c + 4) x[r - c] += d;
+            if (J.border) {
+                const float ur = last[r] * ic;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = fmaf(-ur, u[e], x[e]);
+            }
+            *(vec4 *)(J.dst + (long long)r * J.ldd + c) = x;
+        }
+    }
+    for (int r = r0; r < r1; ++r) {
         const float ur = J.border ? last[r] * ic : 0.f;
-        for (int c = threadIdx.x; c < J.n; c += 256) {
+        for (int c = n4 + (int)threadIdx.x; c < J.n; c += 256) {
             float v = J.src[(long long)r * J.lds + c];
             if (r == c) v += d;
             if (J.border) v = fmaf(-ur, last[c], v);
@@ -103,8 +129,17 @@ __global__ __launch_bounds__(256) void border_kernel(const BorderJob *__restrict
         if (i >= J.n) return;
         const float *u = J.src + (long long)J.n * J.lds;
         const float *x = J.X + (long long)i * J.ldx;
-        float acc = 0.f;
-        for (int j = lane; j < J.n; j += 64) acc = fmaf(x[j], u[j], acc);
+        // 16-byte accesses that only need element alignment (the leading dimensions are odd)
+        typedef float vec4 __attribute__((ext_vector_type(4), aligned(4)));
+        float a4[4] = {0.f, 0.f, 0.f, 0.f};
+        const int n4 = J.n & ~3;
+        for (int j = 4 * lane; j < n4; j += 256) {
+            const vec4 xv = *(const vec4 *)(x + j), uv = *(const vec4 *)(u + j);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) a4[e] = fmaf(xv[e], uv[e], a4[e]);
+        }
+        float acc = (a4[0] + a4[1]) + (a4[2] + a4[3]);
+        for (int j = n4 + lane; j < J.n; j += 64) acc = fmaf(x[j], u[j], acc);
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
         if (lane == 0) {

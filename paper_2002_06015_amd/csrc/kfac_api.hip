@@ -332,6 +332,8 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
             R.off_b = plan.tab.add(rstart.data(), rstart.size() * sizeof(int));
             R.n = (int)sel.size();
             R.total_wgs = rstart.back();
+            for (auto &P : sel)
+                if (P.splits > 1) R.bytes += 4.0 * P.n_tiles * B * B * (P.splits + 1.0);   // partial tiles read, the sum written
             if (deferred) deferred->push_back(R);
             else plan.launches.push_back(R);
         }
@@ -406,7 +408,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
     std::vector<AssembleJob> asmjobs;
     std::vector<GemmProblem> probs;
     int patch_wgs = 0, pad_wgs = 0, asm_wgs = 0;
-    double patch_bytes = 0, pad_bytes = 0;
+    double patch_bytes = 0, pad_bytes = 0, asm_bytes = 0;
     // An NCHW tensor [N, c, hw] is contracted in place when its runs are whole chunks; otherwise (and for every k > 1 / strided / padded layer) it is first rewritten
     // as [c k^2][ld] with the contraction index contiguous.
     auto operand_for = [&](const void *src, int N, int c, int k, int stride, int pad, int h_in, int w_in, int h,
@@ -483,6 +485,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             S.count = (float)((double)N * (double)hw);
             S.wg_start = asm_wgs;
             asm_wgs += dA;   // one workgroup per row of A
+            asm_bytes += 4.0 * dA * dA * (a.decay != 0.f ? 2.0 : 1.0) + 4.0 * 50.0 * C * C;   // A (read too under a running average) and about 50 C x C Gram matrices / transposed copies
             // one Gram matrix per contraction; those with displacement 0 are symmetric and carry the row sums
             auto gram = [&](const Operand &oa, const Operand &ob, int K, bool zero_shift, const float **out,
                             const float **out_t, int *ld) {
@@ -602,6 +605,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         L.off_a = plan.tab.add(asmjobs.data(), asmjobs.size() * sizeof(AssembleJob));
         L.n = (int)asmjobs.size();
         L.total_wgs = asm_wgs;
+        L.bytes = asm_bytes;
         L.stream = post;
         plan.launches.push_back(L);
     }
@@ -777,6 +781,7 @@ void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const Inve
     std::vector<CopyJob> cjobs;
     std::vector<BorderJob> bjobs;
     int copy_wgs = 0, border_wgs = 0;
+    double copy_bytes = 0, border_bytes = 0;
     std::vector<InvOp> ops;
     for (const InvMatrix &m : mats) {
         if (m.n <= kLeafMax) {
@@ -801,6 +806,7 @@ void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const Inve
             C.border = m.bias ? 1 : 0;
             C.wg_start = copy_wgs;
             copy_wgs += (core + 7) / 8;
+            copy_bytes += 8.0 * core * core;   // every element read once and written once
             cjobs.push_back(C);
             build_inverse(ops, arena, m.dst, m.n, 0, core, 0, m.info_idx, tun.rec_leaf);
             if (m.bias) {
@@ -810,6 +816,7 @@ void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const Inve
                 B.damp_idx = m.damp_idx; B.info_idx = m.info_idx;
                 B.wg_start = border_wgs;
                 border_wgs += (core + 3) / 4;
+                border_bytes += 4.0 * core * core;   // pass 0 reads the core inverse once
                 bjobs.push_back(B);
             }
         }
@@ -821,6 +828,7 @@ void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const Inve
         C.n = (int)cjobs.size();
         C.total_wgs = copy_wgs;
         C.p0 = damp;
+        C.bytes = copy_bytes;
         plan.launches.push_back(C);
     }
     int max_level = -1;
@@ -859,6 +867,7 @@ void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const Inve
             B.cfg = pass;
             B.p0 = damp;
             B.p1 = a.info;
+            B.bytes = pass == 0 ? border_bytes : 0.0;
             plan.launches.push_back(B);
         }
     }
