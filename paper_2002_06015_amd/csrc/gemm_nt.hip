@@ -978,20 +978,35 @@ __device__ __forceinline__ void reduce_slab(const GemmProblem &P, int tile, int 
 {
     const bool diag_tile = (P.flags & GEMM_SYM) && tm == tn;
     const float *part = P.partial + (long long)tile * P.splits * (B * B) + slab * 32 * B;
-    // 32 * B elements, 4 per thread per pass
-    for (int e = threadIdx.x * 4; e < 32 * B; e += 1024) {
-        // four interleaved partial sums (splits q = 0, 4, 8, ... etc.), combined in a fixed order:
-        // as reproducible as one running sum, with four loads in flight instead of one
-        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, s2 = s0, s3 = s0;
-        int q = 0;
-        for (; q + 3 < P.splits; q += 4) {
-            s0 += *(const floatx4 *)(part + (long long)q * (B * B) + e);
-            s1 += *(const floatx4 *)(part + (long long)(q + 1) * (B * B) + e);
-            s2 += *(const floatx4 *)(part + (long long)(q + 2) * (B * B) + e);
-            s3 += *(const floatx4 *)(part + (long long)(q + 3) * (B * B) + e);
-        }
-        for (; q < P.splits; ++q) s0 += *(const floatx4 *)(part + (long long)q * (B * B) + e);
-        const floatx4 s = (s0 + s1) + (s2 + s3);
+    // 32 * B elements, 4 per thread per pass.  Split q goes into partial sum q % 4 of its element;
+    // the four are combined in a fixed order: as reproducible as one running sum, with the loads
+    // of four splits and all passes in flight at once (the partial tiles are read exactly once)
+    constexpr int PASSES = 32 * B / 1024;
+    floatx4 acc[PASSES][4];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[p][k] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < P.splits; q += 4) {
+        floatx4 v[PASSES][4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                v[p][k] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (q + k < P.splits)
+                    v[p][k] = __builtin_nontemporal_load((const floatx4 *)(part + (long long)(q + k) * (B * B) + threadIdx.x * 4 + p * 1024));
+            }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p)
+                if (q + k < P.splits) acc[p][k] += v[p][k];
+    }
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const floatx4 s = (acc[p][0] + acc[p][1]) + (acc[p][2] + acc[p][3]);
+        const int e = threadIdx.x * 4 + p * 1024;
         const int r = e / B, c = e - r * B;
         float *t = T + r * (B + 1) + c;
         t[0] = s[0]; t[1] = s[1]; t[2] = s[2]; t[3] = s[3];
