@@ -288,6 +288,21 @@ __device__ __forceinline__ int lb_sweep_diag(lb_floatx16 (&acc)[NSLOT], int slot
     return badl;
 }
 
+// Which wavefront holds which tile.  In step k the tiles of block row / column k only copy the
+// panel, the other 36 (of 45, for 9 blocks) take 16 matrix instructions each and the sweep of the
+// next diagonal tile another 32, all on the SIMD of their wavefront (wavefront % 4).  Dealing
+// the tiles out in order (tile t to wavefront t % 16) loads the busiest SIMD with 176 of the
+// 608 matrix instructions of a step on average; the table below (found by local search over
+// assignments with at most 3 tiles per wavefront) brings every step to 160, the least
+// possible at 16 per tile.  Other sizes keep the plain order.
+__constant__ signed char kLeafTile9[16][3] = {{2, 22, 39}, {5, 9, 23}, {0, 31, 41}, {8, 29, 34}, {17, 19, 21}, {16, 33, 44},
+                                              {3, 18, 42}, {6, 37, 38}, {20, 30, 40}, {28, -1, -1}, {4, 25, 32}, {13, 24, 43},
+                                              {1, 10, -1}, {11, 27, 35}, {7, 12, 36}, {14, 15, 26}};
+__constant__ signed char kLeafWave9[45] = {2, 12, 0, 6, 10, 1, 7, 14, 3, 1, 12, 13, 14, 11, 15, 15, 5, 4, 6, 4, 8, 4, 0,
+                                           1, 11, 10, 15, 13, 9, 3, 8, 2, 10, 5, 3, 13, 14, 7, 7, 0, 8, 2, 6, 11, 5};
+__constant__ signed char kLeafSlot9[45] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 1, 1, 0, 1, 0, 0, 1, 0, 0, 1, 1, 0, 2, 1,
+                                           2, 1, 1, 2, 1, 0, 1, 1, 1, 2, 1, 2, 2, 2, 1, 2, 2, 2, 2, 2, 2, 2};
+
 template <int NSLOT>
 __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restrict__ jobs,
                                                           const float *__restrict__ damp,
@@ -309,13 +324,18 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
     const float d = (J.damp_idx >= 0) ? damp[J.damp_idx] : 0.f;
     const unsigned lds = (unsigned)J.lds, ldd = (unsigned)J.ldd;
 
-    // my tiles: tile t = w + 16 s is block (ti, tj), ti >= tj, in row-major order of the lower triangle.
+    // my tiles: tile t is block (ti, tj), ti >= tj, in row-major order of the lower triangle; slot s
+    // of wavefront w holds tile w + 16 s, or what the balanced table says for 9 blocks.
     // The raw loads are issued first; the scaling needs the diagonal (through LDS) and comes after.
+    const bool balanced = NSLOT == 3 && T == 9;
+    auto diag_owner = [&](int b) { const int t = b * (b + 1) / 2 + b; return balanced ? (int)kLeafWave9[t] : (t & 15); };
+    auto diag_slot = [&](int b) { const int t = b * (b + 1) / 2 + b; return balanced ? (int)kLeafSlot9[t] : (t >> 4); };
     lb_floatx16 acc[NSLOT];
     int ti[NSLOT], tj[NSLOT];
 #pragma unroll
     for (int s = 0; s < NSLOT; ++s) {
-        const int t = w + 16 * s;
+        int t = w + 16 * s;
+        if (balanced) { t = kLeafTile9[w][s < 3 ? s : 0]; t = t < 0 ? ntiles : t; }
         int r = 0;
         while ((r + 1) * (r + 2) / 2 <= t) ++r;
         ti[s] = t < ntiles ? r : -1;
@@ -353,10 +373,10 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
     // The diagonal tile of block k + 1 is swept by its owner during the trailing update of
     // block k (right after the owner has brought that tile up to date), so that the serial
     // sweep runs beside the other wavefronts' products instead of in front of them.
-    if (w == 0) {
+    if (w == diag_owner(0)) {
         int l32 = l32_, h = h_;
         asm volatile("" : "+v"(l32), "+v"(h));
-        const int badl = lb_sweep_diag<NSLOT>(acc, 0, 0, l32, h, Dl);
+        const int badl = lb_sweep_diag<NSLOT>(acc, diag_slot(0), 0, l32, h, Dl);
         if (badl != 0 && lane == 0) bad_s = badl;
     }
     for (int k = 0; k < T; ++k) {
@@ -391,10 +411,9 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
         }
         __syncthreads();   // P is in LDS; D of block k is no longer needed
         // ---- row / column k take P, every other tile N_ij += P_i R_j^T
-        const int tnext = (k + 1) * (k + 2) / 2 + (k + 1);   // diagonal tile of block k + 1
-        const bool sweeps_next = k + 1 < T && w == (tnext & 15);
+        const bool sweeps_next = k + 1 < T && w == diag_owner(k + 1);   // holds the diagonal tile of block k + 1
         if (sweeps_next) {
-            const int slot = tnext >> 4;
+            const int slot = diag_slot(k + 1);
 #pragma unroll
             for (int s = 0; s < NSLOT; ++s)
                 if (s == slot)
