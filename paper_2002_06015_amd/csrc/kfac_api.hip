@@ -36,6 +36,8 @@ struct Tunables {
                          // couple of calls makes the chains of small launches slower, not faster.
     int pipe;            // fused step: 1 spreads each factor phase over streams (rewrites of the next phase and
                          // reductions of the previous one under the matrix launches of the current one)
+    double chunk_gf;     // fused step: matrix launches of the later factor phases in parts of about this many
+                         // GFLOP (0: whole)
     Tunables()
     {
         const char *e = getenv("KFAC_TARGET_WGS");
@@ -56,6 +58,8 @@ struct Tunables {
         slots = e ? std::min(kSlots, std::max(2, atoi(e))) : 2;
         e = getenv("KFAC_PIPE");
         pipe = e ? (atoi(e) != 0) : 1;
+        e = getenv("KFAC_CHUNK_GF");
+        chunk_gf = e ? std::max(0.0, atof(e)) : 48.0;
     }
 };
 
@@ -394,6 +398,7 @@ PatchJob make_patch_job(const void *src, void *dst, long long ld, int N, int c, 
 struct StatsSplit {
     int pre_stream, ev_pre;     // event recorded when the rewrites are done
     int post_stream, ev_gemm;   // event recorded when the matrix launches are done
+    int gemm_chunks;            // the matrix launches are cut into this many successive parts (<= 1: not)
 };
 
 void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &a, bool dry,
@@ -590,7 +595,28 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
     }
     const int post = split ? split->post_stream : 0;
     std::vector<Launch> reductions;
-    emit_gemm_phase(plan, arena, tun, probs, a.in == KFAC_BF16 ? 1 : 0, true, false, post > 0 ? &reductions : nullptr);
+    {
+        const int nchunk = split ? std::max(1, split->gemm_chunks) : 1;
+        if (nchunk <= 1) {
+            emit_gemm_phase(plan, arena, tun, probs, a.in == KFAC_BF16 ? 1 : 0, true, false, post > 0 ? &reductions : nullptr);
+        } else {
+            // chunks of similar work (largest problems first, each to the lightest chunk)
+            std::vector<size_t> order(probs.size());
+            for (size_t i = 0; i < order.size(); ++i) order[i] = i;
+            auto work = [&](const GemmProblem &P) { return (double)P.M * P.N * P.K; };
+            std::stable_sort(order.begin(), order.end(), [&](size_t x, size_t y) { return work(probs[x]) > work(probs[y]); });
+            std::vector<std::vector<GemmProblem>> chunks(nchunk);
+            std::vector<double> load(nchunk, 0.0);
+            for (size_t i : order) {
+                int g = 0;
+                for (int q = 1; q < nchunk; ++q) if (load[q] < load[g]) g = q;
+                chunks[g].push_back(probs[i]);
+                load[g] += work(probs[i]);
+            }
+            for (auto &c : chunks)
+                emit_gemm_phase(plan, arena, tun, c, a.in == KFAC_BF16 ? 1 : 0, true, false, post > 0 ? &reductions : nullptr);
+        }
+    }
     if (post > 0) {
         plan.sync(L_RECORD, split->ev_gemm, 0);
         plan.sync(L_WAIT, split->ev_gemm, post);
@@ -1041,11 +1067,40 @@ void plan_step(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &s
     const std::vector<int> *phases[3] = {&cls[0], &cls[1], &late};
     const bool pipe = n_aux > 0 && tun.pipe;
     if (pipe) plan.sync(L_RECORD, 6, 0);
+    // Beside running chains, the matrix launches of the later phases are cut into successive parts
+    // of about chunk_gf GFLOP (at most 8): a chain's workgroups mostly get compute units where a
+    // large launch drains, so more such points let the chains advance (configuration 4: -2 % on
+    // the step, although the parts cost the factor contractions themselves 5-10 %).  Only when
+    // the early chains are long against the contractions they run beside (n^3 per inverse against
+    // K d^2 per factor); with few or short chains the parts only cost (configuration 5: +2.7 %).
+    auto factor_gf = [&](int l) {
+        int dA, dG, h, w;
+        layer_ok(st.L[l], &dA, &dG, &h, &w);
+        return 1e-9 * (double)st.L[l].N * h * w * ((double)dA * dA + (double)dG * dG);
+    };
+    bool chunked = false;
+    if (tun.chunk_gf > 0) {
+        double inv_early = 0, gf_later = 0;
+        for (int c = 0; c < 2; ++c)
+            for (int l : cls[c]) {
+                int dA, dG;
+                layer_ok(st.L[l], &dA, &dG, nullptr, nullptr);
+                inv_early += 1e-9 * ((double)dA * dA * dA + (double)dG * dG * dG);
+            }
+        for (int l : cls[1]) gf_later += factor_gf(l);
+        for (int l : late) gf_later += factor_gf(l);
+        chunked = gf_later <= 2.0 * inv_early;
+    }
     bool pre_waited = false;
     int n_phase = 0;
     for (int ph = 0; ph < 3; ++ph) {
         if (phases[ph]->empty()) continue;
-        StatsSplit sp{0, 0, 0, 0};
+        StatsSplit sp{0, 0, 0, 0, 1};
+        if (pipe && n_phase > 0 && chunked) {
+            double gf = 0;
+            for (int l : *phases[ph]) gf += factor_gf(l);
+            sp.gemm_chunks = std::min(8, std::max(1, (int)std::lround(gf / tun.chunk_gf)));
+        }
         if (pipe) {
             if (n_phase > 0) {
                 sp.pre_stream = n_aux;
