@@ -389,10 +389,12 @@ def test_config2_conv3x3_full_size(gpu):
 
 
 # ------------------------------------------------------------------ fused step
-def _fused_vs_separate(layers, mask, early_n, monkeypatch):
+def _fused_vs_separate(layers, mask, early_n, monkeypatch, env=None):
     """kfac_step against the oracle and against the three separate calls, two steps (the
     second with the running average and, if a mask is given, stale inverses for the rest)."""
     monkeypatch.setenv("KFAC_EARLY_N", str(early_n))   # read when the context is created
+    for k, v in (env or {}).items():
+        monkeypatch.setenv(k, v)
     ctx = kfac.Context(layers)
     n = len(layers)
     mk = lambda: ([torch.full((L.dA, L.dA), float("nan"), device="cuda") for L in layers],
@@ -456,6 +458,18 @@ def test_fused_step_all_layers(gpu, monkeypatch, early_n):
     """early_n = 100: five layers take the early path on the auxiliary streams; 300: two;
     100000: none (everything in order on the context's stream)."""
     _fused_vs_separate(FUSED_LAYERS, None, early_n, monkeypatch)
+
+
+@pytest.mark.parametrize("env", [
+    {"KFAC_CHUNK_GF": "0.0001"},                          # factor launches of the later phases in 8 parts (some empty)
+    {"KFAC_CHUNK_GF": "0.002", "KFAC_INV_STREAMS": "2"},  # a few parts; one auxiliary stream for everything
+    {"KFAC_PIPE": "0", "KFAC_INV_STREAMS": "3"},          # phases one after the other on the context's stream
+    {"KFAC_INV_STREAMS": "1"},                            # no auxiliary streams at all
+])
+def test_fused_step_schedules(gpu, monkeypatch, env):
+    """The schedule variants of the fused step give the same results."""
+    _fused_vs_separate(FUSED_LAYERS, None, 100, monkeypatch, env)
+    _fused_vs_separate(FUSED_LAYERS, [True, False, True, True, False, False], 100, monkeypatch, env)
 
 
 def test_fused_step_stale_subset(gpu, monkeypatch):
