@@ -10,7 +10,7 @@ from oracle import stale
 
 
 def _alpha():
-    with open(os.path.join(os.path.dirname(__file__), "golden", "paper_facts.txt")) as f:
+    with open(os.path.join(os.path.dirname(__file__), "golden", "stale_facts.txt")) as f:
         for line in f:
             if line.startswith("stale_alpha"):
                 return float(line.split("=")[1])
