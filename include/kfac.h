@@ -188,6 +188,53 @@ kfac_status bn_unitwise_reduce_nchw(kfac_ctx *ctx, int32_t n_layers, int32_t N, 
                                     float *const *g_gamma, float *const *g_beta);
 
 /*
+ * Staleness of statistics, Sec. 4.3 (the similarity criterion under Algorithm 2).
+ * For each of n dense matrices X[i] of dims[i] x dims[i] floats (a Kronecker factor,
+ * an inverse, any statistic the caller refreshes) and its two predecessors:
+ *   ratios[2i]     = ||X[i] - X_m1[i]||_F / ||X_m1[i]||_F
+ *   ratios[2i + 1] = ||X[i] - X_m2[i]||_F / ||X_m2[i]||_F
+ * X[i] is "similar to" a predecessor when the ratio is below the threshold alpha
+ * (0.1 in the paper's experiments).  A predecessor that does not exist yet is passed
+ * as NULL (the array itself may be NULL: none exists) and gives +infinity; a
+ * predecessor of norm 0 gives 0 if X[i] equals it and +infinity otherwise.
+ * dims, X, X_m1, X_m2: host arrays (X, X_m1, X_m2 of device pointers);
+ * ratios: dev out [2 n] doubles.  Sums are accumulated in double in a fixed order
+ * (the same inputs give the same bits).  Uses 32 bytes of the workspace per 4096
+ * matrix elements (KFAC_ERR_WORKSPACE if it does not fit).
+ */
+kfac_status kfac_staleness(kfac_ctx *ctx, int32_t n, const int32_t *dims, const float *const *X,
+                           const float *const *X_m1, const float *const *X_m2, double *ratios);
+
+/*
+ * Algorithm 2 (Sec. 4.3): the acceptable interval, in steps, until a statistic is
+ * refreshed next.  delta_m1: its last interval, delta_m2: the one before (both >= 1).
+ *   not similar to the last value:                       max(1, delta_m1 / 2)
+ *   similar to the last, not to the one before the last: delta_m1
+ *   similar to both:                                     delta_m1 + delta_m2
+ * Host only, no GPU work.  Returns 0 for an interval argument below 1.
+ */
+int32_t kfac_next_interval(int32_t similar_to_last, int32_t similar_to_before_last, int32_t delta_m1,
+                           int32_t delta_m2);
+
+/*
+ * What Algorithm 1 (Sec. 4.3) keeps per statistic: the step t_X of its next refresh
+ * and its two most recent intervals.  kfac_refresh_init: t_X = 1 and both intervals 1
+ * (the paper leaves the initial intervals open).  kfac_refresh_due: t == t_X.
+ * kfac_refresh_advance, called after the statistic has been recomputed at step t_X and
+ * compared with its predecessors (ratios as kfac_staleness writes them, alpha > 0):
+ * the interval of Algorithm 2 becomes the last interval and t_X moves on by it.
+ * Host only; all three ignore a NULL state.
+ */
+typedef struct {
+    int32_t t_next;    /* t_X */
+    int32_t delta;     /* the last interval */
+    int32_t delta_m1;  /* the interval before the last */
+} kfac_refresh_state;
+void kfac_refresh_init(kfac_refresh_state *s, int32_t n);
+int32_t kfac_refresh_due(const kfac_refresh_state *s, int32_t t);
+void kfac_refresh_advance(kfac_refresh_state *s, double ratio_m1, double ratio_m2, double alpha);
+
+/*
  * Optional per-launch timing for benchmarks (not part of the method).  While enabled,
  * every kernel launch of this context is bracketed by HIP events on the context's stream.
  * kfac_profile_read waits for the stream, copies up to max_entries records (in launch
@@ -199,7 +246,7 @@ kfac_status bn_unitwise_reduce_nchw(kfac_ctx *ctx, int32_t n_layers, int32_t N, 
 typedef enum {
     KFAC_K_GEMM_F32 = 0, KFAC_K_GEMM_BF16 = 1, KFAC_K_GEMM_REDUCE = 2, KFAC_K_PATCH = 3, KFAC_K_TRACE = 4,
     KFAC_K_COPY_DAMP = 5, KFAC_K_LEAF_INVERSE = 6, KFAC_K_ZERO = 7, KFAC_K_BN_UNIT = 8, KFAC_K_BN_REDUCE = 9,
-    KFAC_K_PAD = 10, KFAC_K_ASSEMBLE = 11, KFAC_K_BORDER = 12
+    KFAC_K_PAD = 10, KFAC_K_ASSEMBLE = 11, KFAC_K_BORDER = 12, KFAC_K_STALENESS = 13
 } kfac_kernel;
 
 typedef struct {

@@ -6,7 +6,9 @@
 #include "kfac_internal.h"
 
 #include <algorithm>
+#include <climits>
 #include <cmath>
+#include <cstdint>
 #include <cstdlib>
 #include <cstring>
 #include <vector>
@@ -120,6 +122,7 @@ struct Tables {
 };
 
 enum LaunchKind { L_GEMM, L_REDUCE, L_PATCH, L_TRACE, L_COPY, L_LEAF, L_ZERO, L_BN, L_BNRED, L_PAD, L_ASSEMBLE, L_BORDER,
+                  L_STALE,   // cfg: pass 0 / 1
                   L_RECORD, L_WAIT };   // stream ordering: record / wait for sync event `n` on `stream`
 
 struct Launch {
@@ -1232,6 +1235,7 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 case L_PAD: pe.kernel = KFAC_K_PAD; break;
                 case L_ASSEMBLE: pe.kernel = KFAC_K_ASSEMBLE; break;
                 case L_BORDER: pe.kernel = KFAC_K_BORDER; break;
+                case L_STALE: pe.kernel = KFAC_K_STALENESS; break;
                 case L_RECORD: case L_WAIT: break;
             }
             pe.variant = (L.kind == L_GEMM || L.kind == L_LEAF) ? L.cfg : 0;
@@ -1282,6 +1286,9 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 break;
             case L_BNRED:
                 e = launch_bn_reduce((const BnReduceJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, ls);
+                break;
+            case L_STALE:
+                e = launch_staleness((const StaleJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, ls);
                 break;
             case L_RECORD: case L_WAIT: break;
         }
@@ -1607,6 +1614,75 @@ kfac_status bn_unitwise_reduce_nchw(kfac_ctx *ctx, int32_t n_layers, int32_t N, 
     Lc.cfg = N;
     plan.launches.push_back(Lc);
     return run_plan(ctx, plan, arena);
+}
+
+kfac_status kfac_staleness(kfac_ctx *ctx, int32_t n, const int32_t *dims, const float *const *X,
+                           const float *const *X_m1, const float *const *X_m2, double *ratios)
+{
+    if (!ctx || n < 1 || n > 65536 || !dims || !X || !ratios) return KFAC_ERR_INVALID;
+    Plan plan; Arena arena(ctx->ws);
+    std::vector<StaleJob> jobs;
+    long long wgs = 0;
+    double bytes = 0;
+    for (int i = 0; i < n; ++i) {
+        if (dims[i] < 1 || dims[i] > (1 << 20) || !X[i]) return KFAC_ERR_INVALID;
+        StaleJob J{};
+        J.X = X[i];
+        J.P = X_m1 ? X_m1[i] : nullptr;
+        J.Q = X_m2 ? X_m2[i] : nullptr;
+        if (J.P == J.X || J.Q == J.X) return KFAC_ERR_INVALID;   // a statistic is not its own predecessor
+        J.n = (long long)dims[i] * dims[i];
+        J.wgs = (int)((J.n + kStaleChunk - 1) / kStaleChunk);
+        J.partial = (double *)arena.take((size_t)J.wgs * 4 * sizeof(double));
+        J.out = ratios + 2 * i;
+        J.wg_start = (int)wgs;
+        wgs += J.wgs;
+        if (wgs > (1LL << 30)) return KFAC_ERR_INVALID;
+        bytes += 4.0 * J.n * (1 + (J.P ? 1 : 0) + (J.Q ? 1 : 0));
+        jobs.push_back(J);
+    }
+    const size_t off = plan.tab.add(jobs.data(), jobs.size() * sizeof(StaleJob));
+    for (int pass = 0; pass < 2; ++pass) {
+        Launch L{};
+        L.kind = L_STALE;
+        L.off_a = off;
+        L.n = n;
+        L.total_wgs = pass == 0 ? (int)wgs : n;
+        L.cfg = pass;
+        L.bytes = pass == 0 ? bytes : 0.0;
+        plan.launches.push_back(L);
+    }
+    return run_plan(ctx, plan, arena);
+}
+
+int32_t kfac_next_interval(int32_t similar_to_last, int32_t similar_to_before_last, int32_t delta_m1,
+                           int32_t delta_m2)
+{
+    if (delta_m1 < 1 || delta_m2 < 1) return 0;
+    if (!similar_to_last) return std::max(1, delta_m1 / 2);
+    if (!similar_to_before_last) return delta_m1;
+    const long long sum = (long long)delta_m1 + delta_m2;
+    return (int32_t)std::min<long long>(sum, INT32_MAX);
+}
+
+void kfac_refresh_init(kfac_refresh_state *s, int32_t n)
+{
+    if (!s) return;
+    for (int32_t i = 0; i < n; ++i) { s[i].t_next = 1; s[i].delta = 1; s[i].delta_m1 = 1; }
+}
+
+int32_t kfac_refresh_due(const kfac_refresh_state *s, int32_t t) { return s && t == s->t_next ? 1 : 0; }
+
+void kfac_refresh_advance(kfac_refresh_state *s, double ratio_m1, double ratio_m2, double alpha)
+{
+    if (!s) return;
+    // (a NaN ratio compares false: not similar)
+    const int32_t next = kfac_next_interval(ratio_m1 < alpha, ratio_m2 < alpha, std::max(1, s->delta),
+                                            std::max(1, s->delta_m1));
+    s->delta_m1 = s->delta;
+    s->delta = next;
+    const long long t = (long long)s->t_next + next;
+    s->t_next = (int32_t)std::min<long long>(t, INT32_MAX);
 }
 
 }  // extern "C"

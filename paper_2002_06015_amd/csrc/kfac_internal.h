@@ -155,6 +155,17 @@ struct BnReduceJob {
     int wg_start;   // one wave per (n, c) row; 4 rows per workgroup
 };
 
+// Staleness of one statistic (Sec. 4.3): X against its predecessors P = X_-1 and Q = X_-2 (null: none).
+struct StaleJob {
+    const float *X, *P, *Q;
+    long long n;        // elements
+    double *partial;    // [wgs][4]: sum (x-p)^2, sum p^2, sum (x-q)^2, sum q^2 of each workgroup's chunk
+    double *out;        // [2]: the two ratios
+    int wgs;            // workgroups of the first pass (chunks of kStaleChunk elements)
+    int wg_start;
+};
+constexpr int kStaleChunk = 4096;
+
 // ---- launchers (implemented in the kernel files) -----------------------------------
 hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, int n_probs,
                        int total_wgs, int tile_cfg, int dtype, hipStream_t s);
@@ -176,6 +187,8 @@ hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t s);
 hipError_t launch_bn(const BnJob *jobs_dev, int n_jobs, int total_wgs, int N, float decay, float lambda,
                      hipStream_t s);
 hipError_t launch_bn_reduce(const BnReduceJob *jobs_dev, int n_jobs, int total_wgs, int N, hipStream_t s);
+// pass 0: per-chunk sums (total_wgs workgroups); pass 1: one workgroup per job adds them up and writes the ratios
+hipError_t launch_staleness(const StaleJob *jobs_dev, int n_jobs, int total_wgs, int pass, hipStream_t s);
 
 // leaf size classes: a class value B serves n <= 32*B (one launch per class and level)
 static const int kLeafClasses[] = {5, 7, 9};

@@ -22,10 +22,11 @@ EXPORTS = [
     "kfac_status_string", "kfac_layer_dims", "kfac_workspace_bytes", "kfac_create", "kfac_destroy",
     "kfac_im2col", "kfac_stats", "kfac_invert", "kfac_precondition", "kfac_step",
     "bn_unitwise_precondition", "bn_unitwise_reduce_nchw", "kfac_profile_enable", "kfac_profile_read",
+    "kfac_staleness", "kfac_next_interval", "kfac_refresh_init", "kfac_refresh_due", "kfac_refresh_advance",
 ]
 
 KERNEL_NAMES = ["gemm_f32", "gemm_bf16", "gemm_reduce", "patch", "trace", "copy_damp", "leaf_inverse", "zero",
-                "bn_unit", "bn_reduce", "pad", "assemble", "border"]
+                "bn_unit", "bn_reduce", "pad", "assemble", "border", "staleness"]
 
 
 class kfac_profile_entry(ctypes.Structure):
@@ -74,6 +75,15 @@ def lib() -> ctypes.CDLL:
         L.kfac_profile_enable.argtypes = [vp, i32]
         L.kfac_profile_read.restype = i32
         L.kfac_profile_read.argtypes = [vp, vp, i32]
+        L.kfac_staleness.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+        L.kfac_next_interval.restype = i32
+        L.kfac_next_interval.argtypes = [i32, i32, i32, i32]
+        L.kfac_refresh_init.restype = None
+        L.kfac_refresh_init.argtypes = [vp, i32]
+        L.kfac_refresh_due.restype = i32
+        L.kfac_refresh_due.argtypes = [vp, i32]
+        L.kfac_refresh_advance.restype = None
+        L.kfac_refresh_advance.argtypes = [vp, ctypes.c_double, ctypes.c_double, ctypes.c_double]
         _lib = L
     return _lib
 
@@ -263,6 +273,43 @@ def bn_unitwise_reduce_nchw(ctx: Context, N: int, C: Sequence[int], HW: Sequence
                                        *[p and ctypes.addressof(p) for p in ps])
     if st != KFAC_OK:
         raise KfacError(st, "bn_unitwise_reduce_nchw")
+
+
+def kfac_staleness(ctx: Context, dims: Sequence[int], X, X_m1, X_m2, ratios: torch.Tensor) -> None:
+    """ratios: device float64 [2 * len(dims)] (contiguous)."""
+    n = len(dims)
+    ds = _i32(dims)
+    ps = [_ptrs(x, n, torch.float32) for x in (X, X_m1, X_m2)]
+    if not (ratios.is_cuda and ratios.is_contiguous() and ratios.dtype == torch.float64 and ratios.numel() >= 2 * n):
+        raise ValueError("ratios must be a contiguous device float64 tensor of at least 2 n elements")
+    st = lib().kfac_staleness(ctx.handle, n, ctypes.addressof(ds), *[p and ctypes.addressof(p) for p in ps],
+                              ratios.data_ptr())
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_staleness")
+
+
+class kfac_refresh_state(ctypes.Structure):
+    _fields_ = [("t_next", ctypes.c_int32), ("delta", ctypes.c_int32), ("delta_m1", ctypes.c_int32)]
+
+
+def kfac_next_interval(similar_to_last: bool, similar_to_before_last: bool, delta_m1: int, delta_m2: int) -> int:
+    return int(lib().kfac_next_interval(int(bool(similar_to_last)), int(bool(similar_to_before_last)), int(delta_m1),
+                                        int(delta_m2)))
+
+
+def kfac_refresh_init(n: int):
+    """A ctypes array of n refresh states, initialised by the library."""
+    arr = (kfac_refresh_state * n)()
+    lib().kfac_refresh_init(ctypes.addressof(arr), n)
+    return arr
+
+
+def kfac_refresh_due(state: kfac_refresh_state, t: int) -> bool:
+    return bool(lib().kfac_refresh_due(ctypes.addressof(state), int(t)))
+
+
+def kfac_refresh_advance(state: kfac_refresh_state, ratio_m1: float, ratio_m2: float, alpha: float) -> None:
+    lib().kfac_refresh_advance(ctypes.addressof(state), float(ratio_m1), float(ratio_m2), float(alpha))
 
 
 def kfac_profile_enable(ctx: Context, on: bool) -> None:

@@ -168,3 +168,70 @@ def test_resnet50_layer_set_matches_planned_histogram():
     assert sum(C for C, _ in bns) == 26560
     tot = sum(sum(wl.flops(L).values()) for L in layers)
     assert abs(tot / 1e12 - 1.396) < 0.01
+
+
+# ------------------------------------------------------------------ stale statistics: host logic (Sec. 4.3)
+def test_next_interval_matches_oracle_exhaustively():
+    from oracle import stale
+    for s1 in (False, True):
+        for s2 in (False, True):
+            for d1 in range(1, 40):
+                for d2 in range(1, 40):
+                    assert kfac.kfac_next_interval(s1, s2, d1, d2) == stale.next_interval(s1, s2, d1, d2)
+    assert kfac.kfac_next_interval(True, True, 0, 1) == 0 and kfac.kfac_next_interval(True, True, 1, -3) == 0
+    assert kfac.kfac_next_interval(True, True, 2 ** 31 - 1, 2 ** 31 - 1) == 2 ** 31 - 1      # saturates
+
+
+def test_refresh_state_follows_algorithm_1():
+    """Ratio streams (to the last value, to the one before) drive the library's state and the oracle's side by side."""
+    import math
+    import numpy as np
+    from oracle import stale
+    rng = np.random.default_rng(11)
+    alpha = 0.1
+    for trial in range(20):
+        st = kfac.kfac_refresh_init(1)
+        ref = stale.RefreshState()
+        assert (st[0].t_next, st[0].delta, st[0].delta_m1) == (1, 1, 1)
+        for t in range(1, 300):
+            assert kfac.kfac_refresh_due(st[0], t) == ref.due(t)
+            if ref.due(t):
+                r1, r2 = rng.choice([0.0, 0.05, 0.0999, 0.1, 0.3, math.inf, math.nan], 2)
+                kfac.kfac_refresh_advance(st[0], r1, r2, alpha)
+                ref.refreshed(r1 < alpha, r2 < alpha)
+                assert (st[0].t_next, st[0].delta, st[0].delta_m1) == (ref.t_next, ref.delta, ref.delta_m1)
+    # always similar: Fibonacci refresh steps
+    st = kfac.kfac_refresh_init(1)
+    steps = []
+    for t in range(1, 60):
+        if kfac.kfac_refresh_due(st[0], t):
+            steps.append(t)
+            k = len(steps)
+            kfac.kfac_refresh_advance(st[0], 0.0 if k >= 2 else math.inf, 0.0 if k >= 3 else math.inf, alpha)
+    assert steps == [1, 2, 3, 5, 8, 13, 21, 34, 55]
+
+
+def test_staleness_rejects_bad_arguments_without_a_gpu():
+    L = kfac.lib()
+    h = _fake_ctx()
+    fake = (ctypes.c_void_p * 1)(0x200000)
+    other = (ctypes.c_void_p * 1)(0x400000)
+    null1 = (ctypes.c_void_p * 1)(None)
+    fp, op, np_ = ctypes.addressof(fake), ctypes.addressof(other), ctypes.addressof(null1)
+    d = (ctypes.c_int32 * 1)(8)
+    dp = ctypes.addressof(d)
+    out = ctypes.c_void_p(0x600000)
+    INV = kfac.KFAC_ERR_INVALID
+    assert L.kfac_staleness(None, 1, dp, fp, op, None, out) == INV
+    assert L.kfac_staleness(h, 0, dp, fp, op, None, out) == INV
+    assert L.kfac_staleness(h, 1, None, fp, op, None, out) == INV
+    assert L.kfac_staleness(h, 1, dp, None, op, None, out) == INV
+    assert L.kfac_staleness(h, 1, dp, np_, op, None, out) == INV
+    assert L.kfac_staleness(h, 1, dp, fp, op, None, None) == INV
+    assert L.kfac_staleness(h, 1, dp, fp, fp, None, out) == INV          # X is its own predecessor
+    assert L.kfac_staleness(h, 1, dp, fp, op, fp, out) == INV
+    z = (ctypes.c_int32 * 1)(0)
+    assert L.kfac_staleness(h, 1, ctypes.addressof(z), fp, op, None, out) == INV
+    big = (ctypes.c_int32 * 1)(1 << 20)                                    # 2^40 elements: workspace of 1 MB is too small
+    assert L.kfac_staleness(h, 1, ctypes.addressof(big), fp, op, None, out) == kfac.KFAC_ERR_WORKSPACE
+    L.kfac_destroy(h)
