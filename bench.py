@@ -265,6 +265,32 @@ def main():
                                   "%.2f s measured), scaled to the whole step by algorithmic flops (x%.1f)"
                                   % (len(sample), acc / 1e9, t_cpu, total_flops / acc)}
 
+    # ---------------------------------------------------------------- beside the step: staleness of the factors
+    # (Sec. 4.3: what a refresh under Algorithm 1 adds -- every factor against its two predecessors)
+    dims = [L.dA for L in layers] + [L.dG for L in layers]
+    X = A + G
+    P = [x * 1.02 for x in X]
+    Q = [x * 0.95 for x in X]
+    ratios = torch.zeros(2 * len(dims), dtype=torch.float64, device="cuda")
+    kfac.kfac_staleness(ctx, dims, X, P, Q, ratios)
+    torch.cuda.synchronize()
+    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s0.record()
+    for _ in range(10):
+        kfac.kfac_staleness(ctx, dims, X, P, Q, ratios)
+    s1.record()
+    torch.cuda.synchronize()
+    stale_ms = s0.elapsed_time(s1) / 10
+    stale_bytes = 12.0 * sum(d * d for d in dims)
+    r = ratios.cpu().numpy().reshape(-1, 2)
+    assert abs(float(r[:, 0].max()) - 0.02 / 1.02) < 1e-4 and abs(float(r[:, 1].min()) - 0.05 / 0.95) < 1e-4
+    staleness = {"matrices": len(dims), "ms": round(stale_ms, 4), "gbytes": round(stale_bytes / 1e9, 3),
+                 "gbs": round(stale_bytes / (stale_ms * 1e-3) / 1e9, 1),
+                 "frac_of_hbm_peak": round(stale_bytes / (stale_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                 "note": "kfac_staleness over all factors of the configuration against two predecessors each "
+                         "(12 bytes per element); not part of the timed step"}
+    del P, Q
+
     out = {
         "metric": "K-FAC step ms for ResNet-50 layer set; factor+inverse TFLOP/s vs MFMA peak",
         "value": round(ms_per_step, 4),
@@ -301,6 +327,7 @@ def main():
                     for k, v in sorted(kernels.items())},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "staleness": staleness,
     }
     ctx.close()
     print(json.dumps(out))
