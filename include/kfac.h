@@ -206,6 +206,23 @@ kfac_status kfac_staleness(kfac_ctx *ctx, int32_t n, const int32_t *dims, const 
                            const float *const *X_m1, const float *const *X_m2, double *ratios);
 
 /*
+ * Symmetry-aware packing of the statistics, Sec. 5.2: a symmetric d x d matrix is
+ * communicated as its upper triangle, d (d + 1) / 2 elements.  Layout of `packed`
+ * (the paper fixes only the count): matrix i starts at element sum_{j<i} d_j (d_j + 1) / 2;
+ * inside it row r contributes X[r][r], X[r][r+1], ..., X[r][d-1], rows in order.
+ * kfac_packed_elems: the total number of elements (0 for invalid arguments).
+ * kfac_pack_upper: X[i] (dev, dense d_i x d_i floats; only the upper triangle is read)
+ * -> packed (dev, type floats or, for KFAC_BF16, bfloat16 rounded to nearest, ties to
+ * even).  kfac_unpack_upper: packed -> X[i], both triangles written (exactly symmetric).
+ * dims, X: host arrays.  X[i] must not overlap `packed`.  fp32 packing is a bit-exact copy.
+ */
+size_t kfac_packed_elems(int32_t n, const int32_t *dims);
+kfac_status kfac_pack_upper(kfac_ctx *ctx, int32_t n, const int32_t *dims, const float *const *X,
+                            kfac_dtype type, void *packed);
+kfac_status kfac_unpack_upper(kfac_ctx *ctx, int32_t n, const int32_t *dims, kfac_dtype type,
+                              const void *packed, float *const *X);
+
+/*
  * Algorithm 2 (Sec. 4.3): the acceptable interval, in steps, until a statistic is
  * refreshed next.  delta_m1: its last interval, delta_m2: the one before (both >= 1).
  *   not similar to the last value:                       max(1, delta_m1 / 2)
@@ -246,7 +263,7 @@ void kfac_refresh_advance(kfac_refresh_state *s, double ratio_m1, double ratio_m
 typedef enum {
     KFAC_K_GEMM_F32 = 0, KFAC_K_GEMM_BF16 = 1, KFAC_K_GEMM_REDUCE = 2, KFAC_K_PATCH = 3, KFAC_K_TRACE = 4,
     KFAC_K_COPY_DAMP = 5, KFAC_K_LEAF_INVERSE = 6, KFAC_K_ZERO = 7, KFAC_K_BN_UNIT = 8, KFAC_K_BN_REDUCE = 9,
-    KFAC_K_PAD = 10, KFAC_K_ASSEMBLE = 11, KFAC_K_BORDER = 12, KFAC_K_STALENESS = 13
+    KFAC_K_PAD = 10, KFAC_K_ASSEMBLE = 11, KFAC_K_BORDER = 12, KFAC_K_STALENESS = 13, KFAC_K_PACK = 14
 } kfac_kernel;
 
 typedef struct {

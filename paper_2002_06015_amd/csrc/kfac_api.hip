@@ -123,6 +123,7 @@ struct Tables {
 
 enum LaunchKind { L_GEMM, L_REDUCE, L_PATCH, L_TRACE, L_COPY, L_LEAF, L_ZERO, L_BN, L_BNRED, L_PAD, L_ASSEMBLE, L_BORDER,
                   L_STALE,   // cfg: pass 0 / 1
+                  L_PACK,    // cfg: 1 = unpack; dtype: 1 = bf16; p0: packed buffer
                   L_RECORD, L_WAIT };   // stream ordering: record / wait for sync event `n` on `stream`
 
 struct Launch {
@@ -1236,6 +1237,7 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 case L_ASSEMBLE: pe.kernel = KFAC_K_ASSEMBLE; break;
                 case L_BORDER: pe.kernel = KFAC_K_BORDER; break;
                 case L_STALE: pe.kernel = KFAC_K_STALENESS; break;
+                case L_PACK: pe.kernel = KFAC_K_PACK; break;
                 case L_RECORD: case L_WAIT: break;
             }
             pe.variant = (L.kind == L_GEMM || L.kind == L_LEAF) ? L.cfg : 0;
@@ -1286,6 +1288,9 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 break;
             case L_BNRED:
                 e = launch_bn_reduce((const BnReduceJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, ls);
+                break;
+            case L_PACK:
+                e = launch_pack((const PackJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.dtype, L.cfg, L.p0, ls);
                 break;
             case L_STALE:
                 e = launch_staleness((const StaleJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, ls);
@@ -1653,6 +1658,72 @@ kfac_status kfac_staleness(kfac_ctx *ctx, int32_t n, const int32_t *dims, const 
         plan.launches.push_back(L);
     }
     return run_plan(ctx, plan, arena);
+}
+
+size_t kfac_packed_elems(int32_t n, const int32_t *dims)
+{
+    if (n < 1 || !dims) return 0;
+    size_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        if (dims[i] < 1 || dims[i] > (1 << 20)) return 0;
+        total += (size_t)dims[i] * ((size_t)dims[i] + 1) / 2;
+    }
+    return total;
+}
+
+static kfac_status pack_call(kfac_ctx *ctx, int32_t n, const int32_t *dims, const float *const *X, kfac_dtype type,
+                             void *packed, int unpack)
+{
+    if (!ctx || n < 1 || n > 65536 || !dims || !X || !packed) return KFAC_ERR_INVALID;
+    if (type != KFAC_F32 && type != KFAC_BF16) return KFAC_ERR_INVALID;
+    const size_t total = kfac_packed_elems(n, dims);
+    if (total == 0) return KFAC_ERR_INVALID;
+    const size_t esize = type == KFAC_BF16 ? 2 : 4;
+    const char *p0 = (const char *)packed, *p1 = p0 + total * esize;
+    Plan plan; Arena arena(ctx->ws);
+    std::vector<PackJob> jobs;
+    long long wgs = 0, off = 0;
+    for (int i = 0; i < n; ++i) {
+        if (!X[i]) return KFAC_ERR_INVALID;
+        const char *x0 = (const char *)X[i], *x1 = x0 + (size_t)dims[i] * dims[i] * sizeof(float);
+        if (x0 < p1 && p0 < x1) return KFAC_ERR_INVALID;   // a matrix overlaps the packed buffer
+        PackJob J{};
+        J.X = X[i];
+        J.off = off;
+        J.d = dims[i];
+        J.tiles = (dims[i] + 63) / 64;
+        J.wg_start = (int)wgs;
+        wgs += (long long)J.tiles * (J.tiles + 1) / 2;
+        off += (long long)dims[i] * (dims[i] + 1) / 2;
+        if (wgs > (1LL << 30)) return KFAC_ERR_INVALID;
+        jobs.push_back(J);
+    }
+    Launch L{};
+    L.kind = L_PACK;
+    L.off_a = plan.tab.add(jobs.data(), jobs.size() * sizeof(PackJob));
+    L.n = n;
+    L.total_wgs = (int)wgs;
+    L.cfg = unpack;
+    L.dtype = type == KFAC_BF16 ? 1 : 0;
+    L.p0 = packed;
+    // packing reads and writes the triangle; unpacking reads it and writes the whole matrix
+    double full = 0;
+    for (int i = 0; i < n; ++i) full += 4.0 * dims[i] * dims[i];
+    L.bytes = unpack ? (double)total * esize + full : (double)total * (4.0 + esize);
+    plan.launches.push_back(L);
+    return run_plan(ctx, plan, arena);
+}
+
+kfac_status kfac_pack_upper(kfac_ctx *ctx, int32_t n, const int32_t *dims, const float *const *X,
+                            kfac_dtype type, void *packed)
+{
+    return pack_call(ctx, n, dims, X, type, packed, 0);
+}
+
+kfac_status kfac_unpack_upper(kfac_ctx *ctx, int32_t n, const int32_t *dims, kfac_dtype type,
+                              const void *packed, float *const *X)
+{
+    return pack_call(ctx, n, dims, (const float *const *)X, type, const_cast<void *>(packed), 1);
 }
 
 int32_t kfac_next_interval(int32_t similar_to_last, int32_t similar_to_before_last, int32_t delta_m1,

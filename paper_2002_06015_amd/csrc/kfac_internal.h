@@ -166,6 +166,15 @@ struct StaleJob {
 };
 constexpr int kStaleChunk = 4096;
 
+// Upper triangle of one d x d matrix <-> its place in the packed buffer (Sec. 5.2).
+struct PackJob {
+    const float *X;     // the matrix (written by the unpack kernel)
+    long long off;      // first element of this matrix in the packed buffer
+    int d;
+    int tiles;          // ceil(d / 64): the job has tiles (tiles + 1) / 2 workgroups
+    int wg_start;
+};
+
 // ---- launchers (implemented in the kernel files) -----------------------------------
 hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, int n_probs,
                        int total_wgs, int tile_cfg, int dtype, hipStream_t s);
@@ -188,6 +197,8 @@ hipError_t launch_bn(const BnJob *jobs_dev, int n_jobs, int total_wgs, int N, fl
                      hipStream_t s);
 hipError_t launch_bn_reduce(const BnReduceJob *jobs_dev, int n_jobs, int total_wgs, int N, hipStream_t s);
 // pass 0: per-chunk sums (total_wgs workgroups); pass 1: one workgroup per job adds them up and writes the ratios
+hipError_t launch_pack(const PackJob *jobs_dev, int n_jobs, int total_wgs, int bf16, int unpack, void *packed,
+                       hipStream_t s);
 hipError_t launch_staleness(const StaleJob *jobs_dev, int n_jobs, int total_wgs, int pass, hipStream_t s);
 
 // leaf size classes: a class value B serves n <= 32*B (one launch per class and level)

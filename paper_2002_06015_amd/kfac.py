@@ -22,11 +22,12 @@ EXPORTS = [
     "kfac_status_string", "kfac_layer_dims", "kfac_workspace_bytes", "kfac_create", "kfac_destroy",
     "kfac_im2col", "kfac_stats", "kfac_invert", "kfac_precondition", "kfac_step",
     "bn_unitwise_precondition", "bn_unitwise_reduce_nchw", "kfac_profile_enable", "kfac_profile_read",
+    "kfac_packed_elems", "kfac_pack_upper", "kfac_unpack_upper",
     "kfac_staleness", "kfac_next_interval", "kfac_refresh_init", "kfac_refresh_due", "kfac_refresh_advance",
 ]
 
 KERNEL_NAMES = ["gemm_f32", "gemm_bf16", "gemm_reduce", "patch", "trace", "copy_damp", "leaf_inverse", "zero",
-                "bn_unit", "bn_reduce", "pad", "assemble", "border", "staleness"]
+                "bn_unit", "bn_reduce", "pad", "assemble", "border", "staleness", "pack"]
 
 
 class kfac_profile_entry(ctypes.Structure):
@@ -75,6 +76,10 @@ def lib() -> ctypes.CDLL:
         L.kfac_profile_enable.argtypes = [vp, i32]
         L.kfac_profile_read.restype = i32
         L.kfac_profile_read.argtypes = [vp, vp, i32]
+        L.kfac_packed_elems.restype = ctypes.c_size_t
+        L.kfac_packed_elems.argtypes = [i32, vp]
+        L.kfac_pack_upper.argtypes = [vp, i32, vp, vp, ctypes.c_int, vp]
+        L.kfac_unpack_upper.argtypes = [vp, i32, vp, ctypes.c_int, vp, vp]
         L.kfac_staleness.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         L.kfac_next_interval.restype = i32
         L.kfac_next_interval.argtypes = [i32, i32, i32, i32]
@@ -273,6 +278,38 @@ def bn_unitwise_reduce_nchw(ctx: Context, N: int, C: Sequence[int], HW: Sequence
                                        *[p and ctypes.addressof(p) for p in ps])
     if st != KFAC_OK:
         raise KfacError(st, "bn_unitwise_reduce_nchw")
+
+
+def kfac_packed_elems(dims: Sequence[int]) -> int:
+    ds = _i32(dims)
+    return int(lib().kfac_packed_elems(len(dims), ctypes.addressof(ds)))
+
+
+def _packed_ok(packed: torch.Tensor, dims: Sequence[int], type_: int) -> None:
+    want = torch.bfloat16 if type_ == KFAC_BF16 else torch.float32
+    if not (packed.is_cuda and packed.is_contiguous() and packed.dtype == want and
+            packed.numel() >= kfac_packed_elems(dims)):
+        raise ValueError("packed must be a contiguous device tensor of the packed type and size")
+
+
+def kfac_pack_upper(ctx: Context, dims: Sequence[int], X, type_: int, packed: torch.Tensor) -> None:
+    n = len(dims)
+    ds, ps = _i32(dims), _ptrs(X, n, torch.float32)
+    _packed_ok(packed, dims, type_)
+    st = lib().kfac_pack_upper(ctx.handle, n, ctypes.addressof(ds), ps and ctypes.addressof(ps), int(type_),
+                               packed.data_ptr())
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_pack_upper")
+
+
+def kfac_unpack_upper(ctx: Context, dims: Sequence[int], type_: int, packed: torch.Tensor, X) -> None:
+    n = len(dims)
+    ds, ps = _i32(dims), _ptrs(X, n, torch.float32)
+    _packed_ok(packed, dims, type_)
+    st = lib().kfac_unpack_upper(ctx.handle, n, ctypes.addressof(ds), int(type_), packed.data_ptr(),
+                                 ps and ctypes.addressof(ps))
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_unpack_upper")
 
 
 def kfac_staleness(ctx: Context, dims: Sequence[int], X, X_m1, X_m2, ratios: torch.Tensor) -> None:

@@ -235,3 +235,31 @@ def test_staleness_rejects_bad_arguments_without_a_gpu():
     big = (ctypes.c_int32 * 1)(1 << 20)                                    # 2^40 elements: workspace of 1 MB is too small
     assert L.kfac_staleness(h, 1, ctypes.addressof(big), fp, op, None, out) == kfac.KFAC_ERR_WORKSPACE
     L.kfac_destroy(h)
+
+
+# ------------------------------------------------------------------ symmetric packing (Sec. 5.2): arguments
+def test_pack_rejects_bad_arguments_without_a_gpu():
+    L = kfac.lib()
+    h = _fake_ctx()
+    d = (ctypes.c_int32 * 2)(8, 5)
+    dp = ctypes.addressof(d)
+    assert kfac.kfac_packed_elems([8, 5]) == 36 + 15 and kfac.kfac_packed_elems([4609]) == 4609 * 4610 // 2
+    assert L.kfac_packed_elems(0, dp) == 0 and L.kfac_packed_elems(2, None) == 0
+    z = (ctypes.c_int32 * 1)(0)
+    assert L.kfac_packed_elems(1, ctypes.addressof(z)) == 0
+    mats = (ctypes.c_void_p * 2)(0x200000, 0x300000)
+    mp = ctypes.addressof(mats)
+    buf = ctypes.c_void_p(0x800000)
+    INV = kfac.KFAC_ERR_INVALID
+    assert L.kfac_pack_upper(None, 2, dp, mp, 0, buf) == INV
+    assert L.kfac_pack_upper(h, 0, dp, mp, 0, buf) == INV
+    assert L.kfac_pack_upper(h, 2, None, mp, 0, buf) == INV
+    assert L.kfac_pack_upper(h, 2, dp, None, 0, buf) == INV
+    assert L.kfac_pack_upper(h, 2, dp, mp, 0, None) == INV
+    assert L.kfac_pack_upper(h, 2, dp, mp, 5, buf) == INV                      # unknown type
+    hole = (ctypes.c_void_p * 2)(0x200000, None)
+    assert L.kfac_pack_upper(h, 2, dp, ctypes.addressof(hole), 0, buf) == INV
+    assert L.kfac_pack_upper(h, 2, dp, mp, 0, ctypes.c_void_p(0x200010)) == INV  # packed buffer inside a matrix
+    assert L.kfac_unpack_upper(h, 2, dp, 0, ctypes.c_void_p(0x300000), mp) == INV
+    assert L.kfac_unpack_upper(h, 2, dp, 1, None, mp) == INV
+    L.kfac_destroy(h)
