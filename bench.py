@@ -291,6 +291,32 @@ def main():
                          "(12 bytes per element); not part of the timed step"}
     del P, Q
 
+    # ---------------------------------------------------------------- beside the step: packing of the factors
+    # (Sec. 5.2: upper triangles of all factors into one send buffer, and back)
+    total = kfac.kfac_packed_elems(dims)
+    full_bytes = 4.0 * sum(d * d for d in dims)
+    packing = {"matrices": len(dims), "packed_elements": total}
+    for tname, ttype, tdtype, esize in (("f32", kfac.KFAC_F32, torch.float32, 4), ("bf16", kfac.KFAC_BF16, torch.bfloat16, 2)):
+        buf = torch.empty(total, dtype=tdtype, device="cuda")
+        back = [torch.empty_like(x) for x in X]
+        for name, call, nbytes in (("pack", lambda: kfac.kfac_pack_upper(ctx, dims, X, ttype, buf), total * (4.0 + esize)),
+                                   ("unpack", lambda: kfac.kfac_unpack_upper(ctx, dims, ttype, buf, back), total * esize + full_bytes)):
+            call()
+            torch.cuda.synchronize()
+            s0.record()
+            for _ in range(10):
+                call()
+            s1.record()
+            torch.cuda.synchronize()
+            ms = s0.elapsed_time(s1) / 10
+            packing["%s_%s" % (name, tname)] = {"ms": round(ms, 4), "gbytes": round(nbytes / 1e9, 3),
+                                               "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                                               "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        del buf, back
+    packing["note"] = ("kfac_pack_upper / kfac_unpack_upper over all factors of the configuration; bytes: the triangle "
+                       "read and written (pack), the triangle read and the whole matrix written (unpack); not part of "
+                       "the timed step")
+
     out = {
         "metric": "K-FAC step ms for ResNet-50 layer set; factor+inverse TFLOP/s vs MFMA peak",
         "value": round(ms_per_step, 4),
@@ -328,6 +354,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "staleness": staleness,
+        "packing": packing,
     }
     ctx.close()
     print(json.dumps(out))

@@ -42,14 +42,22 @@ __global__ __launch_bounds__(256) void pack_upper_kernel(const PackJob *__restri
     pack_tile_of(blockIdx.x - J.wg_start, J.tiles, tr, tc);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = 64 * tc + lane;
-#pragma unroll 4
+    // all 16 loads of a thread first (they are independent), then the stores
+    float v[16];
+    bool in[16];
+#pragma unroll
     for (int q = 0; q < 16; ++q) {
         const int r = 64 * tr + wave + 4 * q;
-        if (r >= J.d || c >= J.d || c < r) continue;
+        in[q] = r < J.d && c < J.d && c >= r;
+        v[q] = in[q] ? __builtin_nontemporal_load(J.X + (long long)r * J.d + c) : 0.f;
+    }
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        if (!in[q]) continue;
+        const int r = 64 * tr + wave + 4 * q;
         const long long k = J.off + (long long)r * J.d - (long long)r * (r - 1) / 2 + (c - r);
-        const float v = J.X[(long long)r * J.d + c];
-        if (BF16) ((unsigned short *)packed)[k] = pack_bf16(v);
-        else      ((float *)packed)[k] = v;
+        if (BF16) ((unsigned short *)packed)[k] = pack_bf16(v[q]);
+        else      ((float *)packed)[k] = v[q];
     }
 }
 
@@ -64,21 +72,28 @@ __global__ __launch_bounds__(256) void unpack_upper_kernel(const PackJob *__rest
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float *X = const_cast<float *>(J.X);
     const int c = 64 * tc + lane;
-#pragma unroll 4
+    float v[16];
+    bool in[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int r = 64 * tr + wave + 4 * q;
+        in[q] = r < J.d && c < J.d && c >= r;
+        v[q] = 0.f;
+        if (in[q]) {
+            const long long k = J.off + (long long)r * J.d - (long long)r * (r - 1) / 2 + (c - r);
+            v[q] = BF16 ? __uint_as_float((unsigned)((const unsigned short *)packed)[k] << 16) : ((const float *)packed)[k];
+        }
+    }
+#pragma unroll
     for (int q = 0; q < 16; ++q) {
         const int rl = wave + 4 * q, r = 64 * tr + rl;
-        float v = 0.f;
-        if (r < J.d && c < J.d && c >= r) {
-            const long long k = J.off + (long long)r * J.d - (long long)r * (r - 1) / 2 + (c - r);
-            v = BF16 ? __uint_as_float((unsigned)((const unsigned short *)packed)[k] << 16) : ((const float *)packed)[k];
-            X[(long long)r * J.d + c] = v;
-        }
-        tile[rl][lane] = v;
+        if (in[q]) X[(long long)r * J.d + c] = v[q];
+        tile[rl][lane] = v[q];
     }
     __syncthreads();
     // mirror image: element (c, r) for c > r, written along row c
     const int r = 64 * tr + lane;
-#pragma unroll 4
+#pragma unroll
     for (int q = 0; q < 16; ++q) {
         const int cl = wave + 4 * q, cc = 64 * tc + cl;
         if (cc < J.d && r < J.d && cc > r) X[(long long)cc * J.d + r] = tile[lane][cl];
