@@ -317,6 +317,30 @@ def main():
                        "read and written (pack), the triangle read and the whole matrix written (unpack); not part of "
                        "the timed step")
 
+    # ---------------------------------------------------------------- beside the step: the parameter update
+    # (Sec. 6.2, 6.3: w <- w - eta U + m v for all layers, then the rescaling to norm sqrt(2 d_out))
+    n_w = sum(L.dA * L.dG for L in layers)
+    Wt = [torch.randn(L.dG, L.dA, device="cuda") * (2.0 / L.dA) ** 0.5 for L in layers]
+    Wp = [w.clone() for w in Wt]
+    updating = {"layers": n, "weights": n_w}
+    for name, resc, per_elem in (("update", False, 20.0), ("update_rescale", True, 28.0)):
+        kfac.kfac_update_weights(ctx, layers, U, 1e-3, 0.9, resc, 1e-9, Wt, Wp)
+        torch.cuda.synchronize()
+        s0.record()
+        for _ in range(10):
+            kfac.kfac_update_weights(ctx, layers, U, 1e-3, 0.9, resc, 1e-9, Wt, Wp)
+        s1.record()
+        torch.cuda.synchronize()
+        ms = s0.elapsed_time(s1) / 10
+        updating[name] = {"ms": round(ms, 4), "gbytes": round(per_elem * n_w / 1e9, 3),
+                          "gbs": round(per_elem * n_w / (ms * 1e-3) / 1e9, 1),
+                          "frac_of_hbm_peak": round(per_elem * n_w / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    assert all(abs(float(w.double().norm()) - (2.0 * L.dG) ** 0.5) < 1e-4 * (2.0 * L.dG) ** 0.5 for w, L in zip(Wt, layers))
+    updating["note"] = ("kfac_update_weights over all layers of the configuration with the preconditioned gradients of "
+                        "the step; 20 bytes per weight for the update (U, w, w_prev read; w, w_prev written), 8 more for "
+                        "the rescaling; not part of the timed step")
+    del Wt, Wp
+
     out = {
         "metric": "K-FAC step ms for ResNet-50 layer set; factor+inverse TFLOP/s vs MFMA peak",
         "value": round(ms_per_step, 4),
@@ -355,6 +379,7 @@ def main():
         "cpu_baseline": cpu_baseline,
         "staleness": staleness,
         "packing": packing,
+        "update": updating,
     }
     ctx.close()
     print(json.dumps(out))

@@ -206,6 +206,31 @@ kfac_status kfac_staleness(kfac_ctx *ctx, int32_t n, const int32_t *dims, const 
                            const float *const *X_m1, const float *const *X_m2, double *ratios);
 
 /*
+ * Learning rate and momentum schedules, Sec. 6.2 (host only, no GPU work):
+ *   kfac_lr_polynomial:    eta(e) = eta0 (1 - (e - e_start) / (e_end - e_start))^p_decay  for
+ *                          e_start <= e <= e_end; eta0 before e_start, 0 after e_end
+ *   kfac_momentum_coupled: m(e) = m0 / eta0 * eta(e)   (the ratio m / eta stays fixed)
+ * NaN for e_end <= e_start or eta0 == 0 respectively.
+ */
+double kfac_lr_polynomial(double eta0, double e, double e_start, double e_end, double p_decay);
+double kfac_momentum_coupled(double m0, double eta0, double eta);
+
+/*
+ * Parameter update and weight rescaling, Sec. 6.2 Eq. "paramupdate" and Sec. 6.3.
+ * Per layer l, with the preconditioned gradient U[l] (as kfac_precondition writes it):
+ *   w' = W[l] - eta U[l] + momentum (W[l] - W_prev[l]);   W_prev[l] <- W[l];   W[l] <- w'
+ * and, if rescale != 0,  W[l] <- sqrt(2 c_out) W[l] / (||W[l]||_F + eps)  (the paper uses
+ * eps = 1e-9).  W[l], W_prev[l]: dev in/out, U[l]: dev in, all [dG, dA] floats
+ * (the layer's weights as a matrix, bias column last if it has one); the three must
+ * not overlap.  Arithmetic in fp32 (fused multiply-adds), the norm accumulated in
+ * double in a fixed order.  Uses 8 bytes of the workspace per 4096 weights plus 4 per
+ * layer when rescaling.
+ */
+kfac_status kfac_update_weights(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, const float *const *U,
+                                float eta, float momentum, int32_t rescale, float eps, float *const *W,
+                                float *const *W_prev);
+
+/*
  * Symmetry-aware packing of the statistics, Sec. 5.2: a symmetric d x d matrix is
  * communicated as its upper triangle, d (d + 1) / 2 elements.  Layout of `packed`
  * (the paper fixes only the count): matrix i starts at element sum_{j<i} d_j (d_j + 1) / 2;
@@ -263,7 +288,7 @@ void kfac_refresh_advance(kfac_refresh_state *s, double ratio_m1, double ratio_m
 typedef enum {
     KFAC_K_GEMM_F32 = 0, KFAC_K_GEMM_BF16 = 1, KFAC_K_GEMM_REDUCE = 2, KFAC_K_PATCH = 3, KFAC_K_TRACE = 4,
     KFAC_K_COPY_DAMP = 5, KFAC_K_LEAF_INVERSE = 6, KFAC_K_ZERO = 7, KFAC_K_BN_UNIT = 8, KFAC_K_BN_REDUCE = 9,
-    KFAC_K_PAD = 10, KFAC_K_ASSEMBLE = 11, KFAC_K_BORDER = 12, KFAC_K_STALENESS = 13, KFAC_K_PACK = 14
+    KFAC_K_PAD = 10, KFAC_K_ASSEMBLE = 11, KFAC_K_BORDER = 12, KFAC_K_STALENESS = 13, KFAC_K_PACK = 14, KFAC_K_UPDATE = 15
 } kfac_kernel;
 
 typedef struct {

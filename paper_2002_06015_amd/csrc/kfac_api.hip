@@ -124,6 +124,7 @@ struct Tables {
 enum LaunchKind { L_GEMM, L_REDUCE, L_PATCH, L_TRACE, L_COPY, L_LEAF, L_ZERO, L_BN, L_BNRED, L_PAD, L_ASSEMBLE, L_BORDER,
                   L_STALE,   // cfg: pass 0 / 1
                   L_PACK,    // cfg: 1 = unpack; dtype: 1 = bf16; p0: packed buffer
+                  L_UPDATE,  // cfg: pass 0 / 1 / 2; f0: eta; f1: momentum (pass 1: f0 = eps)
                   L_RECORD, L_WAIT };   // stream ordering: record / wait for sync event `n` on `stream`
 
 struct Launch {
@@ -1238,6 +1239,7 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 case L_BORDER: pe.kernel = KFAC_K_BORDER; break;
                 case L_STALE: pe.kernel = KFAC_K_STALENESS; break;
                 case L_PACK: pe.kernel = KFAC_K_PACK; break;
+                case L_UPDATE: pe.kernel = KFAC_K_UPDATE; break;
                 case L_RECORD: case L_WAIT: break;
             }
             pe.variant = (L.kind == L_GEMM || L.kind == L_LEAF) ? L.cfg : 0;
@@ -1288,6 +1290,9 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 break;
             case L_BNRED:
                 e = launch_bn_reduce((const BnReduceJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, ls);
+                break;
+            case L_UPDATE:
+                e = launch_update((const UpdateJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, L.f0, L.f1, L.f0, ls);
                 break;
             case L_PACK:
                 e = launch_pack((const PackJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.dtype, L.cfg, L.p0, ls);
@@ -1656,6 +1661,68 @@ kfac_status kfac_staleness(kfac_ctx *ctx, int32_t n, const int32_t *dims, const 
         L.cfg = pass;
         L.bytes = pass == 0 ? bytes : 0.0;
         plan.launches.push_back(L);
+    }
+    return run_plan(ctx, plan, arena);
+}
+
+double kfac_lr_polynomial(double eta0, double e, double e_start, double e_end, double p_decay)
+{
+    if (!(e_end > e_start)) return NAN;
+    if (e <= e_start) return eta0;
+    if (e >= e_end) return 0.0;
+    return eta0 * pow(1.0 - (e - e_start) / (e_end - e_start), p_decay);
+}
+
+double kfac_momentum_coupled(double m0, double eta0, double eta)
+{
+    if (eta0 == 0.0) return NAN;
+    return m0 / eta0 * eta;
+}
+
+kfac_status kfac_update_weights(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, const float *const *U,
+                                float eta, float momentum, int32_t rescale, float eps, float *const *W,
+                                float *const *W_prev)
+{
+    if (!ctx || n_layers < 1 || n_layers > 65536 || !L || !U || !W || !W_prev) return KFAC_ERR_INVALID;
+    if (!std::isfinite(eta) || !std::isfinite(momentum) || !(eps >= 0.f) || !std::isfinite(eps)) return KFAC_ERR_INVALID;
+    Plan plan; Arena arena(ctx->ws);
+    std::vector<UpdateJob> jobs;
+    long long wgs = 0;
+    double bytes = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        int dA, dG;
+        if (!layer_ok(L[l], &dA, &dG, nullptr, nullptr)) return KFAC_ERR_INVALID;
+        if (!U[l] || !W[l] || !W_prev[l]) return KFAC_ERR_INVALID;
+        const size_t sz = (size_t)dA * dG * sizeof(float);
+        auto overlap = [&](const void *a, const void *b) { return (const char *)a < (const char *)b + sz && (const char *)b < (const char *)a + sz; };
+        if (overlap(U[l], W[l]) || overlap(U[l], W_prev[l]) || overlap(W[l], W_prev[l])) return KFAC_ERR_INVALID;
+        UpdateJob J{};
+        J.W = W[l]; J.W_prev = W_prev[l]; J.U = U[l];
+        J.n = (long long)dA * dG;
+        J.d_out = dG;
+        J.wgs = (int)((J.n + kUpdateChunk - 1) / kUpdateChunk);
+        if (rescale) {
+            J.partial = (double *)arena.take((size_t)J.wgs * sizeof(double));
+            J.scale = (float *)arena.take(sizeof(float));
+        }
+        J.wg_start = (int)wgs;
+        wgs += J.wgs;
+        if (wgs > (1LL << 30)) return KFAC_ERR_INVALID;
+        bytes += 4.0 * J.n;
+        jobs.push_back(J);
+    }
+    const size_t off = plan.tab.add(jobs.data(), jobs.size() * sizeof(UpdateJob));
+    for (int pass = 0; pass < (rescale ? 3 : 1); ++pass) {
+        Launch Lc{};
+        Lc.kind = L_UPDATE;
+        Lc.off_a = off;
+        Lc.n = n_layers;
+        Lc.total_wgs = (int)wgs;
+        Lc.cfg = pass;
+        Lc.f0 = pass == 1 ? eps : eta;
+        Lc.f1 = momentum;
+        Lc.bytes = pass == 0 ? 5.0 * bytes : (pass == 2 ? 2.0 * bytes : 0.0);
+        plan.launches.push_back(Lc);
     }
     return run_plan(ctx, plan, arena);
 }

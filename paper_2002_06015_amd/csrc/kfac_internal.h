@@ -166,6 +166,19 @@ struct StaleJob {
 };
 constexpr int kStaleChunk = 4096;
 
+// Parameter update of one layer (Sec. 6.2, 6.3): n = d_out * d_in weights.
+struct UpdateJob {
+    float *W, *W_prev;
+    const float *U;
+    long long n;
+    double *partial;    // [wgs] sums of squares of the new weights per chunk; null: no rescaling
+    float *scale;       // [1] sqrt(2 d_out) / (||w'|| + eps)
+    int d_out;
+    int wgs;            // chunks of kUpdateChunk weights
+    int wg_start;
+};
+constexpr int kUpdateChunk = 4096;
+
 // Upper triangle of one d x d matrix <-> its place in the packed buffer (Sec. 5.2).
 struct PackJob {
     const float *X;     // the matrix (written by the unpack kernel)
@@ -199,6 +212,9 @@ hipError_t launch_bn_reduce(const BnReduceJob *jobs_dev, int n_jobs, int total_w
 // pass 0: per-chunk sums (total_wgs workgroups); pass 1: one workgroup per job adds them up and writes the ratios
 hipError_t launch_pack(const PackJob *jobs_dev, int n_jobs, int total_wgs, int bf16, int unpack, void *packed,
                        hipStream_t s);
+// pass 0: the update (+ sums of squares); 1: scale factor per layer; 2: rescale
+hipError_t launch_update(const UpdateJob *jobs_dev, int n_jobs, int total_wgs, int pass, float eta, float momentum,
+                         float eps, hipStream_t s);
 hipError_t launch_staleness(const StaleJob *jobs_dev, int n_jobs, int total_wgs, int pass, hipStream_t s);
 
 // leaf size classes: a class value B serves n <= 32*B (one launch per class and level)

@@ -23,11 +23,12 @@ EXPORTS = [
     "kfac_im2col", "kfac_stats", "kfac_invert", "kfac_precondition", "kfac_step",
     "bn_unitwise_precondition", "bn_unitwise_reduce_nchw", "kfac_profile_enable", "kfac_profile_read",
     "kfac_packed_elems", "kfac_pack_upper", "kfac_unpack_upper",
+    "kfac_lr_polynomial", "kfac_momentum_coupled", "kfac_update_weights",
     "kfac_staleness", "kfac_next_interval", "kfac_refresh_init", "kfac_refresh_due", "kfac_refresh_advance",
 ]
 
 KERNEL_NAMES = ["gemm_f32", "gemm_bf16", "gemm_reduce", "patch", "trace", "copy_damp", "leaf_inverse", "zero",
-                "bn_unit", "bn_reduce", "pad", "assemble", "border", "staleness", "pack"]
+                "bn_unit", "bn_reduce", "pad", "assemble", "border", "staleness", "pack", "update"]
 
 
 class kfac_profile_entry(ctypes.Structure):
@@ -76,6 +77,12 @@ def lib() -> ctypes.CDLL:
         L.kfac_profile_enable.argtypes = [vp, i32]
         L.kfac_profile_read.restype = i32
         L.kfac_profile_read.argtypes = [vp, vp, i32]
+        f64 = ctypes.c_double
+        L.kfac_lr_polynomial.restype = f64
+        L.kfac_lr_polynomial.argtypes = [f64, f64, f64, f64, f64]
+        L.kfac_momentum_coupled.restype = f64
+        L.kfac_momentum_coupled.argtypes = [f64, f64, f64]
+        L.kfac_update_weights.argtypes = [vp, i32, vp, vp, f32, f32, i32, f32, vp, vp]
         L.kfac_packed_elems.restype = ctypes.c_size_t
         L.kfac_packed_elems.argtypes = [i32, vp]
         L.kfac_pack_upper.argtypes = [vp, i32, vp, vp, ctypes.c_int, vp]
@@ -278,6 +285,26 @@ def bn_unitwise_reduce_nchw(ctx: Context, N: int, C: Sequence[int], HW: Sequence
                                        *[p and ctypes.addressof(p) for p in ps])
     if st != KFAC_OK:
         raise KfacError(st, "bn_unitwise_reduce_nchw")
+
+
+def kfac_lr_polynomial(eta0: float, e: float, e_start: float, e_end: float, p_decay: float) -> float:
+    return float(lib().kfac_lr_polynomial(eta0, e, e_start, e_end, p_decay))
+
+
+def kfac_momentum_coupled(m0: float, eta0: float, eta: float) -> float:
+    return float(lib().kfac_momentum_coupled(m0, eta0, eta))
+
+
+def kfac_update_weights(ctx: Context, layers: Sequence, U, eta: float, momentum: float, rescale: bool, eps: float,
+                        W, W_prev) -> None:
+    n = len(layers)
+    ls = _layers(layers)
+    ps = [_ptrs(x, n, torch.float32) for x in (U, W, W_prev)]
+    st = lib().kfac_update_weights(ctx.handle, n, ctypes.addressof(ls), ps[0] and ctypes.addressof(ps[0]), float(eta),
+                                   float(momentum), int(bool(rescale)), float(eps), ps[1] and ctypes.addressof(ps[1]),
+                                   ps[2] and ctypes.addressof(ps[2]))
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_update_weights")
 
 
 def kfac_packed_elems(dims: Sequence[int]) -> int:

@@ -263,3 +263,55 @@ def test_pack_rejects_bad_arguments_without_a_gpu():
     assert L.kfac_unpack_upper(h, 2, dp, 0, ctypes.c_void_p(0x300000), mp) == INV
     assert L.kfac_unpack_upper(h, 2, dp, 1, None, mp) == INV
     L.kfac_destroy(h)
+
+
+# ------------------------------------------------------------------ parameter update (Sec. 6.2, 6.3): host logic, arguments
+def test_schedules_match_oracle():
+    import math
+    import numpy as np
+    from oracle import update
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        eta0, p = float(rng.uniform(1e-4, 1.0)), float(rng.uniform(0.5, 12.0))
+        e0 = float(rng.uniform(0, 5))
+        e1 = e0 + float(rng.uniform(0.5, 90))
+        for e in (0.0, e0, e0 + 1e-9, 0.5 * (e0 + e1), e1 - 1e-9, e1, e1 + 3, float(rng.uniform(0, 100))):
+            ref = update.lr_polynomial(eta0, e, e0, e1, p)
+            assert math.isclose(kfac.kfac_lr_polynomial(eta0, e, e0, e1, p), ref, rel_tol=1e-13, abs_tol=1e-300)
+            m0 = float(rng.uniform(0.0, 1.0))
+            assert math.isclose(kfac.kfac_momentum_coupled(m0, eta0, ref), update.momentum_coupled(m0, eta0, ref),
+                                rel_tol=1e-15, abs_tol=0.0)
+    assert math.isnan(kfac.kfac_lr_polynomial(0.1, 1.0, 5.0, 5.0, 2.0))
+    assert math.isnan(kfac.kfac_lr_polynomial(0.1, 1.0, 5.0, 4.0, 2.0))
+    assert math.isnan(kfac.kfac_momentum_coupled(0.9, 0.0, 0.1))
+
+
+def test_update_rejects_bad_arguments_without_a_gpu():
+    L = kfac.lib()
+    INV = kfac.KFAC_ERR_INVALID
+    h = _fake_ctx(1 << 20)
+    lays = (kfac.kfac_layer * 2)(kfac.kfac_layer(*wl.fc_layer(2, 64, 32)), kfac.kfac_layer(*wl.fc_layer(2, 16, 8)))
+    lp = ctypes.addressof(lays)
+    u = (ctypes.c_void_p * 2)(0x200000, 0x300000)
+    w = (ctypes.c_void_p * 2)(0x400000, 0x500000)
+    wp = (ctypes.c_void_p * 2)(0x600000, 0x700000)
+    up, wpt, wpp = ctypes.addressof(u), ctypes.addressof(w), ctypes.addressof(wp)
+    call = L.kfac_update_weights
+    assert call(None, 2, lp, up, 0.1, 0.9, 1, 1e-9, wpt, wpp) == INV
+    assert call(h, 0, lp, up, 0.1, 0.9, 1, 1e-9, wpt, wpp) == INV
+    assert call(h, 2, None, up, 0.1, 0.9, 1, 1e-9, wpt, wpp) == INV
+    assert call(h, 2, lp, None, 0.1, 0.9, 1, 1e-9, wpt, wpp) == INV
+    assert call(h, 2, lp, up, 0.1, 0.9, 1, 1e-9, None, wpp) == INV
+    assert call(h, 2, lp, up, 0.1, 0.9, 1, 1e-9, wpt, None) == INV
+    assert call(h, 2, lp, up, float("nan"), 0.9, 1, 1e-9, wpt, wpp) == INV
+    assert call(h, 2, lp, up, 0.1, float("inf"), 1, 1e-9, wpt, wpp) == INV
+    assert call(h, 2, lp, up, 0.1, 0.9, 1, -1.0, wpt, wpp) == INV
+    hole = (ctypes.c_void_p * 2)(0x400000, None)
+    assert call(h, 2, lp, up, 0.1, 0.9, 1, 1e-9, ctypes.addressof(hole), wpp) == INV
+    same = (ctypes.c_void_p * 2)(0x400000 + 64, 0x500000)                          # W_prev inside W
+    assert call(h, 2, lp, up, 0.1, 0.9, 1, 1e-9, wpt, ctypes.addressof(same)) == INV
+    assert call(h, 2, lp, wpt, 0.1, 0.9, 0, 1e-9, wpt, wpp) == INV                 # U aliases W
+    bad = (kfac.kfac_layer * 1)(kfac.kfac_layer(*wl.fc_layer(2, 64, 32)))
+    bad[0].c_out = 0
+    assert call(h, 1, ctypes.addressof(bad), up, 0.1, 0.9, 1, 1e-9, wpt, wpp) == INV
+    L.kfac_destroy(h)
