@@ -178,6 +178,30 @@ kfac_status bn_unitwise_precondition(kfac_ctx *ctx, int32_t n_layers, int32_t N,
                                      float *const *out_gamma, float *const *out_beta);
 
 /*
+ * Natural gradient for BatchNorm with the Fisher block of the whole layer (Sec. 4.2, the
+ * 2c x 2c matrix that the unit-wise approximation replaces; "fullBN" in Sec. 7).  With
+ * g_n = (g_gamma[n,0], g_beta[n,0], ..., g_gamma[n,c-1], g_beta[n,c-1]) the per-sample
+ * gradient in the order of the layer's parameter vector:
+ *   F_ema[l] <- decay F_ema[l] + (1-decay) (1/N) sum_n g_n g_n^T      (decay == 0: F_ema is not read)
+ *   F_inv[l] <- (F_ema[l] + lambda I)^-1      for layers with invert_mask[l] != 0
+ *   (out_gamma[l][i], out_beta[l][i]) = rows 2i, 2i+1 of F_inv[l] mean_n g_n
+ * g_gamma[l], g_beta[l]: dev [N, C[l]];  F_ema[l]: dev in/out [2C, 2C];  F_inv[l]: dev
+ * [2C, 2C], out for inverted layers and in otherwise (stale inverse, Sec. 4.3), must
+ * not be F_ema[l];  out_gamma[l], out_beta[l]: dev [C[l]].  invert_mask: host uint8
+ * [n_layers] or NULL (all).  info: dev int32 [n_layers] or NULL, 0 or the first
+ * non-positive pivot (1-based) as for kfac_invert.  C: host, 1 <= C[l] <= 32768.
+ * Scratch comes from the context's workspace: bn_full_workspace_bytes reports the size
+ * (0 for invalid arguments) that serves every layer inverted and any one layer alone;
+ * KFAC_ERR_WORKSPACE before any launch if a call needs more than the context has.
+ */
+size_t bn_full_workspace_bytes(int32_t n_layers, int32_t N, const int32_t *C);
+kfac_status bn_full_precondition(kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,
+                                 const float *const *g_gamma, const float *const *g_beta,
+                                 float decay, float lambda, float *const *F_ema,
+                                 const uint8_t *invert_mask, float *const *F_inv, int32_t *info,
+                                 float *const *out_gamma, float *const *out_beta);
+
+/*
  * Producer of the per-sample BatchNorm gradients used above (Sec. 4.2): for
  * y = gamma*xhat + beta,  g_gamma[n, c] = sum_t dy[n,c,t]*xhat[n,c,t],
  * g_beta[n, c] = sum_t dy[n,c,t].  dy[l], xhat[l]: dev fp32 [N, C[l], HW[l]];
@@ -288,7 +312,7 @@ void kfac_refresh_advance(kfac_refresh_state *s, double ratio_m1, double ratio_m
 typedef enum {
     KFAC_K_GEMM_F32 = 0, KFAC_K_GEMM_BF16 = 1, KFAC_K_GEMM_REDUCE = 2, KFAC_K_PATCH = 3, KFAC_K_TRACE = 4,
     KFAC_K_COPY_DAMP = 5, KFAC_K_LEAF_INVERSE = 6, KFAC_K_ZERO = 7, KFAC_K_BN_UNIT = 8, KFAC_K_BN_REDUCE = 9,
-    KFAC_K_PAD = 10, KFAC_K_ASSEMBLE = 11, KFAC_K_BORDER = 12, KFAC_K_STALENESS = 13, KFAC_K_PACK = 14, KFAC_K_UPDATE = 15
+    KFAC_K_PAD = 10, KFAC_K_ASSEMBLE = 11, KFAC_K_BORDER = 12, KFAC_K_STALENESS = 13, KFAC_K_PACK = 14, KFAC_K_UPDATE = 15, KFAC_K_BN_FULL = 16
 } kfac_kernel;
 
 typedef struct {

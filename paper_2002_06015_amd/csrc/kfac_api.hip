@@ -125,6 +125,7 @@ enum LaunchKind { L_GEMM, L_REDUCE, L_PATCH, L_TRACE, L_COPY, L_LEAF, L_ZERO, L_
                   L_STALE,   // cfg: pass 0 / 1
                   L_PACK,    // cfg: 1 = unpack; dtype: 1 = bf16; p0: packed buffer
                   L_UPDATE,  // cfg: pass 0 / 1 / 2; f0: eta; f1: momentum (pass 1: f0 = eps)
+                  L_BNFULL,  // cfg: pass 0 / 1 / 2; dtype: N; f0: decay; f1: lambda; p0: damp
                   L_RECORD, L_WAIT };   // stream ordering: record / wait for sync event `n` on `stream`
 
 struct Launch {
@@ -776,39 +777,12 @@ struct InvertArgs {
     int32_t *info;
 };
 
-// Inversion of both factors of the layers `ids` as one chain of launches on `stream`:
-// traces / damping, the damped copies, then the recursion of every matrix with the launches
-// of equal depth merged.  damp: [3 * n_layers] floats shared by all groups of the call.
-void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs &a, bool dry,
-                       const std::vector<int> &ids, float *damp, int stream)
+// Inversion of a list of damped SPD matrices as one chain of launches: the damped copies, then
+// the recursion of every matrix with the launches of equal depth merged, then the bias borders.
+// damp: device array the matrices' damp_idx point into; info: device array for info_idx or null.
+void plan_invert_mats(Plan &plan, Arena &arena, const Tunables &tun, const std::vector<InvMatrix> &mats,
+                      float *damp, int32_t *info)
 {
-    if (ids.empty()) return;
-    const size_t first_launch = plan.launches.size();
-    std::vector<TraceJob> tjobs;
-    std::vector<InvMatrix> mats;
-    for (int l : ids) {
-        int dA, dG;
-        layer_ok(a.L[l], &dA, &dG, nullptr, nullptr);
-        TraceJob T{};
-        T.A = dry ? nullptr : a.A_ema[l];
-        T.G = dry ? nullptr : a.G_ema[l];
-        T.dA = dA; T.dG = dG;
-        T.idx = l;
-        tjobs.push_back(T);
-        // dry runs only need distinct, well-aligned stand-in addresses for planning
-        mats.push_back({T.A, dry ? (float *)nullptr : a.A_inv[l], dA, 3 * l + 1, 2 * l, a.L[l].bias != 0});
-        mats.push_back({T.G, dry ? (float *)nullptr : a.G_inv[l], dG, 3 * l + 2, 2 * l + 1, false});
-    }
-    {
-        Launch T{};
-        T.kind = L_TRACE;
-        T.off_a = plan.tab.add(tjobs.data(), tjobs.size() * sizeof(TraceJob));
-        T.n = (int)tjobs.size();
-        T.f0 = a.gamma;
-        T.p0 = damp;
-        T.p1 = a.pi_out;
-        plan.launches.push_back(T);
-    }
     std::vector<CopyJob> cjobs;
     std::vector<BorderJob> bjobs;
     int copy_wgs = 0, border_wgs = 0;
@@ -876,7 +850,7 @@ void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const Inve
             Lf.n = (int)lj.size();
             Lf.cfg = c;
             Lf.p0 = damp;
-            Lf.p1 = a.info;
+            Lf.p1 = info;
             plan.launches.push_back(Lf);
         }
         std::vector<GemmProblem> gp;
@@ -897,11 +871,47 @@ void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const Inve
             B.total_wgs = border_wgs;
             B.cfg = pass;
             B.p0 = damp;
-            B.p1 = a.info;
+            B.p1 = info;
             B.bytes = pass == 0 ? border_bytes : 0.0;
             plan.launches.push_back(B);
         }
     }
+}
+
+// Inversion of both factors of the layers `ids` as one chain of launches on `stream`:
+// traces / damping, the damped copies, then the recursion of every matrix with the launches
+// of equal depth merged.  damp: [3 * n_layers] floats shared by all groups of the call.
+void plan_invert_group(Plan &plan, Arena &arena, const Tunables &tun, const InvertArgs &a, bool dry,
+                       const std::vector<int> &ids, float *damp, int stream)
+{
+    if (ids.empty()) return;
+    const size_t first_launch = plan.launches.size();
+    std::vector<TraceJob> tjobs;
+    std::vector<InvMatrix> mats;
+    for (int l : ids) {
+        int dA, dG;
+        layer_ok(a.L[l], &dA, &dG, nullptr, nullptr);
+        TraceJob T{};
+        T.A = dry ? nullptr : a.A_ema[l];
+        T.G = dry ? nullptr : a.G_ema[l];
+        T.dA = dA; T.dG = dG;
+        T.idx = l;
+        tjobs.push_back(T);
+        // dry runs only need distinct, well-aligned stand-in addresses for planning
+        mats.push_back({T.A, dry ? (float *)nullptr : a.A_inv[l], dA, 3 * l + 1, 2 * l, a.L[l].bias != 0});
+        mats.push_back({T.G, dry ? (float *)nullptr : a.G_inv[l], dG, 3 * l + 2, 2 * l + 1, false});
+    }
+    {
+        Launch T{};
+        T.kind = L_TRACE;
+        T.off_a = plan.tab.add(tjobs.data(), tjobs.size() * sizeof(TraceJob));
+        T.n = (int)tjobs.size();
+        T.f0 = a.gamma;
+        T.p0 = damp;
+        T.p1 = a.pi_out;
+        plan.launches.push_back(T);
+    }
+    plan_invert_mats(plan, arena, tun, mats, damp, a.info);
     plan.set_stream(first_launch, stream);
 }
 
@@ -1240,6 +1250,7 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 case L_STALE: pe.kernel = KFAC_K_STALENESS; break;
                 case L_PACK: pe.kernel = KFAC_K_PACK; break;
                 case L_UPDATE: pe.kernel = KFAC_K_UPDATE; break;
+                case L_BNFULL: pe.kernel = KFAC_K_BN_FULL; break;
                 case L_RECORD: case L_WAIT: break;
             }
             pe.variant = (L.kind == L_GEMM || L.kind == L_LEAF) ? L.cfg : 0;
@@ -1290,6 +1301,10 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 break;
             case L_BNRED:
                 e = launch_bn_reduce((const BnReduceJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, ls);
+                break;
+            case L_BNFULL:
+                e = launch_bn_full((const BnFullJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, L.dtype, L.f0, L.f1,
+                                   (float *)L.p0, ls);
                 break;
             case L_UPDATE:
                 e = launch_update((const UpdateJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, L.f0, L.f1, L.f0, ls);
@@ -1592,6 +1607,171 @@ kfac_status bn_unitwise_precondition(kfac_ctx *ctx, int32_t n_layers, int32_t N,
     Lc.f0 = decay;
     Lc.f1 = lambda;
     plan.launches.push_back(Lc);
+    return run_plan(ctx, plan, arena);
+}
+
+namespace {
+struct BnFullArgs {
+    int n_layers, N;
+    const int32_t *C;
+    const float *const *g_gamma, *const *g_beta;
+    float decay, lambda;
+    float *const *F_ema;
+    const uint8_t *invert_mask;
+    float *const *F_inv;
+    int32_t *info;
+    float *const *out_gamma, *const *out_beta;
+};
+
+// factor update -> mean gradient and damping -> inversions (dealt by n^3 onto the context's
+// stream and the auxiliary ones, as kfac_invert does) -> u = F_inv gbar
+void plan_bn_full(Plan &plan, Arena &arena, const Tunables &tun, const BnFullArgs &a, bool dry)
+{
+    const int n = a.n_layers;
+    float *damp = (float *)arena.take((size_t)n * sizeof(float));
+    std::vector<BnFullJob> jobs(n);
+    long long wgs[3] = {0, 0, 0};
+    double bytes[3] = {0, 0, 0};
+    std::vector<int> inv_ids;
+    for (int l = 0; l < n; ++l) {
+        BnFullJob &J = jobs[l];
+        const long long d = 2LL * a.C[l];
+        const bool inv = !a.invert_mask || a.invert_mask[l];
+        J.g_gamma = dry ? nullptr : a.g_gamma[l];
+        J.g_beta = dry ? nullptr : a.g_beta[l];
+        J.F_ema = dry ? nullptr : a.F_ema[l];
+        J.F_inv = dry ? nullptr : a.F_inv[l];
+        J.out_gamma = dry ? nullptr : a.out_gamma[l];
+        J.out_beta = dry ? nullptr : a.out_beta[l];
+        J.gbar = (float *)arena.take((size_t)d * sizeof(float));
+        J.C = a.C[l];
+        J.damp_idx = inv ? l : -1;
+        const long long tiles = (d + 63) / 64;
+        const long long w[3] = {tiles * tiles, (d + 255) / 256, (d + 3) / 4};
+        for (int q = 0; q < 3; ++q) { J.wg_start[q] = (int)wgs[q]; wgs[q] += w[q]; }
+        bytes[0] += (a.decay == 0.f ? 4.0 : 8.0) * d * d + 4.0 * a.N * d * 2 * tiles;
+        bytes[1] += 4.0 * a.N * d + 4.0 * d;
+        bytes[2] += 4.0 * d * d + 8.0 * d;
+        if (inv) inv_ids.push_back(l);
+    }
+    const size_t off = plan.tab.add(jobs.data(), jobs.size() * sizeof(BnFullJob));
+    auto pass = [&](int q) {
+        Launch Lc{};
+        Lc.kind = L_BNFULL;
+        Lc.off_a = off;
+        Lc.n = n;
+        Lc.total_wgs = (int)wgs[q];
+        Lc.cfg = q;
+        Lc.dtype = a.N;
+        Lc.f0 = a.decay;
+        Lc.f1 = a.lambda;
+        Lc.p0 = damp;
+        Lc.bytes = bytes[q];
+        plan.launches.push_back(Lc);
+    };
+    pass(0);
+    pass(1);
+    if (a.info || dry) {
+        Launch Z{};
+        Z.kind = L_ZERO;
+        Z.p0 = a.info;
+        Z.n = n;
+        plan.launches.push_back(Z);
+    }
+    if (!inv_ids.empty()) {
+        const int n_groups = std::max(1, std::min(tun.inv_streams, 4));
+        auto cube = [&](int l) { const double d = 2.0 * a.C[l]; return d > kLeafMax ? d * d * d : 0.0; };
+        std::stable_sort(inv_ids.begin(), inv_ids.end(), [&](int x, int y) { return cube(x) > cube(y); });
+        std::vector<std::vector<InvMatrix>> groups(n_groups);
+        std::vector<double> load(n_groups, 0.0);
+        for (int l : inv_ids) {
+            int g = 0;
+            if (cube(l) > 0.0)
+                for (int q = 0; q < n_groups; ++q)
+                    if (load[q] < load[g]) g = q;
+            groups[g].push_back({jobs[l].F_ema, dry ? (float *)nullptr : a.F_inv[l], 2 * a.C[l], l, l, false});
+            load[g] += cube(l);
+        }
+        bool forked = false;
+        for (int gi = 0; gi < n_groups; ++gi) {
+            const int g = (gi + 1) % n_groups;   // auxiliary chains are enqueued before the main one
+            if (groups[g].empty()) continue;
+            if (g > 0) {
+                if (!forked) plan.sync(L_RECORD, 0, 0);
+                forked = true;
+                plan.sync(L_WAIT, 0, g);
+            }
+            arena.used = align_up(arena.peak, kAlign);   // scratch of concurrent chains stays apart
+            const size_t first = plan.launches.size();
+            plan_invert_mats(plan, arena, tun, groups[g], damp, a.info);
+            plan.set_stream(first, g);
+            if (g > 0) plan.sync(L_RECORD, g, g);
+        }
+        for (int g = 1; g < n_groups; ++g)
+            if (!groups[g].empty()) plan.sync(L_WAIT, g, 0);
+    }
+    pass(2);
+}
+
+bool bn_full_dims_ok(int32_t n_layers, int32_t N, const int32_t *C)
+{
+    if (n_layers < 1 || n_layers > 65536 || N < 1 || N > (1 << 20) || !C) return false;
+    long long tiles = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        if (C[l] < 1 || C[l] > (1 << 15)) return false;      // 2C up to 65536
+        const long long t = (2LL * C[l] + 63) / 64;
+        tiles += t * t;
+        if (tiles > (1LL << 30)) return false;
+    }
+    return true;
+}
+}  // namespace
+
+size_t bn_full_workspace_bytes(int32_t n_layers, int32_t N, const int32_t *C)
+{
+    if (!bn_full_dims_ok(n_layers, N, C)) return 0;
+    const Tunables tun;
+    BnFullArgs a{};
+    a.n_layers = n_layers; a.N = N; a.C = C;
+    size_t all = 0, single = 0;
+    {
+        Plan plan; Arena arena(nullptr);
+        plan_bn_full(plan, arena, tun, a, true);
+        arena.take_tail(plan.tab.buf.size() + 16);
+        all = arena.peak;
+    }
+    // a partial mask changes which products share a launch and hence their split-K scratch: the
+    // largest single-layer plan on top covers that; the call itself checks the size in any case
+    std::vector<uint8_t> mask(n_layers, 0);
+    a.invert_mask = mask.data();
+    for (int l = 0; l < n_layers; ++l) {
+        bool seen = false;   // only a layer larger than all before it can raise the bound
+        for (int q = 0; q < l; ++q) seen = seen || C[q] >= C[l];
+        if (seen) continue;
+        mask[l] = 1;
+        Plan plan; Arena arena(nullptr);
+        plan_bn_full(plan, arena, tun, a, true);
+        single = std::max(single, arena.peak);
+        mask[l] = 0;
+    }
+    return align_up(all + single + 4096, kAlign);
+}
+
+kfac_status bn_full_precondition(kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,
+                                 const float *const *g_gamma, const float *const *g_beta, float decay, float lambda,
+                                 float *const *F_ema, const uint8_t *invert_mask, float *const *F_inv, int32_t *info,
+                                 float *const *out_gamma, float *const *out_beta)
+{
+    if (!ctx || !bn_full_dims_ok(n_layers, N, C)) return KFAC_ERR_INVALID;
+    if (!g_gamma || !g_beta || !F_ema || !F_inv || !out_gamma || !out_beta) return KFAC_ERR_INVALID;
+    if (!(decay >= 0.0f && decay < 1.0f) || !(lambda >= 0.0f) || !std::isfinite(lambda)) return KFAC_ERR_INVALID;
+    for (int l = 0; l < n_layers; ++l) {
+        if (!g_gamma[l] || !g_beta[l] || !F_ema[l] || !F_inv[l] || !out_gamma[l] || !out_beta[l]) return KFAC_ERR_INVALID;
+        if (F_ema[l] == F_inv[l]) return KFAC_ERR_INVALID;
+    }
+    BnFullArgs a{n_layers, N, C, g_gamma, g_beta, decay, lambda, F_ema, invert_mask, F_inv, info, out_gamma, out_beta};
+    Plan plan; Arena arena(ctx->ws);
+    plan_bn_full(plan, arena, ctx->tun, a, false);
     return run_plan(ctx, plan, arena);
 }
 

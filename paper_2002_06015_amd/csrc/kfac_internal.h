@@ -155,6 +155,18 @@ struct BnReduceJob {
     int wg_start;   // one wave per (n, c) row; 4 rows per workgroup
 };
 
+// BatchNorm layer treated with its whole 2C x 2C Fisher block (Sec. 4.2 before the unit-wise approximation).
+struct BnFullJob {
+    const float *g_gamma, *g_beta;   // [N, C] per-sample gradients
+    float *F_ema;                    // [2C, 2C]
+    const float *F_inv;              // [2C, 2C]
+    float *gbar;                     // [2C] scratch: mean gradient, (gamma_i, beta_i) interleaved
+    float *out_gamma, *out_beta;     // [C]
+    int C;
+    int damp_idx;                    // slot of the layer's damping; -1: the layer is not inverted
+    int wg_start[3];                 // per pass: factor tiles, mean, apply
+};
+
 // Staleness of one statistic (Sec. 4.3): X against its predecessors P = X_-1 and Q = X_-2 (null: none).
 struct StaleJob {
     const float *X, *P, *Q;
@@ -208,6 +220,9 @@ hipError_t launch_leaf(const LeafJob *jobs_dev, int n_jobs, int size_class, cons
 hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t s);
 hipError_t launch_bn(const BnJob *jobs_dev, int n_jobs, int total_wgs, int N, float decay, float lambda,
                      hipStream_t s);
+// pass 0: F update; 1: mean gradient and damping; 2: u = F_inv gbar
+hipError_t launch_bn_full(const BnFullJob *jobs_dev, int n_jobs, int total_wgs, int pass, int N, float decay,
+                          float lambda, float *damp, hipStream_t s);
 hipError_t launch_bn_reduce(const BnReduceJob *jobs_dev, int n_jobs, int total_wgs, int N, hipStream_t s);
 // pass 0: per-chunk sums (total_wgs workgroups); pass 1: one workgroup per job adds them up and writes the ratios
 hipError_t launch_pack(const PackJob *jobs_dev, int n_jobs, int total_wgs, int bf16, int unpack, void *packed,

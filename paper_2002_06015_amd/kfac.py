@@ -24,11 +24,12 @@ EXPORTS = [
     "bn_unitwise_precondition", "bn_unitwise_reduce_nchw", "kfac_profile_enable", "kfac_profile_read",
     "kfac_packed_elems", "kfac_pack_upper", "kfac_unpack_upper",
     "kfac_lr_polynomial", "kfac_momentum_coupled", "kfac_update_weights",
+    "bn_full_workspace_bytes", "bn_full_precondition",
     "kfac_staleness", "kfac_next_interval", "kfac_refresh_init", "kfac_refresh_due", "kfac_refresh_advance",
 ]
 
 KERNEL_NAMES = ["gemm_f32", "gemm_bf16", "gemm_reduce", "patch", "trace", "copy_damp", "leaf_inverse", "zero",
-                "bn_unit", "bn_reduce", "pad", "assemble", "border", "staleness", "pack", "update"]
+                "bn_unit", "bn_reduce", "pad", "assemble", "border", "staleness", "pack", "update", "bn_full"]
 
 
 class kfac_profile_entry(ctypes.Structure):
@@ -77,6 +78,9 @@ def lib() -> ctypes.CDLL:
         L.kfac_profile_enable.argtypes = [vp, i32]
         L.kfac_profile_read.restype = i32
         L.kfac_profile_read.argtypes = [vp, vp, i32]
+        L.bn_full_workspace_bytes.restype = ctypes.c_size_t
+        L.bn_full_workspace_bytes.argtypes = [i32, i32, vp]
+        L.bn_full_precondition.argtypes = [vp, i32, i32, vp, vp, vp, f32, f32, vp, vp, vp, vp, vp, vp]
         f64 = ctypes.c_double
         L.kfac_lr_polynomial.restype = f64
         L.kfac_lr_polynomial.argtypes = [f64, f64, f64, f64, f64]
@@ -285,6 +289,28 @@ def bn_unitwise_reduce_nchw(ctx: Context, N: int, C: Sequence[int], HW: Sequence
                                        *[p and ctypes.addressof(p) for p in ps])
     if st != KFAC_OK:
         raise KfacError(st, "bn_unitwise_reduce_nchw")
+
+
+def bn_full_workspace_bytes(N: int, C: Sequence[int]) -> int:
+    c = _i32(C)
+    return int(lib().bn_full_workspace_bytes(len(C), int(N), ctypes.addressof(c)))
+
+
+def bn_full_precondition(ctx: Context, N: int, C: Sequence[int], g_gamma, g_beta, decay: float, lam: float,
+                         F_ema, F_inv, out_gamma, out_beta, invert_mask: Optional[Sequence[int]] = None,
+                         info: Optional[torch.Tensor] = None) -> None:
+    n = len(C)
+    c = _i32(C)
+    ps = [_ptrs(x, n, torch.float32) for x in (g_gamma, g_beta, F_ema, F_inv, out_gamma, out_beta)]
+    mask = None if invert_mask is None else (ctypes.c_uint8 * n)(*[1 if m else 0 for m in invert_mask])
+    if info is not None and (info.dtype != torch.int32 or info.numel() < n):
+        raise ValueError("info must be int32 [n_layers]")
+    ad = [p and ctypes.addressof(p) for p in ps]
+    st = lib().bn_full_precondition(ctx.handle, n, int(N), ctypes.addressof(c), ad[0], ad[1], float(decay), float(lam),
+                                    ad[2], None if mask is None else ctypes.addressof(mask), ad[3],
+                                    None if info is None else info.data_ptr(), ad[4], ad[5])
+    if st != KFAC_OK:
+        raise KfacError(st, "bn_full_precondition")
 
 
 def kfac_lr_polynomial(eta0: float, e: float, e_start: float, e_end: float, p_decay: float) -> float:

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "kfac.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b(kfac_[a-z0-9_]+|bn_unitwise_[a-z0-9_]+)\s*\(", text)
+    names = re.findall(r"\b(kfac_[a-z0-9_]+|bn_[a-z0-9_]+)\s*\(", text)
     return sorted(set(names))
 
 
@@ -314,4 +314,43 @@ def test_update_rejects_bad_arguments_without_a_gpu():
     bad = (kfac.kfac_layer * 1)(kfac.kfac_layer(*wl.fc_layer(2, 64, 32)))
     bad[0].c_out = 0
     assert call(h, 1, ctypes.addressof(bad), up, 0.1, 0.9, 1, 1e-9, wpt, wpp) == INV
+    L.kfac_destroy(h)
+
+
+# ------------------------------------------------------------------ whole-layer BatchNorm Fisher (Sec. 4.2): arguments
+def test_bn_full_rejects_bad_arguments_without_a_gpu():
+    L = kfac.lib()
+    INV = kfac.KFAC_ERR_INVALID
+    assert kfac.bn_full_workspace_bytes(32, [64, 256]) > 0
+    assert kfac.bn_full_workspace_bytes(32, [64, 0]) == 0 and kfac.bn_full_workspace_bytes(0, [64]) == 0
+    assert kfac.bn_full_workspace_bytes(32, [40000]) == 0
+    assert L.bn_full_workspace_bytes(1, 32, None) == 0
+    # the size serves every layer inverted and any one alone, and grows with the layers
+    assert kfac.bn_full_workspace_bytes(32, [512, 1024]) >= kfac.bn_full_workspace_bytes(32, [1024])
+    h = _fake_ctx(1 << 20)
+    C = (ctypes.c_int32 * 2)(8, 4)
+    cp = ctypes.addressof(C)
+    arrs = [(ctypes.c_void_p * 2)(0x200000 + 0x10000 * k, 0x208000 + 0x10000 * k) for k in range(6)]
+    gg, gb, F, Fi, og, ob = [ctypes.addressof(a) for a in arrs]
+    call = L.bn_full_precondition
+    assert call(None, 2, 32, cp, gg, gb, 0.0, 1e-6, F, None, Fi, None, og, ob) == INV
+    assert call(h, 0, 32, cp, gg, gb, 0.0, 1e-6, F, None, Fi, None, og, ob) == INV
+    assert call(h, 2, 0, cp, gg, gb, 0.0, 1e-6, F, None, Fi, None, og, ob) == INV
+    assert call(h, 2, 32, None, gg, gb, 0.0, 1e-6, F, None, Fi, None, og, ob) == INV
+    for k in range(6):
+        a = [gg, gb, F, Fi, og, ob]
+        a[k] = None
+        assert call(h, 2, 32, cp, a[0], a[1], 0.0, 1e-6, a[2], None, a[3], None, a[4], a[5]) == INV
+    assert call(h, 2, 32, cp, gg, gb, 1.0, 1e-6, F, None, Fi, None, og, ob) == INV         # decay must stay below 1
+    assert call(h, 2, 32, cp, gg, gb, 0.0, -1.0, F, None, Fi, None, og, ob) == INV
+    assert call(h, 2, 32, cp, gg, gb, 0.0, 1e-6, F, None, F, None, og, ob) == INV          # inverse in place
+    hole = (ctypes.c_void_p * 2)(0x900000, None)
+    assert call(h, 2, 32, cp, gg, gb, 0.0, 1e-6, ctypes.addressof(hole), None, Fi, None, og, ob) == INV
+    bad = (ctypes.c_int32 * 2)(8, -1)
+    assert call(h, 2, 32, ctypes.addressof(bad), gg, gb, 0.0, 1e-6, F, None, Fi, None, og, ob) == INV
+    L.kfac_destroy(h)
+    # a layer that needs more scratch than the context has is refused before any launch
+    h = _fake_ctx(1 << 16)
+    big = (ctypes.c_int32 * 1)(1024)
+    assert call(h, 1, 32, ctypes.addressof(big), gg, gb, 0.0, 1e-6, F, None, Fi, None, og, ob) == kfac.KFAC_ERR_WORKSPACE
     L.kfac_destroy(h)
