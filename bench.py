@@ -341,6 +341,49 @@ def main():
                         "the rescaling; not part of the timed step")
     del Wt, Wp
 
+    # ---------------------------------------------------------------- beside the step: BatchNorm with the whole-layer Fisher
+    # (Sec. 4.2 / Sec. 7 "fullBN": dense 2c x 2c Fisher per BatchNorm layer instead of the unit-wise 2 x 2 blocks)
+    full_bn = None
+    if Cs:
+        bctx = kfac.Context(layers[:1], workspace_bytes=kfac.bn_full_workspace_bytes(N, Cs))
+        Ff = [torch.zeros(2 * C, 2 * C, device="cuda") for C in Cs]
+        Ffi = [torch.zeros(2 * C, 2 * C, device="cuda") for C in Cs]
+        binfo = torch.zeros(len(Cs), dtype=torch.int32, device="cuda")
+        kfac.bn_full_precondition(bctx, N, Cs, bn_gg, bn_gb, 0.0, wl.BN_LAMBDA, Ff, Ffi, og, ob, info=binfo)
+        torch.cuda.synchronize()
+        assert int(binfo.abs().sum().item()) == 0
+        s0.record()
+        for _ in range(3):
+            kfac.bn_full_precondition(bctx, N, Cs, bn_gg, bn_gb, wl.DECAY, wl.BN_LAMBDA, Ff, Ffi, og, ob, info=binfo)
+        s1.record()
+        torch.cuda.synchronize()
+        full_ms = s0.elapsed_time(s1) / 3
+        kfac.kfac_profile_enable(bctx, True)
+        kfac.bn_full_precondition(bctx, N, Cs, bn_gg, bn_gb, wl.DECAY, wl.BN_LAMBDA, Ff, Ffi, og, ob, info=binfo)
+        torch.cuda.synchronize()
+        parts = {}
+        for e in kfac.kfac_profile_read(bctx, 16384):
+            key = {"bn_full": "bn_full_pass%d" % e["variant"]}.get(e["kernel"], "inversion")
+            parts[key] = parts.get(key, 0.0) + e["ms"]
+        kfac.kfac_profile_enable(bctx, False)
+        s0.record()
+        for _ in range(10):
+            bn(wl.DECAY)
+        s1.record()
+        torch.cuda.synchronize()
+        unit_ms = s0.elapsed_time(s1) / 10
+        inv_flops = float(sum((2.0 * C) ** 3 for C in Cs))
+        full_bn = {"bn_layers": len(Cs), "ms": round(full_ms, 4), "unit_wise_ms": round(unit_ms, 4),
+                   "fisher_gbytes": round(4.0 * sum((2 * C) ** 2 for C in Cs) / 1e9, 3),
+                   "inverse_gflop": round(inv_flops / 1e9, 1),
+                   "inverse_tflops": round(inv_flops / (full_ms * 1e-3) / 1e12, 2),
+                   "serial_ms_by_part": {k: round(v, 4) for k, v in sorted(parts.items())},
+                   "note": "bn_full_precondition over all BatchNorm layers of the configuration, every layer inverted; "
+                           "unit_wise_ms is bn_unitwise_precondition on the same gradients; serial_ms_by_part comes from "
+                           "a profiled call whose launches run one after the other; not part of the timed step"}
+        del Ff, Ffi
+        bctx.close()
+
     out = {
         "metric": "K-FAC step ms for ResNet-50 layer set; factor+inverse TFLOP/s vs MFMA peak",
         "value": round(ms_per_step, 4),
@@ -380,6 +423,7 @@ def main():
         "staleness": staleness,
         "packing": packing,
         "update": updating,
+        "full_bn": full_bn,
     }
     ctx.close()
     print(json.dumps(out))

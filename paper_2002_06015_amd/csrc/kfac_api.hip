@@ -1253,7 +1253,7 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 case L_BNFULL: pe.kernel = KFAC_K_BN_FULL; break;
                 case L_RECORD: case L_WAIT: break;
             }
-            pe.variant = (L.kind == L_GEMM || L.kind == L_LEAF) ? L.cfg : 0;
+            pe.variant = (L.kind == L_GEMM || L.kind == L_LEAF || L.kind == L_BNFULL) ? L.cfg : 0;
             pe.workgroups = (L.kind == L_TRACE || L.kind == L_LEAF) ? L.n : L.total_wgs;
             pe.flops = L.flops;
             pe.bytes = L.bytes;

@@ -124,6 +124,22 @@ def test_stats_two_steps(gpu, layer, spatial_mean):
         assert abs(hA[-1, -1] - 1.0) < 1e-5
 
 
+@pytest.mark.parametrize("layer", [wl.fc_layer(4, 70, 33), wl.conv_layer(4, 6, 9, 3, 1, 1, 8), wl.conv_layer(4, 12, 7, 1, 1, 0, 6)])
+def test_micro_batch_accumulation_equals_the_whole_batch(gpu, layer):
+    """Statistics accumulated over micro-batches (Sec. 7.1): decay = (j-1)/j at micro-batch j makes the running
+    average the plain mean, which is the statistic of the concatenated batch."""
+    k = 3
+    acts = [wl.make_act(layer, 700 + j) for j in range(k)]
+    grads = [wl.make_grad_out(layer, 700 + j) for j in range(k)]
+    A = G = None
+    for j in range(k):
+        A, G = run_stats([layer], [acts[j]], [grads[j]], j / (j + 1.0), True, A, G)
+    whole = layer._replace(N=k * layer.N)
+    Ar, Gr = oracle.kfac_stats(tuple(whole), np.concatenate(acts), np.concatenate(grads), 0.0, True, None, None)
+    assert relerr(host(A[0]), Ar) <= TOL_FACTOR
+    assert relerr(host(G[0]), Gr) <= TOL_FACTOR
+
+
 def test_stats_grouped_and_partial_inputs(gpu):
     """Several layers in one call; A-only and G-only forms leave the other factor alone."""
     layers = SMALL_LAYERS[:6]

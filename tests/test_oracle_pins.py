@@ -367,3 +367,17 @@ def test_paper_facts_golden():
     assert 4 * c * c // (4 * c) == c
     n = 577
     assert len(np.triu_indices(n)[0]) == n * (n + 1) // 2
+
+
+def test_accumulating_micro_batches_gives_the_whole_batch_statistics():
+    """Sec. 7.1 (accumulation over steps): with decay (j-1)/j at micro-batch j the running average is the plain
+    mean, and the mean of the micro-batch statistics is the statistic of the concatenated batch."""
+    layer = wl.conv_layer(4, 6, 9, 3, 1, 1, 8)
+    acts = [wl.make_act(layer, 700 + j) for j in range(3)]
+    grads = [wl.make_grad_out(layer, 700 + j) for j in range(3)]
+    A = G = None
+    for j in range(3):
+        A, G = oracle.kfac_stats(tuple(layer), acts[j], grads[j], j / (j + 1.0), True, A, G)
+    whole = layer._replace(N=12)
+    Ar, Gr = oracle.kfac_stats(tuple(whole), np.concatenate(acts), np.concatenate(grads), 0.0, True, None, None)
+    assert np.allclose(A, Ar, rtol=1e-12, atol=1e-18) and np.allclose(G, Gr, rtol=1e-12, atol=1e-18)
