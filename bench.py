@@ -37,6 +37,7 @@ def main():
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32", help="type of activations / output gradients")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=2)
+    ap.add_argument("--no-extras", action="store_true", help="skip the measurements beside the step")
     ap.add_argument("--schedule", choices=["fused", "staged"], default="fused",
                     help="fused: one kfac_step call per step (factors, inverses and preconditioning planned as one "
                          "graph); staged: kfac_stats, kfac_invert, kfac_precondition one after the other")
@@ -265,124 +266,126 @@ def main():
                                   "%.2f s measured), scaled to the whole step by algorithmic flops (x%.1f)"
                                   % (len(sample), acc / 1e9, t_cpu, total_flops / acc)}
 
-    # ---------------------------------------------------------------- beside the step: staleness of the factors
-    # (Sec. 4.3: what a refresh under Algorithm 1 adds -- every factor against its two predecessors)
-    dims = [L.dA for L in layers] + [L.dG for L in layers]
-    X = A + G
-    P = [x * 1.02 for x in X]
-    Q = [x * 0.95 for x in X]
-    ratios = torch.zeros(2 * len(dims), dtype=torch.float64, device="cuda")
-    kfac.kfac_staleness(ctx, dims, X, P, Q, ratios)
-    torch.cuda.synchronize()
-    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    s0.record()
-    for _ in range(10):
+    staleness = packing = updating = full_bn = None
+    extras = not args.no_extras      # the calls beside the step are left out of profiler runs of the step itself
+    if extras:
+        # ---------------------------------------------------------------- beside the step: staleness of the factors
+        # (Sec. 4.3: what a refresh under Algorithm 1 adds -- every factor against its two predecessors)
+        dims = [L.dA for L in layers] + [L.dG for L in layers]
+        X = A + G
+        P = [x * 1.02 for x in X]
+        Q = [x * 0.95 for x in X]
+        ratios = torch.zeros(2 * len(dims), dtype=torch.float64, device="cuda")
         kfac.kfac_staleness(ctx, dims, X, P, Q, ratios)
-    s1.record()
-    torch.cuda.synchronize()
-    stale_ms = s0.elapsed_time(s1) / 10
-    stale_bytes = 12.0 * sum(d * d for d in dims)
-    r = ratios.cpu().numpy().reshape(-1, 2)
-    assert abs(float(r[:, 0].max()) - 0.02 / 1.02) < 1e-4 and abs(float(r[:, 1].min()) - 0.05 / 0.95) < 1e-4
-    staleness = {"matrices": len(dims), "ms": round(stale_ms, 4), "gbytes": round(stale_bytes / 1e9, 3),
-                 "gbs": round(stale_bytes / (stale_ms * 1e-3) / 1e9, 1),
-                 "frac_of_hbm_peak": round(stale_bytes / (stale_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                 "note": "kfac_staleness over all factors of the configuration against two predecessors each "
-                         "(12 bytes per element); not part of the timed step"}
-    del P, Q
+        torch.cuda.synchronize()
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s0.record()
+        for _ in range(10):
+            kfac.kfac_staleness(ctx, dims, X, P, Q, ratios)
+        s1.record()
+        torch.cuda.synchronize()
+        stale_ms = s0.elapsed_time(s1) / 10
+        stale_bytes = 12.0 * sum(d * d for d in dims)
+        r = ratios.cpu().numpy().reshape(-1, 2)
+        assert abs(float(r[:, 0].max()) - 0.02 / 1.02) < 1e-4 and abs(float(r[:, 1].min()) - 0.05 / 0.95) < 1e-4
+        staleness = {"matrices": len(dims), "ms": round(stale_ms, 4), "gbytes": round(stale_bytes / 1e9, 3),
+                     "gbs": round(stale_bytes / (stale_ms * 1e-3) / 1e9, 1),
+                     "frac_of_hbm_peak": round(stale_bytes / (stale_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                     "note": "kfac_staleness over all factors of the configuration against two predecessors each "
+                             "(12 bytes per element); not part of the timed step"}
+        del P, Q
 
-    # ---------------------------------------------------------------- beside the step: packing of the factors
-    # (Sec. 5.2: upper triangles of all factors into one send buffer, and back)
-    total = kfac.kfac_packed_elems(dims)
-    full_bytes = 4.0 * sum(d * d for d in dims)
-    packing = {"matrices": len(dims), "packed_elements": total}
-    for tname, ttype, tdtype, esize in (("f32", kfac.KFAC_F32, torch.float32, 4), ("bf16", kfac.KFAC_BF16, torch.bfloat16, 2)):
-        buf = torch.empty(total, dtype=tdtype, device="cuda")
-        back = [torch.empty_like(x) for x in X]
-        for name, call, nbytes in (("pack", lambda: kfac.kfac_pack_upper(ctx, dims, X, ttype, buf), total * (4.0 + esize)),
-                                   ("unpack", lambda: kfac.kfac_unpack_upper(ctx, dims, ttype, buf, back), total * esize + full_bytes)):
-            call()
+        # ---------------------------------------------------------------- beside the step: packing of the factors
+        # (Sec. 5.2: upper triangles of all factors into one send buffer, and back)
+        total = kfac.kfac_packed_elems(dims)
+        full_bytes = 4.0 * sum(d * d for d in dims)
+        packing = {"matrices": len(dims), "packed_elements": total}
+        for tname, ttype, tdtype, esize in (("f32", kfac.KFAC_F32, torch.float32, 4), ("bf16", kfac.KFAC_BF16, torch.bfloat16, 2)):
+            buf = torch.empty(total, dtype=tdtype, device="cuda")
+            back = [torch.empty_like(x) for x in X]
+            for name, call, nbytes in (("pack", lambda: kfac.kfac_pack_upper(ctx, dims, X, ttype, buf), total * (4.0 + esize)),
+                                       ("unpack", lambda: kfac.kfac_unpack_upper(ctx, dims, ttype, buf, back), total * esize + full_bytes)):
+                call()
+                torch.cuda.synchronize()
+                s0.record()
+                for _ in range(10):
+                    call()
+                s1.record()
+                torch.cuda.synchronize()
+                ms = s0.elapsed_time(s1) / 10
+                packing["%s_%s" % (name, tname)] = {"ms": round(ms, 4), "gbytes": round(nbytes / 1e9, 3),
+                                                   "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                                                   "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+            del buf, back
+        packing["note"] = ("kfac_pack_upper / kfac_unpack_upper over all factors of the configuration; bytes: the triangle "
+                           "read and written (pack), the triangle read and the whole matrix written (unpack); not part of "
+                           "the timed step")
+
+        # ---------------------------------------------------------------- beside the step: the parameter update
+        # (Sec. 6.2, 6.3: w <- w - eta U + m v for all layers, then the rescaling to norm sqrt(2 d_out))
+        n_w = sum(L.dA * L.dG for L in layers)
+        Wt = [torch.randn(L.dG, L.dA, device="cuda") * (2.0 / L.dA) ** 0.5 for L in layers]
+        Wp = [w.clone() for w in Wt]
+        updating = {"layers": n, "weights": n_w}
+        for name, resc, per_elem in (("update", False, 20.0), ("update_rescale", True, 28.0)):
+            kfac.kfac_update_weights(ctx, layers, U, 1e-3, 0.9, resc, 1e-9, Wt, Wp)
             torch.cuda.synchronize()
             s0.record()
             for _ in range(10):
-                call()
+                kfac.kfac_update_weights(ctx, layers, U, 1e-3, 0.9, resc, 1e-9, Wt, Wp)
             s1.record()
             torch.cuda.synchronize()
             ms = s0.elapsed_time(s1) / 10
-            packing["%s_%s" % (name, tname)] = {"ms": round(ms, 4), "gbytes": round(nbytes / 1e9, 3),
-                                               "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
-                                               "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
-        del buf, back
-    packing["note"] = ("kfac_pack_upper / kfac_unpack_upper over all factors of the configuration; bytes: the triangle "
-                       "read and written (pack), the triangle read and the whole matrix written (unpack); not part of "
-                       "the timed step")
+            updating[name] = {"ms": round(ms, 4), "gbytes": round(per_elem * n_w / 1e9, 3),
+                              "gbs": round(per_elem * n_w / (ms * 1e-3) / 1e9, 1),
+                              "frac_of_hbm_peak": round(per_elem * n_w / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        assert all(abs(float(w.double().norm()) - (2.0 * L.dG) ** 0.5) < 1e-4 * (2.0 * L.dG) ** 0.5 for w, L in zip(Wt, layers))
+        updating["note"] = ("kfac_update_weights over all layers of the configuration with the preconditioned gradients of "
+                            "the step; 20 bytes per weight for the update (U, w, w_prev read; w, w_prev written), 8 more for "
+                            "the rescaling; not part of the timed step")
+        del Wt, Wp
 
-    # ---------------------------------------------------------------- beside the step: the parameter update
-    # (Sec. 6.2, 6.3: w <- w - eta U + m v for all layers, then the rescaling to norm sqrt(2 d_out))
-    n_w = sum(L.dA * L.dG for L in layers)
-    Wt = [torch.randn(L.dG, L.dA, device="cuda") * (2.0 / L.dA) ** 0.5 for L in layers]
-    Wp = [w.clone() for w in Wt]
-    updating = {"layers": n, "weights": n_w}
-    for name, resc, per_elem in (("update", False, 20.0), ("update_rescale", True, 28.0)):
-        kfac.kfac_update_weights(ctx, layers, U, 1e-3, 0.9, resc, 1e-9, Wt, Wp)
-        torch.cuda.synchronize()
-        s0.record()
-        for _ in range(10):
-            kfac.kfac_update_weights(ctx, layers, U, 1e-3, 0.9, resc, 1e-9, Wt, Wp)
-        s1.record()
-        torch.cuda.synchronize()
-        ms = s0.elapsed_time(s1) / 10
-        updating[name] = {"ms": round(ms, 4), "gbytes": round(per_elem * n_w / 1e9, 3),
-                          "gbs": round(per_elem * n_w / (ms * 1e-3) / 1e9, 1),
-                          "frac_of_hbm_peak": round(per_elem * n_w / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
-    assert all(abs(float(w.double().norm()) - (2.0 * L.dG) ** 0.5) < 1e-4 * (2.0 * L.dG) ** 0.5 for w, L in zip(Wt, layers))
-    updating["note"] = ("kfac_update_weights over all layers of the configuration with the preconditioned gradients of "
-                        "the step; 20 bytes per weight for the update (U, w, w_prev read; w, w_prev written), 8 more for "
-                        "the rescaling; not part of the timed step")
-    del Wt, Wp
-
-    # ---------------------------------------------------------------- beside the step: BatchNorm with the whole-layer Fisher
-    # (Sec. 4.2 / Sec. 7 "fullBN": dense 2c x 2c Fisher per BatchNorm layer instead of the unit-wise 2 x 2 blocks)
-    full_bn = None
-    if Cs:
-        bctx = kfac.Context(layers[:1], workspace_bytes=kfac.bn_full_workspace_bytes(N, Cs))
-        Ff = [torch.zeros(2 * C, 2 * C, device="cuda") for C in Cs]
-        Ffi = [torch.zeros(2 * C, 2 * C, device="cuda") for C in Cs]
-        binfo = torch.zeros(len(Cs), dtype=torch.int32, device="cuda")
-        kfac.bn_full_precondition(bctx, N, Cs, bn_gg, bn_gb, 0.0, wl.BN_LAMBDA, Ff, Ffi, og, ob, info=binfo)
-        torch.cuda.synchronize()
-        assert int(binfo.abs().sum().item()) == 0
-        s0.record()
-        for _ in range(3):
+        # ---------------------------------------------------------------- beside the step: BatchNorm with the whole-layer Fisher
+        # (Sec. 4.2 / Sec. 7 "fullBN": dense 2c x 2c Fisher per BatchNorm layer instead of the unit-wise 2 x 2 blocks)
+        if Cs:
+            bctx = kfac.Context(layers[:1], workspace_bytes=kfac.bn_full_workspace_bytes(N, Cs))
+            Ff = [torch.zeros(2 * C, 2 * C, device="cuda") for C in Cs]
+            Ffi = [torch.zeros(2 * C, 2 * C, device="cuda") for C in Cs]
+            binfo = torch.zeros(len(Cs), dtype=torch.int32, device="cuda")
+            kfac.bn_full_precondition(bctx, N, Cs, bn_gg, bn_gb, 0.0, wl.BN_LAMBDA, Ff, Ffi, og, ob, info=binfo)
+            torch.cuda.synchronize()
+            assert int(binfo.abs().sum().item()) == 0
+            s0.record()
+            for _ in range(3):
+                kfac.bn_full_precondition(bctx, N, Cs, bn_gg, bn_gb, wl.DECAY, wl.BN_LAMBDA, Ff, Ffi, og, ob, info=binfo)
+            s1.record()
+            torch.cuda.synchronize()
+            full_ms = s0.elapsed_time(s1) / 3
+            kfac.kfac_profile_enable(bctx, True)
             kfac.bn_full_precondition(bctx, N, Cs, bn_gg, bn_gb, wl.DECAY, wl.BN_LAMBDA, Ff, Ffi, og, ob, info=binfo)
-        s1.record()
-        torch.cuda.synchronize()
-        full_ms = s0.elapsed_time(s1) / 3
-        kfac.kfac_profile_enable(bctx, True)
-        kfac.bn_full_precondition(bctx, N, Cs, bn_gg, bn_gb, wl.DECAY, wl.BN_LAMBDA, Ff, Ffi, og, ob, info=binfo)
-        torch.cuda.synchronize()
-        parts = {}
-        for e in kfac.kfac_profile_read(bctx, 16384):
-            key = {"bn_full": "bn_full_pass%d" % e["variant"]}.get(e["kernel"], "inversion")
-            parts[key] = parts.get(key, 0.0) + e["ms"]
-        kfac.kfac_profile_enable(bctx, False)
-        s0.record()
-        for _ in range(10):
-            bn(wl.DECAY)
-        s1.record()
-        torch.cuda.synchronize()
-        unit_ms = s0.elapsed_time(s1) / 10
-        inv_flops = float(sum((2.0 * C) ** 3 for C in Cs))
-        full_bn = {"bn_layers": len(Cs), "ms": round(full_ms, 4), "unit_wise_ms": round(unit_ms, 4),
-                   "fisher_gbytes": round(4.0 * sum((2 * C) ** 2 for C in Cs) / 1e9, 3),
-                   "inverse_gflop": round(inv_flops / 1e9, 1),
-                   "inverse_tflops": round(inv_flops / (full_ms * 1e-3) / 1e12, 2),
-                   "serial_ms_by_part": {k: round(v, 4) for k, v in sorted(parts.items())},
-                   "note": "bn_full_precondition over all BatchNorm layers of the configuration, every layer inverted; "
-                           "unit_wise_ms is bn_unitwise_precondition on the same gradients; serial_ms_by_part comes from "
-                           "a profiled call whose launches run one after the other; not part of the timed step"}
-        del Ff, Ffi
-        bctx.close()
+            torch.cuda.synchronize()
+            parts = {}
+            for e in kfac.kfac_profile_read(bctx, 16384):
+                key = {"bn_full": "bn_full_pass%d" % e["variant"]}.get(e["kernel"], "inversion")
+                parts[key] = parts.get(key, 0.0) + e["ms"]
+            kfac.kfac_profile_enable(bctx, False)
+            s0.record()
+            for _ in range(10):
+                bn(wl.DECAY)
+            s1.record()
+            torch.cuda.synchronize()
+            unit_ms = s0.elapsed_time(s1) / 10
+            inv_flops = float(sum((2.0 * C) ** 3 for C in Cs))
+            full_bn = {"bn_layers": len(Cs), "ms": round(full_ms, 4), "unit_wise_ms": round(unit_ms, 4),
+                       "fisher_gbytes": round(4.0 * sum((2 * C) ** 2 for C in Cs) / 1e9, 3),
+                       "inverse_gflop": round(inv_flops / 1e9, 1),
+                       "inverse_tflops": round(inv_flops / (full_ms * 1e-3) / 1e12, 2),
+                       "serial_ms_by_part": {k: round(v, 4) for k, v in sorted(parts.items())},
+                       "note": "bn_full_precondition over all BatchNorm layers of the configuration, every layer inverted; "
+                               "unit_wise_ms is bn_unitwise_precondition on the same gradients; serial_ms_by_part comes from "
+                               "a profiled call whose launches run one after the other; not part of the timed step"}
+            del Ff, Ffi
+            bctx.close()
 
     out = {
         "metric": "K-FAC step ms for ResNet-50 layer set; factor+inverse TFLOP/s vs MFMA peak",
