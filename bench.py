@@ -266,7 +266,7 @@ def main():
                                   "%.2f s measured), scaled to the whole step by algorithmic flops (x%.1f)"
                                   % (len(sample), acc / 1e9, t_cpu, total_flops / acc)}
 
-    staleness = packing = updating = full_bn = None
+    staleness = adaptive = packing = updating = full_bn = None
     extras = not args.no_extras      # the calls beside the step are left out of profiler runs of the step itself
     if extras:
         # ---------------------------------------------------------------- beside the step: staleness of the factors
@@ -294,6 +294,60 @@ def main():
                      "note": "kfac_staleness over all factors of the configuration against two predecessors each "
                              "(12 bytes per element); not part of the timed step"}
         del P, Q
+
+
+        # ------------------------------------------------------------ beside the step: Algorithm 1 over a run of steps
+        # (Sec. 4.3: every statistic is rebuilt only when its own interval says so; a layer is re-inverted when one of
+        # its factors was rebuilt; every step preconditions all gradients.  The inputs are the same in every step, so
+        # the statistics are stationary: the most favourable case, refreshes at the Fibonacci steps 1 2 3 5 8 13 21 34.)
+        T = 34
+        actx = kfac.Context(layers, in_dtype, workspace_bytes=2 * kfac.kfac_workspace_bytes(layers, in_dtype))
+        Ax = [torch.zeros_like(x) for x in A]
+        Gx = [torch.zeros_like(x) for x in G]
+        Xs = Ax + Gx
+        P1 = [None] * (2 * n)
+        P2 = [None] * (2 * n)
+        states = kfac.kfac_refresh_init(2 * n)
+        rat = torch.zeros(4 * n, dtype=torch.float64, device="cuda")
+        refreshed_stats = 0
+        refresh_steps = []
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for t in range(1, T + 1):
+            due = [i for i in range(2 * n) if kfac.kfac_refresh_due(states[i], t)]
+            if due:
+                dueset = set(due)
+                kfac.kfac_stats(actx, layers, in_dtype, [acts[l] if l in dueset else None for l in range(n)],
+                                [grads[l] if n + l in dueset else None for l in range(n)],
+                                0.0 if t == 1 else wl.DECAY, spatial_mean, Ax, Gx)
+                have1 = [i for i in due if P1[i] is not None]
+                if have1:
+                    kfac.kfac_staleness(actx, [dims[i] for i in have1], [Xs[i] for i in have1], [P1[i] for i in have1],
+                                        [P2[i] for i in have1], rat)
+                    r = rat[:2 * len(have1)].cpu().numpy().reshape(-1, 2)      # the host decides: one sync per refresh
+                ratio = {i: (float("inf"), float("inf")) for i in due}
+                for j, i in enumerate(have1):
+                    ratio[i] = (float(r[j, 0]), float(r[j, 1]))
+                for i in due:
+                    kfac.kfac_refresh_advance(states[i], ratio[i][0], ratio[i][1], 0.1)
+                    P2[i] = P1[i]                                              # X_-2 <- X_-1 <- X (copies, as Algorithm 1 keeps them)
+                    P1[i] = Xs[i].clone()
+                inv = sorted({i % n for i in due})
+                kfac.kfac_invert(actx, sel(layers, inv), sel(Ax, inv), sel(Gx, inv), wl.GAMMA, sel(Ai, inv), sel(Gi, inv),
+                                 None, None)
+                refreshed_stats += len(due)
+                refresh_steps.append(t)
+            kfac.kfac_precondition(actx, layers, Gi, Ai, gws, U)
+        torch.cuda.synchronize()
+        adaptive_ms = (time.perf_counter() - t_begin) * 1e3 / T
+        adaptive = {"steps": T, "ms_per_step": round(adaptive_ms, 4), "refresh_steps": refresh_steps,
+                    "statistics_rebuilt_fraction": round(refreshed_stats / (2.0 * n * T), 4),
+                    "note": "Algorithm 1 with alpha = 0.1 driving kfac_stats (due statistics only), kfac_staleness, "
+                            "kfac_invert (layers with a rebuilt factor) and kfac_precondition (all layers) over %d steps "
+                            "of identical inputs (stationary statistics, the most favourable case); wall clock including "
+                            "the host's decisions and the copies of X_-1, X_-2; not part of the timed step" % T}
+        del Ax, Gx, Xs, P1, P2
+        actx.close()
 
         # ---------------------------------------------------------------- beside the step: packing of the factors
         # (Sec. 5.2: upper triangles of all factors into one send buffer, and back)
@@ -424,6 +478,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "staleness": staleness,
+        "adaptive_refresh": adaptive,
         "packing": packing,
         "update": updating,
         "full_bn": full_bn,
