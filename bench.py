@@ -266,7 +266,7 @@ def main():
                                   "%.2f s measured), scaled to the whole step by algorithmic flops (x%.1f)"
                                   % (len(sample), acc / 1e9, t_cpu, total_flops / acc)}
 
-    staleness = adaptive = packing = updating = full_bn = None
+    staleness = adaptive = layout_obj = packing = updating = full_bn = None
     extras = not args.no_extras      # the calls beside the step are left out of profiler runs of the step itself
     if extras:
         # ---------------------------------------------------------------- beside the step: staleness of the factors
@@ -348,6 +348,32 @@ def main():
                             "the host's decisions and the copies of X_-1, X_-2; not part of the timed step" % T}
         del Ax, Gx, Xs, P1, P2
         actx.close()
+
+
+        # ------------------------------------------------------------ beside the step: inputs that arrive in NHWC
+        # (Sec. 5.2: converted to the layout the statistics kernels read; contents do not matter for the timing, so
+        # the step's own tensors serve as the source)
+        layout_obj = {}
+        tot_ms = 0.0
+        for name, which, srcs in (("activations", 0, acts), ("output_gradients", 1, grads)):
+            dsts = [torch.empty_like(x) for x in srcs]
+            kfac.kfac_nhwc_to_nchw(ctx, layers, which, in_dtype, srcs, dsts)
+            torch.cuda.synchronize()
+            s0.record()
+            for _ in range(5):
+                kfac.kfac_nhwc_to_nchw(ctx, layers, which, in_dtype, srcs, dsts)
+            s1.record()
+            torch.cuda.synchronize()
+            ms = s0.elapsed_time(s1) / 5
+            nbytes = 2.0 * sum(x.numel() * x.element_size() for x in srcs)
+            layout_obj[name] = {"ms": round(ms, 4), "gbytes": round(nbytes / 1e9, 3), "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                                "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+            tot_ms += ms
+            del dsts
+        layout_obj["ms"] = round(tot_ms, 4)
+        layout_obj["note"] = ("kfac_nhwc_to_nchw over all activations and all output gradients of the configuration "
+                              "(every element read once and written once): what a caller with NHWC tensors pays in "
+                              "front of the step; not part of the timed step")
 
         # ---------------------------------------------------------------- beside the step: packing of the factors
         # (Sec. 5.2: upper triangles of all factors into one send buffer, and back)
@@ -479,6 +505,7 @@ def main():
         "cpu_baseline": cpu_baseline,
         "staleness": staleness,
         "adaptive_refresh": adaptive,
+        "nhwc_inputs": layout_obj,
         "packing": packing,
         "update": updating,
         "full_bn": full_bn,

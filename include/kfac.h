@@ -255,6 +255,18 @@ kfac_status kfac_update_weights(kfac_ctx *ctx, int32_t n_layers, const kfac_laye
                                 float *const *W_prev);
 
 /*
+ * Convolution inputs kept in NHWC (Sec. 5.2 names that layout for the tensors around
+ * convolution layers): converts them to the NCHW layout kfac_stats, kfac_step and kfac_im2col
+ * read.  which = 0: activations, src[l] dev [N, h_in, w_in, c_in] -> dst[l] dev [N, c_in, h_in, w_in];
+ * which = 1: output gradients, src[l] dev [N, h, w, c_out] -> dst[l] dev [N, c_out, h, w].
+ * type: element type of both (fp32 or bf16); bits are copied unchanged.  src[l] == NULL skips
+ * layer l (dst[l] is not touched); src[l] and dst[l] must not overlap.  For fully-connected
+ * layers (h = w = 1) the two layouts coincide and the call copies.
+ */
+kfac_status kfac_nhwc_to_nchw(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, int32_t which, kfac_dtype type,
+                              const void *const *src, void *const *dst);
+
+/*
  * Symmetry-aware packing of the statistics, Sec. 5.2: a symmetric d x d matrix is
  * communicated as its upper triangle, d (d + 1) / 2 elements.  Layout of `packed`
  * (the paper fixes only the count): matrix i starts at element sum_{j<i} d_j (d_j + 1) / 2;
@@ -312,7 +324,7 @@ void kfac_refresh_advance(kfac_refresh_state *s, double ratio_m1, double ratio_m
 typedef enum {
     KFAC_K_GEMM_F32 = 0, KFAC_K_GEMM_BF16 = 1, KFAC_K_GEMM_REDUCE = 2, KFAC_K_PATCH = 3, KFAC_K_TRACE = 4,
     KFAC_K_COPY_DAMP = 5, KFAC_K_LEAF_INVERSE = 6, KFAC_K_ZERO = 7, KFAC_K_BN_UNIT = 8, KFAC_K_BN_REDUCE = 9,
-    KFAC_K_PAD = 10, KFAC_K_ASSEMBLE = 11, KFAC_K_BORDER = 12, KFAC_K_STALENESS = 13, KFAC_K_PACK = 14, KFAC_K_UPDATE = 15, KFAC_K_BN_FULL = 16
+    KFAC_K_PAD = 10, KFAC_K_ASSEMBLE = 11, KFAC_K_BORDER = 12, KFAC_K_STALENESS = 13, KFAC_K_PACK = 14, KFAC_K_UPDATE = 15, KFAC_K_BN_FULL = 16, KFAC_K_LAYOUT = 17
 } kfac_kernel;
 
 typedef struct {

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libkfac_hip.so")
-SOURCES = ["kfac_api.hip", "gemm_nt.hip", "patch.hip", "corr.hip", "inverse.hip", "bn.hip", "stale.hip", "pack.hip", "update.hip", "bn_full.hip"]
+SOURCES = ["kfac_api.hip", "gemm_nt.hip", "patch.hip", "corr.hip", "inverse.hip", "bn.hip", "stale.hip", "pack.hip", "update.hip", "bn_full.hip", "layout.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option", "-Wno-null-pointer-arithmetic"]

@@ -125,6 +125,7 @@ enum LaunchKind { L_GEMM, L_REDUCE, L_PATCH, L_TRACE, L_COPY, L_LEAF, L_ZERO, L_
                   L_STALE,   // cfg: pass 0 / 1
                   L_PACK,    // cfg: 1 = unpack; dtype: 1 = bf16; p0: packed buffer
                   L_UPDATE,  // cfg: pass 0 / 1 / 2; f0: eta; f1: momentum (pass 1: f0 = eps)
+                  L_LAYOUT,  // cfg: element size in bytes
                   L_BNFULL,  // cfg: pass 0 / 1 / 2; dtype: N; f0: decay; f1: lambda; p0: damp
                   L_RECORD, L_WAIT };   // stream ordering: record / wait for sync event `n` on `stream`
 
@@ -1251,6 +1252,7 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 case L_PACK: pe.kernel = KFAC_K_PACK; break;
                 case L_UPDATE: pe.kernel = KFAC_K_UPDATE; break;
                 case L_BNFULL: pe.kernel = KFAC_K_BN_FULL; break;
+                case L_LAYOUT: pe.kernel = KFAC_K_LAYOUT; break;
                 case L_RECORD: case L_WAIT: break;
             }
             pe.variant = (L.kind == L_GEMM || L.kind == L_LEAF || L.kind == L_BNFULL) ? L.cfg : 0;
@@ -1301,6 +1303,9 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 break;
             case L_BNRED:
                 e = launch_bn_reduce((const BnReduceJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, ls);
+                break;
+            case L_LAYOUT:
+                e = launch_nhwc_to_nchw((const LayoutJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, ls);
                 break;
             case L_BNFULL:
                 e = launch_bn_full((const BnFullJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, L.dtype, L.f0, L.f1,
@@ -1904,6 +1909,49 @@ kfac_status kfac_update_weights(kfac_ctx *ctx, int32_t n_layers, const kfac_laye
         Lc.bytes = pass == 0 ? 5.0 * bytes : (pass == 2 ? 2.0 * bytes : 0.0);
         plan.launches.push_back(Lc);
     }
+    return run_plan(ctx, plan, arena);
+}
+
+kfac_status kfac_nhwc_to_nchw(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, int32_t which, kfac_dtype type,
+                              const void *const *src, void *const *dst)
+{
+    if (!ctx || !layers_ok(L, n_layers) || !src || !dst) return KFAC_ERR_INVALID;
+    if ((which != 0 && which != 1) || (type != KFAC_F32 && type != KFAC_BF16)) return KFAC_ERR_INVALID;
+    const int esize = type == KFAC_F32 ? 4 : 2;
+    std::vector<LayoutJob> jobs;
+    long long wgs = 0;
+    double bytes = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        if (!src[l]) continue;
+        if (!dst[l]) return KFAC_ERR_INVALID;
+        int h, w;
+        layer_ok(L[l], nullptr, nullptr, &h, &w);
+        LayoutJob J{};
+        J.src = src[l]; J.dst = dst[l];
+        J.N = L[l].N;
+        J.C = which == 0 ? L[l].c_in : L[l].c_out;
+        J.HW = which == 0 ? L[l].h_in * L[l].w_in : h * w;
+        const size_t sz = (size_t)J.N * J.C * J.HW * esize;
+        if ((const char *)J.src < (const char *)J.dst + sz && (const char *)J.dst < (const char *)J.src + sz)
+            return KFAC_ERR_INVALID;   // the conversion is not done in place
+        J.tiles_c = (J.C + 63) / 64;
+        J.tiles_hw = (J.HW + 63) / 64;
+        J.wg_start = (int)wgs;
+        wgs += (long long)J.N * J.tiles_c * J.tiles_hw;
+        if (wgs > (1LL << 30)) return KFAC_ERR_INVALID;
+        bytes += 2.0 * sz;
+        jobs.push_back(J);
+    }
+    if (jobs.empty()) return KFAC_OK;
+    Plan plan; Arena arena(ctx->ws);
+    Launch Lc{};
+    Lc.kind = L_LAYOUT;
+    Lc.off_a = plan.tab.add(jobs.data(), jobs.size() * sizeof(LayoutJob));
+    Lc.n = (int)jobs.size();
+    Lc.total_wgs = (int)wgs;
+    Lc.cfg = esize;
+    Lc.bytes = bytes;
+    plan.launches.push_back(Lc);
     return run_plan(ctx, plan, arena);
 }
 

@@ -155,6 +155,15 @@ struct BnReduceJob {
     int wg_start;   // one wave per (n, c) row; 4 rows per workgroup
 };
 
+// One tensor [N, HW, C] -> [N, C, HW] (NHWC -> NCHW).
+struct LayoutJob {
+    const void *src;
+    void *dst;
+    int N, C, HW;
+    int tiles_c, tiles_hw;   // 64 x 64 tiles per image
+    int wg_start;
+};
+
 // BatchNorm layer treated with its whole 2C x 2C Fisher block (Sec. 4.2 before the unit-wise approximation).
 struct BnFullJob {
     const float *g_gamma, *g_beta;   // [N, C] per-sample gradients
@@ -223,6 +232,7 @@ hipError_t launch_bn(const BnJob *jobs_dev, int n_jobs, int total_wgs, int N, fl
 // pass 0: F update; 1: mean gradient and damping; 2: u = F_inv gbar
 hipError_t launch_bn_full(const BnFullJob *jobs_dev, int n_jobs, int total_wgs, int pass, int N, float decay,
                           float lambda, float *damp, hipStream_t s);
+hipError_t launch_nhwc_to_nchw(const LayoutJob *jobs_dev, int n_jobs, int total_wgs, int esize, hipStream_t s);
 hipError_t launch_bn_reduce(const BnReduceJob *jobs_dev, int n_jobs, int total_wgs, int N, hipStream_t s);
 // pass 0: per-chunk sums (total_wgs workgroups); pass 1: one workgroup per job adds them up and writes the ratios
 hipError_t launch_pack(const PackJob *jobs_dev, int n_jobs, int total_wgs, int bf16, int unpack, void *packed,

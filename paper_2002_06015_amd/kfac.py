@@ -24,12 +24,12 @@ EXPORTS = [
     "bn_unitwise_precondition", "bn_unitwise_reduce_nchw", "kfac_profile_enable", "kfac_profile_read",
     "kfac_packed_elems", "kfac_pack_upper", "kfac_unpack_upper",
     "kfac_lr_polynomial", "kfac_momentum_coupled", "kfac_update_weights",
-    "bn_full_workspace_bytes", "bn_full_precondition",
+    "bn_full_workspace_bytes", "bn_full_precondition", "kfac_nhwc_to_nchw",
     "kfac_staleness", "kfac_next_interval", "kfac_refresh_init", "kfac_refresh_due", "kfac_refresh_advance",
 ]
 
 KERNEL_NAMES = ["gemm_f32", "gemm_bf16", "gemm_reduce", "patch", "trace", "copy_damp", "leaf_inverse", "zero",
-                "bn_unit", "bn_reduce", "pad", "assemble", "border", "staleness", "pack", "update", "bn_full"]
+                "bn_unit", "bn_reduce", "pad", "assemble", "border", "staleness", "pack", "update", "bn_full", "layout"]
 
 
 class kfac_profile_entry(ctypes.Structure):
@@ -78,6 +78,7 @@ def lib() -> ctypes.CDLL:
         L.kfac_profile_enable.argtypes = [vp, i32]
         L.kfac_profile_read.restype = i32
         L.kfac_profile_read.argtypes = [vp, vp, i32]
+        L.kfac_nhwc_to_nchw.argtypes = [vp, i32, vp, i32, i32, vp, vp]
         L.bn_full_workspace_bytes.restype = ctypes.c_size_t
         L.bn_full_workspace_bytes.argtypes = [i32, i32, vp]
         L.bn_full_precondition.argtypes = [vp, i32, i32, vp, vp, vp, f32, f32, vp, vp, vp, vp, vp, vp]
@@ -289,6 +290,16 @@ def bn_unitwise_reduce_nchw(ctx: Context, N: int, C: Sequence[int], HW: Sequence
                                        *[p and ctypes.addressof(p) for p in ps])
     if st != KFAC_OK:
         raise KfacError(st, "bn_unitwise_reduce_nchw")
+
+
+def kfac_nhwc_to_nchw(ctx: Context, layers: Sequence, which: int, type_: int, src, dst) -> None:
+    n = len(layers)
+    ls = _layers(layers)
+    ps, pd = _ptrs(src, n, _tdtype(type_)), _ptrs(dst, n, _tdtype(type_))
+    st = lib().kfac_nhwc_to_nchw(ctx.handle, n, ctypes.addressof(ls), int(which), int(type_),
+                                 ps and ctypes.addressof(ps), pd and ctypes.addressof(pd))
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_nhwc_to_nchw")
 
 
 def bn_full_workspace_bytes(N: int, C: Sequence[int]) -> int:

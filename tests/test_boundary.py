@@ -354,3 +354,30 @@ def test_bn_full_rejects_bad_arguments_without_a_gpu():
     big = (ctypes.c_int32 * 1)(1024)
     assert call(h, 1, 32, ctypes.addressof(big), gg, gb, 0.0, 1e-6, F, None, Fi, None, og, ob) == kfac.KFAC_ERR_WORKSPACE
     L.kfac_destroy(h)
+
+
+# ------------------------------------------------------------------ NHWC -> NCHW conversion (Sec. 5.2): arguments
+def test_layout_conversion_rejects_bad_arguments_without_a_gpu():
+    L = kfac.lib()
+    INV = kfac.KFAC_ERR_INVALID
+    h = _fake_ctx(1 << 20)
+    lays = (kfac.kfac_layer * 2)(kfac.kfac_layer(*wl.conv_layer(2, 8, 4, 3, 1, 1, 6)), kfac.kfac_layer(*wl.fc_layer(2, 16, 8)))
+    lp = ctypes.addressof(lays)
+    src = (ctypes.c_void_p * 2)(0x200000, 0x300000)
+    dst = (ctypes.c_void_p * 2)(0x400000, 0x500000)
+    sp, dp = ctypes.addressof(src), ctypes.addressof(dst)
+    call = L.kfac_nhwc_to_nchw
+    assert call(None, 2, lp, 0, 0, sp, dp) == INV
+    assert call(h, 0, lp, 0, 0, sp, dp) == INV
+    assert call(h, 2, None, 0, 0, sp, dp) == INV
+    assert call(h, 2, lp, 2, 0, sp, dp) == INV                                   # which is 0 or 1
+    assert call(h, 2, lp, 0, 7, sp, dp) == INV                                   # unknown element type
+    assert call(h, 2, lp, 0, 0, None, dp) == INV
+    assert call(h, 2, lp, 0, 0, sp, None) == INV
+    hole = (ctypes.c_void_p * 2)(0x400000, None)
+    assert call(h, 2, lp, 0, 0, sp, ctypes.addressof(hole)) == INV               # source without destination
+    over = (ctypes.c_void_p * 2)(0x200000 + 256, 0x500000)
+    assert call(h, 2, lp, 0, 0, sp, ctypes.addressof(over)) == INV               # in place / overlapping
+    none = (ctypes.c_void_p * 2)(None, None)
+    assert call(h, 2, lp, 0, 0, ctypes.addressof(none), dp) == kfac.KFAC_OK      # nothing to do
+    L.kfac_destroy(h)

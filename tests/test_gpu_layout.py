@@ -1,0 +1,99 @@
+"""GPU parity of the NHWC -> NCHW conversion (Sec. 5.2) against the oracle: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import layout
+from paper_2002_06015_amd import kfac, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    kfac.lib()
+    return torch.device("cuda")
+
+
+# channels / positions that are and are not multiples of 4 and of the 64-wide tile, one-pixel images, a fully-connected layer
+LAYERS = [wl.conv_layer(2, 3, 5, 3, 1, 1, 5), wl.conv_layer(3, 8, 12, 1, 1, 0, 6), wl.conv_layer(2, 64, 70, 3, 2, 1, 9),
+          wl.conv_layer(2, 130, 64, 1, 1, 0, 8), wl.conv_layer(1, 7, 9, 1, 1, 0, 1), wl.Layer(2, 20, 6, 3, 1, 1, 10, 14, 1),
+          wl.fc_layer(5, 33, 17), wl.conv_layer(2, 260, 4, 1, 2, 0, 14)]
+
+
+def _shape(L, which):
+    h, w = kfac.kfac_layer_dims(L)[2:]
+    return (L.N, L.h_in, L.w_in, L.c_in) if which == 0 else (L.N, h, w, L.c_out)
+
+
+@pytest.mark.parametrize("which", [0, 1])
+@pytest.mark.parametrize("type_", [kfac.KFAC_F32, kfac.KFAC_BF16])
+def test_conversion_is_the_oracle_permutation_bit_for_bit(gpu, which, type_):
+    rng = np.random.default_rng(3 + which)
+    ctx = kfac.Context(LAYERS)
+    if type_ == kfac.KFAC_F32:
+        host = [rng.standard_normal(_shape(L, which)).astype(np.float32) for L in LAYERS]
+        src = [torch.from_numpy(x).cuda() for x in host]
+    else:
+        host = [rng.integers(0, 65536, size=_shape(L, which)).astype(np.uint16) for L in LAYERS]     # any bit pattern
+        src = [torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16) for x in host]
+    dst = [torch.full((x.size + 16,), 1.0, dtype=s.dtype, device="cuda") for x, s in zip(host, src)]
+    guard = [d.clone() for d in dst]
+    src[3] = None                                                                # a skipped layer
+    kfac.kfac_nhwc_to_nchw(ctx, LAYERS, which, type_, src, dst)
+    torch.cuda.synchronize()
+    for i, L in enumerate(LAYERS):
+        n = host[i].size
+        if i == 3:
+            assert torch.equal(dst[i], guard[i])
+            continue
+        got = dst[i][:n].view(torch.int16 if type_ == kfac.KFAC_BF16 else torch.int32).cpu().numpy()
+        ref = layout.nhwc_to_nchw(host[i]).ravel()
+        ref = ref.view(np.int16) if type_ == kfac.KFAC_BF16 else ref.view(np.int32)
+        assert np.array_equal(got, ref), i
+        assert torch.equal(dst[i][n:], guard[i][n:]), i                           # nothing written past the end
+    ctx.close()
+
+
+def test_statistics_from_converted_nhwc_inputs_match_the_oracle(gpu):
+    """kfac_stats on the converted tensors against the oracle fed with the NHWC data through its own conversion."""
+    layers = [wl.conv_layer(2, 8, 12, 3, 1, 1, 6), wl.conv_layer(3, 12, 7, 1, 1, 0, 5), wl.conv_layer(2, 5, 6, 3, 2, 1, 9)]
+    ctx = kfac.Context(layers)
+    rng = np.random.default_rng(9)
+    a_nhwc = [rng.standard_normal(_shape(L, 0)).astype(np.float32) for L in layers]
+    g_nhwc = [(rng.standard_normal(_shape(L, 1)) * 1e-3).astype(np.float32) for L in layers]
+    a = [torch.empty(x.size, device="cuda") for x in a_nhwc]
+    g = [torch.empty(x.size, device="cuda") for x in g_nhwc]
+    kfac.kfac_nhwc_to_nchw(ctx, layers, 0, kfac.KFAC_F32, [torch.from_numpy(x).cuda() for x in a_nhwc], a)
+    kfac.kfac_nhwc_to_nchw(ctx, layers, 1, kfac.KFAC_F32, [torch.from_numpy(x).cuda() for x in g_nhwc], g)
+    A = [torch.empty(L.dA, L.dA, device="cuda") for L in layers]
+    G = [torch.empty(L.dG, L.dG, device="cuda") for L in layers]
+    kfac.kfac_stats(ctx, layers, kfac.KFAC_F32, a, g, 0.0, True, A, G)
+    torch.cuda.synchronize()
+    for i, L in enumerate(layers):
+        Ar, Gr = oracle.kfac_stats(tuple(L), layout.nhwc_to_nchw(a_nhwc[i]), layout.nhwc_to_nchw(g_nhwc[i]), 0.0, True,
+                                   None, None)
+        for got, ref in ((A[i], Ar), (G[i], Gr)):
+            assert np.abs(got.cpu().numpy() - ref).max() <= 1e-4 * np.abs(ref).max(), i
+    ctx.close()
+
+
+def test_full_resnet50_activation_set(gpu):
+    """All 54 activation tensors of configuration 4 in one call; the oracle on the largest, the smallest-image and
+    the stem tensors, torch's own permutation on all."""
+    layers = wl.config_layers(4)
+    ctx = kfac.Context(layers[:1])
+    g = torch.Generator(device="cuda"); g.manual_seed(1)
+    src = [torch.randn(_shape(L, 0), device="cuda", generator=g) for L in layers]
+    dst = [torch.empty(x.numel(), device="cuda") for x in src]
+    kfac.kfac_nhwc_to_nchw(ctx, layers, 0, kfac.KFAC_F32, src, dst)
+    torch.cuda.synchronize()
+    sizes = [x.numel() for x in src]
+    for i in sorted({0, int(np.argmax(sizes)), len(layers) - 2, len(layers) - 1}):
+        assert np.array_equal(dst[i].cpu().numpy(), layout.nhwc_to_nchw(src[i].cpu().numpy()).ravel()), i
+    for i in range(len(layers)):
+        assert torch.equal(dst[i], src[i].permute(0, 3, 1, 2).reshape(-1)), i
+    ctx.close()
