@@ -324,7 +324,7 @@ void kfac_refresh_advance(kfac_refresh_state *s, double ratio_m1, double ratio_m
 typedef enum {
     KFAC_K_GEMM_F32 = 0, KFAC_K_GEMM_BF16 = 1, KFAC_K_GEMM_REDUCE = 2, KFAC_K_PATCH = 3, KFAC_K_TRACE = 4,
     KFAC_K_COPY_DAMP = 5, KFAC_K_LEAF_INVERSE = 6, KFAC_K_ZERO = 7, KFAC_K_BN_UNIT = 8, KFAC_K_BN_REDUCE = 9,
-    KFAC_K_PAD = 10, KFAC_K_ASSEMBLE = 11, KFAC_K_BORDER = 12, KFAC_K_STALENESS = 13, KFAC_K_PACK = 14, KFAC_K_UPDATE = 15, KFAC_K_BN_FULL = 16, KFAC_K_LAYOUT = 17
+    KFAC_K_PAD = 10, KFAC_K_ASSEMBLE = 11, KFAC_K_BORDER = 12, KFAC_K_STALENESS = 13, KFAC_K_PACK = 14, KFAC_K_UPDATE = 15, KFAC_K_BN_FULL = 16, KFAC_K_LAYOUT = 17, KFAC_K_GEMM_F32_SPLIT = 18
 } kfac_kernel;
 
 typedef struct {

@@ -499,7 +499,160 @@ __device__ __forceinline__ void gemm_f32_mainloop(const GemmProblem &P, int tm, 
     for (; it < nk; ++it) step(it);
 }
 
-template <int TM, int TN>
+// ------------------------------------------------------------------ fp32 through three bf16 planes
+// The bf16 matrix instruction runs at 16 times the rate of the fp32 one.  An fp32 value is the
+// exact sum of three bf16 values (8 + 8 + 8 significant bits: x = h + m + l by two truncations
+// and two exact subtractions), and a product of two bf16 values is exact in fp32, so
+//     x y  =  h h' + (h m' + m h') + (h l' + m m' + l h')  +  terms below 2^-23 |x y|
+// with fp32 accumulation inside the matrix unit: six bf16 instructions give the product to
+// fp32 accuracy in 6 x 32 cycles per 32x32x16 block instead of 8 x 64.  The operands stay fp32 in
+// HBM; the loader of the fp32 kernel brings a K tile of 32 into registers and the split happens
+// on the way into LDS, which holds one stage of three planes (two barriers per tile; the second
+// workgroup of the compute unit computes while this one stores).
+constexpr int LDQ = 40;     // LDS row length in bf16 (32 + 8 pad: 80-byte rows, conflict-free 16-byte reads)
+
+// two fp32 values -> their packed (h, m, l) bf16 pairs, low half = first value
+__device__ __forceinline__ void split_pair(float x0, float x1, unsigned &h, unsigned &m, unsigned &l)
+{
+    const unsigned b0 = __float_as_uint(x0), b1 = __float_as_uint(x1);
+    const float r0 = x0 - __uint_as_float(b0 & 0xFFFF0000u), r1 = x1 - __uint_as_float(b1 & 0xFFFF0000u);
+    const unsigned c0 = __float_as_uint(r0), c1 = __float_as_uint(r1);
+    const float q0 = r0 - __uint_as_float(c0 & 0xFFFF0000u), q1 = r1 - __uint_as_float(c1 & 0xFFFF0000u);
+    h = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
+    m = __builtin_amdgcn_perm(c1, c0, 0x07060302u);
+    l = __builtin_amdgcn_perm(__float_as_uint(q1), __float_as_uint(q0), 0x07060302u);
+}
+
+// the staged tile of one operand into its rows of the three planes (plane stride in bf16 units)
+template <int BR, bool RS>
+__device__ __forceinline__ void store_split(const LoaderF32<BR> &ld, const floatx4 (&reg)[BR / 32], unsigned short *rows,
+                                            int plane, float (&rs)[BR / 32])
+{
+#pragma unroll
+    for (int s = 0; s < BR / 32; ++s) {
+        floatx4 v = reg[s];
+        if (((ld.dead >> s) & 1) || ld.zero_all) { v[0] = 0.f; v[1] = 0.f; v[2] = 0.f; v[3] = 0.f; }
+        if constexpr (RS) rs[s] += (v[0] + v[1]) + (v[2] + v[3]);
+        uint2 h, m, l;
+        split_pair(v[0], v[1], h.x, m.x, l.x);
+        split_pair(v[2], v[3], h.y, m.y, l.y);
+        unsigned short *dst = rows + (ld.r0 + 32 * s) * LDQ + ld.kq;
+        *(uint2 *)dst = h;
+        *(uint2 *)(dst + plane) = m;
+        *(uint2 *)(dst + 2 * plane) = l;
+    }
+}
+
+// K % 4 remainder tile: thread tid < BR fills row tid of the three planes with the elements
+// k4 .. kend-1 of its operand row followed by zeros; returns their sum
+template <int BR>
+__device__ __forceinline__ float fill_remainder_split(const Operand &op, int tile_row0, int k4, int kend, int tid,
+                                                      unsigned short *rows, int plane)
+{
+    if (tid >= BR) return 0.f;
+    const int row = tile_row0 + tid;
+    float x[4] = {0.f, 0.f, 0.f, 0.f};
+    if (row < op.rows) {
+        gfloat_ptr p = (gfloat_ptr)op.base + (long long)row * op.row_stride + k4;
+        for (int e = 0; e < 3; ++e)
+            if (k4 + e < kend) x[e] = p[e];
+    }
+    uint2 v[3];
+    split_pair(x[0], x[1], v[0].x, v[1].x, v[2].x);
+    split_pair(x[2], x[3], v[0].y, v[1].y, v[2].y);
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+        unsigned short *dst = rows + q * plane + tid * LDQ;
+        *(uint4 *)dst = uint4{v[q].x, v[q].y, 0u, 0u};
+#pragma unroll
+        for (int w = 1; w < 4; ++w) *(uint4 *)(dst + 8 * w) = uint4{0u, 0u, 0u, 0u};
+    }
+    return x[0] + x[1] + x[2];
+}
+
+template <int TM, int TN, bool LIVE, bool RS>
+__device__ __forceinline__ void gemm_split_mainloop(const GemmProblem &P, int tm, int tn, int tid,
+                                                    LoaderF32<64 * TM> &la, LoaderF32<64 * TN> &lb, unsigned short *lds,
+                                                    int k0, int k1, int wave_m, int wave_n, int l32, int half,
+                                                    floatx16 (&acc)[TM][TN], float (&rs)[2 * TM], float &rs_rem)
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int PLANE = (BM + BN) * LDQ;
+    const int klen = max(k1 - k0, 0);
+    const int klen4 = klen & ~3;
+    const int nfull = klen4 / KT;
+    const bool shifted = nfull > 0 && klen4 > nfull * KT;
+    const bool careful = nfull == 0 && klen4 > 0;
+    const int nvec = nfull + ((shifted || careful) ? 1 : 0);
+    const int nk = nvec + (klen4 < klen ? 1 : 0);
+    if (nk == 0) return;
+    floatx4 ra[BM / 32], rb[BN / 32];
+
+    auto load_tile = [&](int it) {
+        if (it < nfull) {
+            if (it > 0) { la.advance(); lb.advance(); }
+            la.load_full(ra); lb.load_full(rb);
+        } else if (it < nvec) {
+            if (careful) {
+                la.load_careful(ra, k0 + klen4); lb.load_careful(rb, k0 + klen4);
+            } else {
+                la.seek(k0 + klen4 - KT); lb.seek(k0 + klen4 - KT);
+                la.load_full(ra); lb.load_full(rb);
+                la.zero_below(k0 + nfull * KT);
+            }
+        }
+    };
+    auto store_tile = [&](int it) {
+        if (it < nvec) {
+            float unused[BN / 32];
+            store_split<BM, RS>(la, ra, lds, PLANE, rs);
+            store_split<BN, false>(lb, rb, lds + BM * LDQ, PLANE, unused);
+        } else {
+            rs_rem = fill_remainder_split<BM>(P.a, tm * BM, k0 + klen4, k1, tid, lds, PLANE);
+            fill_remainder_split<BN>(P.b, tn * BN, k0 + klen4, k1, tid, lds + BM * LDQ, PLANE);
+        }
+    };
+    // v_mfma_f32_32x32x16_bf16: a lane supplies 8 consecutive k of row lane % 32, the half-waves
+    // two different groups of 8; step u of a tile uses k = 16u + 8*half + 0..7 for both operands
+    const int off_a = (wave_m * 32 * TM + l32) * LDQ + 8 * half;
+    const int off_b = BM * LDQ + (wave_n * 32 * TN + l32) * LDQ + 8 * half;
+
+    la.seek(k0); lb.seek(k0);
+    load_tile(0);
+    for (int it = 0; it < nk; ++it) {
+        if (it > 0) __syncthreads();   // every wavefront has read tile it - 1
+        store_tile(it);
+        load_tile(it + 1);
+        __syncthreads();
+        if constexpr (LIVE) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                bf16x8 a[3][TM], b[3][TN];
+#pragma unroll
+                for (int q = 0; q < 3; ++q) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        a[q][i] = __builtin_bit_cast(bf16x8, *(const ushortx8 *)(lds + q * PLANE + off_a + i * 32 * LDQ + 16 * u));
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        b[q][j] = __builtin_bit_cast(bf16x8, *(const ushortx8 *)(lds + q * PLANE + off_b + j * 32 * LDQ + 16 * u));
+                }
+                // plane pairs (p, q) with p + q <= 2, largest terms first (their operands arrive first)
+                constexpr int PA[6] = {0, 0, 1, 0, 1, 2};
+                constexpr int PB[6] = {0, 1, 0, 2, 1, 0};
+#pragma unroll
+                for (int t = 0; t < 6; ++t)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[PA[t]][i], b[PB[t]][j], acc[i][j], 0, 0, 0);
+            }
+        }
+    }
+}
+
+template <int TM, int TN, bool SPLIT>
 __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__restrict__ probs,
                                                           const int *__restrict__ tile_start, int n_probs)
 {
@@ -552,13 +705,22 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__r
     float rs[BM / 32], rs_rem = 0.f;
 #pragma unroll
     for (int s = 0; s < BM / 32; ++s) rs[s] = 0.f;
+    auto mainloop = [&](auto live_c, auto rs_c) {
+        constexpr bool LV = decltype(live_c)::value, RSUM = decltype(rs_c)::value;
+        if constexpr (SPLIT)
+            gemm_split_mainloop<TM, TN, LV, RSUM>(P, tm, tn, tid, la, lb, (unsigned short *)lds, k0, k1, wave_m, wave_n,
+                                                  l32, half, acc, rs, rs_rem);
+        else
+            gemm_f32_mainloop<TM, TN, LV, RSUM>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc, rs,
+                                                rs_rem);
+    };
     if (border) {
-        if (live) gemm_f32_mainloop<TM, TN, true, true>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
-        else      gemm_f32_mainloop<TM, TN, false, true>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        if (live) mainloop(std::true_type{}, std::true_type{});
+        else      mainloop(std::false_type{}, std::true_type{});
         finish_row_sums<BM>(P, lds, tm, tile, split, tid, rs, rs_rem);
     } else {
-        if (live) gemm_f32_mainloop<TM, TN, true, false>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
-        else      gemm_f32_mainloop<TM, TN, false, false>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        if (live) mainloop(std::true_type{}, std::false_type{});
+        else      mainloop(std::false_type{}, std::false_type{});
     }
 
     // accumulator layout of the 32x32 block: column = lane % 32,
@@ -1061,7 +1223,8 @@ static hipError_t launch_one(const GemmProblem *probs_dev, const int *tile_start
 {
     static_assert(2 * LDH == 4 * LDF, "bf16 and fp32 stages have the same size");
     constexpr size_t lds_bytes = gemm_lds_bytes<TM, TN>();
-    auto kernel = DT == 0 ? gemm_nt_f32_kernel<TM, TN> : gemm_nt_bf16_kernel<TM, TN>;
+    static_assert(3 * (64 * TM + 64 * TN) * LDQ * sizeof(unsigned short) <= gemm_lds_bytes<TM, TN>(), "the three planes fit");
+    auto kernel = DT == 0 ? gemm_nt_f32_kernel<TM, TN, false> : DT == 2 ? gemm_nt_f32_kernel<TM, TN, true> : gemm_nt_bf16_kernel<TM, TN>;
     static bool configured = false;   // the attribute is per function, set once per process
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1080,6 +1243,10 @@ hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, 
     if (dtype == 0) {
         if (tile_cfg == 0) return launch_one<2, 2, 0>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
         return launch_one<1, 1, 0>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
+    }
+    if (dtype == 2) {   // fp32 operands, products through three bf16 planes
+        if (tile_cfg == 0) return launch_one<2, 2, 2>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
+        return launch_one<1, 1, 2>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
     }
     if (tile_cfg == 0) return launch_one<2, 2, 1>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
     return launch_one<1, 1, 1>(probs_dev, tile_start_dev, n_probs, total_wgs, s);

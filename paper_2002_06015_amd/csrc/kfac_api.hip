@@ -40,6 +40,8 @@ struct Tunables {
                          // reductions of the previous one under the matrix launches of the current one)
     double chunk_gf;     // fused step: matrix launches of the later factor phases in parts of about this many
                          // GFLOP (0: whole)
+    int split;           // 1: fp32 products through three bf16 planes and six bf16 matrix instructions
+                         // (fp32 accuracy at the bf16 unit's rate) instead of the fp32 matrix instruction
     Tunables()
     {
         const char *e = getenv("KFAC_TARGET_WGS");
@@ -62,6 +64,8 @@ struct Tunables {
         pipe = e ? (atoi(e) != 0) : 1;
         e = getenv("KFAC_CHUNK_GF");
         chunk_gf = e ? std::max(0.0, atof(e)) : 48.0;
+        e = getenv("KFAC_SPLIT");
+        split = e ? (atoi(e) != 0) : 0;
     }
 };
 
@@ -334,7 +338,7 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
         L.n = (int)sel.size();
         L.total_wgs = start.back();
         L.cfg = cfg;
-        L.dtype = dtype;
+        L.dtype = (dtype == 0 && tun.split) ? 2 : dtype;
         plan.launches.push_back(L);
         if (any_split) {
             Launch R{};
@@ -1236,7 +1240,7 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
             }
             kfac_profile_entry pe{};
             switch (L.kind) {
-                case L_GEMM: pe.kernel = L.dtype == 0 ? KFAC_K_GEMM_F32 : KFAC_K_GEMM_BF16; break;
+                case L_GEMM: pe.kernel = L.dtype == 0 ? KFAC_K_GEMM_F32 : L.dtype == 2 ? KFAC_K_GEMM_F32_SPLIT : KFAC_K_GEMM_BF16; break;
                 case L_REDUCE: pe.kernel = KFAC_K_GEMM_REDUCE; break;
                 case L_PATCH: pe.kernel = KFAC_K_PATCH; break;
                 case L_TRACE: pe.kernel = KFAC_K_TRACE; break;

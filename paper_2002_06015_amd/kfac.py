@@ -29,7 +29,7 @@ EXPORTS = [
 ]
 
 KERNEL_NAMES = ["gemm_f32", "gemm_bf16", "gemm_reduce", "patch", "trace", "copy_damp", "leaf_inverse", "zero",
-                "bn_unit", "bn_reduce", "pad", "assemble", "border", "staleness", "pack", "update", "bn_full", "layout"]
+                "bn_unit", "bn_reduce", "pad", "assemble", "border", "staleness", "pack", "update", "bn_full", "layout", "gemm_f32_split"]
 
 
 class kfac_profile_entry(ctypes.Structure):
