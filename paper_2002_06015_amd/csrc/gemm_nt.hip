@@ -586,9 +586,12 @@ __device__ __forceinline__ void gemm_split_mainloop(const GemmProblem &P, int tm
     const int nvec = nfull + ((shifted || careful) ? 1 : 0);
     const int nk = nvec + (klen4 < klen ? 1 : 0);
     if (nk == 0) return;
-    floatx4 ra[BM / 32], rb[BN / 32];
+    // two tiles in flight in registers: the loads of tile it + 2 are issued when tile it has gone
+    // into LDS, and have two tile times to arrive
+    floatx4 ra0[BM / 32], rb0[BN / 32], ra1[BM / 32], rb1[BN / 32];
+    bool za0 = false, zb0 = false, za1 = false, zb1 = false;   // the loaders' zero_all of the tile held
 
-    auto load_tile = [&](int it) {
+    auto load_tile = [&](int it, auto &ra, auto &rb, bool &za, bool &zb) {
         if (it < nfull) {
             if (it > 0) { la.advance(); lb.advance(); }
             la.load_full(ra); lb.load_full(rb);
@@ -601,10 +604,12 @@ __device__ __forceinline__ void gemm_split_mainloop(const GemmProblem &P, int tm
                 la.zero_below(k0 + nfull * KT);
             }
         }
+        za = la.zero_all; zb = lb.zero_all;
     };
-    auto store_tile = [&](int it) {
+    auto store_tile = [&](int it, const auto &ra, const auto &rb, bool za, bool zb) {
         if (it < nvec) {
             float unused[BN / 32];
+            la.zero_all = za; lb.zero_all = zb;
             store_split<BM, RS>(la, ra, lds, PLANE, rs);
             store_split<BN, false>(lb, rb, lds + BM * LDQ, PLANE, unused);
         } else {
@@ -616,45 +621,74 @@ __device__ __forceinline__ void gemm_split_mainloop(const GemmProblem &P, int tm
     // two different groups of 8; step u of a tile uses k = 16u + 8*half + 0..7 for both operands
     const int off_a = (wave_m * 32 * TM + l32) * LDQ + 8 * half;
     const int off_b = BM * LDQ + (wave_n * 32 * TN + l32) * LDQ + 8 * half;
-
-    la.seek(k0); lb.seek(k0);
-    load_tile(0);
-    for (int it = 0; it < nk; ++it) {
-        if (it > 0) __syncthreads();   // every wavefront has read tile it - 1
-        store_tile(it);
-        load_tile(it + 1);
-        __syncthreads();
+    // One step: the fragments of the h and m planes and of l' are requested up front, the l
+    // fragments of the a operand take over the registers of h once its products are issued (their
+    // latency lies under the m products).  Fixed order (the scheduling barriers keep the compiler
+    // from hoisting the next step's reads, which would cost the second workgroup of the compute
+    // unit its registers).
+    auto compute = [&]() {
         if constexpr (LIVE) {
+            auto rd = [&](int q, int off, int u) {
+                return __builtin_bit_cast(bf16x8, *(const ushortx8 *)(lds + q * PLANE + off + 16 * u));
+            };
+            auto mm = [&](const bf16x8 (&x)[TM], const bf16x8 (&y)[TN]) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                bf16x8 a[3][TM], b[3][TN];
-#pragma unroll
-                for (int q = 0; q < 3; ++q) {
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-                        a[q][i] = __builtin_bit_cast(bf16x8, *(const ushortx8 *)(lds + q * PLANE + off_a + i * 32 * LDQ + 16 * u));
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        b[q][j] = __builtin_bit_cast(bf16x8, *(const ushortx8 *)(lds + q * PLANE + off_b + j * 32 * LDQ + 16 * u));
-                }
-                // plane pairs (p, q) with p + q <= 2, largest terms first (their operands arrive first)
-                constexpr int PA[6] = {0, 0, 1, 0, 1, 2};
-                constexpr int PB[6] = {0, 1, 0, 2, 1, 0};
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[i], y[j], acc[i][j], 0, 0, 0);
+            };
 #pragma unroll
-                for (int t = 0; t < 6; ++t)
+            for (int u = 0; u < 2; ++u) {
+                bf16x8 ah[TM], am[TM], bh[TN], bm[TN], bl[TN];
 #pragma unroll
-                    for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < TM; ++i) ah[i] = rd(0, off_a + i * 32 * LDQ, u);
 #pragma unroll
-                        for (int j = 0; j < TN; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[PA[t]][i], b[PB[t]][j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < TN; ++j) bh[j] = rd(0, off_b + j * 32 * LDQ, u);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bm[j] = rd(1, off_b + j * 32 * LDQ, u);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bl[j] = rd(2, off_b + j * 32 * LDQ, u);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) am[i] = rd(1, off_a + i * 32 * LDQ, u);
+                __builtin_amdgcn_sched_barrier(0);
+                mm(ah, bh);
+                mm(ah, bm);
+                mm(ah, bl);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) ah[i] = rd(2, off_a + i * 32 * LDQ, u);   // the l plane of a
+                __builtin_amdgcn_sched_barrier(0);
+                mm(am, bh);
+                mm(am, bm);
+                mm(ah, bh);
+                __builtin_amdgcn_sched_barrier(0);
             }
+        }
+    };
+
+    la.seek(k0); lb.seek(k0);
+    load_tile(0, ra0, rb0, za0, zb0);
+    load_tile(1, ra1, rb1, za1, zb1);
+    for (int it = 0; it < nk; it += 2) {
+        if (it > 0) __syncthreads();   // every wavefront has read the tile before
+        store_tile(it, ra0, rb0, za0, zb0);
+        load_tile(it + 2, ra0, rb0, za0, zb0);
+        __syncthreads();
+        compute();
+        if (it + 1 < nk) {
+            __syncthreads();
+            store_tile(it + 1, ra1, rb1, za1, zb1);
+            load_tile(it + 3, ra1, rb1, za1, zb1);
+            __syncthreads();
+            compute();
         }
     }
 }
 
 template <int TM, int TN, bool SPLIT>
-__global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__restrict__ probs,
-                                                          const int *__restrict__ tile_start, int n_probs)
+__device__ __forceinline__ void gemm_nt_f32_body(const GemmProblem *__restrict__ probs,
+                                                 const int *__restrict__ tile_start, int n_probs)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     extern __shared__ __attribute__((aligned(16))) float lds[];   // 2 stages of (BM + BN) * LDF floats
@@ -755,6 +789,21 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__r
         __syncthreads();
         store_slab<BM, BN>(P, lds, tm * BM, tn * BN, diag_tile, tid);
     }
+}
+
+template <int TM, int TN>
+__global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__restrict__ probs,
+                                                          const int *__restrict__ tile_start, int n_probs)
+{
+    gemm_nt_f32_body<TM, TN, false>(probs, tile_start, n_probs);
+}
+
+// (two wavefronts per SIMD: the register allocation is held to 256)
+template <int TM, int TN>
+__global__ __launch_bounds__(256, 2) void gemm_nt_f32_split_kernel(const GemmProblem *__restrict__ probs,
+                                                                   const int *__restrict__ tile_start, int n_probs)
+{
+    gemm_nt_f32_body<TM, TN, true>(probs, tile_start, n_probs);
 }
 
 // ------------------------------------------------------------------ bf16 operand loader
@@ -1224,7 +1273,7 @@ static hipError_t launch_one(const GemmProblem *probs_dev, const int *tile_start
     static_assert(2 * LDH == 4 * LDF, "bf16 and fp32 stages have the same size");
     constexpr size_t lds_bytes = gemm_lds_bytes<TM, TN>();
     static_assert(3 * (64 * TM + 64 * TN) * LDQ * sizeof(unsigned short) <= gemm_lds_bytes<TM, TN>(), "the three planes fit");
-    auto kernel = DT == 0 ? gemm_nt_f32_kernel<TM, TN, false> : DT == 2 ? gemm_nt_f32_kernel<TM, TN, true> : gemm_nt_bf16_kernel<TM, TN>;
+    auto kernel = DT == 0 ? gemm_nt_f32_kernel<TM, TN> : DT == 2 ? gemm_nt_f32_split_kernel<TM, TN> : gemm_nt_bf16_kernel<TM, TN>;
     static bool configured = false;   // the attribute is per function, set once per process
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,

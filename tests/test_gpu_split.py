@@ -1,0 +1,61 @@
+"""The optional product mode of the GEMM (fp32 operands, products through three bf16 planes, KFAC_SPLIT=1):
+the parity cases of the statistics, the inversion, the preconditioning and the fused step once more under that
+mode, to the same tolerances, and a direct comparison of its error with that of the fp32 matrix instruction."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2002_06015_amd import kfac, workloads as wl
+import test_gpu_parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def split_mode(monkeypatch):
+    monkeypatch.setenv("KFAC_SPLIT", "1")      # read when a context is created
+
+
+gpu = P.gpu
+
+# re-collected here, so that they run with the fixture above
+test_stats_two_steps = P.test_stats_two_steps
+test_stats_grouped_and_partial_inputs = P.test_stats_grouped_and_partial_inputs
+test_stats_split_k_is_reproducible_and_matches = P.test_stats_split_k_is_reproducible_and_matches
+test_invert_matches_oracle = P.test_invert_matches_oracle
+test_invert_badly_scaled_diagonal = P.test_invert_badly_scaled_diagonal
+test_invert_grouped_mixed_sizes = P.test_invert_grouped_mixed_sizes
+test_precondition_matches_oracle = P.test_precondition_matches_oracle
+test_config2_conv3x3_full_size = P.test_config2_conv3x3_full_size
+test_fused_step_stale_subset = P.test_fused_step_stale_subset
+
+
+def _stats_error(layer, act, grad):
+    A, G = P.run_stats([layer], [act], [grad], 0.0, False)
+    Ar, Gr = oracle.kfac_stats(tuple(layer), act, grad, 0.0, False, None, None)
+    return P.relerr(P.host(A[0]), Ar), P.relerr(P.host(G[0]), Gr)
+
+
+def test_products_are_as_accurate_as_the_fp32_instruction(gpu, monkeypatch):
+    """A long contraction (4096 samples) with values spread over many binades: the error against the float64
+    oracle is that of fp32 accumulation in both modes, far below the 1e-4 of the statistics."""
+    layer = wl.fc_layer(4096, 300, 200)
+    rng = np.random.default_rng(12)
+    act = (rng.standard_normal((4096, 300)) * np.exp2(rng.integers(-12, 12, size=(4096, 300)))).astype(np.float32).reshape(4096, 300, 1, 1)
+    grad = (rng.standard_normal((4096, 200)) * np.exp2(rng.integers(-20, -2, size=(4096, 200)))).astype(np.float32).reshape(4096, 200, 1, 1)
+    eA3, eG3 = _stats_error(layer, act, grad)
+    monkeypatch.setenv("KFAC_SPLIT", "0")
+    eA1, eG1 = _stats_error(layer, act, grad)
+    assert eA1 < 2e-6 and eG1 < 2e-6
+    assert eA3 <= 2.0 * eA1 + 5e-7 and eG3 <= 2.0 * eG1 + 5e-7, (eA3, eA1, eG3, eG1)
+
+
+def test_profile_names_the_kernel(gpu):
+    layer = wl.fc_layer(64, 300, 200)
+    ctx = kfac.Context([layer])
+    kfac.kfac_profile_enable(ctx, True)
+    A, G = P.run_stats([layer], [wl.make_act(layer, 1)], [wl.make_grad_out(layer, 1)], 0.0, False, ctx=ctx)
+    names = {e["kernel"] for e in kfac.kfac_profile_read(ctx)}
+    ctx.close()
+    assert "gemm_f32_split" in names and "gemm_f32" not in names
