@@ -266,7 +266,7 @@ def main():
                                   "%.2f s measured), scaled to the whole step by algorithmic flops (x%.1f)"
                                   % (len(sample), acc / 1e9, t_cpu, total_flops / acc)}
 
-    staleness = adaptive = layout_obj = packing = updating = full_bn = None
+    staleness = adaptive = layout_obj = packing = updating = full_bn = split_obj = None
     extras = not args.no_extras      # the calls beside the step are left out of profiler runs of the step itself
     if extras:
         # ---------------------------------------------------------------- beside the step: staleness of the factors
@@ -295,6 +295,49 @@ def main():
                              "(12 bytes per element); not part of the timed step"}
         del P, Q
 
+
+
+        # ------------------------------------------------------------ beside the step: the optional product mode
+        # (fp32 operands, products through three bf16 planes and six bf16 matrix instructions, KFAC_SPLIT=1: the
+        # same step on a context of its own, its results compared with those of the fp32 instruction)
+        split_obj = None
+        if args.dtype == "f32":
+            U_ref = [u.clone() for u in U]
+            A_ref = [a.clone() for a in A]
+            os.environ["KFAC_SPLIT"] = "1"
+            main_ctx2, ctx = ctx, kfac.Context(layers, in_dtype, extra_layer_lists=[sub_layers])
+            del os.environ["KFAC_SPLIT"]
+            step(wl.DECAY, subset)
+            torch.cuda.synchronize()
+            s0.record()
+            for _ in range(args.steps):
+                step(wl.DECAY, subset)
+            s1.record()
+            torch.cuda.synchronize()
+            split_ms = s0.elapsed_time(s1) / args.steps
+            ev3 = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            ev3[0].record(); stats(wl.DECAY)
+            ev3[1].record(); invert(subset)
+            ev3[2].record(); precond()
+            ev3[3].record()
+            torch.cuda.synchronize()
+            assert int(info.abs().sum().item()) == 0
+            # the running averages have moved on by a few steps of the same inputs; with decay they stay within
+            # rounding of each other, so the two modes' results are comparable
+            du = max(float((u - r).abs().max() / r.abs().max()) for u, r in zip(U, U_ref))
+            da = max(float((a - r).abs().max() / r.abs().max()) for a, r in zip(A, A_ref))
+            split_obj = {"ms_per_step": round(split_ms, 4),
+                         "stage_ms": {"stats": round(ev3[0].elapsed_time(ev3[1]), 4),
+                                      "invert": round(ev3[1].elapsed_time(ev3[2]), 4),
+                                      "precondition": round(ev3[2].elapsed_time(ev3[3]), 4)},
+                         "max_rel_diff_to_default": {"A": da, "U": du},
+                         "note": "the timed step with KFAC_SPLIT=1 (every fp32 product of the GEMM kernel formed from "
+                                 "three bf16 planes per operand by six bf16 matrix instructions, fp32 accumulation; "
+                                 "operands and results stay fp32); not the mode of the headline value"}
+            ctx.close()
+            ctx = main_ctx2
+            step(wl.DECAY, subset)       # the buffers back to the default mode's results
+            torch.cuda.synchronize()
 
         # ------------------------------------------------------------ beside the step: Algorithm 1 over a run of steps
         # (Sec. 4.3: every statistic is rebuilt only when its own interval says so; a layer is re-inverted when one of
@@ -509,6 +552,7 @@ def main():
         "packing": packing,
         "update": updating,
         "full_bn": full_bn,
+        "split_products": split_obj,
     }
     ctx.close()
     print(json.dumps(out))
