@@ -1992,8 +1992,9 @@ static kfac_status pack_call(kfac_ctx *ctx, int32_t n, const int32_t *dims, cons
         J.d = dims[i];
         J.tiles = (dims[i] + 63) / 64;
         J.wg_start = (int)wgs;
-        wgs += (long long)J.tiles * (J.tiles + 1) / 2;
-        off += (long long)dims[i] * (dims[i] + 1) / 2;
+        const long long tri = (long long)dims[i] * (dims[i] + 1) / 2;
+        wgs += unpack ? (long long)J.tiles * (J.tiles + 1) / 2 : (tri + kPackChunk - 1) / kPackChunk;
+        off += tri;
         if (wgs > (1LL << 30)) return KFAC_ERR_INVALID;
         jobs.push_back(J);
     }

@@ -205,9 +205,10 @@ struct PackJob {
     const float *X;     // the matrix (written by the unpack kernel)
     long long off;      // first element of this matrix in the packed buffer
     int d;
-    int tiles;          // ceil(d / 64): the job has tiles (tiles + 1) / 2 workgroups
-    int wg_start;
+    int tiles;          // ceil(d / 64): unpacking takes tiles (tiles + 1) / 2 workgroups
+    int wg_start;       // (packing: one workgroup per kPackChunk elements of the triangle)
 };
+constexpr int kPackChunk = 4096;
 
 // ---- launchers (implemented in the kernel files) -----------------------------------
 hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, int n_probs,

@@ -1,10 +1,10 @@
 // Symmetry-aware packing of the statistics (Sec. 5.2): a symmetric d x d matrix travels as its
 // upper triangle, d (d + 1) / 2 elements -- row r contributes X[r][r .. d-1], rows in order,
 // matrices back to back -- optionally rounded to bfloat16 (nearest, ties to even).
-// Both directions are HBM bound and work on 64 x 64 tiles of the upper triangle, one workgroup
-// per tile, one wavefront per row segment: a segment is contiguous in the matrix and in the
-// packed buffer, so every access is a full 256-byte (128-byte for bf16) run.  Unpacking writes the
-// mirror image through an LDS transpose, along rows as well.
+// Both directions are HBM bound.  Packing walks the packed buffer (see pack_upper_kernel).
+// Unpacking works on 64 x 64 tiles of the upper triangle, one workgroup per tile, one wavefront
+// per row segment (contiguous in the matrix and in the packed buffer: 256-byte runs, 128 for
+// bf16), and writes the mirror image through an LDS transpose, along rows as well.
 #include "kfac_internal.h"
 
 namespace kfac {
@@ -34,30 +34,59 @@ __device__ __forceinline__ const PackJob &pack_find(const PackJob *jobs, int n_j
     return jobs[lo];
 }
 
+// Packing is driven by the output: a workgroup produces 4096 consecutive elements of a matrix's
+// triangle, a thread four groups of four.  The row of an element p follows from
+// start(r) = r d - r (r - 1) / 2 <= p by the quadratic formula (in fp32, then corrected by exact integer steps);
+// consecutive elements are consecutive in the matrix except at the ends of rows, so the reads are
+// as contiguous as the writes.
+__device__ __forceinline__ long long pack_row_start(int r, int d) { return (long long)r * d - (long long)r * (r - 1) / 2; }
+
 template <bool BF16>
 __global__ __launch_bounds__(256) void pack_upper_kernel(const PackJob *__restrict__ jobs, int n_jobs, void *packed)
 {
-    const PackJob J = pack_find(jobs, n_jobs, blockIdx.x);
-    int tr, tc;
-    pack_tile_of(blockIdx.x - J.wg_start, J.tiles, tr, tc);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c = 64 * tc + lane;
-    // all 16 loads of a thread first (they are independent), then the stores
-    float v[16];
-    bool in[16];
+    typedef float v4 __attribute__((ext_vector_type(4), aligned(4)));
+    typedef unsigned short h4 __attribute__((ext_vector_type(4), aligned(2)));
+    const PackJob *J = &pack_find(jobs, n_jobs, blockIdx.x);
+    const int d = J->d;
+    const float *X = J->X;
+    const long long tri = (long long)d * (d + 1) / 2, off = J->off;
+    const long long p0 = (long long)(blockIdx.x - J->wg_start) * kPackChunk;
+    v4 v[4];
+    // all loads of a thread first (they are independent), then the stores
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-        const int r = 64 * tr + wave + 4 * q;
-        in[q] = r < J.d && c < J.d && c >= r;
-        v[q] = in[q] ? __builtin_nontemporal_load(J.X + (long long)r * J.d + c) : 0.f;
+    for (int g = 0; g < 4; ++g) {
+        const long long p = p0 + 4LL * ((int)threadIdx.x + 256 * g);
+        v[g] = v4{0.f, 0.f, 0.f, 0.f};
+        if (p >= tri) continue;
+        const float b = 2.0f * d + 1.0f;
+        int r = (int)((b - sqrtf(b * b - 8.0f * (float)p)) * 0.5f);
+        r = r < 0 ? 0 : (r > d - 1 ? d - 1 : r);
+        while (r + 1 < d && pack_row_start(r + 1, d) <= p) ++r;
+        while (r > 0 && pack_row_start(r, d) > p) --r;
+        int c = r + (int)(p - pack_row_start(r, d));
+        if (c + 3 < d) {
+            v[g] = __builtin_nontemporal_load((const v4 *)(X + (long long)r * d + c));
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (p + k < tri) v[g][k] = X[(long long)r * d + c];
+                if (++c == d) { ++r; c = r; }
+            }
+        }
     }
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-        if (!in[q]) continue;
-        const int r = 64 * tr + wave + 4 * q;
-        const long long k = J.off + (long long)r * J.d - (long long)r * (r - 1) / 2 + (c - r);
-        if (BF16) ((unsigned short *)packed)[k] = pack_bf16(v[q]);
-        else      ((float *)packed)[k] = v[q];
+    for (int g = 0; g < 4; ++g) {
+        const long long p = p0 + 4LL * ((int)threadIdx.x + 256 * g);
+        if (p >= tri) continue;
+        if (p + 3 < tri) {
+            if (BF16) *(h4 *)((unsigned short *)packed + off + p) = h4{pack_bf16(v[g][0]), pack_bf16(v[g][1]), pack_bf16(v[g][2]), pack_bf16(v[g][3])};
+            else      *(v4 *)((float *)packed + off + p) = v[g];
+        } else {
+            for (int k = 0; k < 4 && p + k < tri; ++k) {
+                if (BF16) ((unsigned short *)packed)[off + p + k] = pack_bf16(v[g][k]);
+                else      ((float *)packed)[off + p + k] = v[g][k];
+            }
+        }
     }
 }
 
