@@ -23,6 +23,15 @@
  *     buffers untouched.  Numerical failure (a non-positive pivot) is reported
  *     through the device array `info`, never by aborting.
  *   - Outputs must not overlap inputs unless stated.
+ *   - Arithmetic of the dense contractions on fp32 operands (factors, Schur
+ *     products of the inversion, preconditioning): fp32 accumulation of products
+ *     that are exact to fp32 rounding.  By default an fp32 operand is split
+ *     exactly into three bf16 planes and each block product is formed by six bf16
+ *     matrix instructions (every term above 2^-23 of the product kept); with
+ *     KFAC_SPLIT=0 in the environment when the context is created the fp32
+ *     matrix instruction is used instead.  Results of the two agree to fp32
+ *     rounding of the accumulation.  bf16 operands (kfac_dtype KFAC_BF16) are
+ *     multiplied as they are.
  */
 #ifndef KFAC_H
 #define KFAC_H

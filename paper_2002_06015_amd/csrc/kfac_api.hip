@@ -40,8 +40,8 @@ struct Tunables {
                          // reductions of the previous one under the matrix launches of the current one)
     double chunk_gf;     // fused step: matrix launches of the later factor phases in parts of about this many
                          // GFLOP (0: whole)
-    int split;           // 1: fp32 products through three bf16 planes and six bf16 matrix instructions
-                         // (fp32 accuracy at the bf16 unit's rate) instead of the fp32 matrix instruction
+    int split;           // 1 (default): fp32 products through three bf16 planes and six bf16 matrix instructions
+                         // (fp32 accuracy at the bf16 unit's rate); 0: the fp32 matrix instruction
     Tunables()
     {
         const char *e = getenv("KFAC_TARGET_WGS");
@@ -65,7 +65,7 @@ struct Tunables {
         e = getenv("KFAC_CHUNK_GF");
         chunk_gf = e ? std::max(0.0, atof(e)) : 48.0;
         e = getenv("KFAC_SPLIT");
-        split = e ? (atoi(e) != 0) : 0;
+        split = e ? (atoi(e) != 0) : 1;
     }
 };
 

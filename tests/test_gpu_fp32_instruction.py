@@ -1,6 +1,7 @@
-"""The optional product mode of the GEMM (fp32 operands, products through three bf16 planes, KFAC_SPLIT=1):
-the parity cases of the statistics, the inversion, the preconditioning and the fused step once more under that
-mode, to the same tolerances, and a direct comparison of its error with that of the fp32 matrix instruction."""
+"""The two product modes of the fp32 GEMM.  The default forms every product from three bf16 planes per operand
+with six bf16 matrix instructions (all other GPU tests run in it); KFAC_SPLIT=0 selects the fp32 matrix
+instruction.  Here: the parity cases of the statistics, the inversion, the preconditioning and the fused step once
+more under KFAC_SPLIT=0, to the same tolerances, and a direct comparison of the two modes' errors."""
 import numpy as np
 import pytest
 import torch
@@ -13,8 +14,8 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.fixture(autouse=True)
-def split_mode(monkeypatch):
-    monkeypatch.setenv("KFAC_SPLIT", "1")      # read when a context is created
+def fp32_instruction_mode(monkeypatch):
+    monkeypatch.setenv("KFAC_SPLIT", "0")      # read when a context is created
 
 
 gpu = P.gpu
@@ -44,18 +45,26 @@ def test_products_are_as_accurate_as_the_fp32_instruction(gpu, monkeypatch):
     rng = np.random.default_rng(12)
     act = (rng.standard_normal((4096, 300)) * np.exp2(rng.integers(-12, 12, size=(4096, 300)))).astype(np.float32).reshape(4096, 300, 1, 1)
     grad = (rng.standard_normal((4096, 200)) * np.exp2(rng.integers(-20, -2, size=(4096, 200)))).astype(np.float32).reshape(4096, 200, 1, 1)
-    eA3, eG3 = _stats_error(layer, act, grad)
-    monkeypatch.setenv("KFAC_SPLIT", "0")
     eA1, eG1 = _stats_error(layer, act, grad)
+    monkeypatch.setenv("KFAC_SPLIT", "1")
+    eA3, eG3 = _stats_error(layer, act, grad)
     assert eA1 < 2e-6 and eG1 < 2e-6
     assert eA3 <= 2.0 * eA1 + 5e-7 and eG3 <= 2.0 * eG1 + 5e-7, (eA3, eA1, eG3, eG1)
 
 
-def test_profile_names_the_kernel(gpu):
+def _kernel_names():
     layer = wl.fc_layer(64, 300, 200)
     ctx = kfac.Context([layer])
     kfac.kfac_profile_enable(ctx, True)
-    A, G = P.run_stats([layer], [wl.make_act(layer, 1)], [wl.make_grad_out(layer, 1)], 0.0, False, ctx=ctx)
+    P.run_stats([layer], [wl.make_act(layer, 1)], [wl.make_grad_out(layer, 1)], 0.0, False, ctx=ctx)
     names = {e["kernel"] for e in kfac.kfac_profile_read(ctx)}
     ctx.close()
+    return names
+
+
+def test_profile_names_the_kernel_of_each_mode(gpu, monkeypatch):
+    names = _kernel_names()
+    assert "gemm_f32" in names and "gemm_f32_split" not in names
+    monkeypatch.delenv("KFAC_SPLIT")                      # the default
+    names = _kernel_names()
     assert "gemm_f32_split" in names and "gemm_f32" not in names
