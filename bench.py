@@ -543,7 +543,10 @@ def main():
             4: "full ResNet-50 layer set (53 conv + 1 FC + 53 BatchNorm), batch 32",
             5: "full ResNet-50 layer set, batch 128, inverses refreshed for a seeded 25% subset"}[cfg]),
             "layers": n, "bn_layers": len(Cs), "batch": N, "inverted_layers": len(subset),
-            "g_spatial_mean": bool(spatial_mean), "schedule": args.schedule},
+            "g_spatial_mean": bool(spatial_mean), "schedule": args.schedule,
+            "fp32_products": ("fp32 matrix instruction" if os.environ.get("KFAC_SPLIT", "1") == "0" else
+                              "six bf16 matrix instructions on operands split exactly into three bf16 planes, fp32 "
+                              "accumulation (fp32-level accuracy; KFAC_SPLIT=0 selects the fp32 matrix instruction)")},
         "algorithmic_gflop": {k: round(v / 1e9, 2) for k, v in fl.items()},
         "step_tflops": round(total_flops / (ms_per_step * 1e-3) / 1e12, 3),
         "factor_inverse_tflops": round(fi_flops / (fi_ms * 1e-3) / 1e12, 3),
