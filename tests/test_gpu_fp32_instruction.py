@@ -68,3 +68,27 @@ def test_profile_names_the_kernel_of_each_mode(gpu, monkeypatch):
     monkeypatch.delenv("KFAC_SPLIT")                      # the default
     names = _kernel_names()
     assert "gemm_f32_split" in names and "gemm_f32" not in names
+
+
+def test_cancelling_contraction_in_both_modes(gpu, monkeypatch):
+    """Sums whose terms cancel almost completely: the error is measured against sum |x_k y_k| (what fp32 accumulation
+    can promise), and must be of that size in both modes -- the split products drop only terms below 2^-23 |x y|."""
+    N, d = 2048, 96
+    layer = wl.fc_layer(N, d, d, bias=0)
+    rng = np.random.default_rng(31)
+    base = rng.standard_normal((N // 2, d)).astype(np.float32)
+    sign = np.where(rng.random((N // 2, d)) < 0.5, -1.0, 1.0).astype(np.float32)
+    # pairs of samples (a, b): columns either repeat or flip sign, so that A_ij = sum_n a_ni a_nj cancels for many (i, j)
+    act = np.concatenate([base, base * sign], axis=0).reshape(N, d, 1, 1)
+    act += (1e-4 * rng.standard_normal(act.shape)).astype(np.float32)
+    grad = (1e-3 * act[:, ::-1]).copy()
+    a64 = act.reshape(N, d).astype(np.float64)
+    scale = (np.abs(a64).T @ np.abs(a64)).max() / N
+    errs = {}
+    for mode in ("0", "1"):
+        monkeypatch.setenv("KFAC_SPLIT", mode)
+        A, G = P.run_stats([layer], [act], [grad], 0.0, False)
+        Ar, Gr = oracle.kfac_stats(tuple(layer), act, grad, 0.0, False, None, None)
+        errs[mode] = float(np.abs(P.host(A[0]) - Ar).max() / scale)
+    assert errs["0"] < 2e-6 and errs["1"] < 2e-6, errs
+    assert errs["1"] <= 2.0 * errs["0"] + 3e-7, errs
