@@ -107,7 +107,8 @@ hipError_t launch_pad(const PadJob *jobs_dev, int n_jobs, int total_wgs, hipStre
 // Which Gram matrices entry (c', ky', kx') comes from depends only on (ky, kx, ky', kx'): the
 // workgroup first builds that table of 9 entries.  A displacement that is stored the other way
 // round is read from the transposed copy the GEMM wrote alongside, so every read is along a
-// row of a Gram matrix and every write along the row of A.
+// row of a Gram matrix and every write along the row of A (the interleaving of the nine k'
+// goes through LDS).
 struct CorrSource {
     const float *full, *row, *col, *corner;   // row / col / corner: null if no such correction
     int ld_full, ld_row, ld_col;
@@ -170,17 +171,45 @@ __global__ __launch_bounds__(256) void assemble_kernel(const AssembleJob *__rest
     float *out_row = J.A + (long long)i * J.ldA;
     if (i < d0) {
         const int c = i / 9, k = i - 9 * c, ky = k / 3, kx = k - 3 * ky;
+        typedef float v4 __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte access, element alignment
         __shared__ CorrSource src[9];
+        __shared__ float vals[9][257];   // 256 channels c' at a time: [k'][c']
         if (threadIdx.x < 9) src[threadIdx.x] = corr_source(J, ky, kx, threadIdx.x / 3, threadIdx.x % 3);
         __syncthreads();
-        for (int j = threadIdx.x; j < d0; j += 256) {
-            const int cp = j / 9, kp = j - 9 * cp;
-            const CorrSource S = src[kp];
-            float v = S.full[(long long)c * S.ld_full + cp];
-            if (S.row) v -= S.row[(long long)c * S.ld_row + cp];
-            if (S.col) v -= S.col[(long long)c * S.ld_col + cp];
-            if (S.corner) v += S.corner[(long long)c * J.ld_corner + cp];
-            corr_store(J, out_row + j, v);
+        // Reads go along rows of the Gram matrices (consecutive threads, consecutive c'), writes along
+        // the row of A (consecutive threads, consecutive (c', k')); LDS does the interleaving.
+        for (int cp0 = 0; cp0 < J.C; cp0 += 256) {
+            const int cp = cp0 + threadIdx.x;
+            if (cp < J.C) {
+#pragma unroll
+                for (int kp = 0; kp < 9; ++kp) {
+                    const CorrSource S = src[kp];
+                    float v = S.full[(long long)c * S.ld_full + cp];
+                    if (S.row) v -= S.row[(long long)c * S.ld_row + cp];
+                    if (S.col) v -= S.col[(long long)c * S.ld_col + cp];
+                    if (S.corner) v += S.corner[(long long)c * J.ld_corner + cp];
+                    vals[kp][threadIdx.x] = v;
+                }
+            }
+            __syncthreads();
+            const int nout = 9 * min(256, J.C - cp0);
+            float *dst = out_row + 9 * cp0;
+            for (int e = 4 * threadIdx.x; e < nout; e += 1024) {
+                if (e + 3 < nout) {
+                    v4 r;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) r[q] = J.alpha * vals[(e + q) % 9][(e + q) / 9];
+                    if (J.beta != 0.f) {
+                        const v4 o = *(const v4 *)(dst + e);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) r[q] = fmaf(J.beta, o[q], r[q]);
+                    }
+                    *(v4 *)(dst + e) = r;
+                } else {
+                    for (int q = 0; e + q < nout; ++q) corr_store(J, dst + e + q, vals[(e + q) % 9][(e + q) / 9]);
+                }
+            }
+            __syncthreads();
         }
         if (J.bias && threadIdx.x == 0) corr_store(J, out_row + d0, corr_row_sum(J, c, ky, kx));
     } else {
