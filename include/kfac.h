@@ -142,7 +142,10 @@ kfac_status kfac_invert(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L,
  * Natural-gradient direction, Eq. 6 with F = G (x) A (Eq. 7) and Eq. 12, in
  * matrix form for W in R^{dG x dA} (row = output channel):
  *   out = G_inv * grad_W * A_inv .
- * grad_W[l], out[l]: dev [dG, dA]; out[l] may equal grad_W[l].
+ * G_inv[l]: dev [dG, dG], A_inv[l]: dev [dA, dA], both symmetric (as kfac_invert
+ * writes them; the products read them along rows, so a non-symmetric matrix
+ * would enter transposed).  grad_W[l], out[l]: dev [dG, dA]; out[l] may equal
+ * grad_W[l].
  */
 kfac_status kfac_precondition(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L,
                               const float *const *G_inv, const float *const *A_inv,
