@@ -1,14 +1,18 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
-(whole layer lists per call).
+(whole layer lists per call), element by element against the float64 oracle.
 
-Configuration 3 is small enough for the oracle to rebuild everything element by element.
-For the full ResNet-50 layer set (configurations 4 and 5) the oracle computes sampled
-factor entries one by one, and the inverses / preconditioned gradients are checked
-through properties that hold at any size, evaluated in float64 on the host:
-    (X + damp I) X_inv = I        (sampled columns),   X_inv symmetric,
-    U = G_inv dW A_inv            (sampled rows, from the GPU's own inverses),
-with pi and the dampings recomputed on the host from the factor traces.
+For every layer of configurations 3, 4 and 5 (and the three 3x3 / stride-2 layers that only
+the v1.5 variant of ResNet-50 has) the oracle rebuilds A and G from the same seeded inputs,
+inverts them with its own pi and dampings, and forms U from its own inverses; every element
+of the library's A, G (1e-4), A_inv, G_inv and U (1e-3, norm-wise) is compared with it, for
+the separate calls and for the fused step.  In configuration 5 the layers outside the
+refreshed subset hold a seeded symmetric stand-in for their stale inverses, which the oracle
+preconditions with as well.  The oracle's results for a configuration are computed once per
+test session (they do not depend on the schedule).
 """
+import sys
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -19,6 +23,7 @@ from paper_2002_06015_amd import kfac, workloads as wl
 pytestmark = pytest.mark.gpu
 
 TOL_FACTOR = 1e-4
+TOL_INVERSE = 1e-3
 TOL_PRECOND = 1e-3
 
 
@@ -40,9 +45,19 @@ def gpu():
     return torch.device("cuda")
 
 
-def _run_step(layers, config, in_dtype, invert_idx=None, decay=0.0, fused=False):
-    n = len(layers)
-    tdt = torch.bfloat16 if in_dtype == kfac.KFAC_BF16 else torch.float32
+@pytest.fixture
+def progress(request):
+    """Prints a line past pytest's capture: the oracle takes minutes on the large sets."""
+    capman = request.config.pluginmanager.getplugin("capturemanager")
+
+    def say(msg):
+        with capman.global_and_fixture_disabled():
+            sys.stdout.write("  [full-size] %s\n" % msg)
+            sys.stdout.flush()
+    return say
+
+
+def _inputs(layers, config, in_dtype):
     acts, grads, gws = [], [], []
     for i, L in enumerate(layers):
         s = wl.layer_seed(config, i)
@@ -52,6 +67,22 @@ def _run_step(layers, config, in_dtype, invert_idx=None, decay=0.0, fused=False)
         acts.append(a)
         grads.append(g)
         gws.append(wl.make_grad_W(L, s))
+    return acts, grads, gws
+
+
+def _stale_inverse(d, seed):
+    """A seeded symmetric stand-in for an inverse computed at an earlier step."""
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((d, d), dtype=np.float32)
+    X = (X + X.T) * np.float32(0.5 / np.sqrt(d))
+    X[np.arange(d), np.arange(d)] += np.float32(1.0)
+    return X
+
+
+def _run_step(layers, config, in_dtype, inputs, invert_idx=None, decay=0.0, fused=False):
+    n = len(layers)
+    tdt = torch.bfloat16 if in_dtype == kfac.KFAC_BF16 else torch.float32
+    acts, grads, gws = inputs
     d_act = [torch.from_numpy(a).cuda().to(tdt) for a in acts]
     d_grad = [torch.from_numpy(g).cuda().to(tdt) for g in grads]
     d_gw = [torch.from_numpy(g).cuda() for g in gws]
@@ -59,8 +90,16 @@ def _run_step(layers, config, in_dtype, invert_idx=None, decay=0.0, fused=False)
     ctx = kfac.Context(layers, in_dtype, extra_layer_lists=[[layers[i] for i in idx]])
     A = [torch.full((L.dA, L.dA), float("nan"), device="cuda") for L in layers]
     G = [torch.full((L.dG, L.dG), float("nan"), device="cuda") for L in layers]
-    Ai = [torch.zeros_like(x) for x in A]
-    Gi = [torch.zeros_like(x) for x in G]
+    stale = {}
+    Ai, Gi = [], []
+    for i, L in enumerate(layers):
+        if i in idx:
+            Ai.append(torch.zeros(L.dA, L.dA, device="cuda"))
+            Gi.append(torch.zeros(L.dG, L.dG, device="cuda"))
+        else:
+            stale[i] = (_stale_inverse(L.dA, 77_000 + i), _stale_inverse(L.dG, 78_000 + i))
+            Ai.append(torch.from_numpy(stale[i][0]).cuda())
+            Gi.append(torch.from_numpy(stale[i][1]).cuda())
     U = [torch.zeros(L.dG, L.dA, device="cuda") for L in layers]
     pi = torch.zeros(n, device="cuda")
     info = torch.zeros(2 * n, dtype=torch.int32, device="cuda")
@@ -75,91 +114,119 @@ def _run_step(layers, config, in_dtype, invert_idx=None, decay=0.0, fused=False)
     else:
         kfac.kfac_stats(ctx, layers, in_dtype, d_act, d_grad, decay, True, A, G)
         kfac.kfac_invert(ctx, sel(layers), sel(A), sel(G), wl.GAMMA, sel(Ai), sel(Gi), pi, info)
-        kfac.kfac_precondition(ctx, sel(layers), sel(Gi), sel(Ai), sel(d_gw), sel(U))
+        kfac.kfac_precondition(ctx, layers, Gi, Ai, d_gw, U)
         torch.cuda.synchronize()
-        pi_h = host(pi)
+        pi_h = host(pi)[:len(idx)]
     ctx.close()
     assert not info.cpu().numpy().any()
-    return dict(acts=acts, grads=grads, gws=gws, A=A, G=G, Ai=Ai, Gi=Gi, U=U, pi=pi_h, idx=idx)
+    return dict(A=A, G=G, Ai=Ai, Gi=Gi, U=U, pi=pi_h, idx=idx, stale=stale)
+
+
+# oracle results per (config, dtype): computed once, shared by the staged and the fused run
+_ORACLE = {}
+
+
+def _oracle_set(key, layers, inputs, idx, progress):
+    """Per layer: (A, G, A_inv, G_inv, pi) from the oracle; the inverses only for layers in idx."""
+    if key in _ORACLE:
+        return _ORACLE[key]
+    acts, grads, _ = inputs
+    out = []
+    t0 = time.time()
+    for i, L in enumerate(layers):
+        Ar, Gr = oracle.kfac_stats(tuple(L), acts[i], grads[i], 0.0, True, None, None)
+        Air = Gir = pir = None
+        if i in idx:
+            Air, Gir, pir, info = oracle.kfac_invert(Ar, Gr, wl.GAMMA)
+            assert not info.any()
+        out.append((Ar, Gr, Air, Gir, pir))
+        progress("oracle %s layer %d/%d (dA %d, dG %d, M %d) at %.0f s" % (key, i + 1, len(layers), L.dA, L.dG, L.M,
+                                                                         time.time() - t0))
+    _ORACLE[key] = out
+    return out
+
+
+def _compare_all(layers, r, ref, inputs, progress):
+    worst = {"A": 0.0, "G": 0.0, "A_inv": 0.0, "G_inv": 0.0, "pi": 0.0, "U": 0.0}
+    gws = inputs[2]
+    for i, L in enumerate(layers):
+        Ar, Gr, Air, Gir, pir = ref[i]
+        hA, hG = host(r["A"][i]), host(r["G"][i])
+        assert np.array_equal(hA, hA.T) and np.array_equal(hG, hG.T)
+        worst["A"] = max(worst["A"], relerr(hA, Ar))
+        worst["G"] = max(worst["G"], relerr(hG, Gr))
+        hAi, hGi = host(r["Ai"][i]), host(r["Gi"][i])
+        if i in r["idx"]:
+            assert np.array_equal(hAi, hAi.T) and np.array_equal(hGi, hGi.T)
+            worst["A_inv"] = max(worst["A_inv"], relerr(hAi, Air))
+            worst["G_inv"] = max(worst["G_inv"], relerr(hGi, Gir))
+            worst["pi"] = max(worst["pi"], abs(r["pi"][r["idx"].index(i)] - pir) / pir)
+        else:
+            # not refreshed: the stale inverses are untouched, and they are what U is formed with
+            Air, Gir = r["stale"][i]
+            assert np.array_equal(hAi, Air.astype(np.float64)) and np.array_equal(hGi, Gir.astype(np.float64))
+        Ur = oracle.kfac_precondition(Gir, Air, gws[i])
+        worst["U"] = max(worst["U"], relerr(host(r["U"][i]), Ur))
+    progress("worst norm-wise errors: %s" % {k: "%.2e" % v for k, v in worst.items()})
+    assert worst["A"] <= TOL_FACTOR and worst["G"] <= TOL_FACTOR, worst
+    assert worst["A_inv"] <= TOL_INVERSE and worst["G_inv"] <= TOL_INVERSE and worst["pi"] <= 1e-4, worst
+    assert worst["U"] <= TOL_PRECOND, worst
 
 
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("in_dtype", [kfac.KFAC_F32, kfac.KFAC_BF16])
-def test_config3_element_by_element(gpu, in_dtype):
+def test_config3_element_by_element(gpu, progress, in_dtype):
     """Largest 3x3 layer (A 4609x4609 through the blocked inversion, G 512x512) and the
     FC layer (A 2049x2049, G 1000x1000), everything rebuilt by the oracle (on the
     bf16-rounded inputs for the bf16 variant)."""
     layers = wl.config_layers(3)
-    r = _run_step(layers, 3, in_dtype)
-    for i, L in enumerate(layers):
-        Ar, Gr = oracle.kfac_stats(tuple(L), r["acts"][i], r["grads"][i], 0.0, True, None, None)
-        assert relerr(host(r["A"][i]), Ar) <= TOL_FACTOR
-        assert relerr(host(r["G"][i]), Gr) <= TOL_FACTOR
-        Air, Gir, pir, _ = oracle.kfac_invert(Ar, Gr, wl.GAMMA)
-        assert abs(r["pi"][i] - pir) <= 1e-4 * pir
-        assert relerr(host(r["Ai"][i]), Air) <= TOL_PRECOND
-        assert relerr(host(r["Gi"][i]), Gir) <= TOL_PRECOND
-        Ur = oracle.kfac_precondition(Gir, Air, r["gws"][i])
-        assert relerr(host(r["U"][i]), Ur) <= TOL_PRECOND
-
-
-def _check_sampled(layers, r, rng, check_layers, n_pairs=48, n_cols=24):
-    worst = {"A": 0.0, "G": 0.0, "inv": 0.0, "U": 0.0}
-    for i in check_layers:
-        L = layers[i]
-        hA, hG = host(r["A"][i]), host(r["G"][i])
-        assert np.array_equal(hA, hA.T) and np.array_equal(hG, hG.T)
-        # sampled factor entries (always including the bias corner and a diagonal entry)
-        I = np.concatenate([rng.integers(0, L.dA, n_pairs), [L.dA - 1, L.dA - 1, 0]])
-        J = np.concatenate([rng.integers(0, L.dA, n_pairs), [L.dA - 1, 0, 0]])
-        ref = oracle.factor_A_entries(tuple(L), r["acts"][i], I, J)
-        worst["A"] = max(worst["A"], float(np.abs(hA[I, J] - ref).max() / np.abs(hA).max()))
-        I = rng.integers(0, L.dG, n_pairs)
-        J = np.where(rng.random(n_pairs) < 0.5, I, rng.integers(0, L.dG, n_pairs))
-        ref = oracle.factor_G_entries(tuple(L), r["grads"][i], I, J, True)
-        worst["G"] = max(worst["G"], float(np.abs(hG[I, J] - ref).max() / np.abs(hG).max()))
-        if i not in r["idx"]:
-            continue
-        # damping recomputed on the host; defining property of the inverses on sampled columns
-        pi = np.sqrt((np.trace(hA) / L.dA) / (np.trace(hG) / L.dG))
-        assert abs(r["pi"][r["idx"].index(i)] - pi) <= 1e-4 * pi
-        for X, Xi, damp in ((hA, host(r["Ai"][i]), pi * wl.GAMMA), (hG, host(r["Gi"][i]), wl.GAMMA / pi)):
-            assert np.array_equal(Xi, Xi.T)
-            cols = rng.integers(0, X.shape[0], n_cols)
-            R = X @ Xi[:, cols] + damp * Xi[:, cols]
-            R[cols, np.arange(n_cols)] -= 1.0
-            worst["inv"] = max(worst["inv"], float(np.abs(R).max()))
-        rows = rng.integers(0, L.dG, min(8, L.dG))
-        Uref = host(r["Gi"][i])[rows] @ r["gws"][i].astype(np.float64) @ host(r["Ai"][i])
-        worst["U"] = max(worst["U"], relerr(host(r["U"][i])[rows], Uref))
-    return worst
-
-
-@pytest.mark.timeout(600)
-@pytest.mark.parametrize("fused", [False, True])
-def test_config4_full_resnet50_set_sampled(gpu, fused):
-    layers = wl.config_layers(4)
-    r = _run_step(layers, 4, kfac.KFAC_F32, fused=fused)
-    rng = np.random.default_rng(4)
-    worst = _check_sampled(layers, r, rng, range(len(layers)))
-    assert worst["A"] <= TOL_FACTOR and worst["G"] <= TOL_FACTOR, worst
-    assert worst["inv"] <= 1e-3 and worst["U"] <= TOL_PRECOND, worst
+    inputs = _inputs(layers, 3, in_dtype)
+    r = _run_step(layers, 3, in_dtype, inputs)
+    ref = _oracle_set(("config3", in_dtype), layers, inputs, r["idx"], progress)
+    _compare_all(layers, r, ref, inputs, progress)
+    del _ORACLE[("config3", in_dtype)]
 
 
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("fused", [False, True])
-def test_config5_batch128_stale_subset_sampled(gpu, fused):
-    """Batch 128, statistics for every layer, inverses only for the seeded 25 % subset.
-    Sampled checks on the subset plus a few of the largest layers."""
+def test_config4_full_resnet50_set_element_by_element(gpu, progress, fused):
+    """All 54 layers of ResNet-50 at batch 32: every element of A, G, A_inv, G_inv and U
+    against the oracle, for the separate calls and for the fused step."""
+    layers = wl.config_layers(4)
+    inputs = _inputs(layers, 4, kfac.KFAC_F32)
+    r = _run_step(layers, 4, kfac.KFAC_F32, inputs, fused=fused)
+    ref = _oracle_set("config4", layers, inputs, r["idx"], progress)
+    _compare_all(layers, r, ref, inputs, progress)
+    if fused:
+        del _ORACLE["config4"]
+
+
+@pytest.mark.timeout(1500)
+@pytest.mark.parametrize("fused", [False, True])
+def test_config5_batch128_stale_subset_element_by_element(gpu, progress, fused):
+    """Batch 128, statistics for every layer, inverses only for the seeded 25 % subset
+    (Algorithm 1); the other layers are preconditioned with the inverses their buffers hold."""
     layers = wl.config_layers(5)
     subset = [int(i) for i in wl.stale_subset(len(layers), seed=0)]
-    r = _run_step(layers, 5, kfac.KFAC_F32, invert_idx=subset, fused=fused)
-    rng = np.random.default_rng(5)
-    check = sorted(set(subset) | {0, 2, 46, 53})
-    worst = _check_sampled(layers, r, rng, check, n_pairs=24, n_cols=16)
-    assert worst["A"] <= TOL_FACTOR and worst["G"] <= TOL_FACTOR, worst
-    assert worst["inv"] <= 1e-3 and worst["U"] <= TOL_PRECOND, worst
-    # layers outside the subset keep whatever inverse they had (zeros here): untouched
-    for i in range(len(layers)):
-        if i not in subset:
-            assert not bool(r["Ai"][i].any().item())
+    inputs = _inputs(layers, 5, kfac.KFAC_F32)
+    r = _run_step(layers, 5, kfac.KFAC_F32, inputs, invert_idx=subset, fused=fused)
+    ref = _oracle_set("config5", layers, inputs, subset, progress)
+    _compare_all(layers, r, ref, inputs, progress)
+    if fused:
+        del _ORACLE["config5"]
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("in_dtype", [kfac.KFAC_F32, kfac.KFAC_BF16])
+def test_v1_5_stride2_3x3_layers_element_by_element(gpu, progress, in_dtype):
+    """The layers only the v1.5 variant has: 3x3 / stride 2 at 56 -> 28, 28 -> 14 and 14 -> 7
+    (patch path with a contraction up to 25 088 long), at batch 32."""
+    all_layers = wl.resnet50_layers(32, "v1.5")[0]
+    layers = [L for L in all_layers if L.k == 3 and L.stride == 2]
+    assert [(L.c_in, L.h_in, L.h) for L in layers] == [(128, 56, 28), (256, 28, 14), (512, 14, 7)]
+    inputs = _inputs(layers, 6, in_dtype)
+    for fused in (False, True):
+        r = _run_step(layers, 6, in_dtype, inputs, fused=fused)
+        ref = _oracle_set(("v1.5", in_dtype), layers, inputs, r["idx"], progress)
+        _compare_all(layers, r, ref, inputs, progress)
+    del _ORACLE[("v1.5", in_dtype)]
