@@ -242,6 +242,25 @@ kfac_status kfac_staleness(kfac_ctx *ctx, int32_t n, const int32_t *dims, const 
                            const float *const *X_m1, const float *const *X_m2, double *ratios);
 
 /*
+ * kfac_staleness for callers that cannot allocate: code under HIP graph capture, tight
+ * serving or training loops, harnesses that forbid hipMalloc.  Same arguments, same results
+ * (the same kernels' arithmetic in the same order), but no context and no workspace: the
+ * per-chunk sums go to a fixed 512 KiB device array inside the library (one copy per GPU,
+ * held until the process ends) and the job table travels in the kernel arguments.  The call
+ * allocates nothing (no hipMalloc / hipFree / hipHostMalloc, no events or streams); work is
+ * enqueued on `hip_stream` (hipStream_t as void*, NULL = the default stream) of the current
+ * device and the call returns without waiting.
+ * Limit: one matrix may have at most 2^26 elements (dims[i] <= 8192); a larger one gives
+ * KFAC_ERR_WORKSPACE before anything is launched.  Any number of matrices: they are
+ * processed in successive launches that reuse the array in stream order.
+ * All calls on one GPU share that GPU's array: two calls that may run at the same time on
+ * one GPU (different streams, different host threads) race on it and must be ordered by the
+ * caller.  Nothing in the array has to start at zero (every sum is written before it is read).
+ */
+kfac_status kfac_staleness_static(void *hip_stream, int32_t n, const int32_t *dims, const float *const *X,
+                                  const float *const *X_m1, const float *const *X_m2, double *ratios);
+
+/*
  * Learning rate and momentum schedules, Sec. 6.2 (host only, no GPU work):
  *   kfac_lr_polynomial:    eta(e) = eta0 (1 - (e - e_start) / (e_end - e_start))^p_decay  for
  *                          e_start <= e <= e_end; eta0 before e_start, 0 after e_end

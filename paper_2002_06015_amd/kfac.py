@@ -25,7 +25,7 @@ EXPORTS = [
     "kfac_packed_elems", "kfac_pack_upper", "kfac_unpack_upper",
     "kfac_lr_polynomial", "kfac_momentum_coupled", "kfac_update_weights",
     "bn_full_workspace_bytes", "bn_full_precondition", "kfac_nhwc_to_nchw",
-    "kfac_staleness", "kfac_next_interval", "kfac_refresh_init", "kfac_refresh_due", "kfac_refresh_advance",
+    "kfac_staleness", "kfac_staleness_static", "kfac_next_interval", "kfac_refresh_init", "kfac_refresh_due", "kfac_refresh_advance",
 ]
 
 KERNEL_NAMES = ["gemm_f32", "gemm_bf16", "gemm_reduce", "patch", "trace", "copy_damp", "leaf_inverse", "zero",
@@ -93,6 +93,7 @@ def lib() -> ctypes.CDLL:
         L.kfac_pack_upper.argtypes = [vp, i32, vp, vp, ctypes.c_int, vp]
         L.kfac_unpack_upper.argtypes = [vp, i32, vp, ctypes.c_int, vp, vp]
         L.kfac_staleness.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+        L.kfac_staleness_static.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         L.kfac_next_interval.restype = i32
         L.kfac_next_interval.argtypes = [i32, i32, i32, i32]
         L.kfac_refresh_init.restype = None
@@ -387,6 +388,21 @@ def kfac_staleness(ctx: Context, dims: Sequence[int], X, X_m1, X_m2, ratios: tor
                               ratios.data_ptr())
     if st != KFAC_OK:
         raise KfacError(st, "kfac_staleness")
+
+
+def kfac_staleness_static(stream: Optional[torch.cuda.Stream], dims: Sequence[int], X, X_m1, X_m2,
+                          ratios: torch.Tensor) -> None:
+    """kfac_staleness without a context: scratch in the library's fixed device array, nothing allocated."""
+    n = len(dims)
+    ds = _i32(dims)
+    ps = [_ptrs(x, n, torch.float32) for x in (X, X_m1, X_m2)]
+    if not (ratios.is_cuda and ratios.is_contiguous() and ratios.dtype == torch.float64 and ratios.numel() >= 2 * n):
+        raise ValueError("ratios must be a contiguous device float64 tensor of at least 2 n elements")
+    s = stream if stream is not None else torch.cuda.current_stream()
+    st = lib().kfac_staleness_static(ctypes.c_void_p(s.cuda_stream), n, ctypes.addressof(ds),
+                                     *[p and ctypes.addressof(p) for p in ps], ratios.data_ptr())
+    if st != KFAC_OK:
+        raise KfacError(st, "kfac_staleness_static")
 
 
 class kfac_refresh_state(ctypes.Structure):
