@@ -75,23 +75,36 @@ __device__ __forceinline__ void store_slab(const GemmProblem &P, const float *T,
     constexpr int LDT = COLS + 1;
     const bool sym = (P.flags & GEMM_SYM) != 0;
     const float alpha = P.alpha, beta = P.beta;
+    // The old values (beta != 0) of all rows of a pass are requested before the first store of
+    // the pass: a load issued behind a store to the same matrix waits for it, and a pass of
+    // load - store pairs then costs one memory round trip per row.
     // direct pass: a thread owns 4 adjacent columns of one row
     {
-        constexpr int TPR = COLS / 4, RPP = 256 / TPR;
+        constexpr int TPR = COLS / 4, RPP = 256 / TPR, NIT = (ROWS + RPP - 1) / RPP;
         const int c = (tid % TPR) * 4, rr = tid / TPR;
-        for (int r = rr; r < ROWS; r += RPP) {
-            const int i = gi0 + r, j = gj0 + c;
-            if (i >= P.M || j >= P.N) continue;
+        const int j = gj0 + c;
+        floatx4 old[NIT];
+        if (beta != 0.0f) {
+#pragma unroll
+            for (int q = 0; q < NIT; ++q) {
+                const int r = rr + q * RPP, i = gi0 + r;
+                const int jmax = min(diag_tile ? i : P.N - 1, P.N - 1);
+                old[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (r < ROWS && i < P.M && j + 3 <= jmax) old[q] = *(const floatx4_st *)(P.C + (long long)i * P.ldc + j);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < NIT; ++q) {
+            const int r = rr + q * RPP, i = gi0 + r;
+            if (r >= ROWS || i >= P.M || j >= P.N) continue;
             const int jmax = min(diag_tile ? i : P.N - 1, P.N - 1);   // last column this row may write
             if (j > jmax) continue;
             float *dst = P.C + (long long)i * P.ldc + j;
             const float *t = T + r * LDT + c;
             if (j + 3 <= jmax) {
                 floatx4 v = {alpha * t[0], alpha * t[1], alpha * t[2], alpha * t[3]};
-                if (beta != 0.0f) {
-                    const floatx4 o = *(const floatx4_st *)dst;
-                    for (int e = 0; e < 4; ++e) v[e] = fmaf(beta, o[e], v[e]);   // same rounding in every path
-                }
+                if (beta != 0.0f)
+                    for (int e = 0; e < 4; ++e) v[e] = fmaf(beta, old[q][e], v[e]);   // same rounding in every path
                 *(floatx4_st *)dst = v;
             } else {
                 for (int e = 0; e < 4 && j + e <= jmax; ++e) {
@@ -108,11 +121,23 @@ __device__ __forceinline__ void store_slab(const GemmProblem &P, const float *T,
     if (mbase) {
         const long long ldm = sym ? P.ldc : P.ldct;
         const float mbeta = sym ? beta : 0.0f;
-        constexpr int TPR = ROWS / 4, RPP = 256 / TPR;
+        constexpr int TPR = ROWS / 4, RPP = 256 / TPR, NIT = (COLS + RPP - 1) / RPP;
         const int r = (tid % TPR) * 4, cc = tid / TPR;
-        for (int c = cc; c < COLS; c += RPP) {
-            const int i = gi0 + r, j = gj0 + c;
-            if (i >= P.M || j >= P.N) continue;
+        const int i = gi0 + r;
+        floatx4 old[NIT];
+        if (mbeta != 0.0f) {
+#pragma unroll
+            for (int q = 0; q < NIT; ++q) {
+                const int c = cc + q * RPP, j = gj0 + c;
+                const int e0 = (sym && diag_tile) ? max(0, j + 1 - i) : 0;
+                old[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (c < COLS && j < P.N && e0 == 0 && i + 4 <= P.M) old[q] = *(const floatx4_st *)(mbase + (long long)j * ldm + i);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < NIT; ++q) {
+            const int c = cc + q * RPP, j = gj0 + c;
+            if (c >= COLS || i >= P.M || j >= P.N) continue;
             // rows i..i+3 that may be mirrored: i + e < M and, on a diagonal tile, j < i + e
             const int e0 = (sym && diag_tile) ? max(0, j + 1 - i) : 0;
             const int e1 = min(4, P.M - i);
@@ -121,10 +146,8 @@ __device__ __forceinline__ void store_slab(const GemmProblem &P, const float *T,
             const float *t = T + r * LDT + c;
             if (e0 == 0 && e1 == 4) {
                 floatx4 v = {alpha * t[0], alpha * t[LDT], alpha * t[2 * LDT], alpha * t[3 * LDT]};
-                if (mbeta != 0.0f) {
-                    const floatx4 o = *(const floatx4_st *)dst;
-                    for (int e = 0; e < 4; ++e) v[e] = fmaf(mbeta, o[e], v[e]);
-                }
+                if (mbeta != 0.0f)
+                    for (int e = 0; e < 4; ++e) v[e] = fmaf(mbeta, old[q][e], v[e]);
                 *(floatx4_st *)dst = v;
             } else {
                 for (int e = e0; e < e1; ++e) {
