@@ -13,10 +13,13 @@
  *   - Every entry point that takes a layer list processes all listed layers in
  *     a few grouped launches; per-layer device pointers are passed as HOST
  *     arrays of device pointers.
- *   - All work is enqueued on the HIP stream given to kfac_create; calls return
- *     without waiting for the GPU.  A context is used by one host thread at a time.
+ *   - All work is enqueued on the HIP stream given to kfac_create (internal streams
+ *     are joined into it before a call returns); calls return without waiting for
+ *     their own work (see kfac_create for the bounded run-ahead of the host).  A
+ *     context is used by one host thread at a time.
  *   - The library allocates no device memory: scratch comes from the caller's
- *     workspace (size from kfac_workspace_bytes for the same layer list).
+ *     workspace (size from kfac_workspace_bytes for the same layer list).  What
+ *     kfac_create allocates besides is listed there.
  *   - Matrices are dense, row-major, leading dimension = number of columns.
  *     Factors and inverses are stored in full (both triangles, exactly symmetric).
  *   - Argument errors are found before anything is launched and leave all
@@ -27,9 +30,12 @@
  *     products of the inversion, preconditioning): fp32 accumulation of products
  *     that are exact to fp32 rounding.  By default an fp32 operand is split
  *     exactly into three bf16 planes and each block product is formed by six bf16
- *     matrix instructions (every term above 2^-23 of the product kept); with
- *     KFAC_SPLIT=0 in the environment when the context is created the fp32
- *     matrix instruction is used instead.  Results of the two agree to fp32
+ *     matrix instructions (every term above 2^-23 of the product kept); a context
+ *     created with kfac_options.fp32_products = KFAC_PRODUCTS_FP32_MFMA uses the
+ *     fp32 matrix instruction instead.  Range of the default mode: operands of
+ *     magnitude 2^-110 and above keep every bit; smaller ones lose low bits step by
+ *     step (2^-120: about 4e-5 relative) and fp32 subnormals are lost; an infinite
+ *     operand gives NaN where the fp32 instruction gives infinity.  Results of the two agree to fp32
  *     rounding of the accumulation.  bf16 operands (kfac_dtype KFAC_BF16) are
  *     multiplied as they are.
  */
@@ -74,6 +80,36 @@ typedef struct {
 
 typedef struct kfac_ctx kfac_ctx;
 
+/*
+ * How the fp32 contractions are formed and how a context schedules its launches.  None of
+ * this changes what is computed (results of different settings agree to fp32 rounding of the
+ * accumulations).  kfac_options_default fills in the defaults; a NULL options pointer means
+ * the defaults.  The library reads no environment variables and keeps no state outside a context.
+ */
+typedef enum {
+    KFAC_PRODUCTS_SPLIT_BF16 = 0, /* fp32 operands split exactly into three bf16 planes, six bf16 matrix
+                                     instructions per block product, fp32 accumulation (default) */
+    KFAC_PRODUCTS_FP32_MFMA = 1   /* the fp32 matrix instruction */
+} kfac_products;
+
+typedef struct {
+    int32_t struct_size;          /* sizeof(kfac_options); any other value is rejected */
+    int32_t fp32_products;        /* kfac_products */
+    int32_t streams;              /* 1..4: HIP streams a call may use at once (the context's + internal ones); 4 */
+    int32_t staging_slots;        /* 2..8: calls the host may run ahead of the device; 2 */
+    int32_t correlation_form;     /* A factor of 3x3 / stride 1 / pad 1 layers from displaced image correlations; 1 */
+    int32_t pipeline_phases;      /* kfac_step: factor phases spread over the streams; 1 */
+    int32_t early_n;              /* kfac_step: layers with a factor at least this large are built and inverted first; 2048 */
+    int32_t target_workgroups;    /* split along K until a product has this many workgroups; 128 */
+    int32_t min_k_per_split;      /* ... but no part shorter than this; 512 */
+    int32_t max_k_per_workgroup;  /* ... and none longer than this; 4096 */
+    int32_t recursion_leaf;       /* 32..288: the blocked inversion recurses down to blocks of this size; 288 */
+    int32_t force_tile;           /* 0: chosen per product; 64 / 128: every product with that tile */
+    float chunk_gflop;            /* kfac_step: factor launches beside long inversion chains in parts of this size; 48 */
+} kfac_options;
+
+void kfac_options_default(kfac_options *opt);
+
 const char *kfac_status_string(kfac_status s);
 
 /* Validates a layer and returns its derived sizes (any out pointer may be NULL). Host only. */
@@ -84,13 +120,38 @@ kfac_status kfac_layer_dims(const kfac_layer *L, int32_t *dA, int32_t *dG, int32
  * L[0..n_layers) with inputs of type `in`.  Returns 0 on invalid arguments.  Host only.
  */
 size_t kfac_workspace_bytes(const kfac_layer *L, int32_t n_layers, kfac_dtype in);
+/* The same for a context that will be created with `opt` (the options change the scratch layout). */
+size_t kfac_workspace_bytes_opt(const kfac_layer *L, int32_t n_layers, kfac_dtype in, const kfac_options *opt);
+
+/*
+ * Exactly what one kfac_step call with this invert_mask (host uint8 [n_layers] or NULL = all)
+ * takes from the workspace.  kfac_workspace_bytes is sized for the separate calls exactly and
+ * for kfac_step with a margin over every mask tried (the scratch of a masked plan varies by a
+ * few percent with the mask); a caller that changes the mask from step to step (Algorithm 1)
+ * can check a mask here.  Every call checks its own plan and returns KFAC_ERR_WORKSPACE before
+ * launching anything if the workspace is too small.  Host only; 0 on invalid arguments.
+ */
+size_t kfac_step_workspace_bytes(const kfac_layer *L, int32_t n_layers, kfac_dtype in, const uint8_t *invert_mask,
+                                 const kfac_options *opt);
 
 /*
  * Creates a context bound to a HIP stream (hipStream_t passed as void*, NULL =
- * the default stream) and a caller-owned device workspace (256-byte aligned).
- * Touches no GPU state until the first launch.
+ * the default stream) and a caller-owned device workspace (256-byte aligned), on the
+ * current device.  kfac_create also creates what the context needs beyond the workspace:
+ * three internal streams (default priority), the events that order them, and a ring of
+ * `staging_slots` pinned host buffers of 1 MiB through which a call's tables (its layer
+ * list turned into kernel arguments) reach the device.  Nothing is allocated after that,
+ * with one exception: a call whose tables exceed 1 MiB (layer lists of several thousand
+ * layers) re-allocates its staging buffer.  On a machine without a GPU the context is
+ * created without these (argument validation needs none).
+ * Host blocking: a call enqueues its work and returns, but it first waits until the device
+ * has started the call made `staging_slots` calls earlier on this context (its staging
+ * buffer is reused); with the default of 2 the host runs at most two calls ahead.
+ * kfac_create_opt: the same with explicit options (NULL = defaults).
  */
 kfac_status kfac_create(kfac_ctx **out, void *hip_stream, void *workspace_dev, size_t workspace_bytes);
+kfac_status kfac_create_opt(kfac_ctx **out, void *hip_stream, void *workspace_dev, size_t workspace_bytes,
+                            const kfac_options *opt);
 void kfac_destroy(kfac_ctx *ctx);
 
 /*

@@ -42,32 +42,56 @@ struct Tunables {
                          // GFLOP (0: whole)
     int split;           // 1 (default): fp32 products through three bf16 planes and six bf16 matrix instructions
                          // (fp32 accuracy at the bf16 unit's rate); 0: the fp32 matrix instruction
-    Tunables()
+    int force_tile;      // 0: the planner chooses; 64 / 128: every product with that tile
+    explicit Tunables(const kfac_options &o)
     {
-        const char *e = getenv("KFAC_TARGET_WGS");
-        target_wgs = e ? std::max(1, atoi(e)) : 128;
-        e = getenv("KFAC_MIN_K_SPLIT");
-        min_k_per_split = e ? std::max(32, atoi(e) / 32 * 32) : 512;
-        e = getenv("KFAC_MAX_K_PER_WG");
-        max_k_per_wg = e ? std::max(32, atoi(e) / 32 * 32) : 4096;
-        e = getenv("KFAC_INV_STREAMS");
-        inv_streams = e ? std::min(4, std::max(1, atoi(e))) : 4;
-        e = getenv("KFAC_REC_LEAF");
-        rec_leaf = e ? std::min(kLeafMax, std::max(32, atoi(e))) : 288;
-        e = getenv("KFAC_EARLY_N");
-        early_n = e ? std::max(1, atoi(e)) : 2048;
-        e = getenv("KFAC_CORR");
-        corr = e ? (atoi(e) != 0) : 1;
-        e = getenv("KFAC_STAGING_SLOTS");
-        slots = e ? std::min(kSlots, std::max(2, atoi(e))) : 2;
-        e = getenv("KFAC_PIPE");
-        pipe = e ? (atoi(e) != 0) : 1;
-        e = getenv("KFAC_CHUNK_GF");
-        chunk_gf = e ? std::max(0.0, atof(e)) : 48.0;
-        e = getenv("KFAC_SPLIT");
-        split = e ? (atoi(e) != 0) : 1;
+        target_wgs = std::max(1, o.target_workgroups);
+        min_k_per_split = std::max(32, o.min_k_per_split / 32 * 32);
+        max_k_per_wg = std::max(32, o.max_k_per_workgroup / 32 * 32);
+        inv_streams = std::min(4, std::max(1, o.streams));
+        rec_leaf = std::min(kLeafMax, std::max(32, o.recursion_leaf));
+        early_n = std::max(1, o.early_n);
+        corr = o.correlation_form != 0;
+        slots = std::min(kSlots, std::max(2, o.staging_slots));
+        pipe = o.pipeline_phases != 0;
+        chunk_gf = std::max(0.0f, o.chunk_gflop);
+        split = o.fp32_products == KFAC_PRODUCTS_FP32_MFMA ? 0 : 1;
+        force_tile = (o.force_tile == 64 || o.force_tile == 128) ? o.force_tile : 0;
     }
 };
+
+kfac_options default_options()
+{
+    kfac_options o;
+    memset(&o, 0, sizeof(o));
+    o.struct_size = (int32_t)sizeof(kfac_options);
+    o.fp32_products = KFAC_PRODUCTS_SPLIT_BF16;
+    o.streams = 4;
+    o.staging_slots = 2;
+    o.correlation_form = 1;
+    o.pipeline_phases = 1;
+    o.early_n = 2048;
+    o.target_workgroups = 128;
+    o.min_k_per_split = 512;
+    o.max_k_per_workgroup = 4096;
+    o.recursion_leaf = 288;
+    o.chunk_gflop = 48.0f;
+    o.force_tile = 0;
+    return o;
+}
+
+bool options_ok(const kfac_options *o)
+{
+    if (!o) return true;
+    if (o->struct_size != (int32_t)sizeof(kfac_options)) return false;
+    if (o->fp32_products != KFAC_PRODUCTS_SPLIT_BF16 && o->fp32_products != KFAC_PRODUCTS_FP32_MFMA) return false;
+    if (o->streams < 1 || o->streams > 4 || o->staging_slots < 2 || o->staging_slots > kSlots) return false;
+    if (o->early_n < 1 || o->target_workgroups < 1 || o->min_k_per_split < 32 || o->max_k_per_workgroup < 32) return false;
+    if (o->recursion_leaf < 32 || o->recursion_leaf > kLeafMax) return false;
+    if (!(o->chunk_gflop >= 0.0f) || !std::isfinite(o->chunk_gflop)) return false;
+    if (o->force_tile != 0 && o->force_tile != 64 && o->force_tile != 128) return false;
+    return true;
+}
 
 }  // namespace
 
@@ -79,13 +103,13 @@ struct kfac_ctx {
     char *pinned[kSlots];
     size_t pinned_bytes[kSlots];
     hipEvent_t ev[kSlots];
-    bool ev_valid[kSlots];
+    bool ev_used[kSlots];
     int next_slot;
-    Tunables tun;
+    Tunables tun{default_options()};
     // auxiliary streams (default priority) for independent chains of launches inside one call
     hipStream_t aux[3];
     hipEvent_t sync_ev[kSyncEvents];
-    bool aux_valid;
+    bool resources_ready;
     // optional per-launch timing
     bool profiling;
     std::vector<hipEvent_t> ev_pool;      // pairs: [2i] start, [2i+1] stop
@@ -238,9 +262,8 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
     }
     for (auto &P : probs) {
         const bool sym = (P.flags & GEMM_SYM) != 0;
-        static const char *force = getenv("KFAC_FORCE_TILE");
-        if (force && *force) {
-            P.tile_cfg = atoi(force) == 64 ? 1 : 0;
+        if (tun.force_tile) {
+            P.tile_cfg = tun.force_tile == 64 ? 1 : 0;
         } else if (tile_steps128 >= 512.0 * 64) {   // every workgroup slot of the GPU busy for 64 steps
             auto work = [&](int B) {
                 const double tm = (P.M + B - 1) / B, tn = (P.N + B - 1) / B;
@@ -1169,23 +1192,46 @@ void plan_step(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &s
 }
 
 // ---------------------------------------------------------------- execution
+constexpr size_t kPinnedSlotBytes = (size_t)1 << 20;   // table space per staging slot allocated up front
+
+// Internal streams, the events that order them, and the pinned staging ring with its events.
+// Called from kfac_create when a device is present, so that no call allocates anything later
+// (except a call whose tables outgrow a staging slot); otherwise from the first call that launches.
+kfac_status prepare_resources(kfac_ctx *ctx)
+{
+    if (ctx->resources_ready) return KFAC_OK;
+    for (int q = 0; q < 3; ++q)
+        if (!ctx->aux[q] && hipStreamCreateWithFlags(&ctx->aux[q], hipStreamNonBlocking) != hipSuccess) return KFAC_ERR_DEVICE;
+    for (int q = 0; q < kSyncEvents; ++q)
+        if (!ctx->sync_ev[q] && hipEventCreateWithFlags(&ctx->sync_ev[q], hipEventDisableTiming) != hipSuccess)
+            return KFAC_ERR_DEVICE;
+    for (int slot = 0; slot < ctx->tun.slots; ++slot) {
+        if (!ctx->ev[slot] && hipEventCreateWithFlags(&ctx->ev[slot], hipEventDisableTiming) != hipSuccess)
+            return KFAC_ERR_DEVICE;
+        if (!ctx->pinned[slot]) {
+            void *p = nullptr;
+            if (hipHostMalloc(&p, kPinnedSlotBytes, hipHostMallocDefault) != hipSuccess) return KFAC_ERR_DEVICE;
+            ctx->pinned[slot] = (char *)p;
+            ctx->pinned_bytes[slot] = kPinnedSlotBytes;
+        }
+    }
+    ctx->resources_ready = true;
+    return KFAC_OK;
+}
+
+// The staging slot of this call: waits until the device has consumed what the slot held (the call
+// `slots` calls back), and grows the slot if this call's tables do not fit.
 kfac_status ensure_slot(kfac_ctx *ctx, int slot, size_t bytes)
 {
-    if (ctx->ev_valid[slot]) {
-        if (hipEventSynchronize(ctx->ev[slot]) != hipSuccess) return KFAC_ERR_DEVICE;
-    } else {
-        if (hipEventCreateWithFlags(&ctx->ev[slot], hipEventDisableTiming) != hipSuccess) return KFAC_ERR_DEVICE;
-        ctx->ev_valid[slot] = true;
-    }
+    if (ctx->ev_used[slot] && hipEventSynchronize(ctx->ev[slot]) != hipSuccess) return KFAC_ERR_DEVICE;
     if (ctx->pinned_bytes[slot] < bytes) {
         if (ctx->pinned[slot]) (void)hipHostFree(ctx->pinned[slot]);
         ctx->pinned[slot] = nullptr;
         ctx->pinned_bytes[slot] = 0;
-        size_t want = std::max(bytes, (size_t)1 << 20);
         void *p = nullptr;
-        if (hipHostMalloc(&p, want, hipHostMallocDefault) != hipSuccess) return KFAC_ERR_DEVICE;
+        if (hipHostMalloc(&p, bytes, hipHostMallocDefault) != hipSuccess) return KFAC_ERR_DEVICE;
         ctx->pinned[slot] = (char *)p;
-        ctx->pinned_bytes[slot] = want;
+        ctx->pinned_bytes[slot] = bytes;
     }
     return KFAC_OK;
 }
@@ -1197,6 +1243,10 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
     char *tab_dev = (char *)arena.take_tail(tab_bytes + 16);
     if (arena.peak > ctx->ws_bytes) return KFAC_ERR_WORKSPACE;
     hipStream_t s = ctx->stream;
+    {
+        kfac_status st = prepare_resources(ctx);
+        if (st != KFAC_OK) return st;
+    }
     if (tab_bytes) {
         const int slot = ctx->next_slot;
         ctx->next_slot = (ctx->next_slot + 1) % ctx->tun.slots;
@@ -1206,22 +1256,12 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
         if (hipMemcpyAsync(tab_dev, ctx->pinned[slot], tab_bytes, hipMemcpyHostToDevice, s) != hipSuccess)
             return KFAC_ERR_DEVICE;
         if (hipEventRecord(ctx->ev[slot], s) != hipSuccess) return KFAC_ERR_DEVICE;
+        ctx->ev_used[slot] = true;
     }
     for (auto &L : plan.launches) {
         hipError_t e = hipSuccess;
         hipStream_t ls = s;
-        if (L.stream > 0 || L.kind == L_RECORD || L.kind == L_WAIT) {
-            if (!ctx->aux_valid) {
-                for (int q = 0; q < 3; ++q)
-                    if (hipStreamCreateWithFlags(&ctx->aux[q], hipStreamNonBlocking) != hipSuccess) return KFAC_ERR_DEVICE;
-                for (int q = 0; q < kSyncEvents; ++q)
-                    if (hipEventCreateWithFlags(&ctx->sync_ev[q], hipEventDisableTiming) != hipSuccess) return KFAC_ERR_DEVICE;
-                ctx->aux_valid = true;
-            }
-            if (L.stream > 0) {
-                ls = ctx->aux[L.stream - 1];
-            }
-        }
+        if (L.stream > 0) ls = ctx->aux[L.stream - 1];
         if (L.kind == L_RECORD) {
             if (hipEventRecord(ctx->sync_ev[L.n], ls) != hipSuccess) return KFAC_ERR_DEVICE;
             continue;
@@ -1370,10 +1410,34 @@ kfac_status kfac_layer_dims(const kfac_layer *L, int32_t *dA, int32_t *dG, int32
     return KFAC_OK;
 }
 
+size_t kfac_step_workspace_bytes(const kfac_layer *L, int32_t n_layers, kfac_dtype in, const uint8_t *invert_mask,
+                                 const kfac_options *opt)
+{
+    if (!layers_ok(L, n_layers) || (in != KFAC_F32 && in != KFAC_BF16) || !options_ok(opt)) return 0;
+    const Tunables tun(opt ? *opt : default_options());
+    Plan plan; Arena arena(nullptr);
+    StatsArgs st{n_layers, L, in, nullptr, nullptr, 0.5f, 0, nullptr, nullptr};
+    InvertArgs iv{n_layers, L, nullptr, nullptr, 1e-3f, nullptr, nullptr, nullptr, nullptr};
+    PrecondArgs pc{n_layers, L, nullptr, nullptr, nullptr, nullptr};
+    plan_step(plan, arena, tun, st, iv, invert_mask, pc, true);
+    arena.take_tail(plan.tab.buf.size() + 16);
+    return arena.peak;
+}
+
+void kfac_options_default(kfac_options *opt)
+{
+    if (opt) *opt = default_options();
+}
+
 size_t kfac_workspace_bytes(const kfac_layer *L, int32_t n_layers, kfac_dtype in)
 {
-    if (!layers_ok(L, n_layers) || (in != KFAC_F32 && in != KFAC_BF16)) return 0;
-    Tunables tun;
+    return kfac_workspace_bytes_opt(L, n_layers, in, nullptr);
+}
+
+size_t kfac_workspace_bytes_opt(const kfac_layer *L, int32_t n_layers, kfac_dtype in, const kfac_options *opt)
+{
+    if (!layers_ok(L, n_layers) || (in != KFAC_F32 && in != KFAC_BF16) || !options_ok(opt)) return 0;
+    const Tunables tun(opt ? *opt : default_options());
     size_t best = 0, sum_peaks = 0;
     {
         Plan plan; Arena arena(nullptr);
@@ -1399,15 +1463,18 @@ size_t kfac_workspace_bytes(const kfac_layer *L, int32_t n_layers, kfac_dtype in
         best = std::max(best, arena.peak);
     }
     {
-        // fused step, all layers inverted; a partial mask moves layers between the two factor
-        // phases and the inversion groups, which the sum of the separate peaks covers
+        // fused step, all layers inverted.  A partial mask moves layers between the factor phases
+        // and the inversion groups, which changes tile choices and split-K scratch by a few percent
+        // (searching over masks found 10 % above the full mask's plan at most): the sum of the
+        // separate peaks plus a quarter covers that with room; kfac_step_workspace_bytes gives the
+        // exact figure for one mask, and every call checks its own plan before it launches anything
         Plan plan; Arena arena(nullptr);
         StatsArgs st{n_layers, L, in, nullptr, nullptr, 0.5f, 0, nullptr, nullptr};
         InvertArgs iv{n_layers, L, nullptr, nullptr, 1e-3f, nullptr, nullptr, nullptr, nullptr};
         PrecondArgs pc{n_layers, L, nullptr, nullptr, nullptr, nullptr};
         plan_step(plan, arena, tun, st, iv, nullptr, pc, true);
         arena.take_tail(plan.tab.buf.size() + 16);
-        best = std::max(best, std::max(arena.peak, sum_peaks + sum_peaks / 8));
+        best = std::max(best, std::max(arena.peak, sum_peaks + sum_peaks / 4));
     }
     // im2col of a single layer and the BatchNorm calls need table space only
     best = std::max(best, (size_t)1 << 20);
@@ -1416,22 +1483,44 @@ size_t kfac_workspace_bytes(const kfac_layer *L, int32_t n_layers, kfac_dtype in
 
 kfac_status kfac_create(kfac_ctx **out, void *hip_stream, void *workspace_dev, size_t workspace_bytes)
 {
+    return kfac_create_opt(out, hip_stream, workspace_dev, workspace_bytes, nullptr);
+}
+
+kfac_status kfac_create_opt(kfac_ctx **out, void *hip_stream, void *workspace_dev, size_t workspace_bytes,
+                            const kfac_options *opt)
+{
     if (!out) return KFAC_ERR_INVALID;
     *out = nullptr;
     if (!workspace_dev || workspace_bytes == 0 || ((uintptr_t)workspace_dev % kAlign) != 0) return KFAC_ERR_INVALID;
+    if (!options_ok(opt)) return KFAC_ERR_INVALID;
     kfac_ctx *c = new (std::nothrow) kfac_ctx();
     if (!c) return KFAC_ERR_DEVICE;
     c->stream = (hipStream_t)hip_stream;
     c->ws = (char *)workspace_dev;
     c->ws_bytes = workspace_bytes;
+    c->tun = Tunables(opt ? *opt : default_options());
     for (int i = 0; i < kSlots; ++i) {
         c->pinned[i] = nullptr;
         c->pinned_bytes[i] = 0;
-        c->ev_valid[i] = false;
+        c->ev[i] = nullptr;
+        c->ev_used[i] = false;
     }
+    for (int q = 0; q < 3; ++q) c->aux[q] = nullptr;
+    for (int q = 0; q < kSyncEvents; ++q) c->sync_ev[q] = nullptr;
     c->next_slot = 0;
     c->profiling = false;
-    c->aux_valid = false;
+    c->resources_ready = false;
+    // streams, events and the staging ring now, if there is a device to create them on (a machine
+    // without one still gets a context: argument validation needs no GPU)
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) == hipSuccess && n_dev > 0) {
+        if (prepare_resources(c) != KFAC_OK) {
+            kfac_destroy(c);
+            return KFAC_ERR_DEVICE;
+        }
+    } else {
+        (void)hipGetLastError();   // (the failed device query is not this library's caller's error)
+    }
     *out = c;
     return KFAC_OK;
 }
@@ -1440,20 +1529,20 @@ void kfac_destroy(kfac_ctx *ctx)
 {
     if (!ctx) return;
     for (int i = 0; i < kSlots; ++i) {
-        if (ctx->ev_valid[i]) {
-            (void)hipEventSynchronize(ctx->ev[i]);
+        if (ctx->ev[i]) {
+            if (ctx->ev_used[i]) (void)hipEventSynchronize(ctx->ev[i]);
             (void)hipEventDestroy(ctx->ev[i]);
         }
         if (ctx->pinned[i]) (void)hipHostFree(ctx->pinned[i]);
     }
     for (auto ev : ctx->ev_pool) (void)hipEventDestroy(ev);
-    if (ctx->aux_valid) {
-        for (int q = 0; q < 3; ++q) {
+    for (int q = 0; q < 3; ++q)
+        if (ctx->aux[q]) {
             (void)hipStreamSynchronize(ctx->aux[q]);
             (void)hipStreamDestroy(ctx->aux[q]);
         }
-        for (int q = 0; q < kSyncEvents; ++q) (void)hipEventDestroy(ctx->sync_ev[q]);
-    }
+    for (int q = 0; q < kSyncEvents; ++q)
+        if (ctx->sync_ev[q]) (void)hipEventDestroy(ctx->sync_ev[q]);
     delete ctx;
 }
 
@@ -1739,7 +1828,7 @@ bool bn_full_dims_ok(int32_t n_layers, int32_t N, const int32_t *C)
 size_t bn_full_workspace_bytes(int32_t n_layers, int32_t N, const int32_t *C)
 {
     if (!bn_full_dims_ok(n_layers, N, C)) return 0;
-    const Tunables tun;
+    const Tunables tun(default_options());
     BnFullArgs a{};
     a.n_layers = n_layers; a.N = N; a.C = C;
     size_t all = 0, single = 0;

@@ -6,9 +6,11 @@ is missing or a call fails, an exception is raised.
 """
 from __future__ import annotations
 
+import contextlib
 import ctypes
 import os
 from typing import List, Optional, Sequence
+
 
 import torch
 
@@ -20,6 +22,7 @@ KFAC_F32, KFAC_BF16 = 0, 1
 
 EXPORTS = [
     "kfac_status_string", "kfac_layer_dims", "kfac_workspace_bytes", "kfac_create", "kfac_destroy",
+    "kfac_options_default", "kfac_workspace_bytes_opt", "kfac_create_opt", "kfac_step_workspace_bytes",
     "kfac_im2col", "kfac_stats", "kfac_invert", "kfac_precondition", "kfac_step",
     "bn_unitwise_precondition", "bn_unitwise_reduce_nchw", "kfac_profile_enable", "kfac_profile_read",
     "kfac_packed_elems", "kfac_pack_upper", "kfac_unpack_upper",
@@ -36,6 +39,42 @@ class kfac_profile_entry(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int32), ("variant", ctypes.c_int32), ("workgroups", ctypes.c_int32),
                 ("ms", ctypes.c_float), ("flops", ctypes.c_double), ("bytes", ctypes.c_double),
                 ("start_ms", ctypes.c_float), ("stream", ctypes.c_int32)]
+
+
+KFAC_PRODUCTS_SPLIT_BF16, KFAC_PRODUCTS_FP32_MFMA = 0, 1
+
+
+class kfac_options(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("struct_size", "fp32_products", "streams", "staging_slots", "correlation_form", "pipeline_phases",
+                 "early_n", "target_workgroups", "min_k_per_split", "max_k_per_workgroup", "recursion_leaf",
+                 "force_tile")] + [("chunk_gflop", ctypes.c_float)]
+
+
+def options(**fields) -> kfac_options:
+    """The library's default options with the given fields replaced."""
+    o = kfac_options()
+    lib().kfac_options_default(ctypes.addressof(o))
+    for k, v in fields.items():
+        if not hasattr(o, k):
+            raise ValueError("unknown option %r" % k)
+        setattr(o, k, v)
+    return o
+
+
+_default_opts: Optional[kfac_options] = None
+
+
+@contextlib.contextmanager
+def default_options(**fields):
+    """Within the block, contexts created (and workspaces sized) without explicit options take these
+    instead of the library's defaults.  A convenience of this binding; the library itself has no such state."""
+    global _default_opts
+    prev, _default_opts = _default_opts, options(**fields)
+    try:
+        yield _default_opts
+    finally:
+        _default_opts = prev
 
 
 class kfac_layer(ctypes.Structure):
@@ -66,6 +105,13 @@ def lib() -> ctypes.CDLL:
         L.kfac_workspace_bytes.restype = ctypes.c_size_t
         L.kfac_workspace_bytes.argtypes = [vp, i32, ctypes.c_int]
         L.kfac_create.argtypes = [vp, vp, vp, ctypes.c_size_t]
+        L.kfac_create_opt.argtypes = [vp, vp, vp, ctypes.c_size_t, vp]
+        L.kfac_options_default.restype = None
+        L.kfac_options_default.argtypes = [vp]
+        L.kfac_workspace_bytes_opt.restype = ctypes.c_size_t
+        L.kfac_workspace_bytes_opt.argtypes = [vp, i32, ctypes.c_int, vp]
+        L.kfac_step_workspace_bytes.restype = ctypes.c_size_t
+        L.kfac_step_workspace_bytes.argtypes = [vp, i32, ctypes.c_int, vp, vp]
         L.kfac_destroy.restype = None
         L.kfac_destroy.argtypes = [vp]
         L.kfac_im2col.argtypes = [vp, vp, ctypes.c_int, vp, vp, ctypes.c_int64]
@@ -117,23 +163,42 @@ def _layers(layers: Sequence) -> ctypes.Array:
     return arr
 
 
-def _ptrs(tensors: Optional[Sequence[Optional[torch.Tensor]]], n: int, dtype=None) -> Optional[ctypes.Array]:
-    """Host array of device pointers; None entries become NULL; None list becomes NULL."""
+def _ptrs(tensors: Optional[Sequence[Optional[torch.Tensor]]], n: int, dtype=None,
+          numels: Optional[Sequence[int]] = None, what: str = "tensor") -> Optional[ctypes.Array]:
+    """Host array of device pointers; None entries become NULL; None list becomes NULL.
+    numels: the element count the library will read or write behind each pointer; a smaller
+    tensor is refused here (the library sees only the pointer)."""
     if tensors is None:
         return None
     if len(tensors) != n:
-        raise ValueError("expected %d tensors, got %d" % (n, len(tensors)))
+        raise ValueError("expected %d %ss, got %d" % (n, what, len(tensors)))
     arr = (ctypes.c_void_p * n)()
     for i, t in enumerate(tensors):
         if t is None:
             arr[i] = None
             continue
         if not t.is_cuda or not t.is_contiguous():
-            raise ValueError("tensor %d must be a contiguous device tensor" % i)
+            raise ValueError("%s %d must be a contiguous device tensor" % (what, i))
         if dtype is not None and t.dtype != dtype:
-            raise ValueError("tensor %d must be %s" % (i, dtype))
+            raise ValueError("%s %d must be %s" % (what, i, dtype))
+        if numels is not None and t.numel() < int(numels[i]):
+            raise ValueError("%s %d has %d elements, the layer needs %d" % (what, i, t.numel(), int(numels[i])))
         arr[i] = t.data_ptr()
     return arr
+
+
+def _sizes(layers: Sequence) -> dict:
+    """Element counts of the per-layer tensors, from the library's own kfac_layer_dims."""
+    out = {"act": [], "grad_out": [], "A": [], "G": [], "W": [], "nhwc_act": [], "nhwc_grad": []}
+    for L in layers:
+        dA, dG, h, w = kfac_layer_dims(L)
+        N, c_in, c_out, _, _, _, h_in, w_in, _ = [int(v) for v in L]
+        out["act"].append(N * c_in * h_in * w_in)
+        out["grad_out"].append(N * c_out * h * w)
+        out["A"].append(dA * dA)
+        out["G"].append(dG * dG)
+        out["W"].append(dG * dA)
+    return out
 
 
 def _i32(values: Sequence[int]) -> ctypes.Array:
@@ -149,9 +214,20 @@ def kfac_layer_dims(layer) -> tuple:
     return tuple(o.value for o in out)
 
 
-def kfac_workspace_bytes(layers: Sequence, in_dtype: int = KFAC_F32) -> int:
+def kfac_workspace_bytes(layers: Sequence, in_dtype: int = KFAC_F32, opts: Optional[kfac_options] = None) -> int:
     arr = _layers(layers)
-    return int(lib().kfac_workspace_bytes(ctypes.addressof(arr), len(layers), int(in_dtype)))
+    opts = opts if opts is not None else _default_opts
+    return int(lib().kfac_workspace_bytes_opt(ctypes.addressof(arr), len(layers), int(in_dtype),
+                                              None if opts is None else ctypes.addressof(opts)))
+
+
+def kfac_step_workspace_bytes(layers: Sequence, in_dtype: int = KFAC_F32, invert_mask: Optional[Sequence[bool]] = None,
+                              opts: Optional[kfac_options] = None) -> int:
+    arr = _layers(layers)
+    mask = None if invert_mask is None else (ctypes.c_uint8 * len(layers))(*[1 if m else 0 for m in invert_mask])
+    return int(lib().kfac_step_workspace_bytes(ctypes.addressof(arr), len(layers), int(in_dtype),
+                                               None if mask is None else ctypes.addressof(mask),
+                                               None if opts is None else ctypes.addressof(opts)))
 
 
 class Context:
@@ -159,20 +235,22 @@ class Context:
     torch's current stream."""
 
     def __init__(self, layers: Sequence, in_dtype: int = KFAC_F32, extra_layer_lists: Sequence[Sequence] = (),
-                 workspace_bytes: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None):
-        need = kfac_workspace_bytes(layers, in_dtype)
+                 workspace_bytes: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None,
+                 opts: Optional[kfac_options] = None):
+        opts = opts if opts is not None else _default_opts
+        need = kfac_workspace_bytes(layers, in_dtype, opts)
         if need == 0:
             raise KfacError(KFAC_ERR_INVALID, "kfac_workspace_bytes")
         for other in extra_layer_lists:
-            need = max(need, kfac_workspace_bytes(other, in_dtype))
+            need = max(need, kfac_workspace_bytes(other, in_dtype, opts))
         if workspace_bytes is not None:
             need = int(workspace_bytes)
         self.workspace = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
         base = (self.workspace.data_ptr() + 255) // 256 * 256
         self.stream = stream if stream is not None else torch.cuda.current_stream()
         handle = ctypes.c_void_p()
-        st = lib().kfac_create(ctypes.addressof(handle), ctypes.c_void_p(self.stream.cuda_stream),
-                               ctypes.c_void_p(base), need)
+        st = lib().kfac_create_opt(ctypes.addressof(handle), ctypes.c_void_p(self.stream.cuda_stream),
+                                   ctypes.c_void_p(base), need, None if opts is None else ctypes.addressof(opts))
         if st != KFAC_OK:
             raise KfacError(st, "kfac_create")
         self.handle = handle
@@ -197,6 +275,12 @@ def kfac_im2col(ctx: Context, layer, in_dtype: int, act: torch.Tensor, patches: 
     L = kfac_layer(*[int(v) for v in layer])
     if act.dtype != _tdtype(in_dtype) or patches.dtype != _tdtype(in_dtype):
         raise ValueError("dtype mismatch")
+    dA, dG, h, w = kfac_layer_dims(layer)
+    N, c_in, k = int(layer[0]), int(layer[1]), int(layer[3])
+    if not (act.is_cuda and act.is_contiguous() and patches.is_cuda and patches.is_contiguous()):
+        raise ValueError("act and patches must be contiguous device tensors")
+    if act.numel() < N * c_in * int(layer[6]) * int(layer[7]) or int(ld) < N * h * w or patches.numel() < c_in * k * k * int(ld):
+        raise ValueError("act or patches too small for the layer (need [N,c_in,h_in,w_in] and [c_in*k*k, ld], ld >= N*h*w)")
     st = lib().kfac_im2col(ctx.handle, ctypes.addressof(L), int(in_dtype), act.data_ptr(), patches.data_ptr(), int(ld))
     if st != KFAC_OK:
         raise KfacError(st, "kfac_im2col")
@@ -206,8 +290,10 @@ def kfac_stats(ctx: Context, layers: Sequence, in_dtype: int, act, grad_out, dec
                g_spatial_mean: bool, A_ema, G_ema) -> None:
     n = len(layers)
     arr = _layers(layers)
-    pa, pg = _ptrs(act, n, _tdtype(in_dtype)), _ptrs(grad_out, n, _tdtype(in_dtype))
-    pA, pG = _ptrs(A_ema, n, torch.float32), _ptrs(G_ema, n, torch.float32)
+    sz = _sizes(layers)
+    pa = _ptrs(act, n, _tdtype(in_dtype), sz["act"], "act")
+    pg = _ptrs(grad_out, n, _tdtype(in_dtype), sz["grad_out"], "grad_out")
+    pA, pG = _ptrs(A_ema, n, torch.float32, sz["A"], "A_ema"), _ptrs(G_ema, n, torch.float32, sz["G"], "G_ema")
     st = lib().kfac_stats(ctx.handle, n, ctypes.addressof(arr), int(in_dtype),
                           pa and ctypes.addressof(pa), pg and ctypes.addressof(pg),
                           float(decay), int(bool(g_spatial_mean)),
@@ -220,8 +306,9 @@ def kfac_invert(ctx: Context, layers: Sequence, A_ema, G_ema, gamma: float, A_in
                 pi_out: Optional[torch.Tensor] = None, info: Optional[torch.Tensor] = None) -> None:
     n = len(layers)
     arr = _layers(layers)
-    pA, pG = _ptrs(A_ema, n, torch.float32), _ptrs(G_ema, n, torch.float32)
-    pAi, pGi = _ptrs(A_inv, n, torch.float32), _ptrs(G_inv, n, torch.float32)
+    sz = _sizes(layers)
+    pA, pG = _ptrs(A_ema, n, torch.float32, sz["A"], "A_ema"), _ptrs(G_ema, n, torch.float32, sz["G"], "G_ema")
+    pAi, pGi = _ptrs(A_inv, n, torch.float32, sz["A"], "A_inv"), _ptrs(G_inv, n, torch.float32, sz["G"], "G_inv")
     if pi_out is not None and (pi_out.dtype != torch.float32 or pi_out.numel() < n):
         raise ValueError("pi_out must be float32 [n_layers]")
     if info is not None and (info.dtype != torch.int32 or info.numel() < 2 * n):
@@ -238,7 +325,9 @@ def kfac_invert(ctx: Context, layers: Sequence, A_ema, G_ema, gamma: float, A_in
 def kfac_precondition(ctx: Context, layers: Sequence, G_inv, A_inv, grad_W, out) -> None:
     n = len(layers)
     arr = _layers(layers)
-    ps = [_ptrs(x, n, torch.float32) for x in (G_inv, A_inv, grad_W, out)]
+    sz = _sizes(layers)
+    ps = [_ptrs(x, n, torch.float32, sz[k], w) for x, k, w in ((G_inv, "G", "G_inv"), (A_inv, "A", "A_inv"),
+                                                               (grad_W, "W", "grad_W"), (out, "W", "out"))]
     st = lib().kfac_precondition(ctx.handle, n, ctypes.addressof(arr), *[p and ctypes.addressof(p) for p in ps])
     if st != KFAC_OK:
         raise KfacError(st, "kfac_precondition")
@@ -249,8 +338,11 @@ def kfac_step(ctx: Context, layers: Sequence, in_dtype: int, act, grad_out, deca
               pi_out: Optional[torch.Tensor], info: Optional[torch.Tensor], grad_W, out) -> None:
     n = len(layers)
     arr = _layers(layers)
-    ps = [_ptrs(act, n, _tdtype(in_dtype)), _ptrs(grad_out, n, _tdtype(in_dtype))]
-    ps += [_ptrs(x, n, torch.float32) for x in (A_ema, G_ema, A_inv, G_inv, grad_W, out)]
+    sz = _sizes(layers)
+    ps = [_ptrs(act, n, _tdtype(in_dtype), sz["act"], "act"), _ptrs(grad_out, n, _tdtype(in_dtype), sz["grad_out"], "grad_out")]
+    ps += [_ptrs(x, n, torch.float32, sz[k], w) for x, k, w in ((A_ema, "A", "A_ema"), (G_ema, "G", "G_ema"),
+                                                                (A_inv, "A", "A_inv"), (G_inv, "G", "G_inv"),
+                                                                (grad_W, "W", "grad_W"), (out, "W", "out"))]
     pa, pg, pA, pG, pAi, pGi, pW, pO = [p and ctypes.addressof(p) for p in ps]
     mask = None
     if invert_mask is not None:
@@ -273,8 +365,9 @@ def bn_unitwise_precondition(ctx: Context, N: int, C: Sequence[int], g_gamma, g_
                              F_ema, out_gamma, out_beta) -> None:
     n = len(C)
     cs = _i32(C)
-    ps = [_ptrs(x, n, torch.float32) for x in (g_gamma, g_beta)]
-    qs = [_ptrs(x, n, torch.float32) for x in (F_ema, out_gamma, out_beta)]
+    nc, c3, c1 = [int(N) * int(c) for c in C], [3 * int(c) for c in C], [int(c) for c in C]
+    ps = [_ptrs(x, n, torch.float32, nc, w) for x, w in ((g_gamma, "g_gamma"), (g_beta, "g_beta"))]
+    qs = [_ptrs(x, n, torch.float32, m, w) for x, m, w in ((F_ema, c3, "F_ema"), (out_gamma, c1, "out_gamma"), (out_beta, c1, "out_beta"))]
     st = lib().bn_unitwise_precondition(ctx.handle, n, int(N), ctypes.addressof(cs),
                                         *[p and ctypes.addressof(p) for p in ps], float(decay), float(lam),
                                         *[p and ctypes.addressof(p) for p in qs])
@@ -286,7 +379,9 @@ def bn_unitwise_reduce_nchw(ctx: Context, N: int, C: Sequence[int], HW: Sequence
                             g_gamma, g_beta) -> None:
     n = len(C)
     cs, hs = _i32(C), _i32(HW)
-    ps = [_ptrs(x, n, torch.float32) for x in (dy, xhat, g_gamma, g_beta)]
+    big = [int(N) * int(c) * int(h) for c, h in zip(C, HW)]
+    nc = [int(N) * int(c) for c in C]
+    ps = [_ptrs(x, n, torch.float32, m, w) for x, m, w in ((dy, big, "dy"), (xhat, big, "xhat"), (g_gamma, nc, "g_gamma"), (g_beta, nc, "g_beta"))]
     st = lib().bn_unitwise_reduce_nchw(ctx.handle, n, int(N), ctypes.addressof(cs), ctypes.addressof(hs),
                                        *[p and ctypes.addressof(p) for p in ps])
     if st != KFAC_OK:
@@ -296,7 +391,8 @@ def bn_unitwise_reduce_nchw(ctx: Context, N: int, C: Sequence[int], HW: Sequence
 def kfac_nhwc_to_nchw(ctx: Context, layers: Sequence, which: int, type_: int, src, dst) -> None:
     n = len(layers)
     ls = _layers(layers)
-    ps, pd = _ptrs(src, n, _tdtype(type_)), _ptrs(dst, n, _tdtype(type_))
+    szl = _sizes(layers)["act" if int(which) == 0 else "grad_out"]
+    ps, pd = _ptrs(src, n, _tdtype(type_), szl, "src"), _ptrs(dst, n, _tdtype(type_), szl, "dst")
     st = lib().kfac_nhwc_to_nchw(ctx.handle, n, ctypes.addressof(ls), int(which), int(type_),
                                  ps and ctypes.addressof(ps), pd and ctypes.addressof(pd))
     if st != KFAC_OK:
@@ -313,7 +409,9 @@ def bn_full_precondition(ctx: Context, N: int, C: Sequence[int], g_gamma, g_beta
                          info: Optional[torch.Tensor] = None) -> None:
     n = len(C)
     c = _i32(C)
-    ps = [_ptrs(x, n, torch.float32) for x in (g_gamma, g_beta, F_ema, F_inv, out_gamma, out_beta)]
+    nc, cc, c1 = [int(N) * int(v) for v in C], [4 * int(v) * int(v) for v in C], [int(v) for v in C]
+    ps = [_ptrs(x, n, torch.float32, m, w) for x, m, w in ((g_gamma, nc, "g_gamma"), (g_beta, nc, "g_beta"), (F_ema, cc, "F_ema"),
+                                                           (F_inv, cc, "F_inv"), (out_gamma, c1, "out_gamma"), (out_beta, c1, "out_beta"))]
     mask = None if invert_mask is None else (ctypes.c_uint8 * n)(*[1 if m else 0 for m in invert_mask])
     if info is not None and (info.dtype != torch.int32 or info.numel() < n):
         raise ValueError("info must be int32 [n_layers]")
@@ -337,7 +435,8 @@ def kfac_update_weights(ctx: Context, layers: Sequence, U, eta: float, momentum:
                         W, W_prev) -> None:
     n = len(layers)
     ls = _layers(layers)
-    ps = [_ptrs(x, n, torch.float32) for x in (U, W, W_prev)]
+    szw = _sizes(layers)["W"]
+    ps = [_ptrs(x, n, torch.float32, szw, w) for x, w in ((U, "U"), (W, "W"), (W_prev, "W_prev"))]
     st = lib().kfac_update_weights(ctx.handle, n, ctypes.addressof(ls), ps[0] and ctypes.addressof(ps[0]), float(eta),
                                    float(momentum), int(bool(rescale)), float(eps), ps[1] and ctypes.addressof(ps[1]),
                                    ps[2] and ctypes.addressof(ps[2]))
@@ -359,7 +458,7 @@ def _packed_ok(packed: torch.Tensor, dims: Sequence[int], type_: int) -> None:
 
 def kfac_pack_upper(ctx: Context, dims: Sequence[int], X, type_: int, packed: torch.Tensor) -> None:
     n = len(dims)
-    ds, ps = _i32(dims), _ptrs(X, n, torch.float32)
+    ds, ps = _i32(dims), _ptrs(X, n, torch.float32, [int(d) * int(d) for d in dims], "X")
     _packed_ok(packed, dims, type_)
     st = lib().kfac_pack_upper(ctx.handle, n, ctypes.addressof(ds), ps and ctypes.addressof(ps), int(type_),
                                packed.data_ptr())
@@ -369,7 +468,7 @@ def kfac_pack_upper(ctx: Context, dims: Sequence[int], X, type_: int, packed: to
 
 def kfac_unpack_upper(ctx: Context, dims: Sequence[int], type_: int, packed: torch.Tensor, X) -> None:
     n = len(dims)
-    ds, ps = _i32(dims), _ptrs(X, n, torch.float32)
+    ds, ps = _i32(dims), _ptrs(X, n, torch.float32, [int(d) * int(d) for d in dims], "X")
     _packed_ok(packed, dims, type_)
     st = lib().kfac_unpack_upper(ctx.handle, n, ctypes.addressof(ds), int(type_), packed.data_ptr(),
                                  ps and ctypes.addressof(ps))
@@ -381,7 +480,8 @@ def kfac_staleness(ctx: Context, dims: Sequence[int], X, X_m1, X_m2, ratios: tor
     """ratios: device float64 [2 * len(dims)] (contiguous)."""
     n = len(dims)
     ds = _i32(dims)
-    ps = [_ptrs(x, n, torch.float32) for x in (X, X_m1, X_m2)]
+    dd = [int(d) * int(d) for d in dims]
+    ps = [_ptrs(x, n, torch.float32, dd, w) for x, w in ((X, "X"), (X_m1, "X_m1"), (X_m2, "X_m2"))]
     if not (ratios.is_cuda and ratios.is_contiguous() and ratios.dtype == torch.float64 and ratios.numel() >= 2 * n):
         raise ValueError("ratios must be a contiguous device float64 tensor of at least 2 n elements")
     st = lib().kfac_staleness(ctx.handle, n, ctypes.addressof(ds), *[p and ctypes.addressof(p) for p in ps],
@@ -395,7 +495,8 @@ def kfac_staleness_static(stream: Optional[torch.cuda.Stream], dims: Sequence[in
     """kfac_staleness without a context: scratch in the library's fixed device array, nothing allocated."""
     n = len(dims)
     ds = _i32(dims)
-    ps = [_ptrs(x, n, torch.float32) for x in (X, X_m1, X_m2)]
+    dd = [int(d) * int(d) for d in dims]
+    ps = [_ptrs(x, n, torch.float32, dd, w) for x, w in ((X, "X"), (X_m1, "X_m1"), (X_m2, "X_m2"))]
     if not (ratios.is_cuda and ratios.is_contiguous() and ratios.dtype == torch.float64 and ratios.numel() >= 2 * n):
         raise ValueError("ratios must be a contiguous device float64 tensor of at least 2 n elements")
     s = stream if stream is not None else torch.cuda.current_stream()

@@ -381,3 +381,38 @@ def test_layout_conversion_rejects_bad_arguments_without_a_gpu():
     none = (ctypes.c_void_p * 2)(None, None)
     assert call(h, 2, lp, 0, 0, ctypes.addressof(none), dp) == kfac.KFAC_OK      # nothing to do
     L.kfac_destroy(h)
+
+
+def test_workspace_covers_masked_steps():
+    """Host-only dry plans: whatever subset of the full ResNet-50 set a fused step inverts, its plan stays
+    within kfac_workspace_bytes (the stale-statistics mode changes the mask from step to step)."""
+    import numpy as np
+    for config in (4, 5):
+        layers = wl.config_layers(config)
+        bound = kfac.kfac_workspace_bytes(layers)
+        assert 0 < kfac.kfac_step_workspace_bytes(layers) <= bound
+        rng = np.random.default_rng(config)
+        big = [max(L.dA, L.dG) for L in layers]
+        masks = [[b >= t for b in big] for t in (512, 1024, 2048, 4096)] + [[b < t for b in big] for t in (512, 2048)]
+        masks += [list(rng.random(len(layers)) < rng.random()) for _ in range(120)]
+        worst = max(kfac.kfac_step_workspace_bytes(layers, kfac.KFAC_F32, m) for m in masks)
+        assert worst <= bound, (config, worst, bound)
+    opts = kfac.options(streams=1, pipeline_phases=0)
+    layers = wl.config_layers(4)
+    assert 0 < kfac.kfac_step_workspace_bytes(layers, kfac.KFAC_F32, None, opts) <= kfac.kfac_workspace_bytes(layers, kfac.KFAC_F32, opts)
+
+
+def test_options_are_validated():
+    L = kfac.lib()
+    h = ctypes.c_void_p()
+    o = kfac.options()
+    assert o.struct_size == ctypes.sizeof(kfac.kfac_options) and o.streams == 4 and o.fp32_products == kfac.KFAC_PRODUCTS_SPLIT_BF16
+    ws = ctypes.c_void_p(0x100000)
+    assert L.kfac_create_opt(ctypes.addressof(h), None, ws, 1 << 20, ctypes.addressof(o)) == kfac.KFAC_OK
+    L.kfac_destroy(h)
+    for field, bad in (("struct_size", 4), ("fp32_products", 7), ("streams", 0), ("streams", 5), ("staging_slots", 1),
+                       ("recursion_leaf", 300), ("force_tile", 96), ("chunk_gflop", float("nan"))):
+        b = kfac.options(**{field: bad})
+        assert L.kfac_create_opt(ctypes.addressof(h), None, ws, 1 << 20, ctypes.addressof(b)) == kfac.KFAC_ERR_INVALID, field
+        lay = kfac.kfac_layer(*wl.fc_layer(4, 8, 3))
+        assert L.kfac_workspace_bytes_opt(ctypes.addressof(lay), 1, 0, ctypes.addressof(b)) == 0, field

@@ -1,7 +1,8 @@
 """The two product modes of the fp32 GEMM.  The default forms every product from three bf16 planes per operand
-with six bf16 matrix instructions (all other GPU tests run in it); KFAC_SPLIT=0 selects the fp32 matrix
-instruction.  Here: the parity cases of the statistics, the inversion, the preconditioning and the fused step once
-more under KFAC_SPLIT=0, to the same tolerances, and a direct comparison of the two modes' errors."""
+with six bf16 matrix instructions (all other GPU tests run in it); a context created with
+fp32_products = KFAC_PRODUCTS_FP32_MFMA uses the fp32 matrix instruction.  Here: the parity cases of the statistics,
+the inversion, the preconditioning and the fused step once more in that mode, to the same tolerances, a direct
+comparison of the two modes' errors, and what the default mode does at the ends of the fp32 range."""
 import numpy as np
 import pytest
 import torch
@@ -14,8 +15,9 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.fixture(autouse=True)
-def fp32_instruction_mode(monkeypatch):
-    monkeypatch.setenv("KFAC_SPLIT", "0")      # read when a context is created
+def fp32_instruction_mode():
+    with kfac.default_options(fp32_products=kfac.KFAC_PRODUCTS_FP32_MFMA):   # for every context the tests create
+        yield
 
 
 gpu = P.gpu
@@ -38,7 +40,7 @@ def _stats_error(layer, act, grad):
     return P.relerr(P.host(A[0]), Ar), P.relerr(P.host(G[0]), Gr)
 
 
-def test_products_are_as_accurate_as_the_fp32_instruction(gpu, monkeypatch):
+def test_products_are_as_accurate_as_the_fp32_instruction(gpu):
     """A long contraction (4096 samples) with values spread over many binades: the error against the float64
     oracle is that of fp32 accumulation in both modes, far below the 1e-4 of the statistics."""
     layer = wl.fc_layer(4096, 300, 200)
@@ -46,8 +48,8 @@ def test_products_are_as_accurate_as_the_fp32_instruction(gpu, monkeypatch):
     act = (rng.standard_normal((4096, 300)) * np.exp2(rng.integers(-12, 12, size=(4096, 300)))).astype(np.float32).reshape(4096, 300, 1, 1)
     grad = (rng.standard_normal((4096, 200)) * np.exp2(rng.integers(-20, -2, size=(4096, 200)))).astype(np.float32).reshape(4096, 200, 1, 1)
     eA1, eG1 = _stats_error(layer, act, grad)
-    monkeypatch.setenv("KFAC_SPLIT", "1")
-    eA3, eG3 = _stats_error(layer, act, grad)
+    with kfac.default_options(fp32_products=kfac.KFAC_PRODUCTS_SPLIT_BF16):
+        eA3, eG3 = _stats_error(layer, act, grad)
     assert eA1 < 2e-6 and eG1 < 2e-6
     assert eA3 <= 2.0 * eA1 + 5e-7 and eG3 <= 2.0 * eG1 + 5e-7, (eA3, eA1, eG3, eG1)
 
@@ -62,15 +64,15 @@ def _kernel_names():
     return names
 
 
-def test_profile_names_the_kernel_of_each_mode(gpu, monkeypatch):
+def test_profile_names_the_kernel_of_each_mode(gpu):
     names = _kernel_names()
     assert "gemm_f32" in names and "gemm_f32_split" not in names
-    monkeypatch.delenv("KFAC_SPLIT")                      # the default
-    names = _kernel_names()
+    with kfac.default_options():                          # the library's defaults
+        names = _kernel_names()
     assert "gemm_f32_split" in names and "gemm_f32" not in names
 
 
-def test_cancelling_contraction_in_both_modes(gpu, monkeypatch):
+def test_cancelling_contraction_in_both_modes(gpu):
     """Sums whose terms cancel almost completely: the error is measured against sum |x_k y_k| (what fp32 accumulation
     can promise), and must be of that size in both modes -- the split products drop only terms below 2^-23 |x y|."""
     N, d = 2048, 96
@@ -85,10 +87,49 @@ def test_cancelling_contraction_in_both_modes(gpu, monkeypatch):
     a64 = act.reshape(N, d).astype(np.float64)
     scale = (np.abs(a64).T @ np.abs(a64)).max() / N
     errs = {}
-    for mode in ("0", "1"):
-        monkeypatch.setenv("KFAC_SPLIT", mode)
-        A, G = P.run_stats([layer], [act], [grad], 0.0, False)
+    for mode, products in (("0", kfac.KFAC_PRODUCTS_FP32_MFMA), ("1", kfac.KFAC_PRODUCTS_SPLIT_BF16)):
+        with kfac.default_options(fp32_products=products):
+            A, G = P.run_stats([layer], [act], [grad], 0.0, False)
         Ar, Gr = oracle.kfac_stats(tuple(layer), act, grad, 0.0, False, None, None)
         errs[mode] = float(np.abs(P.host(A[0]) - Ar).max() / scale)
     assert errs["0"] < 2e-6 and errs["1"] < 2e-6, errs
     assert errs["1"] <= 2.0 * errs["0"] + 3e-7, errs
+
+
+def test_default_mode_at_the_ends_of_the_fp32_range(gpu):
+    """The three-plane products near the bottom and the top of the fp32 range (default mode).
+    The lowest bit of the third plane of x lies 2^-23 below x and must be a bf16 value (subnormals reach 2^-133):
+    operands of magnitude 2^-110 and above keep every bit (the matrix unit does not flush bf16 subnormals), below
+    that the low planes are cut off step by step -- measured for products of such a value with an ordinary one:
+    2^-115: 1e-6, 2^-120: 4e-5, 2^-125: 1e-3 relative error, fp32 subnormals are lost altogether (the fp32 matrix
+    instruction stays exact down to 2^-125).  Infinite operands give NaN (x - high(x) is inf - inf) where the fp32
+    instruction gives inf: not finite either way, and nothing else is touched."""
+    with kfac.default_options():
+        n, d = 64, 40
+        layer = wl.fc_layer(n, d, d, bias=0)
+        grad = np.random.default_rng(6).standard_normal((n, d)).astype(np.float32).reshape(n, d, 1, 1)
+
+        def mixed_error(e):
+            rng = np.random.default_rng(5)
+            act = rng.standard_normal((n, d)).astype(np.float32)
+            act[:, :8] = np.sign(act[:, :8]) * (1.0 + np.abs(act[:, :8]) % 1.0) * np.float32(2.0 ** e)   # magnitudes in [2^e, 2^(e+1))
+            act = act.reshape(n, d, 1, 1)
+            A, _ = P.run_stats([layer], [act], [grad], 0.0, False)
+            Ar, _ = oracle.kfac_stats(tuple(layer), act, grad, 0.0, False, None, None)
+            hA = P.host(A[0])
+            ordinary = np.abs(hA[8:, 8:] - Ar[8:, 8:]).max() / np.abs(Ar[8:, 8:]).max()
+            assert ordinary < 2e-6
+            # tiny x tiny lies below the fp32 range in the oracle's values as well
+            assert np.all(hA[:8, :8] == 0.0) and np.all(np.abs(Ar[:8, :8]) < 2.0 ** -149)
+            return np.abs(hA[:8, 8:] - Ar[:8, 8:]).max() / np.abs(Ar[:8, 8:]).max()
+
+        assert mixed_error(-100) < 2e-6
+        assert mixed_error(-110) < 2e-6
+        assert 1e-6 < mixed_error(-120) < 1e-3       # documented loss: about 4e-5
+        act2 = np.random.default_rng(7).standard_normal((n, d)).astype(np.float32)
+        act2[3, 5] = np.inf
+        A2, _ = P.run_stats([layer], [act2.reshape(n, d, 1, 1)], [grad], 0.0, False)
+        hA2 = P.host(A2[0])
+        assert not np.isfinite(hA2[5, :]).any() and not np.isfinite(hA2[:, 5]).any()     # row / column of the infinite input
+        keep = np.ones(d, bool); keep[5] = False
+        assert np.isfinite(hA2[np.ix_(keep, keep)]).all()                                # nothing else is touched

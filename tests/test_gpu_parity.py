@@ -405,13 +405,14 @@ def test_config2_conv3x3_full_size(gpu):
 
 
 # ------------------------------------------------------------------ fused step
-def _fused_vs_separate(layers, mask, early_n, monkeypatch, env=None):
+def _fused_vs_separate(layers, mask, early_n, opts=None):
     """kfac_step against the oracle and against the three separate calls, two steps (the
     second with the running average and, if a mask is given, stale inverses for the rest)."""
-    monkeypatch.setenv("KFAC_EARLY_N", str(early_n))   # read when the context is created
-    for k, v in (env or {}).items():
-        monkeypatch.setenv(k, v)
-    ctx = kfac.Context(layers)
+    base = kfac._default_opts
+    fields = {} if base is None else {k: getattr(base, k) for k, _ in base._fields_ if k != "struct_size"}
+    fields.update(opts or {})
+    fields["early_n"] = early_n
+    ctx = kfac.Context(layers, opts=kfac.options(**fields))
     n = len(layers)
     mk = lambda: ([torch.full((L.dA, L.dA), float("nan"), device="cuda") for L in layers],
                   [torch.full((L.dG, L.dG), float("nan"), device="cuda") for L in layers])
@@ -470,27 +471,51 @@ FUSED_LAYERS = [
 
 
 @pytest.mark.parametrize("early_n", [100, 300, 100000])
-def test_fused_step_all_layers(gpu, monkeypatch, early_n):
+def test_fused_step_all_layers(gpu, early_n):
     """early_n = 100: five layers take the early path on the auxiliary streams; 300: two;
     100000: none (everything in order on the context's stream)."""
-    _fused_vs_separate(FUSED_LAYERS, None, early_n, monkeypatch)
+    _fused_vs_separate(FUSED_LAYERS, None, early_n)
 
 
-@pytest.mark.parametrize("env", [
-    {"KFAC_CHUNK_GF": "0.0001"},                          # factor launches of the later phases in 8 parts (some empty)
-    {"KFAC_CHUNK_GF": "0.002", "KFAC_INV_STREAMS": "2"},  # a few parts; one auxiliary stream for everything
-    {"KFAC_PIPE": "0", "KFAC_INV_STREAMS": "3"},          # phases one after the other on the context's stream
-    {"KFAC_INV_STREAMS": "1"},                            # no auxiliary streams at all
+@pytest.mark.parametrize("opts", [
+    {"chunk_gflop": 0.0001},                              # factor launches of the later phases in 8 parts (some empty)
+    {"chunk_gflop": 0.002, "streams": 2},                 # a few parts; one auxiliary stream for everything
+    {"pipeline_phases": 0, "streams": 3},                 # phases one after the other on the context's stream
+    {"streams": 1},                                       # no auxiliary streams at all
 ])
-def test_fused_step_schedules(gpu, monkeypatch, env):
+def test_fused_step_schedules(gpu, opts):
     """The schedule variants of the fused step give the same results."""
-    _fused_vs_separate(FUSED_LAYERS, None, 100, monkeypatch, env)
-    _fused_vs_separate(FUSED_LAYERS, [True, False, True, True, False, False], 100, monkeypatch, env)
+    _fused_vs_separate(FUSED_LAYERS, None, 100, opts)
+    _fused_vs_separate(FUSED_LAYERS, [True, False, True, True, False, False], 100, opts)
 
 
-def test_fused_step_stale_subset(gpu, monkeypatch):
-    _fused_vs_separate(FUSED_LAYERS, [True, False, False, True, True, False], 100, monkeypatch)
+def test_fused_step_stale_subset(gpu):
+    _fused_vs_separate(FUSED_LAYERS, [True, False, False, True, True, False], 100)
 
 
-def test_fused_step_nothing_inverted(gpu, monkeypatch):
-    _fused_vs_separate(FUSED_LAYERS, [False] * len(FUSED_LAYERS), 100, monkeypatch)
+def test_fused_step_nothing_inverted(gpu):
+    _fused_vs_separate(FUSED_LAYERS, [False] * len(FUSED_LAYERS), 100)
+
+
+def test_binding_refuses_wrongly_sized_tensors(gpu):
+    """The library sees only pointers; the binding compares every tensor's element count with the layer's
+    dimensions and raises before anything is launched."""
+    L = wl.conv_layer(2, 3, 4, 3, 1, 1, 5)
+    ctx = kfac.Context([L])
+    act, grad = dev(wl.make_act(L, 1)), dev(wl.make_grad_out(L, 1))
+    A, G = torch.zeros(L.dA, L.dA, device="cuda"), torch.zeros(L.dG, L.dG, device="cuda")
+    small = torch.zeros(L.dA * L.dA - 1, device="cuda")
+    with pytest.raises(ValueError):
+        kfac.kfac_stats(ctx, [L], kfac.KFAC_F32, [act[:1].contiguous()], [grad], 0.0, False, [A], [G])
+    with pytest.raises(ValueError):
+        kfac.kfac_stats(ctx, [L], kfac.KFAC_F32, [act], [grad], 0.0, False, [small], [G])
+    with pytest.raises(ValueError):
+        kfac.kfac_invert(ctx, [L], [A], [G], 1e-3, [small], [torch.zeros_like(G)])
+    with pytest.raises(ValueError):
+        kfac.kfac_precondition(ctx, [L], [G], [A], [torch.zeros(L.dG, L.dA - 1, device="cuda")], [torch.zeros(L.dG, L.dA, device="cuda")])
+    with pytest.raises(ValueError):
+        kfac.kfac_im2col(ctx, L, kfac.KFAC_F32, act, torch.zeros(L.c_in * 9, L.M - 1, device="cuda"), L.M)
+    with pytest.raises(ValueError):
+        kfac.bn_unitwise_precondition(ctx, 4, [8], [torch.zeros(4, 7, device="cuda")], [torch.zeros(4, 8, device="cuda")], 0.0, 1e-6,
+                                      [torch.zeros(8, 3, device="cuda")], [torch.zeros(8, device="cuda")], [torch.zeros(8, device="cuda")])
+    ctx.close()

@@ -363,10 +363,15 @@ def test_paper_facts_golden():
     assert sum(1 for L in layers if L.h_in > 1) == facts["resnet50_conv"] == len(bns)
     c = facts["example_c_out"]
     assert c in [C for C, _ in bns]
-    # unit-wise BN: 4 c^2 -> 4 c numbers; our [C,3] state keeps the 3 unique ones of each 2x2 block
-    assert 4 * c * c // (4 * c) == c
-    n = 577
-    assert len(np.triu_indices(n)[0]) == n * (n + 1) // 2
+    # Sec. 4.2: the unit-wise approximation keeps one 2x2 block per channel instead of the 2c x 2c matrix; the
+    # oracle's state holds the three distinct entries of each (symmetric) block
+    gg, gb = wl.make_bn_grads(4, c, 3)
+    F, og, ob = oracle.bn_unitwise_precondition(gg, gb, 0.0, 1e-6)
+    assert F.shape == (c, 3) and og.shape == (c,) and ob.shape == (c,)
+    # Sec. 5.2: a symmetric d x d statistic is communicated as d (d + 1) / 2 elements
+    from oracle import pack as o_pack
+    d = 37
+    assert o_pack.pack_upper([np.zeros((d, d), np.float32)]).size == d * (d + 1) // 2
 
 
 def test_accumulating_micro_batches_gives_the_whole_batch_statistics():
