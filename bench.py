@@ -54,135 +54,186 @@ def main():
     torch.cuda.set_device(0)
     kfac.lib()
     cfg = args.config
+    in_dtype = kfac.KFAC_BF16 if args.dtype == "bf16" else kfac.KFAC_F32
+
+    class Job:
+        """One layer list resident in HBM: inputs, factors, inverses, outputs, a context, and the calls of a step."""
+
+        def __init__(self, layers, bns, seed_cfg, dtype_name, subset=None, schedule="fused", opts=None, device_inputs=False,
+                     share=None):
+            self.layers, self.n, self.N = layers, len(layers), layers[0].N
+            self.in_dtype = kfac.KFAC_BF16 if dtype_name == "bf16" else kfac.KFAC_F32
+            tdt = torch.bfloat16 if dtype_name == "bf16" else torch.float32
+            self.spatial_mean = any(L.h_in > 1 for L in layers)   # the conv configurations ask for spatially averaged output gradients
+            self.schedule = schedule
+            self.subset = list(range(self.n)) if subset is None else list(subset)
+            self.Cs = [C for C, _ in bns]
+            if share is not None:      # the same tensors in another element type
+                self.acts = [x.to(tdt) for x in share.acts]
+                self.grads = [x.to(tdt) for x in share.grads]
+                self.gws, self.bn_gg, self.bn_gb = share.gws, share.bn_gg, share.bn_gb
+            elif device_inputs:
+                # timing only: the same distributions drawn on the device (the seeded host arrays of the
+                # parity tests take minutes to generate at batch 128)
+                g = torch.Generator(device="cuda"); g.manual_seed(1000 * seed_cfg)
+                self.acts = [torch.randn(L.N, L.c_in, L.h_in, L.w_in, device="cuda", generator=g).clamp_(min=0).to(tdt) for L in layers]
+                self.grads = [(torch.randn(L.N, L.c_out, L.h, L.w, device="cuda", generator=g) * wl.GRAD_SIGMA).to(tdt) for L in layers]
+                self.gws = [torch.randn(L.dG, L.dA, device="cuda", generator=g) * wl.GRAD_SIGMA for L in layers]
+                self.bn_gg = [torch.randn(self.N, C, device="cuda", generator=g) * wl.GRAD_SIGMA for C in self.Cs]
+                self.bn_gb = [torch.randn(self.N, C, device="cuda", generator=g) * wl.GRAD_SIGMA for C in self.Cs]
+            else:
+                self.acts, self.grads, self.gws = [], [], []
+                for i, L in enumerate(layers):
+                    s = wl.layer_seed(seed_cfg, i)
+                    self.acts.append(torch.from_numpy(wl.make_act(L, s)).cuda().to(tdt))
+                    self.grads.append(torch.from_numpy(wl.make_grad_out(L, s)).cuda().to(tdt))
+                    self.gws.append(torch.from_numpy(wl.make_grad_W(L, s)).cuda())
+                self.bn_gg, self.bn_gb = [], []
+                for i, C in enumerate(self.Cs):
+                    gg, gb = wl.make_bn_grads(self.N, C, wl.layer_seed(seed_cfg, 100 + i))
+                    self.bn_gg.append(torch.from_numpy(gg).cuda())
+                    self.bn_gb.append(torch.from_numpy(gb).cuda())
+            self.sub_layers = [layers[i] for i in self.subset]
+            self.ctx = kfac.Context(layers, self.in_dtype, extra_layer_lists=[self.sub_layers], opts=opts)
+            self.A = [torch.zeros(L.dA, L.dA, device="cuda") for L in layers]
+            self.G = [torch.zeros(L.dG, L.dG, device="cuda") for L in layers]
+            self.Ai = [torch.zeros_like(x) for x in self.A]
+            self.Gi = [torch.zeros_like(x) for x in self.G]
+            self.U = [torch.zeros(L.dG, L.dA, device="cuda") for L in layers]
+            self.info = torch.zeros(2 * self.n, dtype=torch.int32, device="cuda")
+            self.F = [torch.zeros(C, 3, device="cuda") for C in self.Cs]
+            self.og = [torch.zeros(C, device="cuda") for C in self.Cs]
+            self.ob = [torch.zeros(C, device="cuda") for C in self.Cs]
+
+        def stats(self, decay):
+            kfac.kfac_stats(self.ctx, self.layers, self.in_dtype, self.acts, self.grads, decay, self.spatial_mean, self.A, self.G)
+
+        def invert(self, idx):
+            pick = lambda xs: [xs[i] for i in idx]
+            kfac.kfac_invert(self.ctx, pick(self.layers), pick(self.A), pick(self.G), wl.GAMMA, pick(self.Ai), pick(self.Gi),
+                             None, self.info)
+
+        def precond(self):
+            kfac.kfac_precondition(self.ctx, self.layers, self.Gi, self.Ai, self.gws, self.U)
+
+        def bn(self, decay):
+            if self.Cs:
+                kfac.bn_unitwise_precondition(self.ctx, self.N, self.Cs, self.bn_gg, self.bn_gb, decay, wl.BN_LAMBDA, self.F,
+                                              self.og, self.ob)
+
+        def step(self, decay, idx):
+            if self.schedule == "fused":
+                mask = [False] * self.n
+                for i in idx:
+                    mask[i] = True
+                kfac.kfac_step(self.ctx, self.layers, self.in_dtype, self.acts, self.grads, decay, self.spatial_mean, self.A,
+                               self.G, mask, wl.GAMMA, self.Ai, self.Gi, None, self.info, self.gws, self.U)
+            else:
+                self.stats(decay)
+                self.invert(idx)
+                self.precond()
+            self.bn(decay)
+
+        def start(self, warmup):
+            """Step 0 initialises every running average and every inverse; then the warm-up steps (all untimed)."""
+            self.step(0.0, list(range(self.n)))
+            torch.cuda.synchronize()
+            assert int(self.info.abs().sum().item()) == 0, "a factor was not positive definite"
+            for _ in range(warmup):
+                self.step(wl.DECAY, self.subset)
+            torch.cuda.synchronize()
+
+        def timed(self, steps):
+            """K steps between two synchronisations; events between the steps give the per-step spread."""
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+            # The interpreter's heap is collected and frozen first: a full collection over the objects of the imported
+            # modules takes 30-40 ms here, and one falling into the timed region would show up as a step of 45 ms.
+            # The collector stays enabled.
+            import gc
+            gc.collect()
+            gc.freeze()
+            torch.cuda.synchronize()
+            ev[0].record()
+            for k in range(steps):
+                self.step(wl.DECAY, self.subset)
+                ev[k + 1].record()
+            torch.cuda.synchronize()
+            gc.unfreeze()
+            per = [ev[k].elapsed_time(ev[k + 1]) for k in range(steps)]
+            log("per-step ms: " + " ".join("%.2f" % v for v in per))
+            per.sort()
+            assert int(self.info.abs().sum().item()) == 0
+            return ev[0].elapsed_time(ev[steps]) / steps, per[len(per) // 2], per[0]
+
+        def stage_times(self, reps):
+            out = {"stats": 0.0, "invert": 0.0, "precondition": 0.0, "bn": 0.0}
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+            for _ in range(reps):
+                ev[0].record(); self.stats(wl.DECAY)
+                ev[1].record(); self.invert(self.subset)
+                ev[2].record(); self.precond()
+                ev[3].record(); self.bn(wl.DECAY)
+                ev[4].record()
+                torch.cuda.synchronize()
+                for j, k in enumerate(out):
+                    out[k] += ev[j].elapsed_time(ev[j + 1]) / reps
+            return out
+
+        def close(self):
+            self.ctx.close()
+
     layers = wl.config_layers(cfg)
     N = layers[0].N
     bns = wl.resnet50_layers(N)[1] if cfg >= 4 else []
-    in_dtype = kfac.KFAC_BF16 if args.dtype == "bf16" else kfac.KFAC_F32
-    tdt = torch.bfloat16 if args.dtype == "bf16" else torch.float32
-    spatial_mean = cfg >= 2          # the conv configurations ask for spatially averaged output gradients
-    stale = cfg == 5
     n = len(layers)
+    stale = cfg == 5
 
     # ---------------------------------------------------------------- inputs (seeded, host -> HBM)
     t0 = time.time()
-    acts, grads, gws = [], [], []
-    for i, L in enumerate(layers):
-        s = wl.layer_seed(cfg, i)
-        a, g = wl.make_act(L, s), wl.make_grad_out(L, s)
-        acts.append(torch.from_numpy(a).cuda().to(tdt))
-        grads.append(torch.from_numpy(g).cuda().to(tdt))
-        gws.append(torch.from_numpy(wl.make_grad_W(L, s)).cuda())
-        del a, g
-    bn_gg, bn_gb = [], []
-    for i, (C, _) in enumerate(bns):
-        gg, gb = wl.make_bn_grads(N, C, wl.layer_seed(cfg, 100 + i))
-        bn_gg.append(torch.from_numpy(gg).cuda())
-        bn_gb.append(torch.from_numpy(gb).cuda())
-    log("inputs generated and uploaded in %.1f s" % (time.time() - t0))
-
     subset = list(wl.stale_subset(n, seed=0)) if stale else list(range(n))
-    sub_layers = [layers[i] for i in subset]
-    ctx = kfac.Context(layers, in_dtype, extra_layer_lists=[sub_layers])
-    A = [torch.zeros(L.dA, L.dA, device="cuda") for L in layers]
-    G = [torch.zeros(L.dG, L.dG, device="cuda") for L in layers]
-    Ai = [torch.zeros_like(x) for x in A]
-    Gi = [torch.zeros_like(x) for x in G]
-    U = [torch.zeros(L.dG, L.dA, device="cuda") for L in layers]
-    info = torch.zeros(2 * n, dtype=torch.int32, device="cuda")
-    Cs = [C for C, _ in bns]
-    F = [torch.zeros(C, 3, device="cuda") for C in Cs]
-    og = [torch.zeros(C, device="cuda") for C in Cs]
-    ob = [torch.zeros(C, device="cuda") for C in Cs]
+    job = Job(layers, bns, cfg, args.dtype, subset, args.schedule)
+    log("inputs generated and uploaded in %.1f s" % (time.time() - t0))
+    acts, grads, gws, A, G, Ai, Gi, U, info = job.acts, job.grads, job.gws, job.A, job.G, job.Ai, job.Gi, job.U, job.info
+    bn_gg, bn_gb, F, og, ob, Cs = job.bn_gg, job.bn_gb, job.F, job.og, job.ob, job.Cs
+    sub_layers, spatial_mean, ctx = job.sub_layers, job.spatial_mean, job.ctx
+    stats, invert, precond, bn, step = job.stats, job.invert, job.precond, job.bn, job.step
 
     def sel(xs, idx):
         return [xs[i] for i in idx]
 
-    def stats(decay):
-        kfac.kfac_stats(ctx, layers, in_dtype, acts, grads, decay, spatial_mean, A, G)
-
-    def invert(idx):
-        kfac.kfac_invert(ctx, sel(layers, idx), sel(A, idx), sel(G, idx), wl.GAMMA, sel(Ai, idx), sel(Gi, idx),
-                         None, info)
-
-    def precond():
-        kfac.kfac_precondition(ctx, layers, Gi, Ai, gws, U)
-
-    def bn(decay):
-        if Cs:
-            kfac.bn_unitwise_precondition(ctx, N, Cs, bn_gg, bn_gb, decay, wl.BN_LAMBDA, F, og, ob)
-
-    def step(decay, idx):
-        if args.schedule == "fused":
-            mask = [False] * n
-            for i in idx:
-                mask[i] = True
-            kfac.kfac_step(ctx, layers, in_dtype, acts, grads, decay, spatial_mean, A, G, mask, wl.GAMMA, Ai, Gi,
-                           None, info, gws, U)
-        else:
-            stats(decay)
-            invert(idx)
-            precond()
-        bn(decay)
-
-    # step 0 initialises every running average and every inverse (untimed)
-    step(0.0, list(range(n)))
-    torch.cuda.synchronize()
-    assert int(info.abs().sum().item()) == 0, "a factor was not positive definite"
-    for _ in range(args.warmup):
-        step(wl.DECAY, subset)
-    torch.cuda.synchronize()
+    job.start(args.warmup)
 
     # ---------------------------------------------------------------- timed region
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(args.steps):
-        step(wl.DECAY, subset)
-    e1.record()
-    torch.cuda.synchronize()
-    ms_per_step = e0.elapsed_time(e1) / args.steps
-    assert int(info.abs().sum().item()) == 0
+    ms_per_step, median_ms, min_ms = job.timed(args.steps)
     assert all(bool(torch.isfinite(u).all().item()) for u in U)
 
     # ---------------------------------------------------------------- per-stage and per-kernel times
     # (the stages one after the other, whatever the schedule of the timed region: with the fused
     # schedule they overlap and have no separate durations)
-    stage_ms = {"stats": 0.0, "invert": 0.0, "precondition": 0.0, "bn": 0.0}
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
     args.profile_steps = max(1, args.profile_steps)
-    for _ in range(args.profile_steps):
-        ev[0].record(); stats(wl.DECAY)
-        ev[1].record(); invert(subset)
-        ev[2].record(); precond()
-        ev[3].record(); bn(wl.DECAY)
-        ev[4].record()
-        torch.cuda.synchronize()
-        for j, k in enumerate(stage_ms):
-            stage_ms[k] += ev[j].elapsed_time(ev[j + 1]) / args.profile_steps
+    stage_ms = job.stage_times(args.profile_steps)
     # per-kernel durations (HIP events around every launch, on the launch's own stream), also
-    # taken with the stages one after the other: under the fused schedule launches of different
-    # streams wait for each other's compute units and an event pair then brackets the wait too
-    # ... and on one stream (a context of its own, created with KFAC_INV_STREAMS=1): launches of
-    # concurrent inversion chains would otherwise stretch each other's event pairs
-    prev = os.environ.get("KFAC_INV_STREAMS")
-    os.environ["KFAC_INV_STREAMS"] = "1"
-    main_ctx, ctx = ctx, kfac.Context(layers, in_dtype, extra_layer_lists=[sub_layers])
-    if prev is None:
-        del os.environ["KFAC_INV_STREAMS"]
-    else:
-        os.environ["KFAC_INV_STREAMS"] = prev
-    stats(wl.DECAY); invert(subset); precond(); bn(wl.DECAY)      # warm-up of the new context
+    # taken with the stages one after the other and on one stream (a context of its own with
+    # options.streams = 1): under the fused schedule launches of different streams wait for each
+    # other's compute units and an event pair then brackets the wait too
+    pjob = Job(layers, bns, cfg, args.dtype, subset, "staged", opts=kfac.options(streams=1), share=job)
+    for x, y in zip(pjob.A + pjob.G + pjob.Ai + pjob.Gi, A + G + Ai + Gi):
+        x.copy_(y)
+    pjob.stats(wl.DECAY); pjob.invert(subset); pjob.precond(); pjob.bn(wl.DECAY)      # warm-up of the new context
     torch.cuda.synchronize()
-    kfac.kfac_profile_enable(ctx, True)
+    kfac.kfac_profile_enable(pjob.ctx, True)
+    entries, stage_exec = [], {"stats": [0.0, 0.0], "invert": [0.0, 0.0], "precondition": [0.0, 0.0], "bn": [0.0, 0.0]}
     for _ in range(args.profile_steps):
-        stats(wl.DECAY)
-        invert(subset)
-        precond()
-        bn(wl.DECAY)
-    entries = kfac.kfac_profile_read(ctx, 16384)
-    kfac.kfac_profile_enable(ctx, False)
-    ctx.close()
-    ctx = main_ctx
+        for name, call in (("stats", lambda: pjob.stats(wl.DECAY)), ("invert", lambda: pjob.invert(subset)),
+                           ("precondition", pjob.precond), ("bn", lambda: pjob.bn(wl.DECAY))):
+            call()
+            part = kfac.kfac_profile_read(pjob.ctx, 16384)
+            entries += part
+            stage_exec[name][0] += sum(e["flops"] for e in part) / args.profile_steps    # flops the launches execute
+            stage_exec[name][1] += sum(e["bytes"] for e in part) / args.profile_steps    # bytes of the copy-like launches
+    kfac.kfac_profile_enable(pjob.ctx, False)
+    pjob.close()
+    del pjob
     kernels = {}
     for e in entries:
         name = e["kernel"] + ("_tile%d" % (128 if e["variant"] == 0 else 64) if e["kernel"].startswith("gemm_f") or
@@ -202,37 +253,49 @@ def main():
     else:
         dom_name = max(kernels, key=lambda q: kernels[q]["ms"])
     dom = kernels[dom_name]
-    # HBM traffic per launch of that kernel: measured separately with rocprofv3 --pmc (FETCH_SIZE
-    # and WRITE_SIZE, scaled by what they read for the plain copy kernel of the same run) and
-    # kept with the profile summaries; null if no measurement covers this configuration
-    traffic = None
+    # HBM traffic per launch of that kernel: measured separately with rocprofv3 --pmc (FETCH_SIZE and
+    # WRITE_SIZE, scaled by what they read for the plain copy kernel of the same run) and kept with
+    # the profile summaries.  The record says which kernel, how many launches per step and which
+    # commit it was measured at; it is only reported if this run's dominant kernel matches it.
+    traffic, traffic_source = None, None
     try:
         with open(os.path.join(ROOT, "profiles", "pmc_traffic.json")) as f:
             for rec in json.load(f)["records"]:
-                if rec["config"] == cfg and rec["dtype"] == args.dtype and rec["kernel"] == dom_name:
-                    traffic = rec["bytes_per_launch"]
+                if rec["config"] == cfg and rec["dtype"] == args.dtype and rec["schedule_of_profile"] == "staged":
+                    if rec["kernel"] == dom_name and abs(rec["launches_per_step"] - dom["launches"]) < 0.5:
+                        traffic = rec["bytes_per_launch"]
+                        traffic_source = {"file": "profiles/" + rec["summary"], "measured_at_commit": rec["commit"],
+                                          "kernel": rec["kernel"], "launches_per_step": rec["launches_per_step"]}
+                    else:
+                        traffic_source = {"refused": "the record in profiles/pmc_traffic.json is for %s with %g launches per "
+                                                     "step; this run's dominant kernel is %s with %g"
+                                                     % (rec["kernel"], rec["launches_per_step"], dom_name, dom["launches"])}
     except (OSError, ValueError, KeyError):
-        traffic = None
+        traffic, traffic_source = None, None
     gemm_dt = "bf16" if dom_name.startswith("gemm_bf16") else "f32"
+    split_mode = "split" in dom_name
+    # the peak of the pipe the kernel issues on: the fp32 matrix instruction, the bf16 one, or -- fp32 products
+    # formed by six bf16 instructions each -- a sixth of the bf16 peak in fp32-equivalent flops
+    pipe_peak = PEAK_TFLOPS["bf16"] / 6.0 if split_mode else PEAK_TFLOPS[gemm_dt]
     if dom["flops"] > 0:
         achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
-        roofline = {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_TFLOPS[gemm_dt],
-                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS[gemm_dt], 4), "traffic": traffic,
+        roofline = {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 3), "peak": round(pipe_peak, 1),
+                    "unit": "TFLOP/s", "frac": round(achieved / pipe_peak, 4), "traffic": traffic,
+                    "traffic_source": traffic_source,
                     "launches_per_step": dom["launches"], "avg_launch_ms": round(dom["ms"] / dom["launches"], 4)}
-        if "split" in dom_name:
-            # fp32 operands, every product formed from three bf16 planes per operand by six bf16 matrix
-            # instructions: achieved counts the fp32 flops of the contraction and is set against the fp32 peak
-            # (it can exceed it); the instructions executed are six times that, set against the bf16 peak
+        if split_mode:
+            roofline["frac_of_fp32_mfma_peak"] = round(achieved / PEAK_TFLOPS["f32"], 4)
             roofline["executed_bf16_tflops"] = round(6.0 * achieved, 1)
-            roofline["frac_of_bf16_peak_executed"] = round(6.0 * achieved / PEAK_TFLOPS["bf16"], 4)
-            roofline["note"] = ("fp32 contraction computed by six bf16 matrix instructions per product block (operands "
-                                "split exactly into three bf16 planes, fp32 accumulation, fp32-level accuracy): achieved "
-                                "= fp32 flops of the contraction, peak = the fp32 MFMA peak; KFAC_SPLIT=0 selects the "
-                                "fp32 instruction (object fp32_instruction)")
+            roofline["note"] = ("fp32 contraction computed by six bf16 matrix instructions per product block (operands split "
+                                "exactly into three bf16 planes, fp32 accumulation, fp32-level accuracy): achieved = fp32 flops "
+                                "of the contraction, peak = the dense bf16 peak / 6 (the pipe the kernel issues on); a loop of "
+                                "nothing but these matrix instructions on random operands reaches 0.72 of that peak on this "
+                                "GPU (power limit: 1.82 GHz instead of 2.4; profiles/mfma_bf16_peak_loop.txt)")
     else:
         achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
         roofline = {"kernel": dom_name, "bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": traffic,
+                    "traffic_source": traffic_source,
                     "launches_per_step": dom["launches"], "avg_launch_ms": round(dom["ms"] / dom["launches"], 4)}
 
     fl = {"stats_A": 0.0, "stats_G": 0.0, "inv": 0.0, "precond": 0.0}
@@ -244,14 +307,34 @@ def main():
     total_flops = sum(fl.values())
     fi_flops = fl["stats_A"] + fl["stats_G"] + fl["inv"]
     fi_ms = stage_ms["stats"] + stage_ms["invert"]
+    # which roofline bounds each stage (stages one after the other): the three dense stages against the matrix
+    # pipe they issue on (algorithmic flops = the definitions, executed = what the launches multiply out),
+    # the unit-wise BatchNorm call against HBM
+    mat_peak = PEAK_TFLOPS["bf16"] / 6.0 if (args.dtype == "f32" and split_mode) else PEAK_TFLOPS["f32"]
+    roofline_by_stage = {}
+    for name, alg in (("stats", fl["stats_A"] + fl["stats_G"]), ("invert", fl["inv"]), ("precondition", fl["precond"])):
+        ms = stage_ms[name]
+        roofline_by_stage[name] = {"bound": "mfma", "ms": round(ms, 4), "algorithmic_gflop": round(alg / 1e9, 2),
+                                   "executed_gflop": round(stage_exec[name][0] / 1e9, 2),
+                                   "tflops": round(alg / (ms * 1e-3) / 1e12, 2),
+                                   "executed_tflops": round(stage_exec[name][0] / (ms * 1e-3) / 1e12, 2),
+                                   "peak": round(mat_peak, 1), "unit": "TFLOP/s",
+                                   "frac": round(stage_exec[name][0] / (ms * 1e-3) / 1e12 / mat_peak, 4)}
+    if stage_ms["bn"] > 0 and stage_exec["bn"][1] > 0:
+        gbs = stage_exec["bn"][1] / (stage_ms["bn"] * 1e-3) / 1e9
+        roofline_by_stage["bn"] = {"bound": "hbm", "ms": round(stage_ms["bn"], 4), "gbytes": round(stage_exec["bn"][1] / 1e9, 4),
+                                   "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
+                                   "note": "one launch of 7 MB: latency, not bandwidth"}
 
-    # ---------------------------------------------------------------- oracle on the host cores (bounded sample)
+    # ---------------------------------------------------------------- oracle on the host cores
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
-        # a sample of layers whose oracle time stays within tens of seconds
-        budget_flops = 500e9
+        # the same step on the oracle: every layer once, with the timed step's decay on top of the running averages
+        # the GPU holds.  Configurations whose oracle step would take minutes (batch 128) are bounded to the layers
+        # that fit about 30 s, cheapest first, and the value is then that sample's time, not a step's.
         order = sorted(range(n), key=lambda i: sum(wl.flops(layers[i]).values()))
+        budget_flops = 1.6e12 if N <= 32 else 1.0e12
         sample, acc = [], 0.0
         for i in order:
             f = sum(wl.flops(layers[i]).values())
@@ -259,24 +342,33 @@ def main():
                 break
             sample.append(i)
             acc += f
+        whole = len(sample) == n
         t_cpu = 0.0
-        worst = 0.0
         for i in sample:
             L = layers[i]
-            s = wl.layer_seed(cfg, i)
             a, g, gw = acts[i].float().cpu().numpy(), grads[i].float().cpu().numpy(), gws[i].cpu().numpy()
+            A0, G0 = A[i].cpu().numpy(), G[i].cpu().numpy()
             t1 = time.perf_counter()
-            Ar, Gr = oracle.kfac_stats(tuple(L), a, g, 0.0, spatial_mean, None, None)
-            Air, Gir, _, _ = oracle.kfac_invert(Ar, Gr, wl.GAMMA)
+            Ar, Gr = oracle.kfac_stats(tuple(L), a, g, wl.DECAY, spatial_mean, A0, G0)
+            if i in subset:
+                Air, Gir, _, _ = oracle.kfac_invert(Ar, Gr, wl.GAMMA)
+            else:
+                Air, Gir = Ai[i].cpu().numpy(), Gi[i].cpu().numpy()
             oracle.kfac_precondition(Gir, Air, gw)
             t_cpu += time.perf_counter() - t1
-        est_ms = t_cpu * 1e3 * total_flops / acc
-        cpu_baseline = {"value": round(est_ms, 1), "unit": "ms", "cores": oracle.num_threads(), "kind": "oracle",
-                        "sample": "float64 oracle on the %d cheapest layers of the set (%.1f GFLOP algorithmic, "
-                                  "%.2f s measured), scaled to the whole step by algorithmic flops (x%.1f)"
-                                  % (len(sample), acc / 1e9, t_cpu, total_flops / acc)}
+        if Cs and whole:
+            t1 = time.perf_counter()
+            for gg, gb in zip(bn_gg, bn_gb):
+                oracle.bn_unitwise_precondition(gg.cpu().numpy(), gb.cpu().numpy(), wl.DECAY, wl.BN_LAMBDA)
+            t_cpu += time.perf_counter() - t1
+        cpu_baseline = {"value": round(t_cpu * 1e3, 1), "unit": "ms", "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": ("one whole step of the float64 oracle, measured: all %d layers (factors with decay %.2f, "
+                                   "inverses of the %d refreshed layers, preconditioning) and the %d BatchNorm layers; "
+                                   "%.1f GFLOP algorithmic" % (n, wl.DECAY, len(subset), len(Cs), total_flops / 1e9)) if whole else
+                                  ("NOT a whole step: the %d cheapest of %d layers (%.1f of %.1f GFLOP algorithmic), measured, "
+                                   "no extrapolation" % (len(sample), n, acc / 1e9, total_flops / 1e9))}
 
-    staleness = adaptive = layout_obj = packing = updating = full_bn = split_obj = None
+    staleness = adaptive = layout_obj = packing = updating = full_bn = split_obj = other_configs = None
     extras = not args.no_extras      # the calls beside the step are left out of profiler runs of the step itself
     if extras:
         # ---------------------------------------------------------------- beside the step: staleness of the factors
@@ -308,19 +400,15 @@ def main():
 
 
         # ------------------------------------------------------------ beside the step: the fp32 matrix instruction
-        # (KFAC_SPLIT=0: every product by v_mfma_f32_32x32x2_f32 instead of six bf16 instructions on split operands;
-        # the same step on a context of its own, its results compared with those of the default mode)
+        # (options.fp32_products = KFAC_PRODUCTS_FP32_MFMA: every product by v_mfma_f32_32x32x2_f32 instead of six bf16
+        # instructions on split operands; the same step on a context of its own, its results compared with those of
+        # the default mode)
         split_obj = None
         if args.dtype == "f32":
             U_ref = [u.clone() for u in U]
             A_ref = [a.clone() for a in A]
-            prev_split = os.environ.get("KFAC_SPLIT")
-            os.environ["KFAC_SPLIT"] = "0"
-            main_ctx2, ctx = ctx, kfac.Context(layers, in_dtype, extra_layer_lists=[sub_layers])
-            if prev_split is None:
-                del os.environ["KFAC_SPLIT"]
-            else:
-                os.environ["KFAC_SPLIT"] = prev_split
+            job.ctx = kfac.Context(layers, in_dtype, extra_layer_lists=[sub_layers],
+                                   opts=kfac.options(fp32_products=kfac.KFAC_PRODUCTS_FP32_MFMA))
             step(wl.DECAY, subset)
             torch.cuda.synchronize()
             s0.record()
@@ -345,10 +433,10 @@ def main():
                                       "invert": round(ev3[1].elapsed_time(ev3[2]), 4),
                                       "precondition": round(ev3[2].elapsed_time(ev3[3]), 4)},
                          "max_rel_diff_to_default": {"A": da, "U": du},
-                         "note": "the timed step with KFAC_SPLIT=0 (every product of the GEMM kernel by the fp32 matrix "
-                                 "instruction); not the mode of the headline value"}
-            ctx.close()
-            ctx = main_ctx2
+                         "note": "the timed step on a context with fp32_products = KFAC_PRODUCTS_FP32_MFMA (every product of "
+                                 "the GEMM kernel by the fp32 matrix instruction); not the mode of the headline value"}
+            job.ctx.close()
+            job.ctx = ctx
             step(wl.DECAY, subset)       # the buffers back to the default mode's results
             torch.cuda.synchronize()
 
@@ -523,6 +611,41 @@ def main():
             del Ff, Ffi
             bctx.close()
 
+    if extras and cfg == 4 and args.dtype == "f32":
+        # ------------------------------------------------------------ beside the headline: the other configurations
+        # (short runs of the same step: 2 warm-up + 5 timed, stages once; configuration 4 with bf16 inputs reuses the
+        # tensors of this run rounded to bf16; batch 128 and the v1.5 layer set draw their inputs on the device)
+        other_configs = {}
+
+        def quick(name, jb, note):
+            jb.start(2)
+            mean, med, mn = jb.timed(5)
+            st = jb.stage_times(1)
+            fls = {"stats": sum(wl.flops(L)["stats_A"] + wl.flops(L)["stats_G"] for L in jb.layers),
+                   "invert": sum(wl.flops(jb.layers[i])["inv"] for i in jb.subset),
+                   "precondition": sum(wl.flops(L)["precond"] for L in jb.layers)}
+            other_configs[name] = {"ms_per_step": round(mean, 4), "median_ms": round(med, 4), "min_ms": round(mn, 4),
+                                   "stage_ms": {k: round(v, 4) for k, v in st.items()},
+                                   "algorithmic_gflop": {k: round(v / 1e9, 3) for k, v in fls.items()},
+                                   "step_tflops": round(sum(fls.values()) / (mean * 1e-3) / 1e12, 3),
+                                   "layers": jb.n, "batch": jb.N, "inverted_layers": len(jb.subset), "note": note}
+            jb.close()
+
+        quick("config4_bf16_inputs", Job(layers, bns, 4, "bf16", None, "fused", share=job),
+              "configuration 4 with bf16 activations / output gradients (statistics from bf16 operands; inversion and "
+              "preconditioning in fp32)")
+        for c, note in ((1, "single FC layer 64->32, batch 32: launch-latency bound"),
+                        (2, "one conv3x3 64->64 at 56x56, batch 32"),
+                        (3, "conv3x3 512->512 at 7x7 (A 4609x4609) plus FC 2048->1000, batch 32")):
+            quick("config%d" % c, Job(wl.config_layers(c), [], c, "f32"), note)
+        l15, bn15 = wl.resnet50_layers(32, "v1.5")
+        quick("resnet50_v1_5_batch32", Job(l15, bn15, 6, "f32", device_inputs=True),
+              "the v1.5 variant of the layer set (stride on the 3x3 of stages 3-5: three 3x3 / stride-2 layers on the patch "
+              "path with contractions up to 25 088), inputs drawn on the device")
+        l5 = wl.config_layers(5)
+        quick("config5", Job(l5, wl.resnet50_layers(128)[1], 5, "f32", list(wl.stale_subset(len(l5), seed=0)), device_inputs=True),
+              "full layer set at batch 128, inverses refreshed for the seeded 25 % subset, inputs drawn on the device")
+
     out = {
         "metric": "K-FAC step ms for ResNet-50 layer set; factor+inverse TFLOP/s vs MFMA peak",
         "value": round(ms_per_step, 4),
@@ -531,6 +654,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "median_ms": round(median_ms, 4),
+        "min_ms": round(min_ms, 4),
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
@@ -544,13 +669,13 @@ def main():
             5: "full ResNet-50 layer set, batch 128, inverses refreshed for a seeded 25% subset"}[cfg]),
             "layers": n, "bn_layers": len(Cs), "batch": N, "inverted_layers": len(subset),
             "g_spatial_mean": bool(spatial_mean), "schedule": args.schedule,
-            "fp32_products": ("fp32 matrix instruction" if os.environ.get("KFAC_SPLIT", "1") == "0" else
-                              "six bf16 matrix instructions on operands split exactly into three bf16 planes, fp32 "
-                              "accumulation (fp32-level accuracy; KFAC_SPLIT=0 selects the fp32 matrix instruction)")},
+            "fp32_products": ("six bf16 matrix instructions on operands split exactly into three bf16 planes, fp32 "
+                              "accumulation (fp32-level accuracy; the library's default; object fp32_instruction: the same "
+                              "step with the fp32 matrix instruction)")},
         "algorithmic_gflop": {k: round(v / 1e9, 2) for k, v in fl.items()},
         "step_tflops": round(total_flops / (ms_per_step * 1e-3) / 1e12, 3),
         "factor_inverse_tflops": round(fi_flops / (fi_ms * 1e-3) / 1e12, 3),
-        "factor_inverse_frac_of_mfma_peak": round(fi_flops / (fi_ms * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype if args.dtype == "f32" else "f32"], 4),
+        "factor_inverse_frac_of_fp32_mfma_peak": round(fi_flops / (fi_ms * 1e-3) / 1e12 / PEAK_TFLOPS["f32"], 4),
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
         "stage_ms_note": "stages run one after the other (separate calls); the fused schedule overlaps them",
         "flops_note": "algorithmic_gflop, step_tflops and factor_inverse_tflops count the flops of the definitions "
@@ -561,7 +686,9 @@ def main():
                         "gbs": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["bytes"] else None}
                     for k, v in sorted(kernels.items())},
         "roofline": roofline,
+        "roofline_by_stage": roofline_by_stage,
         "cpu_baseline": cpu_baseline,
+        "configs": other_configs,
         "staleness": staleness,
         "adaptive_refresh": adaptive,
         "nhwc_inputs": layout_obj,

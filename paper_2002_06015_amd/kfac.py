@@ -187,9 +187,19 @@ def _ptrs(tensors: Optional[Sequence[Optional[torch.Tensor]]], n: int, dtype=Non
     return arr
 
 
+_sizes_cache: dict = {}
+
+
 def _sizes(layers: Sequence) -> dict:
-    """Element counts of the per-layer tensors, from the library's own kfac_layer_dims."""
-    out = {"act": [], "grad_out": [], "A": [], "G": [], "W": [], "nhwc_act": [], "nhwc_grad": []}
+    """Element counts of the per-layer tensors, from the library's own kfac_layer_dims (kept per layer
+    list: a training loop passes the same list every step)."""
+    key = tuple(tuple(int(v) for v in L) for L in layers)
+    hit = _sizes_cache.get(key)
+    if hit is not None:
+        return hit
+    if len(_sizes_cache) > 64:
+        _sizes_cache.clear()
+    out = _sizes_cache[key] = {"act": [], "grad_out": [], "A": [], "G": [], "W": []}
     for L in layers:
         dA, dG, h, w = kfac_layer_dims(L)
         N, c_in, c_out, _, _, _, h_in, w_in, _ = [int(v) for v in L]
