@@ -533,6 +533,10 @@ __device__ __forceinline__ void gemm_f32_mainloop(const GemmProblem &P, int tm, 
 // on the way into LDS, which holds one stage of three planes (two barriers per tile; the second
 // workgroup of the compute unit computes while this one stores).
 constexpr int LDQ = 40;     // LDS row length in bf16 (32 + 8 pad: 80-byte rows, conflict-free 16-byte reads)
+// Rows of a group of 8 are stored in the order 0 4 1 5 2 6 3 7: the 8-byte stores of 16 lanes cover two
+// rows, and rows 80 bytes apart share 4 of their 16 banks while rows 4 apart (320 bytes) share none.  The
+// fragment reads take the same 8 rows per group of lanes as before.
+__device__ __forceinline__ int lds_row(int r) { return (r & ~7) | ((r & 1) << 2) | ((r >> 1) & 3); }
 
 // two fp32 values -> their packed (h, m, l) bf16 pairs, low half = first value
 __device__ __forceinline__ void split_pair(float x0, float x1, unsigned &h, unsigned &m, unsigned &l)
@@ -559,7 +563,7 @@ __device__ __forceinline__ void store_split(const LoaderF32<BR> &ld, const float
         uint2 h, m, l;
         split_pair(v[0], v[1], h.x, m.x, l.x);
         split_pair(v[2], v[3], h.y, m.y, l.y);
-        unsigned short *dst = rows + (ld.r0 + 32 * s) * LDQ + ld.kq;
+        unsigned short *dst = rows + (lds_row(ld.r0) + 32 * s) * LDQ + ld.kq;
         *(uint2 *)dst = h;
         *(uint2 *)(dst + plane) = m;
         *(uint2 *)(dst + 2 * plane) = l;
@@ -585,7 +589,7 @@ __device__ __forceinline__ float fill_remainder_split(const Operand &op, int til
     split_pair(x[2], x[3], v[0].y, v[1].y, v[2].y);
 #pragma unroll
     for (int q = 0; q < 3; ++q) {
-        unsigned short *dst = rows + q * plane + tid * LDQ;
+        unsigned short *dst = rows + q * plane + lds_row(tid) * LDQ;
         *(uint4 *)dst = uint4{v[q].x, v[q].y, 0u, 0u};
 #pragma unroll
         for (int w = 1; w < 4; ++w) *(uint4 *)(dst + 8 * w) = uint4{0u, 0u, 0u, 0u};
@@ -642,8 +646,8 @@ __device__ __forceinline__ void gemm_split_mainloop(const GemmProblem &P, int tm
     };
     // v_mfma_f32_32x32x16_bf16: a lane supplies 8 consecutive k of row lane % 32, the half-waves
     // two different groups of 8; step u of a tile uses k = 16u + 8*half + 0..7 for both operands
-    const int off_a = (wave_m * 32 * TM + l32) * LDQ + 8 * half;
-    const int off_b = BM * LDQ + (wave_n * 32 * TN + l32) * LDQ + 8 * half;
+    const int off_a = (wave_m * 32 * TM + lds_row(l32)) * LDQ + 8 * half;
+    const int off_b = BM * LDQ + (wave_n * 32 * TN + lds_row(l32)) * LDQ + 8 * half;
     // One step: the fragments of the h and m planes and of l' are requested up front, the l
     // fragments of the a operand take over the registers of h once its products are issued (their
     // latency lies under the m products).  Fixed order (the scheduling barriers keep the compiler
