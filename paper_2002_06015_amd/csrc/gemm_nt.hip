@@ -538,18 +538,6 @@ constexpr int LDQ = 40;     // LDS row length in bf16 (32 + 8 pad: 80-byte rows,
 // fragment reads take the same 8 rows per group of lanes as before.
 __device__ __forceinline__ int lds_row(int r) { return (r & ~7) | ((r & 1) << 2) | ((r >> 1) & 3); }
 
-// two fp32 values -> their packed (h, m, l) bf16 pairs, low half = first value
-__device__ __forceinline__ void split_pair(float x0, float x1, unsigned &h, unsigned &m, unsigned &l)
-{
-    const unsigned b0 = __float_as_uint(x0), b1 = __float_as_uint(x1);
-    const float r0 = x0 - __uint_as_float(b0 & 0xFFFF0000u), r1 = x1 - __uint_as_float(b1 & 0xFFFF0000u);
-    const unsigned c0 = __float_as_uint(r0), c1 = __float_as_uint(r1);
-    const float q0 = r0 - __uint_as_float(c0 & 0xFFFF0000u), q1 = r1 - __uint_as_float(c1 & 0xFFFF0000u);
-    h = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
-    m = __builtin_amdgcn_perm(c1, c0, 0x07060302u);
-    l = __builtin_amdgcn_perm(__float_as_uint(q1), __float_as_uint(q0), 0x07060302u);
-}
-
 // the staged tile of one operand into its rows of the three planes (plane stride in bf16 units)
 template <int BR, bool RS>
 __device__ __forceinline__ void store_split(const LoaderF32<BR> &ld, const floatx4 (&reg)[BR / 32], unsigned short *rows,

@@ -210,7 +210,6 @@ hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t s)
 // row p and the pivot itself are overwritten directly.  A non-positive pivot is reported.
 typedef float lb_floatx16 __attribute__((ext_vector_type(16)));
 typedef float lb_floatx4 __attribute__((ext_vector_type(4)));
-constexpr int LB_LD = 36;          // LDS row length of the panels (floats): conflict-free 16-byte reads
 constexpr int LB_MAXN = 288;
 
 __device__ __forceinline__ float lb_readlane(float x, int lane)
@@ -218,16 +217,62 @@ __device__ __forceinline__ float lb_readlane(float x, int lane)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
 }
 
-// 16 products of a 32x32x32 block product: rows of `pa` (A operand) and `pb` (B operand, NT
-// form) are LDS panel rows; each half-wave takes 16 of the 32 k (the same for both operands).
-__device__ __forceinline__ void lb_mma32(lb_floatx16 &acc, const float *pa, const float *pb)
+// The panels live in LDS as three bf16 planes per value (x = h + m + l exactly, see split_pair): rows of
+// LB_LQ bf16 (32 + 8 pad: 80-byte rows, conflict-free 16-byte fragment reads), plane stride given.
+typedef __bf16 lb_bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short lb_ushortx8 __attribute__((ext_vector_type(8)));
+constexpr int LB_LQ = 40;
+constexpr int LB_PLANE = LB_MAXN * LB_LQ;     // plane stride of the R and P panels (bf16 elements)
+constexpr int LB_DPLANE = 32 * LB_LQ;         // of D
+
+// acc += A B^T for two 32 x 32 blocks given as plane rows: `pa`, `pb` point at the h plane of the lane's
+// row (lane % 32) plus 8 * (lane / 32), the half-wave's part of each 16-wide k step.  Six bf16 matrix
+// instructions per step form the product to fp32 accuracy: h h' + h m' + h l' + m h' + m m' + l h'.
+__device__ __forceinline__ void lb_mma_planes(lb_floatx16 &acc, const unsigned short *pa, int plane_a,
+                                              const unsigned short *pb, int plane_b)
+{
+    auto rd = [](const unsigned short *p) { return __builtin_bit_cast(lb_bf16x8, *(const lb_ushortx8 *)p); };
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const lb_bf16x8 ah = rd(pa + 16 * u), am = rd(pa + plane_a + 16 * u), al = rd(pa + 2 * plane_a + 16 * u);
+        const lb_bf16x8 bh = rd(pb + 16 * u), bm = rd(pb + plane_b + 16 * u), bl = rd(pb + 2 * plane_b + 16 * u);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bm, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bh, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bm, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc, 0, 0, 0);
+    }
+}
+
+// A 32 x 32 tile held in the accumulator layout (register v: row 8 (v / 4) + 4 h + v % 4, lane % 32: column)
+// into plane rows, split on the way.
+//   lb_store_rows: tile element (row, column) goes to panel row row0 + row, position column  (2-byte stores)
+//   lb_store_cols: ... to panel row row0 + column, position row: the transposed tile; the four rows of a
+//                  register group are four adjacent positions, one 8-byte store per plane
+__device__ __forceinline__ void lb_store_rows(unsigned short *panel, int plane, int row0, const lb_floatx16 &t, int l32, int h)
 {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const lb_floatx4 fa = *(const lb_floatx4 *)(pa + 4 * q);
-        const lb_floatx4 fb = *(const lb_floatx4 *)(pb + 4 * q);
+    for (int v = 0; v < 16; v += 2) {
+        unsigned hh, mm, ll;
+        split_pair(t[v], t[v + 1], hh, mm, ll);
+        unsigned short *d = panel + (row0 + 8 * (v >> 2) + 4 * h + (v & 3)) * LB_LQ + l32;
+        d[0] = (unsigned short)hh; d[LB_LQ] = (unsigned short)(hh >> 16);
+        d[plane] = (unsigned short)mm; d[plane + LB_LQ] = (unsigned short)(mm >> 16);
+        d[2 * plane] = (unsigned short)ll; d[2 * plane + LB_LQ] = (unsigned short)(ll >> 16);
+    }
+}
+__device__ __forceinline__ void lb_store_cols(unsigned short *panel, int plane, int row0, const lb_floatx16 &t, int l32, int h)
+{
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[e], fb[e], acc, 0, 0, 0);
+    for (int g = 0; g < 4; ++g) {
+        uint2 hh, mm, ll;
+        split_pair(t[4 * g], t[4 * g + 1], hh.x, mm.x, ll.x);
+        split_pair(t[4 * g + 2], t[4 * g + 3], hh.y, mm.y, ll.y);
+        unsigned short *d = panel + (row0 + l32) * LB_LQ + 8 * g + 4 * h;
+        *(uint2 *)d = hh;
+        *(uint2 *)(d + plane) = mm;
+        *(uint2 *)(d + 2 * plane) = ll;
     }
 }
 
@@ -235,7 +280,7 @@ __device__ __forceinline__ void lb_mma32(lb_floatx16 &acc, const float *pa, cons
 // (register slot `slot`): leaves D = (-N_kk)^-1 in the slot and in Dl.  Returns the 1-based
 // index (within the matrix) of the first non-positive pivot, or 0.
 template <int NSLOT>
-__device__ __forceinline__ int lb_sweep_diag(lb_floatx16 (&acc)[NSLOT], int slot, int k, int l32, int h, float *Dl)
+__device__ __forceinline__ int lb_sweep_diag(lb_floatx16 (&acc)[NSLOT], int slot, int k, int l32, int h, unsigned short *Dq)
 {
     lb_floatx16 sg;
 #pragma unroll
@@ -277,14 +322,14 @@ __device__ __forceinline__ int lb_sweep_diag(lb_floatx16 (&acc)[NSLOT], int slot
         sg = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, sg, 0, 0, 0);
         xcur = xnext;
     }
-    // sg = -(that tile)^-1 = -D
+    // sg = -(that tile)^-1 = -D;  D is symmetric, so its planes can be written transposed (8-byte stores)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-        const float x = -sg[v];
-        Dl[(8 * (v >> 2) + 4 * h + (v & 3)) * LB_LD + l32] = x;
+        sg[v] = -sg[v];
 #pragma unroll
-        for (int s = 0; s < NSLOT; ++s) acc[s][v] = (slot == s) ? x : acc[s][v];
+        for (int s = 0; s < NSLOT; ++s) acc[s][v] = (slot == s) ? sg[v] : acc[s][v];
     }
+    lb_store_cols(Dq, LB_DPLANE, 0, sg, l32, h);
     return badl;
 }
 
@@ -309,10 +354,10 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
                                                           int32_t *__restrict__ info)
 {
     extern __shared__ __attribute__((aligned(16))) float lb_lds[];
-    float *Rp = lb_lds;                         // [LB_MAXN][LB_LD] column panel R
-    float *Pp = Rp + LB_MAXN * LB_LD;           // [LB_MAXN][LB_LD] P = R D
-    float *Dl = Pp + LB_MAXN * LB_LD;           // [32][LB_LD]      D
-    float *sc = Dl + 32 * LB_LD;                // [LB_MAXN]        diagonal scaling
+    unsigned short *Rq = (unsigned short *)lb_lds;   // [3][LB_MAXN][LB_LQ] column panel R, three bf16 planes
+    unsigned short *Pq = Rq + 3 * LB_PLANE;          // [3][LB_MAXN][LB_LQ] P = R D
+    unsigned short *Dq = Pq + 3 * LB_PLANE;          // [3][32][LB_LQ]      D
+    float *sc = (float *)(Dq + 3 * LB_DPLANE);       // [LB_MAXN]           diagonal scaling
     __shared__ int bad_s;
 
     const LeafJob J = jobs[blockIdx.x];
@@ -376,7 +421,7 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
     if (w == diag_owner(0)) {
         int l32 = l32_, h = h_;
         asm volatile("" : "+v"(l32), "+v"(h));
-        const int badl = lb_sweep_diag<NSLOT>(acc, diag_slot(0), 0, l32, h, Dl);
+        const int badl = lb_sweep_diag<NSLOT>(acc, diag_slot(0), 0, l32, h, Dq);
         if (badl != 0 && lane == 0) bad_s = badl;
     }
     for (int k = 0; k < T; ++k) {
@@ -384,43 +429,45 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
         // sweep and the LDS addresses below would be hoisted and kept live across the whole loop)
         int l32 = l32_, h = h_;
         asm volatile("" : "+v"(l32), "+v"(h));
-        // ---- column panel R of block k into LDS
+        // ---- column panel R of block k into LDS (planes): R_i = N_ik, from tile (i,k) for i > k and from
+        // the transpose of tile (k,i) for i < k
+#pragma unroll
+        for (int s = 0; s < NSLOT; ++s) {
+            if (ti[s] < 0) continue;
+            if (tj[s] == k && ti[s] > k) lb_store_rows(Rq, LB_PLANE, 32 * ti[s], acc[s], l32, h);
+            else if (ti[s] == k && tj[s] < k) lb_store_cols(Rq, LB_PLANE, 32 * tj[s], acc[s], l32, h);
+        }
+        __syncthreads();   // R and (from the previous step or the prologue) D of block k are in LDS
+        // ---- the tiles of block row / column k take their new value P_i = R_i D (tile (i,k)) or its transpose
+        // D R_i^T (tile (k,i)) straight from the product, and put P into LDS for everybody else
 #pragma unroll
         for (int s = 0; s < NSLOT; ++s) {
             if (ti[s] < 0) continue;
             if (tj[s] == k && ti[s] > k) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    Rp[(32 * ti[s] + 8 * (v >> 2) + 4 * h + (v & 3)) * LB_LD + l32] = acc[s][v];
+                for (int v = 0; v < 16; ++v) acc[s][v] = 0.f;
+                lb_mma_planes(acc[s], Rq + (32 * ti[s] + l32) * LB_LQ + 8 * h, LB_PLANE, Dq + l32 * LB_LQ + 8 * h, LB_DPLANE);
+                lb_store_rows(Pq, LB_PLANE, 32 * ti[s], acc[s], l32, h);
             } else if (ti[s] == k && tj[s] < k) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    Rp[(32 * tj[s] + l32) * LB_LD + 8 * (v >> 2) + 4 * h + (v & 3)] = acc[s][v];
+                for (int v = 0; v < 16; ++v) acc[s][v] = 0.f;
+                lb_mma_planes(acc[s], Dq + l32 * LB_LQ + 8 * h, LB_DPLANE, Rq + (32 * tj[s] + l32) * LB_LQ + 8 * h, LB_PLANE);
+                lb_store_cols(Pq, LB_PLANE, 32 * tj[s], acc[s], l32, h);
             }
         }
-        __syncthreads();   // R and (from the previous step or the prologue) D of block k are in LDS
-        // ---- P_i = R_i D for the T - 1 row blocks i != k, one per wavefront
-        if (w < T - 1) {
-            const int i = w < k ? w : w + 1;
-            lb_floatx16 pt;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) pt[v] = 0.f;
-            lb_mma32(pt, Rp + (32 * i + l32) * LB_LD + 16 * h, Dl + l32 * LB_LD + 16 * h);   // D is symmetric
-#pragma unroll
-            for (int v = 0; v < 16; ++v) Pp[(32 * i + 8 * (v >> 2) + 4 * h + (v & 3)) * LB_LD + l32] = pt[v];
-        }
         __syncthreads();   // P is in LDS; D of block k is no longer needed
-        // ---- row / column k take P, every other tile N_ij += P_i R_j^T
+        // ---- every other tile N_ij += P_i R_j^T
         const bool sweeps_next = k + 1 < T && w == diag_owner(k + 1);   // holds the diagonal tile of block k + 1
         if (sweeps_next) {
             const int slot = diag_slot(k + 1);
 #pragma unroll
             for (int s = 0; s < NSLOT; ++s)
                 if (s == slot)
-                    lb_mma32(acc[s], Pp + (32 * (k + 1) + l32) * LB_LD + 16 * h, Rp + (32 * (k + 1) + l32) * LB_LD + 16 * h);
+                    lb_mma_planes(acc[s], Pq + (32 * (k + 1) + l32) * LB_LQ + 8 * h, LB_PLANE,
+                                  Rq + (32 * (k + 1) + l32) * LB_LQ + 8 * h, LB_PLANE);
             // the sweep is one long dependent chain: let it issue ahead of the other wavefronts' products
             __builtin_amdgcn_s_setprio(3);
-            const int badl = lb_sweep_diag<NSLOT>(acc, slot, k + 1, l32, h, Dl);
+            const int badl = lb_sweep_diag<NSLOT>(acc, slot, k + 1, l32, h, Dq);
             __builtin_amdgcn_s_setprio(0);
             if (badl != 0 && lane == 0 && bad_s == 0) bad_s = badl;   // blocks are swept in order: the first one stays
         }
@@ -428,17 +475,9 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
         for (int s = 0; s < NSLOT; ++s) {
             if (ti[s] < 0) continue;
             const int i = ti[s], j = tj[s];
-            if (i == k && j == k) continue;
+            if (i == k || j == k) continue;
             if (sweeps_next && i == k + 1 && j == k + 1) continue;
-            if (j == k) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[s][v] = Pp[(32 * i + 8 * (v >> 2) + 4 * h + (v & 3)) * LB_LD + l32];
-            } else if (i == k) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[s][v] = Pp[(32 * j + l32) * LB_LD + 8 * (v >> 2) + 4 * h + (v & 3)];
-            } else {
-                lb_mma32(acc[s], Pp + (32 * i + l32) * LB_LD + 16 * h, Rp + (32 * j + l32) * LB_LD + 16 * h);
-            }
+            lb_mma_planes(acc[s], Pq + (32 * i + l32) * LB_LQ + 8 * h, LB_PLANE, Rq + (32 * j + l32) * LB_LQ + 8 * h, LB_PLANE);
         }
         __syncthreads();
     }
@@ -474,7 +513,8 @@ template <int NSLOT>
 static hipError_t launch_leaf_block(const LeafJob *jobs_dev, int n_jobs, const float *damp_dev, int32_t *info,
                                     hipStream_t s)
 {
-    constexpr size_t lds_bytes = (size_t)(2 * LB_MAXN * LB_LD + 32 * LB_LD + LB_MAXN) * sizeof(float);
+    constexpr size_t lds_bytes = (size_t)(6 * LB_PLANE + 3 * LB_DPLANE) * sizeof(unsigned short) + LB_MAXN * sizeof(float);
+    static_assert(lds_bytes >= (size_t)16 * 32 * 33 * sizeof(float), "the per-wavefront staging tiles of the final store fit");
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)leaf_block_kernel<NSLOT>,

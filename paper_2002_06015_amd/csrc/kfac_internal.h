@@ -210,6 +210,22 @@ struct PackJob {
 };
 constexpr int kPackChunk = 4096;
 
+#ifdef __HIPCC__
+// ---- fp32 as the exact sum of three bf16 values (8 + 8 + 8 significant bits) -------------------------
+// two fp32 values -> their packed (h, m, l) bf16 pairs, low half = first value
+__device__ __forceinline__ void split_pair(float x0, float x1, unsigned &h, unsigned &m, unsigned &l)
+{
+    const unsigned b0 = __float_as_uint(x0), b1 = __float_as_uint(x1);
+    const float r0 = x0 - __uint_as_float(b0 & 0xFFFF0000u), r1 = x1 - __uint_as_float(b1 & 0xFFFF0000u);
+    const unsigned c0 = __float_as_uint(r0), c1 = __float_as_uint(r1);
+    const float q0 = r0 - __uint_as_float(c0 & 0xFFFF0000u), q1 = r1 - __uint_as_float(c1 & 0xFFFF0000u);
+    h = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
+    m = __builtin_amdgcn_perm(c1, c0, 0x07060302u);
+    l = __builtin_amdgcn_perm(__float_as_uint(q1), __float_as_uint(q0), 0x07060302u);
+}
+
+#endif
+
 // ---- launchers (implemented in the kernel files) -----------------------------------
 hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, int n_probs,
                        int total_wgs, int tile_cfg, int dtype, hipStream_t s);
