@@ -41,6 +41,8 @@ def main():
     ap.add_argument("--schedule", choices=["fused", "staged"], default="fused",
                     help="fused: one kfac_step call per step (factors, inverses and preconditioning planned as one "
                          "graph); staged: kfac_stats, kfac_invert, kfac_precondition one after the other")
+    ap.add_argument("--opt", action="append", default=[], metavar="FIELD=VALUE",
+                    help="a kfac_options field for the context of the timed step (e.g. --opt streams=2)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are built); use --gpus 1", file=sys.stderr)
@@ -191,7 +193,14 @@ def main():
     # ---------------------------------------------------------------- inputs (seeded, host -> HBM)
     t0 = time.time()
     subset = list(wl.stale_subset(n, seed=0)) if stale else list(range(n))
-    job = Job(layers, bns, cfg, args.dtype, subset, args.schedule)
+    main_opts = None
+    if args.opt:
+        fields = {}
+        for kv in args.opt:
+            k, v = kv.split("=", 1)
+            fields[k] = float(v) if k == "chunk_gflop" else int(v)
+        main_opts = kfac.options(**fields)
+    job = Job(layers, bns, cfg, args.dtype, subset, args.schedule, opts=main_opts)
     log("inputs generated and uploaded in %.1f s" % (time.time() - t0))
     acts, grads, gws, A, G, Ai, Gi, U, info = job.acts, job.grads, job.gws, job.A, job.G, job.Ai, job.Gi, job.U, job.info
     bn_gg, bn_gb, F, og, ob, Cs = job.bn_gg, job.bn_gb, job.F, job.og, job.ob, job.Cs

@@ -103,6 +103,116 @@ hipError_t launch_pad(const PadJob *jobs_dev, int n_jobs, int total_wgs, hipStre
     return hipGetLastError();
 }
 
+// bf16 activations: see PadJobBF16.  8 elements (16 bytes) per thread.
+typedef unsigned short corr_ushortx8 __attribute__((ext_vector_type(8)));
+
+__global__ __launch_bounds__(256) void pad_bf16_kernel(const PadJobBF16 *__restrict__ jobs, int n_jobs)
+{
+    const int wg = blockIdx.x;
+    int lo = 0, hi = n_jobs;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (jobs[mid].wg_start <= wg) lo = mid; else hi = mid;
+    }
+    const PadJobBF16 &J = jobs[lo];
+    long long idx = (long long)(wg - J.wg_start) * 256 + threadIdx.x;
+    const int H = J.H, W = J.W, Wp = J.Wp, PP = J.Hp * Wp, y0 = J.Hp - H, x0 = Wp - W;
+    const long long planes = (long long)J.N * J.C;
+    // part 1: the five shifted copies of the padded tensor.  One thread per aligned group of 8 positions:
+    // it gathers the 12 values P(g0 - 2 .. g0 + 9) once (coordinates by one division, then stepped) and
+    // writes the group of every copy from that window.
+    const long long per_copy = J.copy_elems / 8;
+    if (idx < per_copy) {
+        const long long g0 = idx * 8 - J.front_slack - 2;
+        const long long total = planes * PP;
+        long long plane = 0;
+        int yp = 0, xp = 0;
+        if (g0 > 0 && g0 < total) {
+            plane = g0 / PP;
+            const int r = (int)(g0 - plane * PP);
+            yp = r / Wp;
+            xp = r - yp * Wp;
+        }
+        const unsigned short *sp = J.src + plane * H * W;
+        unsigned short win[12];
+#pragma unroll
+        for (int e = 0; e < 12; ++e) {
+            const long long g = g0 + e;
+            unsigned short x = 0;
+            if (g >= 0 && g < total) {
+                if (g0 <= 0) {   // the window starts in the front slack: position g is (plane 0, g / Wp, g % Wp)
+                    yp = (int)(g / Wp);
+                    xp = (int)(g - (long long)yp * Wp);
+                }
+                if (yp >= y0 && xp >= x0) x = sp[(yp - y0) * W + (xp - x0)];
+                if (++xp == Wp) {
+                    xp = 0;
+                    if (++yp == J.Hp) { yp = 0; sp += H * W; }
+                }
+            }
+            win[e] = x;
+        }
+#pragma unroll
+        for (int q = 0; q < 5; ++q) {
+            corr_ushortx8 v;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = win[q + e];
+            *(corr_ushortx8 *)(J.padded + (long long)q * J.copy_elems + idx * 8) = v;
+        }
+        return;
+    }
+    idx -= per_copy;
+    // part 2: border rows, three copies shifted by 0, 1, 2 (one element per thread from here on)
+    if (idx < 3 * J.rows_elems) {
+        const int d = (int)(idx / J.rows_elems);
+        const long long k = idx - d * J.rows_elems + d;      // copy d at position p holds the line buffer at p + d
+        const long long row_elems = (long long)J.C * J.N * J.Lw;
+        unsigned short x = 0;
+        if (k < 2 * row_elems) {
+            const int which = (int)(k / row_elems);
+            const long long r = k - which * row_elems;
+            const int qx = (int)(r % J.Lw);
+            const long long cn = r / J.Lw;
+            const int n = (int)(cn % J.N), c = (int)(cn / J.N);
+            if (qx < W) x = J.src[((long long)n * J.C + c) * H * W + (long long)(which ? H - 1 : 0) * W + qx];
+        }
+        J.rows[idx] = x;
+        return;
+    }
+    idx -= 3 * J.rows_elems;
+    if (idx < 3 * J.cols_elems) {
+        const int d = (int)(idx / J.cols_elems);
+        const long long k = idx - d * J.cols_elems + d;
+        const long long col_elems = (long long)J.C * J.N * J.Lh;
+        unsigned short x = 0;
+        if (k < 2 * col_elems) {
+            const int which = (int)(k / col_elems);
+            const long long r = k - which * col_elems;
+            const int py = (int)(r % J.Lh);
+            const long long cn = r / J.Lh;
+            const int n = (int)(cn % J.N), c = (int)(cn / J.N);
+            if (py < H) x = J.src[((long long)n * J.C + c) * H * W + (long long)py * W + (which ? W - 1 : 0)];
+        }
+        J.cols[idx] = x;
+        return;
+    }
+    idx -= 3 * J.cols_elems;
+    if (idx < 4LL * J.C * J.Ln) {
+        const int which = (int)(idx / ((long long)J.C * J.Ln));
+        const long long r = idx - (long long)which * J.C * J.Ln;
+        const int n = (int)(r % J.Ln), c = (int)(r / J.Ln);
+        const int py = (which & 2) ? H - 1 : 0, qx = (which & 1) ? W - 1 : 0;
+        J.corners[idx] = n < J.N ? J.src[((long long)n * J.C + c) * H * W + (long long)py * W + qx] : (unsigned short)0;
+    }
+}
+
+hipError_t launch_pad_bf16(const PadJobBF16 *jobs_dev, int n_jobs, int total_wgs, hipStream_t s)
+{
+    if (total_wgs <= 0) return hipSuccess;
+    pad_bf16_kernel<<<dim3(total_wgs), dim3(256), 0, s>>>(jobs_dev, n_jobs);
+    return hipGetLastError();
+}
+
 // One workgroup per row i = (c, ky, kx) of A (plus one for the bias row), threads along the row.
 // Which Gram matrices entry (c', ky', kx') comes from depends only on (ky, kx, ky', kx'): the
 // workgroup first builds that table of 9 entries.  A displacement that is stored the other way

@@ -11,6 +11,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
 #include <vector>
 
 using namespace kfac;
@@ -444,6 +445,8 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
     const size_t chunk_align = a.in == KFAC_BF16 ? 16 : 4;
     std::vector<PatchJob> pjobs;
     std::vector<PadJob> padjobs;
+    std::vector<PadJobBF16> padbfjobs;
+    int padbf_wgs = 0;
     std::vector<AssembleJob> asmjobs;
     std::vector<GemmProblem> probs;
     int patch_wgs = 0, pad_wgs = 0, asm_wgs = 0;
@@ -488,33 +491,88 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         const int K = Ly.N * hw;
         const bool want_A = dry || (a.act && a.act[l]);
         const bool want_G = dry || (a.grad_out && a.grad_out[l]);
-        // 3x3 / stride 1 / pad 1 in fp32: 13 displaced correlations of the zero-padded image instead
-        // of the 81 C^2 products of the patch Gram matrix, if the padding does not eat the gain
-        // (at least two zero rows above and two zero columns left of every image; a few more if that
-        // is what makes the padded plane a whole number of 16-byte chunks; 26 PP < 81 hw flops-wise)
+        // 3x3 / stride 1 / pad 1: 13 displaced correlations of the zero-padded image instead of the
+        // 81 C^2 products of the patch Gram matrix, if the padding does not eat the gain (26 PP < 81 hw
+        // flops-wise).  fp32: at least two zero rows above and two zero columns left of every image, a
+        // few more if that is what makes the padded plane a whole number of 16-byte chunks.  bf16: the
+        // padded width a multiple of 8, so that a row displacement keeps 16-byte alignment (the column
+        // displacements come from shifted copies, see PadJobBF16).
+        const bool bf = a.in == KFAC_BF16;
         int Hp = 0, Wp = 0;
-        for (int eh = 2; eh <= 5; ++eh)
-            for (int ew = 2; ew <= 5; ++ew)
-                if (((h + eh) * (w + ew)) % 4 == 0 && (Hp == 0 || (h + eh) * (w + ew) < Hp * Wp)) { Hp = h + eh; Wp = w + ew; }
-        const bool corr = tun.corr && a.in == KFAC_F32 && Ly.k == 3 && Ly.stride == 1 && Ly.pad == 1 && h >= 3 &&
-                          w >= 3 && 2 * Hp * Wp <= 5 * hw;
+        if (bf) { Hp = h + 2; Wp = (int)align_up((size_t)w + 2, 8); }
+        else
+            for (int eh = 2; eh <= 5; ++eh)
+                for (int ew = 2; ew <= 5; ++ew)
+                    if (((h + eh) * (w + ew)) % 4 == 0 && (Hp == 0 || (h + eh) * (w + ew) < Hp * Wp)) { Hp = h + eh; Wp = w + ew; }
+        const bool corr = tun.corr && Ly.k == 3 && Ly.stride == 1 && Ly.pad == 1 && h >= 3 && w >= 3 &&
+                          2 * Hp * Wp <= 5 * hw;
         if (want_A && corr) {
             const int C = Ly.c_in, N = Ly.N, PP = Hp * Wp;
-            const int Lw = (int)align_up((size_t)w + 2, 4), Lh = (int)align_up((size_t)h + 2, 4);
-            PadJob J{};
-            J.src = dry ? nullptr : (const float *)a.act[l];
-            J.front_slack = (int)align_up((size_t)2 * Wp + 2, 4);
-            J.padded_floats = (long long)J.front_slack + (long long)N * C * PP + (long long)align_up((size_t)2 * Wp + 2, 4) + 4;
-            J.padded = (float *)arena.take((size_t)J.padded_floats * sizeof(float));
-            J.rows = (float *)arena.take(((size_t)2 * C * N * Lw + 4) * sizeof(float));
-            J.cols = (float *)arena.take(((size_t)2 * C * N * Lh + 4) * sizeof(float));
-            J.corners = (float *)arena.take(((size_t)4 * C * N + 4) * sizeof(float));
-            J.N = N; J.C = C; J.H = h; J.W = w; J.Hp = Hp; J.Wp = Wp; J.Lw = Lw; J.Lh = Lh;
-            J.wg_start = pad_wgs;
-            const long long threads = J.padded_floats / 4 + (2LL * C * N * Lw + 4) + (2LL * C * N * Lh + 4) + 4LL * C * N;
-            pad_wgs += (int)((threads + 255) / 256);
-            pad_bytes += 4.0 * ((double)N * C * hw + (double)J.padded_floats);
-            padjobs.push_back(J);
+            const int lal = bf ? 8 : 4;   // line lengths in whole 16-byte chunks
+            const int Lw = (int)align_up((size_t)w + 2, lal), Lh = (int)align_up((size_t)h + 2, lal);
+            // operands of the contractions: the image, the image displaced by (dy, dx), border lines shifted by d, corners
+            std::function<Operand(int, int)> image_op;
+            std::function<Operand(int, int)> row_op, col_op;   // (which, shift)
+            std::function<Operand(int)> corner_op;
+            int corner_K = N;
+            if (!bf) {
+                PadJob J{};
+                J.src = dry ? nullptr : (const float *)a.act[l];
+                J.front_slack = (int)align_up((size_t)2 * Wp + 2, 4);
+                J.padded_floats = (long long)J.front_slack + (long long)N * C * PP + (long long)align_up((size_t)2 * Wp + 2, 4) + 4;
+                J.padded = (float *)arena.take((size_t)J.padded_floats * sizeof(float));
+                J.rows = (float *)arena.take(((size_t)2 * C * N * Lw + 4) * sizeof(float));
+                J.cols = (float *)arena.take(((size_t)2 * C * N * Lh + 4) * sizeof(float));
+                J.corners = (float *)arena.take(((size_t)4 * C * N + 4) * sizeof(float));
+                J.N = N; J.C = C; J.H = h; J.W = w; J.Hp = Hp; J.Wp = Wp; J.Lw = Lw; J.Lh = Lh;
+                J.wg_start = pad_wgs;
+                const long long threads = J.padded_floats / 4 + (2LL * C * N * Lw + 4) + (2LL * C * N * Lh + 4) + 4LL * C * N;
+                pad_wgs += (int)((threads + 255) / 256);
+                pad_bytes += 4.0 * ((double)N * C * hw + (double)J.padded_floats);
+                padjobs.push_back(J);
+                image_op = [=](int dy, int dx) {
+                    Operand o{};
+                    o.base = J.padded + J.front_slack + dy * Wp + dx;
+                    o.row_stride = PP; o.batch_stride = (long long)C * PP; o.rows = C; o.hw = PP;
+                    return o;
+                };
+                row_op = [=](int which, int d) { return plain_operand(J.rows + (size_t)which * C * N * Lw + d, (long long)N * Lw, C, N * Lw); };
+                col_op = [=](int which, int d) { return plain_operand(J.cols + (size_t)which * C * N * Lh + d, (long long)N * Lh, C, N * Lh); };
+                corner_op = [=](int wc) { return plain_operand(J.corners + (size_t)wc * C * N, N, C, N); };
+            } else {
+                PadJobBF16 J{};
+                const int Ln = (int)align_up((size_t)N, 8);
+                J.src = dry ? nullptr : (const unsigned short *)a.act[l];
+                J.front_slack = (int)align_up((size_t)2 * Wp + 2, 8);
+                J.copy_elems = (long long)J.front_slack + (long long)N * C * PP + (long long)align_up((size_t)2 * Wp + 2, 8) + 8;
+                J.rows_elems = (long long)align_up((size_t)2 * C * N * Lw + 8, 8);
+                J.cols_elems = (long long)align_up((size_t)2 * C * N * Lh + 8, 8);
+                J.padded = (unsigned short *)arena.take((size_t)5 * J.copy_elems * 2);
+                J.rows = (unsigned short *)arena.take((size_t)3 * J.rows_elems * 2);
+                J.cols = (unsigned short *)arena.take((size_t)3 * J.cols_elems * 2);
+                J.corners = (unsigned short *)arena.take((size_t)4 * C * Ln * 2);
+                J.N = N; J.C = C; J.H = h; J.W = w; J.Hp = Hp; J.Wp = Wp; J.Lw = Lw; J.Lh = Lh; J.Ln = Ln;
+                J.wg_start = padbf_wgs;
+                const long long threads = J.copy_elems / 8 + 3 * J.rows_elems + 3 * J.cols_elems + 4LL * C * Ln;
+                padbf_wgs += (int)((threads + 255) / 256);
+                pad_bytes += 2.0 * ((double)N * C * hw + 5.0 * (double)J.copy_elems);
+                padbfjobs.push_back(J);
+                auto plain16 = [](const unsigned short *base, long long ld, int rows, int K) {
+                    Operand o{};
+                    o.base = base; o.row_stride = ld; o.batch_stride = 0; o.rows = rows; o.hw = std::max(K, 1) + 64;
+                    return o;
+                };
+                image_op = [=](int dy, int dx) {
+                    Operand o{};
+                    o.base = J.padded + (long long)(dx + 2) * J.copy_elems + J.front_slack + dy * Wp;
+                    o.row_stride = PP; o.batch_stride = (long long)C * PP; o.rows = C; o.hw = PP;
+                    return o;
+                };
+                row_op = [=](int which, int d) { return plain16(J.rows + (long long)d * J.rows_elems + (size_t)which * C * N * Lw, (long long)N * Lw, C, N * Lw); };
+                col_op = [=](int which, int d) { return plain16(J.cols + (long long)d * J.cols_elems + (size_t)which * C * N * Lh, (long long)N * Lh, C, N * Lh); };
+                corner_op = [=](int wc) { return plain16(J.corners + (size_t)wc * C * Ln, Ln, C, Ln); };
+                corner_K = Ln;
+            }
 
             AssembleJob S{};
             S.A = dry ? nullptr : a.A_ema[l];
@@ -544,27 +602,19 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
                 *out = P.C; *ld = ldc;
                 if (out_t) *out_t = zero_shift ? P.C : P.Ct;
             };
-            Operand img{};
-            img.base = J.padded + J.front_slack;
-            img.row_stride = PP; img.batch_stride = (long long)C * PP; img.rows = C; img.hw = PP;
+            const Operand img = image_op(0, 0);
             for (int slot = 0; slot < 13; ++slot) {
                 const int dy = slot < 3 ? 0 : (slot - 3) / 5 + 1, dx = slot < 3 ? slot : (slot - 3) % 5 - 2;
-                Operand sh = img;
-                sh.base = (const float *)img.base + dy * Wp + dx;
-                gram(img, sh, N * PP, slot == 0, &S.full[slot], &S.full_t[slot], &S.ld_full[slot]);
+                gram(img, image_op(dy, dx), N * PP, slot == 0, &S.full[slot], &S.full_t[slot], &S.ld_full[slot]);
             }
             for (int which = 0; which < 2; ++which)
                 for (int d = 0; d < 3; ++d) {
-                    const float *rb = J.rows + (size_t)which * C * N * Lw, *cb = J.cols + (size_t)which * C * N * Lh;
-                    gram(plain_operand(rb, (long long)N * Lw, C, N * Lw), plain_operand(rb + d, (long long)N * Lw, C, N * Lw),
-                         N * Lw, d == 0, &S.rows[which][d], &S.rows_t[which][d], &S.ld_rows[which][d]);
-                    gram(plain_operand(cb, (long long)N * Lh, C, N * Lh), plain_operand(cb + d, (long long)N * Lh, C, N * Lh),
-                         N * Lh, d == 0, &S.cols[which][d], &S.cols_t[which][d], &S.ld_cols[which][d]);
+                    gram(row_op(which, 0), row_op(which, d), N * Lw, d == 0, &S.rows[which][d], &S.rows_t[which][d], &S.ld_rows[which][d]);
+                    gram(col_op(which, 0), col_op(which, d), N * Lh, d == 0, &S.cols[which][d], &S.cols_t[which][d], &S.ld_cols[which][d]);
                 }
             for (int wc = 0; wc < 4; ++wc) {
-                const float *kb = J.corners + (size_t)wc * C * N;
                 int ld = 0;
-                gram(plain_operand(kb, N, C, N), plain_operand(kb, N, C, N), N, true, &S.corners[wc], nullptr, &ld);
+                gram(corner_op(wc), corner_op(wc), corner_K, true, &S.corners[wc], nullptr, &ld);
                 S.ld_corner = ld;
             }
             asmjobs.push_back(S);
@@ -619,6 +669,16 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         L.off_a = plan.tab.add(padjobs.data(), padjobs.size() * sizeof(PadJob));
         L.n = (int)padjobs.size();
         L.total_wgs = pad_wgs;
+        L.bytes = pad_bytes;
+        plan.launches.push_back(L);
+    }
+    if (!padbfjobs.empty()) {
+        Launch L{};
+        L.kind = L_PAD;
+        L.off_a = plan.tab.add(padbfjobs.data(), padbfjobs.size() * sizeof(PadJobBF16));
+        L.n = (int)padbfjobs.size();
+        L.total_wgs = padbf_wgs;
+        L.cfg = 1;   // the bf16 form
         L.bytes = pad_bytes;
         plan.launches.push_back(L);
     }
@@ -1320,7 +1380,8 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 e = launch_patch((const PatchJob *)(tab_dev + L.off_a), L.n, L.total_wgs, ls);
                 break;
             case L_PAD:
-                e = launch_pad((const PadJob *)(tab_dev + L.off_a), L.n, L.total_wgs, ls);
+                e = L.cfg == 1 ? launch_pad_bf16((const PadJobBF16 *)(tab_dev + L.off_a), L.n, L.total_wgs, ls)
+                               : launch_pad((const PadJob *)(tab_dev + L.off_a), L.n, L.total_wgs, ls);
                 break;
             case L_ASSEMBLE:
                 e = launch_assemble((const AssembleJob *)(tab_dev + L.off_a), L.n, L.total_wgs, ls);

@@ -74,6 +74,25 @@ struct PadJob {
     int wg_start;
 };
 
+// The same for bf16 activations.  The bf16 GEMM loader reads 16-byte chunks at 16-byte aligned addresses,
+// so a displaced operand cannot simply be an offset base pointer: the padded tensor is written five times,
+// copy q (q = 0..4) shifted by dx = q - 2 elements, so that copy q read at an aligned position g gives the
+// padded tensor at g + dx; a displacement (dy, dx) is then copy dx + 2 at offset dy * Wp with Wp a multiple
+// of 8.  Likewise three copies (shift 0, 1, 2) of the border lines.
+struct PadJobBF16 {
+    const unsigned short *src;   // [N, C, H, W]
+    unsigned short *padded;      // 5 copies of copy_elems each: front slack, N*C planes of Hp*Wp, back slack
+    long long copy_elems;        // multiple of 8
+    int front_slack;             // multiple of 8
+    unsigned short *rows;        // 3 copies of rows_elems: [2][C][N][Lw] top / bottom image row, then zeros
+    unsigned short *cols;        // 3 copies of cols_elems: [2][C][N][Lh] left / right image column, then zeros
+    unsigned short *corners;     // [4][C][Ln]: the four corner pixels per sample, rows padded with zeros to Ln
+    long long rows_elems, cols_elems;   // multiples of 8
+    int N, C, H, W, Lw, Lh, Ln;
+    int Hp, Wp;                  // Hp - H >= 2 zero rows on top, Wp - W >= 2 zero columns on the left, Wp % 8 == 0
+    int wg_start;
+};
+
 struct AssembleJob {
     // Gram matrices of the contractions, [c][c'] with the leading dimensions given; those of
     // displacement 0 carry the GEMM_BORDER column (row sums) at index C
@@ -233,6 +252,7 @@ hipError_t launch_gemm_reduce(const GemmProblem *probs_dev, const int *red_start
                               int total_wgs, hipStream_t s);
 hipError_t launch_patch(const PatchJob *jobs_dev, int n_jobs, int total_wgs, hipStream_t s);
 hipError_t launch_pad(const PadJob *jobs_dev, int n_jobs, int total_wgs, hipStream_t s);
+hipError_t launch_pad_bf16(const PadJobBF16 *jobs_dev, int n_jobs, int total_wgs, hipStream_t s);
 hipError_t launch_assemble(const AssembleJob *jobs_dev, int n_jobs, int total_wgs, hipStream_t s);
 hipError_t launch_trace(const TraceJob *jobs_dev, int n_layers, float gamma, float *damp_dev,
                         float *pi_out, hipStream_t s);

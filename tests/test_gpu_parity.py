@@ -176,14 +176,20 @@ def test_stats_split_k_is_reproducible_and_matches(gpu):
     assert relerr(host(G1[0]), Gr) <= TOL_FACTOR
 
 
-@pytest.mark.parametrize("layer", [SMALL_LAYERS[0], SMALL_LAYERS[5], SMALL_LAYERS[6], SMALL_LAYERS[9]])
-def test_stats_bf16_inputs(gpu, layer):
+@pytest.mark.parametrize("corr", [1, 0])
+@pytest.mark.parametrize("layer", [SMALL_LAYERS[i] for i in (0, 3, 5, 6, 9, 10, 11, 12)] +
+                         [wl.conv_layer(9, 5, 6, 3, 1, 1, 14), wl.Layer(3, 7, 4, 3, 1, 1, 3, 19, 1)])
+def test_stats_bf16_inputs(gpu, layer, corr):
     """bf16-input variant: against the oracle on the bf16-rounded inputs the bound is the
     fp32 one (products of bf16 values are exact in fp32); against the oracle on the
-    original fp32 inputs the error is that of the input rounding (2^-9 relative per value)."""
+    original fp32 inputs the error is that of the input rounding (2^-9 relative per value).
+    The 3x3 / stride-1 layers take the correlation form on shifted bf16 copies where the padding
+    to a width of a multiple of 8 leaves a gain (not the 7x7 image), with a batch that is not a
+    multiple of 8 among them; corr = 0 sends them through the patch matrix."""
     a, g = wl.make_act(layer, 51), wl.make_grad_out(layer, 51)
     ab, gb = wl.round_to_bf16(a), wl.round_to_bf16(g)
-    A, G = run_stats([layer], [ab], [gb], 0.0, True, dtype=kfac.KFAC_BF16)
+    with kfac.default_options(correlation_form=corr):
+        A, G = run_stats([layer], [ab], [gb], 0.0, True, dtype=kfac.KFAC_BF16)
     Ar, Gr = oracle.kfac_stats(tuple(layer), ab, gb, 0.0, True, None, None)
     assert relerr(host(A[0]), Ar) <= TOL_FACTOR
     assert relerr(host(G[0]), Gr) <= TOL_FACTOR
