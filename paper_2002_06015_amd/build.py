@@ -33,6 +33,13 @@ def build(verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         objs = list(ex.map(compile_one, SOURCES))
+    # the calibration program (a stand-alone executable, not part of the library)
+    calib = os.path.join(HERE, "calib", "mfma_bf16_peak.hip")
+    r = subprocess.run([hipcc, "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                        calib, "-o", os.path.join(objdir, "mfma_bf16_peak")], capture_output=True, text=True)
+    if r.returncode != 0:
+        sys.stderr.write(r.stdout + r.stderr)
+        raise RuntimeError("hipcc failed on %s" % calib)
     tmp = OUT + ".tmp%d" % os.getpid()
     subprocess.run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs, check=True)
     os.replace(tmp, OUT)

@@ -39,16 +39,35 @@ __global__ __launch_bounds__(256) void pad_kernel(const PadJob *__restrict__ job
     // part 1: the padded tensor including its zero slack in front and behind, 4 elements per thread
     const long long n4 = J.padded_floats / 4;
     if (idx < n4) {
+        // coordinates of the first of the four positions by division (32-bit where the tensor allows), the others by stepping
+        const long long g0 = idx * 4 - J.front_slack, total = planes * PP;
+        long long plane = 0;
+        int yp = 0, xp = 0;
+        if (g0 > 0 && g0 < total) {
+            int r;
+            if (total < (1LL << 31)) {
+                const unsigned q = (unsigned)g0 / (unsigned)PP;
+                plane = q;
+                r = (int)((unsigned)g0 - q * (unsigned)PP);
+            } else {
+                plane = g0 / PP;
+                r = (int)(g0 - plane * PP);
+            }
+            yp = r / Wp;
+            xp = r - yp * Wp;
+        }
+        const float *sp = J.src + plane * H * W;
         corr_floatx4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const long long g = idx * 4 + e - J.front_slack;
+            const long long g = g0 + e;
             float x = 0.f;
-            if (g >= 0 && g < planes * PP) {
-                const long long plane = g / PP;
-                const int r = (int)(g - plane * PP);
-                const int yp = r / Wp, xp = r - yp * Wp;
-                if (yp >= y0 && xp >= x0) x = J.src[plane * H * W + (long long)(yp - y0) * W + (xp - x0)];
+            if (g >= 0 && g < total) {
+                if (yp >= y0 && xp >= x0) x = sp[(yp - y0) * W + (xp - x0)];
+                if (++xp == Wp) {
+                    xp = 0;
+                    if (++yp == J.Hp) { yp = 0; sp += H * W; }
+                }
             }
             v[e] = x;
         }
