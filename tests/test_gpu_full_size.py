@@ -217,6 +217,22 @@ def test_config5_batch128_stale_subset_element_by_element(gpu, progress, fused):
 
 
 @pytest.mark.timeout(600)
+def test_bf16_correlation_layers_element_by_element(gpu, progress):
+    """bf16 activations through the correlation form at the benchmark's sizes: the 3x3 / stride-1
+    layers at 56x56 (64 channels), 28x28 (128) and 14x14 (256), batch 32 (their A factors come from
+    13 displaced Gram matrices of shifted bf16 copies of the padded tensor; the 7x7 ones of
+    configuration 3 take the patch matrix).  Separate calls and the fused step."""
+    layers = [wl.conv_layer(32, 64, 64, 3, 1, 1, 56), wl.conv_layer(32, 128, 128, 3, 1, 1, 28),
+              wl.conv_layer(32, 256, 256, 3, 1, 1, 14)]
+    inputs = _inputs(layers, 7, kfac.KFAC_BF16)
+    for fused in (False, True):
+        r = _run_step(layers, 7, kfac.KFAC_BF16, inputs, fused=fused)
+        ref = _oracle_set("bf16corr", layers, inputs, r["idx"], progress)
+        _compare_all(layers, r, ref, inputs, progress)
+    del _ORACLE["bf16corr"]
+
+
+@pytest.mark.timeout(600)
 @pytest.mark.parametrize("in_dtype", [kfac.KFAC_F32, kfac.KFAC_BF16])
 def test_v1_5_stride2_3x3_layers_element_by_element(gpu, progress, in_dtype):
     """The layers only the v1.5 variant has: 3x3 / stride 2 at 56 -> 28, 28 -> 14 and 14 -> 7
