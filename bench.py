@@ -298,8 +298,9 @@ def main():
             roofline["note"] = ("fp32 contraction computed by six bf16 matrix instructions per product block (operands split "
                                 "exactly into three bf16 planes, fp32 accumulation, fp32-level accuracy): achieved = fp32 flops "
                                 "of the contraction, peak = the dense bf16 peak / 6 (the pipe the kernel issues on); a loop of "
-                                "nothing but these matrix instructions on random operands reaches 0.72 of that peak on this "
-                                "GPU (power limit: 1.82 GHz instead of 2.4; profiles/mfma_bf16_peak_loop.txt)")
+                                "nothing but these matrix instructions on operands with random sign, exponent and mantissa "
+                                "reaches about 0.7 of that peak on this GPU (the clock settles at 1.7-1.8 GHz instead of 2.4; "
+                                "profiles/mfma_bf16_peak_loop.txt)")
     else:
         achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
         roofline = {"kernel": dom_name, "bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,

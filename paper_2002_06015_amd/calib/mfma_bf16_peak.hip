@@ -25,9 +25,11 @@ typedef unsigned short ushortx8 __attribute__((ext_vector_type(8)));
     } while (0)
 
 // Four independent accumulator blocks per wavefront (the instruction's latency is covered),
-// four wavefronts per workgroup.  random == 0: every operand is zero; 1: bf16 values of
-// magnitude 1..2 with random mantissas, a positive, b negative (the sums stay finite).
-__global__ __launch_bounds__(256) void mfma_loop(float *out, long long *clocks, int iters, int random)
+// four wavefronts per workgroup.  pattern 0: every operand is zero; 1: bf16 values of magnitude
+// 1..2 with random mantissas, a positive, b negative; 2: random sign, random mantissa and one of
+// eight binary exponents (2^-7 .. 1), which is what the planes of real operands look like.  The
+// sums stay finite in every case.
+__global__ __launch_bounds__(256) void mfma_loop(float *out, long long *clocks, int iters, int pattern)
 {
     constexpr int NACC = 4;
     floatx16 acc[NACC];
@@ -38,9 +40,11 @@ __global__ __launch_bounds__(256) void mfma_loop(float *out, long long *clocks, 
     for (int i = 0; i < 4; ++i)
         for (int e = 0; e < 8; ++e) {
             h = h * 1664525u + 1013904223u;
-            a[i][e] = random ? (unsigned short)(0x3f80 + (h >> 25)) : 0;
+            a[i][e] = pattern == 0 ? 0 : pattern == 1 ? (unsigned short)(0x3f80 + (h >> 25))
+                                       : (unsigned short)(((h >> 16) & 0x8000) | ((120 + ((h >> 28) & 7)) << 7) | ((h >> 20) & 0x7f));
             h = h * 1664525u + 1013904223u;
-            b[i][e] = random ? (unsigned short)(0xbf80 + (h >> 25)) : 0;
+            b[i][e] = pattern == 0 ? 0 : pattern == 1 ? (unsigned short)(0xbf80 + (h >> 25))
+                                       : (unsigned short)(((h >> 16) & 0x8000) | ((120 + ((h >> 28) & 7)) << 7) | ((h >> 20) & 0x7f));
         }
     const long long c0 = clock64(), w0 = wall_clock64();
     for (int it = 0; it < iters; ++it) {
@@ -75,12 +79,13 @@ int main()
     CHECK(hipEventCreate(&e0));
     CHECK(hipEventCreate(&e1));
     const int grids[] = {256, 512, 2048};   // 1, 2 and 8 workgroups per compute unit
-    for (int random = 0; random < 2; ++random)
+    const char *names[3] = {"zero operands", "random mantissas", "random sign / exponent / mantissa"};
+    for (int pattern = 0; pattern < 3; ++pattern)
         for (int rep = 0; rep < 2; ++rep)   // the second pass of each is the sustained one
             for (int blocks : grids) {
                 const int iters = 40000 * 256 / blocks;
                 CHECK(hipEventRecord(e0, 0));
-                mfma_loop<<<dim3(blocks), dim3(256), 0, 0>>>(out, clocks, iters, random);
+                mfma_loop<<<dim3(blocks), dim3(256), 0, 0>>>(out, clocks, iters, pattern);
                 CHECK(hipGetLastError());
                 CHECK(hipEventRecord(e1, 0));
                 CHECK(hipDeviceSynchronize());
@@ -90,8 +95,8 @@ int main()
                 // per workgroup: 4 wavefronts x iters x 16 instructions x (2 * 32 * 32 * 16) flops
                 const double flops = (double)blocks * 4.0 * iters * 16.0 * 32768.0;
                 const double seconds = (double)host[1] / (wall_khz * 1e3);
-                printf("%s operands, pass %d, %4d workgroups x %6d iterations: %8.3f ms  %7.1f TFLOP/s  shader clock %4.0f MHz\n",
-                       random ? "random" : "zero  ", rep, blocks, iters, ms, flops / ms / 1e9, (double)host[0] / seconds / 1e6);
+                printf("%-33s pass %d, %4d workgroups x %6d iterations: %8.3f ms  %7.1f TFLOP/s  shader clock %4.0f MHz\n",
+                       names[pattern], rep, blocks, iters, ms, flops / ms / 1e9, (double)host[0] / seconds / 1e6);
             }
     CHECK(hipFree(out));
     CHECK(hipFree(clocks));
