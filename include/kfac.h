@@ -105,6 +105,8 @@ typedef struct {
     int32_t max_k_per_workgroup;  /* ... and none longer than this; 4096 */
     int32_t recursion_leaf;       /* 32..288: the blocked inversion recurses down to blocks of this size; 288 */
     int32_t force_tile;           /* 0: chosen per product; 64 / 128: every product with that tile */
+    int32_t group_by_depth;       /* kfac_invert: layers share a stream with layers whose chains are as long (1) or
+                                     the streams get equal sums of n^3 (0); 1 */
     float chunk_gflop;            /* kfac_step: factor launches beside long inversion chains in parts of this size; 48 */
 } kfac_options;
 

@@ -48,7 +48,7 @@ class kfac_options(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("struct_size", "fp32_products", "streams", "staging_slots", "correlation_form", "pipeline_phases",
                  "early_n", "target_workgroups", "min_k_per_split", "max_k_per_workgroup", "recursion_leaf",
-                 "force_tile")] + [("chunk_gflop", ctypes.c_float)]
+                 "force_tile", "group_by_depth")] + [("chunk_gflop", ctypes.c_float)]
 
 
 def options(**fields) -> kfac_options:
