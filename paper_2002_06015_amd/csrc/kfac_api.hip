@@ -44,6 +44,7 @@ struct Tunables {
     int split;           // 1 (default): fp32 products through three bf16 planes and six bf16 matrix instructions
                          // (fp32 accuracy at the bf16 unit's rate); 0: the fp32 matrix instruction
     int force_tile;      // 0: the planner chooses; 64 / 128: every product with that tile
+    bool worst_case_splits = false;   // set for the workspace bound: every product split as if it were alone in its launch
     int by_depth;        // kfac_invert: layers grouped onto streams by the length of their chains (1) or by total n^3 (0)
     explicit Tunables(const kfac_options &o)
     {
@@ -289,8 +290,14 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
             // Per problem (independent of what else is in the launch, so that the workspace need of
             // a layer list does not depend on which of its inputs are present): enough splits for
             // target_wgs workgroups and at most max_k_per_wg of contraction each.
+            // ... unless the launch fills the GPU twice over without that: then only max_k_per_wg splits (the
+            // partial tiles of needless splits are written, read again and summed by a second launch).  The
+            // workspace bound is computed with the per-problem rule, which needs the most scratch.
+            long long base_wgs = 0;
+            for (auto &P : sel) base_wgs += (long long)P.n_tiles * ((P.K + tun.max_k_per_wg - 1) / tun.max_k_per_wg);
+            const bool launch_is_full = !tun.worst_case_splits && base_wgs >= (cfg == 0 ? 1024 : 2048);
             auto splits_for = [&](const GemmProblem &P, int boost, int *kps_out) {
-                const int want = std::max(boost, (tun.target_wgs + P.n_tiles - 1) / P.n_tiles);
+                const int want = std::max(boost, launch_is_full ? 1 : (tun.target_wgs + P.n_tiles - 1) / P.n_tiles);
                 int splits = std::max((P.K + tun.max_k_per_wg - 1) / tun.max_k_per_wg,
                                       std::min(want, P.K / tun.min_k_per_split));
                 int kps = std::max(32, (P.K + 31) / 32 * 32);
@@ -1523,7 +1530,8 @@ size_t kfac_workspace_bytes(const kfac_layer *L, int32_t n_layers, kfac_dtype in
 size_t kfac_workspace_bytes_opt(const kfac_layer *L, int32_t n_layers, kfac_dtype in, const kfac_options *opt)
 {
     if (!layers_ok(L, n_layers) || (in != KFAC_F32 && in != KFAC_BF16) || !options_ok(opt)) return 0;
-    const Tunables tun(opt ? *opt : default_options());
+    Tunables tun(opt ? *opt : default_options());
+    tun.worst_case_splits = true;
     size_t best = 0, sum_peaks = 0;
     {
         Plan plan; Arena arena(nullptr);
