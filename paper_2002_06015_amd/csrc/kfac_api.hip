@@ -258,10 +258,10 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
 {
     if (probs.empty()) return;
     // Tile configuration per problem.  When the phase as a whole keeps the GPU busy with 128x128
-    // tiles, a problem takes the big tile unless that pads its work by more than half (the 64x64
-    // tile reaches 55-60 % of the big tile's rate on long contractions; measured, a 256 x 256
-    // symmetric product -- 3 big tiles for 10 small ones, 1.2x the work -- costs the same either
-    // way and the products of the preconditioning gain 7 %); otherwise the latency model decides.
+    // tiles, each problem takes the configuration with less padded work (the big tile moves half the
+    // operand bytes per flop, worth ~15 %; up to 1.5x the work for the rectangular products of the
+    // preconditioning, measured: -7 %; for the symmetric products of the factors -- 256 x 256 is 3 big
+    // tiles or 10 small ones, 1.2x -- it costs the same either way); otherwise the latency model decides.
     double tile_steps128 = 0;   // 128x128 tiles times 32-wide K steps: the work of the phase
     for (auto &P : probs) {
         const double tm = (P.M + 127) / 128, tn = (P.N + 127) / 128;
@@ -276,7 +276,7 @@ void emit_gemm_phase(Plan &plan, Arena &arena, const Tunables &tun, std::vector<
                 const double tm = (P.M + B - 1) / B, tn = (P.N + B - 1) / B;
                 return (sym ? tm * (tm + 1) / 2 : tm * tn) * B * B;
             };
-            P.tile_cfg = work(128) <= 1.5 * work(64) ? 0 : 1;
+            P.tile_cfg = work(128) <= (phase_boost ? 1.5 : 1.15) * work(64) ? 0 : 1;
         } else {
             P.tile_cfg = choose_tile_cfg(P.M, P.N, P.K, sym);
         }
