@@ -173,7 +173,7 @@ __device__ __forceinline__ void store_border(const GemmProblem &P, int row, floa
 __device__ __forceinline__ void store_corner(const GemmProblem &P)
 {
     float *pc = P.C + (long long)P.M * P.ldc + P.M;
-    float v = P.alpha * (float)P.K;
+    float v = P.alpha * (float)P.ones;
     if (P.beta != 0.0f) v = fmaf(P.beta, *pc, v);
     *pc = v;
 }
@@ -831,7 +831,7 @@ constexpr int LDH = 72;     // LDS row length in bf16 (64 + 8 pad: 144-byte rows
 typedef const unsigned short __attribute__((address_space(1))) *gushort_ptr;
 typedef const ushortx8 __attribute__((address_space(1))) *gushort8_ptr;
 
-template <int BR>
+template <int BR, bool TAIL = false>
 struct LoaderBF16 {
     static constexpr int SLOTS = BR / 32;
     gushort_ptr base;
@@ -840,13 +840,17 @@ struct LoaderBF16 {
     long long batch_stride;
     long long col;             // offset of the thread's chunk within a row: n * batch_stride + t
     int hw, kq, r0, m, n, t;
+    int tail;                  // see Operand
+    int n_last;                // TAIL: index of the last run of a row
+    unsigned lastrow;          // TAIL: bit s set if slot s reads the last row of the operand
     bool zero_all;
 
-    __device__ __forceinline__ void init(const Operand &op, int tile_row0, int tid)
+    __device__ __forceinline__ void init(const Operand &op, int tile_row0, int tid, int K = 0)
     {
         base = (gushort_ptr)op.base;
         batch_stride = op.batch_stride;
         hw = op.hw;
+        tail = op.tail;
         kq = (tid & 7) * 8; r0 = tid >> 3;
         dead = 0;
 #pragma unroll
@@ -858,6 +862,14 @@ struct LoaderBF16 {
         m = n = t = 0;
         col = 0;
         zero_all = false;
+        n_last = 0;
+        lastrow = 0;
+        if constexpr (TAIL) {
+            n_last = K / hw - 1;
+#pragma unroll
+            for (int s = 0; s < SLOTS; ++s)
+                if (tile_row0 + r0 + 32 * s >= op.rows - 1) lastrow |= 1u << s;
+        }
     }
     __device__ __forceinline__ void seek(int tile_k0)
     {
@@ -869,7 +881,10 @@ struct LoaderBF16 {
     __device__ __forceinline__ void advance()
     {
         m += KTH; t += KTH; col += KTH;
-        while (t >= hw) { t -= hw; col += batch_stride - hw; }
+        while (t >= hw) {
+            t -= hw; col += batch_stride - hw;
+            if constexpr (TAIL) ++n;
+        }
     }
     // the same for runs of at least one tile (hw >= KTH): at most one wrap, no branch
     __device__ __forceinline__ void advance_once()
@@ -878,11 +893,29 @@ struct LoaderBF16 {
         const bool wrap = t >= hw;
         t -= wrap ? hw : 0;
         col += wrap ? batch_stride - hw : 0;
+        if constexpr (TAIL) n += wrap ? 1 : 0;
+    }
+    // The thread's chunk of row slot s.  Runs with a tail: the last chunk of a run is loaded whole as well (its
+    // upper half lies in the next row of the tensor) and the upper half set to zero; only behind the last run
+    // of the last row there is no next row, so that one chunk is loaded four elements lower and moved up.
+    __device__ __forceinline__ ushortx8 fetch(int s) const
+    {
+        const long long off = rowoff[s] + col;
+        if constexpr (!TAIL) return *(gushort8_ptr)(base + off);
+        typedef unsigned short ushortx8_a8 __attribute__((ext_vector_type(8), aligned(8)));
+        typedef const ushortx8_a8 __attribute__((address_space(1))) *gushort8a8_ptr;
+        const bool last = tail != 0 && t + 8 == hw;
+        const bool edge = last && n == n_last && ((lastrow >> s) & 1);
+        const ushortx8_a8 v = *(gushort8a8_ptr)(base + off - (edge ? 4 : 0));
+        ushortx8 r = {v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7]};
+        if (edge) { r[0] = v[4]; r[1] = v[5]; r[2] = v[6]; r[3] = v[7]; }
+        if (last) { r[4] = 0; r[5] = 0; r[6] = 0; r[7] = 0; }
+        return r;
     }
     __device__ __forceinline__ void load_full(ushortx8 (&reg)[SLOTS])
     {
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s) reg[s] = *(gushort8_ptr)(base + rowoff[s] + col);
+        for (int s = 0; s < SLOTS; ++s) reg[s] = fetch(s);
         zero_all = false;
     }
     __device__ __forceinline__ void zero_below(int mlo) { zero_all = m < mlo; }
@@ -892,7 +925,7 @@ struct LoaderBF16 {
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             ushortx8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (in) v = *(gushort8_ptr)(base + rowoff[s] + col);
+            if (in) v = fetch(s);
             reg[s] = v;
         }
         zero_all = !in;
@@ -923,7 +956,7 @@ struct LoaderBF16 {
     }
     __device__ __forceinline__ void load_slot(ushortx8 (&reg)[SLOTS], int s)
     {
-        reg[s] = *(gushort8_ptr)(base + rowoff[s] + col);
+        reg[s] = fetch(s);
     }
     // K % 8 remainder tile (repacked operands only): thread tid < BR fills LDS row tid
     __device__ __forceinline__ static float fill_remainder(const Operand &op, int tile_row0, int k8, int kend,
@@ -978,9 +1011,9 @@ __device__ __forceinline__ void mma_frag16(const FragBF16<TM, TN> &f, floatx16 (
                                                                 __builtin_bit_cast(bf16x8, f.b[j]), acc[i][j], 0, 0, 0);
 }
 
-template <int TM, int TN, bool LIVE, bool RS>
+template <int TM, int TN, bool LIVE, bool RS, bool TAIL>
 __device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm, int tn, int tid,
-                                                   LoaderBF16<64 * TM> &la, LoaderBF16<64 * TN> &lb,
+                                                   LoaderBF16<64 * TM, TAIL> &la, LoaderBF16<64 * TN, TAIL> &lb,
                                                    unsigned short *lds, int k0, int k1, int wave_m, int wave_n,
                                                    int l32, int half, floatx16 (&acc)[TM][TN], float (&rs)[2 * TM],
                                                    float &rs_rem)
@@ -1108,19 +1141,12 @@ __device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm,
     for (; it < nk; ++it) step(it);
 }
 
-template <int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__restrict__ probs,
-                                                           const int *__restrict__ tile_start, int n_probs)
+// TAIL: an operand of the problem has runs with a four-element tail (Operand::tail); a variant of its
+// own, so that the loads of all other problems stay single 16-byte loads without a branch.
+template <int TM, int TN, bool TAIL>
+__device__ __forceinline__ void gemm_nt_bf16_body(const GemmProblem &P, int local, float *lds)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    extern __shared__ __attribute__((aligned(16))) float lds[];   // operand stages, then the output tile
-
-    const int wg = blockIdx.x;
-    const int pi = find_problem(tile_start, n_probs, wg);
-    const GemmProblem &P = probs[pi];
-    const int n_local = P.n_tiles * P.splits;
-    const int local = xcd_remap(wg - tile_start[pi], (n_local + 7) & ~7);
-    if (local >= n_local) return;
     const int split = local / P.n_tiles;
     const int tile = local - split * P.n_tiles;
     int tm, tn;
@@ -1130,10 +1156,10 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__
     const int k1 = min(P.K, k0 + P.k_per_split);
     const int tid = threadIdx.x;
 
-    LoaderBF16<BM> la;
-    LoaderBF16<BN> lb;
-    la.init(P.a, tm * BM, tid);
-    lb.init(P.b, tn * BN, tid);
+    LoaderBF16<BM, TAIL> la;
+    LoaderBF16<BN, TAIL> lb;
+    la.init(P.a, tm * BM, tid, P.K);
+    lb.init(P.b, tn * BN, tid, P.K);
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -1156,12 +1182,12 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__
 #pragma unroll
     for (int s = 0; s < BM / 32; ++s) rs[s] = 0.f;
     if (border) {
-        if (live) gemm_bf16_mainloop<TM, TN, true, true>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
-        else      gemm_bf16_mainloop<TM, TN, false, true>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        if (live) gemm_bf16_mainloop<TM, TN, true, true, TAIL>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        else      gemm_bf16_mainloop<TM, TN, false, true, TAIL>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
         finish_row_sums<BM>(P, lds, tm, tile, split, tid, rs, rs_rem);
     } else {
-        if (live) gemm_bf16_mainloop<TM, TN, true, false>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
-        else      gemm_bf16_mainloop<TM, TN, false, false>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        if (live) gemm_bf16_mainloop<TM, TN, true, false, TAIL>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        else      gemm_bf16_mainloop<TM, TN, false, false, TAIL>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
     }
 
     if (P.splits > 1) {
@@ -1273,6 +1299,22 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmProblem *__r
 }
 
 // LDS per workgroup: two operand stages, reused for the (BM x BN+1) fp32 output tile.
+
+template <int TM, int TN>
+__global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__restrict__ probs,
+                                                           const int *__restrict__ tile_start, int n_probs)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // operand stages, then the output tile
+
+    const int wg = blockIdx.x;
+    const int pi = find_problem(tile_start, n_probs, wg);
+    const GemmProblem &P = probs[pi];
+    const int n_local = P.n_tiles * P.splits;
+    const int local = xcd_remap(wg - tile_start[pi], (n_local + 7) & ~7);
+    if (local >= n_local) return;
+    if (P.a.tail | P.b.tail) gemm_nt_bf16_body<TM, TN, true>(P, local, lds);
+    else                     gemm_nt_bf16_body<TM, TN, false>(P, local, lds);
+}
 template <int TM, int TN>
 constexpr size_t gemm_lds_bytes()
 {

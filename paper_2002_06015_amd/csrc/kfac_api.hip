@@ -248,6 +248,7 @@ void finish_problem(GemmProblem &P)
     P.k_per_split = std::max(32, (P.K + 31) / 32 * 32);
     P.partial = nullptr;
     P.partial_rs = nullptr;
+    if (P.ones == 0) P.ones = P.K;
 }
 
 // Emits the launches of one phase: per tile configuration one GEMM launch, plus one
@@ -465,18 +466,25 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
     double patch_bytes = 0, pad_bytes = 0, asm_bytes = 0;
     // An NCHW tensor [N, c, hw] is contracted in place when its runs are whole chunks; otherwise (and for every k > 1 / strided / padded layer) it is first rewritten
     // as [c k^2][ld] with the contraction index contiguous.
+    // (*K_out: the length of the contraction over this operand)
     auto operand_for = [&](const void *src, int N, int c, int k, int stride, int pad, int h_in, int w_in, int h,
-                           int w) {
+                           int w, int *K_out) {
         const int hw = h * w, K = N * hw, d0 = c * k * k;
+        *K_out = K;
         Operand op{};
-        const bool direct = (k == 1 && stride == 1 && pad == 0 && hw % chunk == 0 &&
-                             (dry || ((uintptr_t)src % chunk_align) == 0));
-        if (direct) {
+        const bool pointwise = k == 1 && stride == 1 && pad == 0;
+        const bool direct = pointwise && hw % chunk == 0 && (dry || ((uintptr_t)src % chunk_align) == 0);
+        // bf16 runs of 8q + 4 (14 x 14 planes): in place as well, the last chunk of a run in two halves
+        const bool direct_tail = pointwise && !direct && a.in == KFAC_BF16 && hw % 8 == 4 && hw >= 12 &&
+                                 (dry || ((uintptr_t)src % 8) == 0);
+        if (direct || direct_tail) {
             op.base = src;
             op.row_stride = hw;
             op.batch_stride = (long long)c * hw;
             op.rows = d0;
-            op.hw = hw;
+            op.hw = direct ? hw : hw + 4;
+            op.tail = direct ? 0 : 4;
+            *K_out = N * op.hw;
         } else {
             const long long ld = align_up((size_t)K, 32);
             void *P = arena.take((size_t)d0 * ld * esize);
@@ -631,8 +639,9 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             }
             asmjobs.push_back(S);
         } else if (want_A) {
+            int Kop = K;
             Operand op = operand_for(dry ? nullptr : a.act[l], Ly.N, Ly.c_in, Ly.k, Ly.stride, Ly.pad, Ly.h_in,
-                                     Ly.w_in, h, w);
+                                     Ly.w_in, h, w, &Kop);
             // the bias row of the patch matrix is not multiplied out: the border of A comes
             // from row sums (GEMM_BORDER), which keeps c_in k^2 a whole number of tiles
             GemmProblem P{};
@@ -640,7 +649,8 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             P.C = dry ? nullptr : a.A_ema[l];
             P.Ct = nullptr;
             P.ldc = dA; P.ldct = 0;
-            P.M = op.rows; P.N = op.rows; P.K = K;
+            P.M = op.rows; P.N = op.rows; P.K = Kop;
+            P.ones = K;   // the bias row has a one per real position (Kop counts the zero tail of bf16 runs as well)
             P.flags = GEMM_SYM | (Ly.bias ? GEMM_BORDER : 0);
             P.tile_cfg = choose_tile_cfg(P.M, P.N, K, true);
             P.alpha = (float)((1.0 - (double)a.decay) / ((double)Ly.N * (double)hw));
@@ -649,12 +659,13 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             probs.push_back(P);
         }
         if (want_G) {
-            Operand op = operand_for(dry ? nullptr : a.grad_out[l], Ly.N, Ly.c_out, 1, 1, 0, h, w, h, w);
+            int Kop = K;
+            Operand op = operand_for(dry ? nullptr : a.grad_out[l], Ly.N, Ly.c_out, 1, 1, 0, h, w, h, w, &Kop);
             GemmProblem P{};
             P.a = op; P.b = op;
             P.C = dry ? nullptr : a.G_ema[l];
             P.ldc = dG;
-            P.M = dG; P.N = dG; P.K = K;
+            P.M = dG; P.N = dG; P.K = Kop;
             P.flags = GEMM_SYM;
             P.tile_cfg = choose_tile_cfg(dG, dG, K, true);
             double scale = 1.0 / (double)Ly.N;

@@ -17,12 +17,16 @@ namespace kfac {
 // A thread loads 16-byte chunks along m: fp32 operands need hw % 4 == 0 (or a plain
 // matrix, any leading dimension); bf16 operands need hw % 8 == 0 or a plain matrix, and
 // base, row_stride and batch_stride that keep every chunk 16-byte aligned.
+// bf16 runs of 8q + 4 elements (14 x 14 planes): tail = 4, hw is the run length rounded up to
+// 8q + 8 and the contraction runs over N * hw positions, of which the last four of every run
+// read as 0 (the last chunk of a run is loaded as two halves; 8-byte alignment is enough then).
 struct Operand {
     const void *base;
     long long row_stride;
     long long batch_stride;
     int rows;
     int hw;
+    int tail;   // 0, or 4 (bf16 only): valid elements in the last 8-element chunk of a run
 };
 
 // GEMM_SYM:    M == N and a == b; only tiles tm >= tn are computed and mirrored.
@@ -30,7 +34,7 @@ struct Operand {
 //              an all-ones row (the bias row of the patch matrix, Sec. 3.3).  The border is
 //              not multiplied out: C[i][M] = C[M][i] = alpha * sum_m a(i, m) + beta * old
 //              comes from row sums taken while the diagonal tiles stage their operand,
-//              and C[M][M] = alpha * K + beta * old.
+//              and C[M][M] = alpha * ones + beta * old.
 enum : int { GEMM_SYM = 1, GEMM_BORDER = 2 };
 
 struct GemmProblem {
@@ -41,6 +45,7 @@ struct GemmProblem {
     float *partial_rs;  // split-K scratch of the border row sums: [tiles_m][splits][BM] (GEMM_BORDER, splits > 1)
     long long ldc, ldct;
     int M, N, K;
+    int ones;                 // GEMM_BORDER: the sum of the all-ones row with itself (K, unless the contraction includes padding)
     int tiles_m, tiles_n, n_tiles;
     int splits, k_per_split;  // k_per_split is a multiple of 32
     int flags;

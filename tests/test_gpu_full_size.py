@@ -221,9 +221,10 @@ def test_bf16_correlation_layers_element_by_element(gpu, progress):
     """bf16 activations through the correlation form at the benchmark's sizes: the 3x3 / stride-1
     layers at 56x56 (64 channels), 28x28 (128) and 14x14 (256), batch 32 (their A factors come from
     13 displaced Gram matrices of shifted bf16 copies of the padded tensor; the 7x7 ones of
-    configuration 3 take the patch matrix).  Separate calls and the fused step."""
+    configuration 3 take the patch matrix), and a pointwise layer on 14x14 planes (1024 -> 256), whose bf16
+    operands are contracted in place with a four-element tail per run.  Separate calls and the fused step."""
     layers = [wl.conv_layer(32, 64, 64, 3, 1, 1, 56), wl.conv_layer(32, 128, 128, 3, 1, 1, 28),
-              wl.conv_layer(32, 256, 256, 3, 1, 1, 14)]
+              wl.conv_layer(32, 256, 256, 3, 1, 1, 14), wl.conv_layer(32, 1024, 256, 1, 1, 0, 14)]
     inputs = _inputs(layers, 7, kfac.KFAC_BF16)
     for fused in (False, True):
         r = _run_step(layers, 7, kfac.KFAC_BF16, inputs, fused=fused)

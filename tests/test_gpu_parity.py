@@ -178,11 +178,16 @@ def test_stats_split_k_is_reproducible_and_matches(gpu):
 
 @pytest.mark.parametrize("corr", [1, 0])
 @pytest.mark.parametrize("layer", [SMALL_LAYERS[i] for i in (0, 3, 5, 6, 9, 10, 11, 12)] +
-                         [wl.conv_layer(9, 5, 6, 3, 1, 1, 14), wl.Layer(3, 7, 4, 3, 1, 1, 3, 19, 1)])
+                         [wl.conv_layer(9, 5, 6, 3, 1, 1, 14), wl.Layer(3, 7, 4, 3, 1, 1, 3, 19, 1),
+                          wl.conv_layer(3, 16, 24, 1, 1, 0, 14), wl.conv_layer(5, 70, 9, 1, 1, 0, 14, bias=0),
+                          wl.Layer(2, 8, 8, 1, 1, 0, 2, 6, 1), wl.Layer(2, 8, 8, 1, 1, 0, 2, 2, 1),
+                          wl.Layer(33, 130, 3, 1, 1, 0, 6, 6, 1)])
 def test_stats_bf16_inputs(gpu, layer, corr):
     """bf16-input variant: against the oracle on the bf16-rounded inputs the bound is the
     fp32 one (products of bf16 values are exact in fp32); against the oracle on the
     original fp32 inputs the error is that of the input rounding (2^-9 relative per value).
+    Pointwise layers on planes of 8q + 4 positions (14 x 14, 2 x 6, 6 x 6) are contracted in place with
+    the last chunk of every run loaded in two halves; 2 x 2 goes through the copying path.
     The 3x3 / stride-1 layers take the correlation form on shifted bf16 copies where the padding
     to a width of a multiple of 8 leaves a gain (not the 7x7 image), with a batch that is not a
     multiple of 8 among them; corr = 0 sends them through the patch matrix."""
