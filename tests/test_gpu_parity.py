@@ -438,6 +438,7 @@ def _fused_vs_separate(layers, mask, early_n, opts=None):
     info2 = torch.zeros(2 * n, dtype=torch.int32, device="cuda")
     Ar, Gr = [None] * n, [None] * n
     Air, Gir = [None] * n, [None] * n
+    pi_before = pi.cpu().numpy().copy()            # what a layer outside the mask must still hold afterwards
     for step in range(2):
         decay = 0.0 if step == 0 else wl.DECAY
         m = None if step == 0 else mask       # the first step gives every layer an inverse
