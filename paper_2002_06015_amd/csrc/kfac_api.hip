@@ -1280,7 +1280,24 @@ void plan_step(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &s
         }
     }
     arena.used = align_up(arena.peak, kAlign);
-    plan_invert_group(plan, arena, tun, inv, dry, late_inv, damp, 0);
+    if (early_classes == 0 && n_aux > 0 && late_inv.size() > 1) {
+        // no layer large enough for a class of its own (or none of them inverted): the inversions start when all
+        // factors exist, the longest chains on the first auxiliary stream and the others here (as kfac_invert)
+        std::vector<std::vector<int>> groups = deal_by_depth(st.L, late_inv, 2, 0);
+        if (!groups[0].empty() && !groups[1].empty()) {
+            plan.sync(L_RECORD, 4, 0);
+            plan.sync(L_WAIT, 4, 1);
+            plan_invert_group(plan, arena, tun, inv, dry, groups[0], damp, 1);
+            plan.sync(L_RECORD, 1, 1);
+            arena.used = align_up(arena.peak, kAlign);
+            plan_invert_group(plan, arena, tun, inv, dry, groups[1], damp, 0);
+            plan.sync(L_WAIT, 1, 0);
+        } else {
+            plan_invert_group(plan, arena, tun, inv, dry, late_inv, damp, 0);
+        }
+    } else {
+        plan_invert_group(plan, arena, tun, inv, dry, late_inv, damp, 0);
+    }
     // Preconditioning in the order in which the inverses arrive: the layers inverted on this
     // stream first, then each class once its chains have been joined, so that these products
     // fill the time in which only the longest chain is still running.  (Scratch beyond
