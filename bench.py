@@ -527,7 +527,35 @@ def main():
         layout_obj["ms"] = round(tot_ms, 4)
         layout_obj["note"] = ("kfac_nhwc_to_nchw over all activations and all output gradients of the configuration "
                               "(every element read once and written once): what a caller with NHWC tensors pays in "
-                              "front of the step; not part of the timed step")
+                              "front of the step when it converts everything; not part of the timed step")
+        # the same tensors in NHWC order handed to kfac_stats_nhwc / kfac_step_nhwc: pointwise layers and output
+        # gradients are contracted in place, the rest is converted inside the call
+        a_t = [x.permute(0, 2, 3, 1).contiguous() for x in acts]
+        g_t = [x.permute(0, 2, 3, 1).contiguous() for x in grads]
+        mask_all = [i in subset for i in range(n)]
+        in_place = {}
+        for name, call_nchw, call_nhwc in (
+                ("stats", lambda: kfac.kfac_stats(ctx, layers, in_dtype, acts, grads, wl.DECAY, spatial_mean, A, G),
+                 lambda: kfac.kfac_stats(ctx, layers, in_dtype, a_t, g_t, wl.DECAY, spatial_mean, A, G, nhwc=True)),
+                ("step", lambda: kfac.kfac_step(ctx, layers, in_dtype, acts, grads, wl.DECAY, spatial_mean, A, G, mask_all,
+                                                wl.GAMMA, Ai, Gi, None, info, gws, U),
+                 lambda: kfac.kfac_step(ctx, layers, in_dtype, a_t, g_t, wl.DECAY, spatial_mean, A, G, mask_all,
+                                        wl.GAMMA, Ai, Gi, None, info, gws, U, nhwc=True))):
+            for tag, call in (("nchw", call_nchw), ("nhwc", call_nhwc)):
+                for _ in range(2):
+                    call()
+                torch.cuda.synchronize()
+                s0.record()
+                for _ in range(5):
+                    call()
+                s1.record()
+                torch.cuda.synchronize()
+                in_place["%s_ms_%s" % (name, tag)] = round(s0.elapsed_time(s1) / 5, 4)
+        in_place["note"] = ("kfac_stats / kfac_step on the step's tensors in NCHW order and kfac_stats_nhwc / kfac_step_nhwc on "
+                            "the same tensors in NHWC order (same results up to the order of the sums); five calls each, back "
+                            "to back; not part of the timed step")
+        layout_obj["in_place"] = in_place
+        del a_t, g_t
 
         # ---------------------------------------------------------------- beside the step: packing of the factors
         # (Sec. 5.2: upper triangles of all factors into one send buffer, and back)

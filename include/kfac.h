@@ -361,6 +361,25 @@ kfac_status kfac_nhwc_to_nchw(kfac_ctx *ctx, int32_t n_layers, const kfac_layer 
                               const void *const *src, void *const *dst);
 
 /*
+ * kfac_stats and kfac_step on tensors kept in NHWC (Sec. 5.2): act[l] dev [N, h_in, w_in, c_in],
+ * grad_out[l] dev [N, h, w, c_out]; every other argument, every result and every error as for
+ * kfac_stats / kfac_step (the statistics of Sec. 3.3 do not depend on the storage order).
+ * Tensors of pointwise layers (1 x 1, stride 1, no padding, fully connected) and all output
+ * gradients are contracted where they are when they are fp32, the context forms products in its
+ * default mode (KFAC_PRODUCTS_SPLIT_BF16) and the channel count is a multiple of 4; all other
+ * tensors are first brought into NCHW order inside the workspace (the conversion of
+ * kfac_nhwc_to_nchw, the scratch is part of kfac_workspace_bytes).
+ */
+kfac_status kfac_stats_nhwc(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
+                            const void *const *act, const void *const *grad_out, float decay, int32_t g_spatial_mean,
+                            float *const *A_ema, float *const *G_ema);
+kfac_status kfac_step_nhwc(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
+                           const void *const *act, const void *const *grad_out, float decay, int32_t g_spatial_mean,
+                           float *const *A_ema, float *const *G_ema, const uint8_t *invert_mask, float gamma,
+                           float *const *A_inv, float *const *G_inv, float *pi_out, int32_t *info,
+                           const float *const *grad_W, float *const *out);
+
+/*
  * Symmetry-aware packing of the statistics, Sec. 5.2: a symmetric d x d matrix is
  * communicated as its upper triangle, d (d + 1) / 2 elements.  Layout of `packed`
  * (the paper fixes only the count): matrix i starts at element sum_{j<i} d_j (d_j + 1) / 2;

@@ -701,7 +701,179 @@ __device__ __forceinline__ void gemm_split_mainloop(const GemmProblem &P, int tm
     }
 }
 
-template <int TM, int TN, bool SPLIT>
+// ------------------------------------------------------------------ transposed operands (NHWC in place)
+// Element (r, m) of the operand lives at base + m * ld + r: the rows are the contiguous direction.  A thread
+// loads 16 bytes = four adjacent rows at one m (lanes along the rows: 512 contiguous bytes per 32 lanes), splits
+// them and stores 8 bytes per plane into an LDS tile that keeps this order, [m][row]; the fragments of the
+// matrix instruction (8 consecutive m of one row per lane) come out of that tile through the transposing LDS
+// read of gfx950 (ds_read_b64_tr_b16: within 16 lanes, lane i receives element i % 4 of the four 8-byte groups
+// addressed by lanes i / 4, i / 4 + 4, i / 4 + 8, i / 4 + 12).  Every m of the range is read where it is: no
+// shifted tile, no remainder tile; loads beyond the range are clamped and zeroed by value.
+template <int BR>
+struct LoaderF32T {
+    static constexpr int SLOTS = BR / 32;
+    static constexpr int CG = BR / 4;          // row chunks of the tile
+    static constexpr int MSTEP = 256 / CG;     // m positions covered by one slot of all threads
+    static constexpr int RS = BR + 16;         // LDS row (one m) in bf16: four rows of a read 32 bytes apart in banks
+    gfloat_ptr base;
+    long long ld;
+    int c_local, c_load, mk, K;
+    bool dead;
+
+    __device__ __forceinline__ void init(const Operand &op, int tile_row0, int tid, int K_)
+    {
+        base = (gfloat_ptr)op.base;
+        ld = op.row_stride;
+        c_local = 4 * (tid % CG);
+        mk = tid / CG;
+        const int c = tile_row0 + c_local;
+        dead = c >= op.rows;                         // rows % 4 == 0: a chunk is inside or outside as a whole
+        c_load = min(c, op.rows - 4);
+        K = K_;
+    }
+    __device__ __forceinline__ void load(floatx4 (&reg)[SLOTS], int tile_m0) const
+    {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const int m = min(tile_m0 + mk + MSTEP * s, K - 1);
+            reg[s] = *(gfloat4_ptr)(base + (long long)m * ld + c_load);
+        }
+    }
+    // mend: end of the workgroup's range; rs: running sums of the thread's four rows
+    template <bool RSUM>
+    __device__ __forceinline__ void store(const floatx4 (&reg)[SLOTS], unsigned short *rows, int plane, int tile_m0,
+                                          int mend, float (&rs)[4]) const
+    {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            floatx4 v = reg[s];
+            const int ml = mk + MSTEP * s;
+            if (dead || tile_m0 + ml >= mend) { v[0] = 0.f; v[1] = 0.f; v[2] = 0.f; v[3] = 0.f; }
+            if constexpr (RSUM) { rs[0] += v[0]; rs[1] += v[1]; rs[2] += v[2]; rs[3] += v[3]; }
+            uint2 h, m, l;
+            split_pair(v[0], v[1], h.x, m.x, l.x);
+            split_pair(v[2], v[3], h.y, m.y, l.y);
+            unsigned short *dst = rows + ml * RS + c_local;
+            *(uint2 *)dst = h;
+            *(uint2 *)(dst + plane) = m;
+            *(uint2 *)(dst + 2 * plane) = l;
+        }
+    }
+};
+
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) shortx4 *lds_shortx4_ptr;
+
+template <int TM, int TN, bool LIVE, bool RSUM>
+__device__ __forceinline__ void gemm_split_mainloop_trans(const GemmProblem &P, int tm, int tn, int tid,
+                                                          unsigned short *lds, int k0, int k1, int wave_m, int wave_n,
+                                                          int lane, floatx16 (&acc)[TM][TN], float (&rs)[4])
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int RSA = LoaderF32T<BM>::RS, RSB = LoaderF32T<BN>::RS;
+    constexpr int PLANE_A = KT * RSA, PLANE_B = KT * RSB;
+    unsigned short *lds_b = lds + 3 * PLANE_A;
+    LoaderF32T<BM> la;
+    LoaderF32T<BN> lb;
+    la.init(P.a, tm * BM, tid, P.K);
+    lb.init(P.b, tn * BN, tid, P.K);
+    const int nk = (max(k1 - k0, 0) + KT - 1) / KT;
+    if (nk == 0) return;
+    floatx4 ra0[BM / 32], rb0[BN / 32], ra1[BM / 32], rb1[BN / 32];
+    // fragment addressing of the transposing read: lane -> (m within the 16-wide step, first of four rows)
+    const int frag_m = 8 * (lane >> 5) + ((lane & 15) >> 2);
+    const int frag_r = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    const int off_a = frag_m * RSA + wave_m * 32 * TM + frag_r;
+    const int off_b = frag_m * RSB + wave_n * 32 * TN + frag_r;
+    auto compute = [&]() {
+        if constexpr (LIVE) {
+            auto rd = [&](const unsigned short *plane, int rs_, int off, int u) {
+                const unsigned short *p = plane + off + 16 * u * rs_;
+                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4_ptr)p);
+                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4_ptr)(p + 4 * rs_));
+                typedef short shortx8 __attribute__((ext_vector_type(8)));
+                return __builtin_bit_cast(bf16x8, shortx8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
+            };
+            auto mm = [&](const bf16x8 (&x)[TM], const bf16x8 (&y)[TN]) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[i], y[j], acc[i][j], 0, 0, 0);
+            };
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                bf16x8 ah[TM], am[TM], bh[TN], bm[TN], bl[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) ah[i] = rd(lds, RSA, off_a + i * 32, u);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bh[j] = rd(lds_b, RSB, off_b + j * 32, u);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bm[j] = rd(lds_b + PLANE_B, RSB, off_b + j * 32, u);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bl[j] = rd(lds_b + 2 * PLANE_B, RSB, off_b + j * 32, u);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) am[i] = rd(lds + PLANE_A, RSA, off_a + i * 32, u);
+                __builtin_amdgcn_sched_barrier(0);
+                mm(ah, bh);
+                mm(ah, bm);
+                mm(ah, bl);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) ah[i] = rd(lds + 2 * PLANE_A, RSA, off_a + i * 32, u);   // the l plane of a
+                __builtin_amdgcn_sched_barrier(0);
+                mm(am, bh);
+                mm(am, bm);
+                mm(ah, bh);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    float unused[4] = {0.f, 0.f, 0.f, 0.f};
+    la.load(ra0, k0); lb.load(rb0, k0);
+    la.load(ra1, k0 + KT); lb.load(rb1, k0 + KT);
+    for (int it = 0; it < nk; it += 2) {
+        if (it > 0) __syncthreads();   // every wavefront has read the tile before
+        la.template store<RSUM>(ra0, lds, PLANE_A, k0 + it * KT, k1, rs);
+        lb.template store<false>(rb0, lds_b, PLANE_B, k0 + it * KT, k1, unused);
+        la.load(ra0, k0 + (it + 2) * KT); lb.load(rb0, k0 + (it + 2) * KT);
+        __syncthreads();
+        compute();
+        if (it + 1 < nk) {
+            __syncthreads();
+            la.template store<RSUM>(ra1, lds, PLANE_A, k0 + (it + 1) * KT, k1, rs);
+            lb.template store<false>(rb1, lds_b, PLANE_B, k0 + (it + 1) * KT, k1, unused);
+            la.load(ra1, k0 + (it + 3) * KT); lb.load(rb1, k0 + (it + 3) * KT);
+            __syncthreads();
+            compute();
+        }
+    }
+}
+
+// Row sums of a diagonal tile whose operand is stored transposed: a thread holds the sums of its four rows over
+// the m positions it loaded; the 256 / (BM / 4) threads that share a row chunk are added up through LDS.
+template <int BM>
+__device__ __forceinline__ void finish_row_sums_trans(const GemmProblem &P, float *lds, int tm, int tile, int split,
+                                                      int tid, const float (&rs)[4])
+{
+    constexpr int CG = BM / 4, PARTS = 256 / CG;
+    __syncthreads();   // the operand stages are dead
+#pragma unroll
+    for (int e = 0; e < 4; ++e) lds[(tid / CG) * BM + 4 * (tid % CG) + e] = rs[e];
+    __syncthreads();
+    if (tid < BM) {
+        float total = 0.f;
+#pragma unroll
+        for (int q = 0; q < PARTS; ++q) total += lds[q * BM + tid];
+        const int row = tm * BM + tid;
+        if (P.splits > 1) P.partial_rs[((long long)tm * P.splits + split) * BM + tid] = total;
+        else if (row < P.M) store_border(P, row, total);
+    }
+    if (tile == 0 && tid == 0 && P.splits == 1) store_corner(P);
+    __syncthreads();
+}
+
+template <int TM, int TN, bool SPLIT, bool TRANS = false>
 __device__ __forceinline__ void gemm_nt_f32_body(const GemmProblem *__restrict__ probs,
                                                  const int *__restrict__ tile_start, int n_probs)
 {
@@ -763,7 +935,19 @@ __device__ __forceinline__ void gemm_nt_f32_body(const GemmProblem *__restrict__
             gemm_f32_mainloop<TM, TN, LV, RSUM>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc, rs,
                                                 rs_rem);
     };
-    if (border) {
+    if constexpr (TRANS) {   // both operands stored with the rows contiguous (a launch of its own)
+        static_assert(SPLIT, "transposed operands: product mode of three bf16 planes only");
+        float rst[4] = {0.f, 0.f, 0.f, 0.f};
+        unsigned short *l16 = (unsigned short *)lds;
+        if (border) {
+            if (live) gemm_split_mainloop_trans<TM, TN, true, true>(P, tm, tn, tid, l16, k0, k1, wave_m, wave_n, lane, acc, rst);
+            else      gemm_split_mainloop_trans<TM, TN, false, true>(P, tm, tn, tid, l16, k0, k1, wave_m, wave_n, lane, acc, rst);
+            finish_row_sums_trans<BM>(P, lds, tm, tile, split, tid, rst);
+        } else {
+            if (live) gemm_split_mainloop_trans<TM, TN, true, false>(P, tm, tn, tid, l16, k0, k1, wave_m, wave_n, lane, acc, rst);
+            else      gemm_split_mainloop_trans<TM, TN, false, false>(P, tm, tn, tid, l16, k0, k1, wave_m, wave_n, lane, acc, rst);
+        }
+    } else if (border) {
         if (live) mainloop(std::true_type{}, std::true_type{});
         else      mainloop(std::false_type{}, std::true_type{});
         finish_row_sums<BM>(P, lds, tm, tile, split, tid, rs, rs_rem);
@@ -811,6 +995,14 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmProblem *__r
                                                           const int *__restrict__ tile_start, int n_probs)
 {
     gemm_nt_f32_body<TM, TN, false>(probs, tile_start, n_probs);
+}
+
+// the same for problems whose operands are stored transposed (GEMM_TRANS)
+template <int TM, int TN>
+__global__ __launch_bounds__(256, 2) void gemm_nt_f32_split_trans_kernel(const GemmProblem *__restrict__ probs,
+                                                                         const int *__restrict__ tile_start, int n_probs)
+{
+    gemm_nt_f32_body<TM, TN, true, true>(probs, tile_start, n_probs);
 }
 
 // (two wavefronts per SIMD: the register allocation is held to 256)
@@ -1330,7 +1522,9 @@ static hipError_t launch_one(const GemmProblem *probs_dev, const int *tile_start
     static_assert(2 * LDH == 4 * LDF, "bf16 and fp32 stages have the same size");
     constexpr size_t lds_bytes = gemm_lds_bytes<TM, TN>();
     static_assert(3 * (64 * TM + 64 * TN) * LDQ * sizeof(unsigned short) <= gemm_lds_bytes<TM, TN>(), "the three planes fit");
-    auto kernel = DT == 0 ? gemm_nt_f32_kernel<TM, TN> : DT == 2 ? gemm_nt_f32_split_kernel<TM, TN> : gemm_nt_bf16_kernel<TM, TN>;
+    static_assert(3 * KT * (64 * TM + 16 + 64 * TN + 16) * sizeof(unsigned short) <= gemm_lds_bytes<TM, TN>(), "and so do the transposed ones");
+    auto kernel = DT == 0 ? gemm_nt_f32_kernel<TM, TN> : DT == 2 ? gemm_nt_f32_split_kernel<TM, TN>
+                  : DT == 3 ? gemm_nt_f32_split_trans_kernel<TM, TN> : gemm_nt_bf16_kernel<TM, TN>;
     static bool configured = false;   // the attribute is per function, set once per process
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1349,6 +1543,10 @@ hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, 
     if (dtype == 0) {
         if (tile_cfg == 0) return launch_one<2, 2, 0>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
         return launch_one<1, 1, 0>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
+    }
+    if (dtype == 3) {   // the same on operands stored transposed
+        if (tile_cfg == 0) return launch_one<2, 2, 3>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
+        return launch_one<1, 1, 3>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
     }
     if (dtype == 2) {   // fp32 operands, products through three bf16 planes
         if (tile_cfg == 0) return launch_one<2, 2, 2>(probs_dev, tile_start_dev, n_probs, total_wgs, s);

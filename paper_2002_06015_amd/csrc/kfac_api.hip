@@ -414,6 +414,7 @@ struct StatsArgs {
     int g_spatial_mean;
     float *const *A_ema;
     float *const *G_ema;
+    int nhwc = 0;   // 1: act is [N, H, W, C_in] and grad_out [N, h, w, C_out]
 };
 
 // Workgroups of one patch / repack job.
@@ -462,6 +463,26 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
     int padbf_wgs = 0;
     std::vector<AssembleJob> asmjobs;
     std::vector<GemmProblem> probs;
+    std::vector<GemmProblem> tprobs;   // products of operands stored transposed (NHWC tensors in place): launches of their own
+    std::vector<LayoutJob> ljobs;      // NHWC tensors whose layer needs the NCHW order: converted into scratch first
+    long long layout_wgs = 0;
+    double layout_bytes = 0;
+    // An NHWC tensor is contracted in place by the transposed loader if it belongs to a pointwise layer, is fp32,
+    // the products run in the three-plane mode and the channel count is a whole number of 16-byte chunks;
+    // everything else is first brought into NCHW order (the kernel of kfac_nhwc_to_nchw) and then treated as usual.
+    auto to_nchw = [&](const void *src, int N, int c, int hw_in) -> const void * {
+        void *dst = arena.take((size_t)N * c * hw_in * esize);
+        LayoutJob J{};
+        J.src = src; J.dst = dst;
+        J.N = N; J.C = c; J.HW = hw_in;
+        J.tiles_c = (c + 63) / 64;
+        J.tiles_hw = (hw_in + 63) / 64;
+        J.wg_start = (int)layout_wgs;
+        layout_wgs += (long long)N * J.tiles_c * J.tiles_hw;
+        layout_bytes += 2.0 * (double)N * c * hw_in * esize;
+        ljobs.push_back(J);
+        return dry ? nullptr : dst;
+    };
     int patch_wgs = 0, pad_wgs = 0, asm_wgs = 0;
     double patch_bytes = 0, pad_bytes = 0, asm_bytes = 0;
     // An NCHW tensor [N, c, hw] is contracted in place when its runs are whole chunks; otherwise (and for every k > 1 / strided / padded layer) it is first rewritten
@@ -473,6 +494,18 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         *K_out = K;
         Operand op{};
         const bool pointwise = k == 1 && stride == 1 && pad == 0;
+        if (a.nhwc) {
+            if (pointwise && a.in == KFAC_F32 && tun.split && c % 4 == 0 && (dry || ((uintptr_t)src % 4) == 0)) {
+                op.base = src;
+                op.row_stride = c;     // from one position to the next
+                op.batch_stride = 0;
+                op.rows = c;
+                op.hw = K + 64;
+                op.trans = 1;
+                return op;
+            }
+            src = to_nchw(src, N, c, h_in * w_in);
+        }
         const bool direct = pointwise && hw % chunk == 0 && (dry || ((uintptr_t)src % chunk_align) == 0);
         // bf16 runs of 8q + 4 (14 x 14 planes): in place as well, the last chunk of a run in two halves
         const bool direct_tail = pointwise && !direct && a.in == KFAC_BF16 && hw % 8 == 4 && hw >= 12 &&
@@ -528,6 +561,8 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
                           2 * Hp * Wp <= 5 * hw;
         if (want_A && corr) {
             const int C = Ly.c_in, N = Ly.N, PP = Hp * Wp;
+            const void *act_l = dry ? nullptr : a.act[l];
+            if (a.nhwc) act_l = to_nchw(act_l, N, C, h * w);
             const int lal = bf ? 8 : 4;   // line lengths in whole 16-byte chunks
             const int Lw = (int)align_up((size_t)w + 2, lal), Lh = (int)align_up((size_t)h + 2, lal);
             // operands of the contractions: the image, the image displaced by (dy, dx), border lines shifted by d, corners
@@ -537,7 +572,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             int corner_K = N;
             if (!bf) {
                 PadJob J{};
-                J.src = dry ? nullptr : (const float *)a.act[l];
+                J.src = (const float *)act_l;
                 J.front_slack = (int)align_up((size_t)2 * Wp + 2, 4);
                 J.padded_floats = (long long)J.front_slack + (long long)N * C * PP + (long long)align_up((size_t)2 * Wp + 2, 4) + 4;
                 J.padded = (float *)arena.take((size_t)J.padded_floats * sizeof(float));
@@ -562,7 +597,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             } else {
                 PadJobBF16 J{};
                 const int Ln = (int)align_up((size_t)N, 8);
-                J.src = dry ? nullptr : (const unsigned short *)a.act[l];
+                J.src = (const unsigned short *)act_l;
                 J.front_slack = (int)align_up((size_t)2 * Wp + 2, 8);
                 J.copy_elems = (long long)J.front_slack + (long long)N * C * PP + (long long)align_up((size_t)2 * Wp + 2, 8) + 8;
                 J.rows_elems = (long long)align_up((size_t)2 * C * N * Lw + 8, 8);
@@ -655,8 +690,9 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             P.tile_cfg = choose_tile_cfg(P.M, P.N, K, true);
             P.alpha = (float)((1.0 - (double)a.decay) / ((double)Ly.N * (double)hw));
             P.beta = a.decay;
+            if (op.trans) P.flags |= GEMM_TRANS;
             finish_problem(P);
-            probs.push_back(P);
+            (op.trans ? tprobs : probs).push_back(P);
         }
         if (want_G) {
             int Kop = K;
@@ -672,11 +708,22 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             if (a.g_spatial_mean) scale /= (double)hw;
             P.alpha = (float)((1.0 - (double)a.decay) * scale);
             P.beta = a.decay;
+            if (op.trans) P.flags |= GEMM_TRANS;
             finish_problem(P);
-            probs.push_back(P);
+            (op.trans ? tprobs : probs).push_back(P);
         }
     }
     const size_t first_pre = plan.launches.size();
+    if (!ljobs.empty()) {
+        Launch L{};
+        L.kind = L_LAYOUT;
+        L.off_a = plan.tab.add(ljobs.data(), ljobs.size() * sizeof(LayoutJob));
+        L.n = (int)ljobs.size();
+        L.total_wgs = (int)layout_wgs;
+        L.cfg = esize;
+        L.bytes = layout_bytes;
+        plan.launches.push_back(L);
+    }
     if (!pjobs.empty()) {
         Launch L{};
         L.kind = L_PATCH;
@@ -733,6 +780,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             for (auto &c : chunks)
                 emit_gemm_phase(plan, arena, tun, c, a.in == KFAC_BF16 ? 1 : 0, true, false, post > 0 ? &reductions : nullptr);
         }
+        emit_gemm_phase(plan, arena, tun, tprobs, 3, true, false, post > 0 ? &reductions : nullptr);
     }
     if (post > 0) {
         plan.sync(L_RECORD, split->ev_gemm, 0);
@@ -1402,7 +1450,7 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
             }
             kfac_profile_entry pe{};
             switch (L.kind) {
-                case L_GEMM: pe.kernel = L.dtype == 0 ? KFAC_K_GEMM_F32 : L.dtype == 2 ? KFAC_K_GEMM_F32_SPLIT : KFAC_K_GEMM_BF16; break;
+                case L_GEMM: pe.kernel = L.dtype == 0 ? KFAC_K_GEMM_F32 : (L.dtype == 2 || L.dtype == 3) ? KFAC_K_GEMM_F32_SPLIT : KFAC_K_GEMM_BF16; break;
                 case L_REDUCE: pe.kernel = KFAC_K_GEMM_REDUCE; break;
                 case L_PATCH: pe.kernel = KFAC_K_PATCH; break;
                 case L_TRACE: pe.kernel = KFAC_K_TRACE; break;
@@ -1564,12 +1612,17 @@ size_t kfac_workspace_bytes_opt(const kfac_layer *L, int32_t n_layers, kfac_dtyp
     tun.worst_case_splits = true;
     size_t best = 0, sum_peaks = 0;
     {
-        Plan plan; Arena arena(nullptr);
-        StatsArgs a{n_layers, L, in, nullptr, nullptr, 0.5f, 0, nullptr, nullptr};
-        plan_stats(plan, arena, tun, a, true);
-        arena.take_tail(plan.tab.buf.size() + 16);
-        best = std::max(best, arena.peak);
-        sum_peaks += arena.peak;
+        size_t stats_peak = 0;
+        for (int nhwc = 0; nhwc < 2; ++nhwc) {   // NHWC inputs add the scratch of the tensors that are converted
+            Plan plan; Arena arena(nullptr);
+            StatsArgs a{n_layers, L, in, nullptr, nullptr, 0.5f, 0, nullptr, nullptr};
+            a.nhwc = nhwc;
+            plan_stats(plan, arena, tun, a, true);
+            arena.take_tail(plan.tab.buf.size() + 16);
+            stats_peak = std::max(stats_peak, arena.peak);
+        }
+        best = std::max(best, stats_peak);
+        sum_peaks += stats_peak;
     }
     {
         Plan plan; Arena arena(nullptr);
@@ -1592,13 +1645,16 @@ size_t kfac_workspace_bytes_opt(const kfac_layer *L, int32_t n_layers, kfac_dtyp
         // (searching over masks found 10 % above the full mask's plan at most): the sum of the
         // separate peaks plus a quarter covers that with room; kfac_step_workspace_bytes gives the
         // exact figure for one mask, and every call checks its own plan before it launches anything
-        Plan plan; Arena arena(nullptr);
-        StatsArgs st{n_layers, L, in, nullptr, nullptr, 0.5f, 0, nullptr, nullptr};
-        InvertArgs iv{n_layers, L, nullptr, nullptr, 1e-3f, nullptr, nullptr, nullptr, nullptr};
-        PrecondArgs pc{n_layers, L, nullptr, nullptr, nullptr, nullptr};
-        plan_step(plan, arena, tun, st, iv, nullptr, pc, true);
-        arena.take_tail(plan.tab.buf.size() + 16);
-        best = std::max(best, std::max(arena.peak, sum_peaks + sum_peaks / 4));
+        for (int nhwc = 0; nhwc < 2; ++nhwc) {
+            Plan plan; Arena arena(nullptr);
+            StatsArgs st{n_layers, L, in, nullptr, nullptr, 0.5f, 0, nullptr, nullptr};
+            st.nhwc = nhwc;
+            InvertArgs iv{n_layers, L, nullptr, nullptr, 1e-3f, nullptr, nullptr, nullptr, nullptr};
+            PrecondArgs pc{n_layers, L, nullptr, nullptr, nullptr, nullptr};
+            plan_step(plan, arena, tun, st, iv, nullptr, pc, true);
+            arena.take_tail(plan.tab.buf.size() + 16);
+            best = std::max(best, std::max(arena.peak, sum_peaks + sum_peaks / 4));
+        }
     }
     // im2col of a single layer and the BatchNorm calls need table space only
     best = std::max(best, (size_t)1 << 20);
@@ -1720,7 +1776,7 @@ kfac_status kfac_im2col(kfac_ctx *ctx, const kfac_layer *L, kfac_dtype dt, const
     return run_plan(ctx, plan, arena);
 }
 
-kfac_status kfac_stats(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
+static kfac_status stats_call(int nhwc, kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
                        const void *const *act, const void *const *grad_out, float decay, int32_t g_spatial_mean,
                        float *const *A_ema, float *const *G_ema)
 {
@@ -1737,8 +1793,23 @@ kfac_status kfac_stats(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfa
     }
     Plan plan; Arena arena(ctx->ws);
     StatsArgs a{n_layers, L, in, act, grad_out, decay, g_spatial_mean != 0, A_ema, G_ema};
+    a.nhwc = nhwc;
     plan_stats(plan, arena, ctx->tun, a, false);
     return run_plan(ctx, plan, arena);
+}
+
+kfac_status kfac_stats(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
+                       const void *const *act, const void *const *grad_out, float decay, int32_t g_spatial_mean,
+                       float *const *A_ema, float *const *G_ema)
+{
+    return stats_call(0, ctx, n_layers, L, in, act, grad_out, decay, g_spatial_mean, A_ema, G_ema);
+}
+
+kfac_status kfac_stats_nhwc(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
+                            const void *const *act, const void *const *grad_out, float decay, int32_t g_spatial_mean,
+                            float *const *A_ema, float *const *G_ema)
+{
+    return stats_call(1, ctx, n_layers, L, in, act, grad_out, decay, g_spatial_mean, A_ema, G_ema);
 }
 
 kfac_status kfac_invert(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, const float *const *A_ema,
@@ -1771,7 +1842,7 @@ kfac_status kfac_precondition(kfac_ctx *ctx, int32_t n_layers, const kfac_layer 
     return run_plan(ctx, plan, arena);
 }
 
-kfac_status kfac_step(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
+static kfac_status step_call(int nhwc, kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
                       const void *const *act, const void *const *grad_out, float decay, int32_t g_spatial_mean,
                       float *const *A_ema, float *const *G_ema, const uint8_t *invert_mask, float gamma,
                       float *const *A_inv, float *const *G_inv, float *pi_out, int32_t *info,
@@ -1791,10 +1862,31 @@ kfac_status kfac_step(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac
     }
     Plan plan; Arena arena(ctx->ws);
     StatsArgs st{n_layers, L, in, act, grad_out, decay, g_spatial_mean != 0, A_ema, G_ema};
+    st.nhwc = nhwc;
     InvertArgs iv{n_layers, L, A_ema, G_ema, gamma, A_inv, G_inv, pi_out, info};
     PrecondArgs pc{n_layers, L, G_inv, A_inv, grad_W, out};
     plan_step(plan, arena, ctx->tun, st, iv, invert_mask, pc, false);
     return run_plan(ctx, plan, arena);
+}
+
+kfac_status kfac_step(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
+                      const void *const *act, const void *const *grad_out, float decay, int32_t g_spatial_mean,
+                      float *const *A_ema, float *const *G_ema, const uint8_t *invert_mask, float gamma,
+                      float *const *A_inv, float *const *G_inv, float *pi_out, int32_t *info,
+                      const float *const *grad_W, float *const *out)
+{
+    return step_call(0, ctx, n_layers, L, in, act, grad_out, decay, g_spatial_mean, A_ema, G_ema, invert_mask, gamma,
+                     A_inv, G_inv, pi_out, info, grad_W, out);
+}
+
+kfac_status kfac_step_nhwc(kfac_ctx *ctx, int32_t n_layers, const kfac_layer *L, kfac_dtype in,
+                           const void *const *act, const void *const *grad_out, float decay, int32_t g_spatial_mean,
+                           float *const *A_ema, float *const *G_ema, const uint8_t *invert_mask, float gamma,
+                           float *const *A_inv, float *const *G_inv, float *pi_out, int32_t *info,
+                           const float *const *grad_W, float *const *out)
+{
+    return step_call(1, ctx, n_layers, L, in, act, grad_out, decay, g_spatial_mean, A_ema, G_ema, invert_mask, gamma,
+                     A_inv, G_inv, pi_out, info, grad_W, out);
 }
 
 kfac_status bn_unitwise_precondition(kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,

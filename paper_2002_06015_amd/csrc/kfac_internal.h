@@ -27,6 +27,9 @@ struct Operand {
     int rows;
     int hw;
     int tail;   // 0, or 4 (bf16 only): valid elements in the last 8-element chunk of a run
+    int trans;  // 1 (fp32, product mode of three bf16 planes only): the operand is stored with its rows as the
+                // contiguous direction, element (r, m) at base + m * row_stride + r (an NHWC tensor [N*hw, rows]
+                // contracted in place); rows % 4 == 0, a chunk is four adjacent rows at one m
 };
 
 // GEMM_SYM:    M == N and a == b; only tiles tm >= tn are computed and mirrored.
@@ -35,7 +38,8 @@ struct Operand {
 //              not multiplied out: C[i][M] = C[M][i] = alpha * sum_m a(i, m) + beta * old
 //              comes from row sums taken while the diagonal tiles stage their operand,
 //              and C[M][M] = alpha * ones + beta * old.
-enum : int { GEMM_SYM = 1, GEMM_BORDER = 2 };
+// GEMM_TRANS:  both operands are stored transposed (Operand::trans).
+enum : int { GEMM_SYM = 1, GEMM_BORDER = 2, GEMM_TRANS = 4 };
 
 struct GemmProblem {
     Operand a, b;

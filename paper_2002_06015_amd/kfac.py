@@ -27,7 +27,7 @@ EXPORTS = [
     "bn_unitwise_precondition", "bn_unitwise_reduce_nchw", "kfac_profile_enable", "kfac_profile_read",
     "kfac_packed_elems", "kfac_pack_upper", "kfac_unpack_upper",
     "kfac_lr_polynomial", "kfac_momentum_coupled", "kfac_update_weights",
-    "bn_full_workspace_bytes", "bn_full_precondition", "kfac_nhwc_to_nchw",
+    "bn_full_workspace_bytes", "bn_full_precondition", "kfac_nhwc_to_nchw", "kfac_stats_nhwc", "kfac_step_nhwc",
     "kfac_staleness", "kfac_staleness_static", "kfac_next_interval", "kfac_refresh_init", "kfac_refresh_due", "kfac_refresh_advance",
 ]
 
@@ -116,9 +116,11 @@ def lib() -> ctypes.CDLL:
         L.kfac_destroy.argtypes = [vp]
         L.kfac_im2col.argtypes = [vp, vp, ctypes.c_int, vp, vp, ctypes.c_int64]
         L.kfac_stats.argtypes = [vp, i32, vp, ctypes.c_int, vp, vp, f32, i32, vp, vp]
+        L.kfac_stats_nhwc.argtypes = L.kfac_stats.argtypes
         L.kfac_invert.argtypes = [vp, i32, vp, vp, vp, f32, vp, vp, vp, vp]
         L.kfac_precondition.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         L.kfac_step.argtypes = [vp, i32, vp, ctypes.c_int, vp, vp, f32, i32, vp, vp, vp, f32, vp, vp, vp, vp, vp, vp]
+        L.kfac_step_nhwc.argtypes = L.kfac_step.argtypes
         L.bn_unitwise_precondition.argtypes = [vp, i32, i32, vp, vp, vp, f32, f32, vp, vp, vp]
         L.bn_unitwise_reduce_nchw.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
         L.kfac_profile_enable.argtypes = [vp, i32]
@@ -297,19 +299,21 @@ def kfac_im2col(ctx: Context, layer, in_dtype: int, act: torch.Tensor, patches: 
 
 
 def kfac_stats(ctx: Context, layers: Sequence, in_dtype: int, act, grad_out, decay: float,
-               g_spatial_mean: bool, A_ema, G_ema) -> None:
+               g_spatial_mean: bool, A_ema, G_ema, nhwc: bool = False) -> None:
+    """nhwc: act / grad_out are stored [N, H, W, C] (kfac_stats_nhwc); same element counts."""
     n = len(layers)
     arr = _layers(layers)
     sz = _sizes(layers)
     pa = _ptrs(act, n, _tdtype(in_dtype), sz["act"], "act")
     pg = _ptrs(grad_out, n, _tdtype(in_dtype), sz["grad_out"], "grad_out")
     pA, pG = _ptrs(A_ema, n, torch.float32, sz["A"], "A_ema"), _ptrs(G_ema, n, torch.float32, sz["G"], "G_ema")
-    st = lib().kfac_stats(ctx.handle, n, ctypes.addressof(arr), int(in_dtype),
-                          pa and ctypes.addressof(pa), pg and ctypes.addressof(pg),
-                          float(decay), int(bool(g_spatial_mean)),
-                          pA and ctypes.addressof(pA), pG and ctypes.addressof(pG))
+    entry = lib().kfac_stats_nhwc if nhwc else lib().kfac_stats
+    st = entry(ctx.handle, n, ctypes.addressof(arr), int(in_dtype),
+               pa and ctypes.addressof(pa), pg and ctypes.addressof(pg),
+               float(decay), int(bool(g_spatial_mean)),
+               pA and ctypes.addressof(pA), pG and ctypes.addressof(pG))
     if st != KFAC_OK:
-        raise KfacError(st, "kfac_stats")
+        raise KfacError(st, "kfac_stats_nhwc" if nhwc else "kfac_stats")
 
 
 def kfac_invert(ctx: Context, layers: Sequence, A_ema, G_ema, gamma: float, A_inv, G_inv,
@@ -345,7 +349,8 @@ def kfac_precondition(ctx: Context, layers: Sequence, G_inv, A_inv, grad_W, out)
 
 def kfac_step(ctx: Context, layers: Sequence, in_dtype: int, act, grad_out, decay: float, g_spatial_mean: bool,
               A_ema, G_ema, invert_mask: Optional[Sequence[bool]], gamma: float, A_inv, G_inv,
-              pi_out: Optional[torch.Tensor], info: Optional[torch.Tensor], grad_W, out) -> None:
+              pi_out: Optional[torch.Tensor], info: Optional[torch.Tensor], grad_W, out, nhwc: bool = False) -> None:
+    """nhwc: act / grad_out are stored [N, H, W, C] (kfac_step_nhwc); same element counts."""
     n = len(layers)
     arr = _layers(layers)
     sz = _sizes(layers)
@@ -363,12 +368,13 @@ def kfac_step(ctx: Context, layers: Sequence, in_dtype: int, act, grad_out, deca
         raise ValueError("pi_out must be float32 [n_layers]")
     if info is not None and (info.dtype != torch.int32 or info.numel() < 2 * n):
         raise ValueError("info must be int32 [2*n_layers]")
-    st = lib().kfac_step(ctx.handle, n, ctypes.addressof(arr), int(in_dtype), pa, pg, float(decay),
-                         int(bool(g_spatial_mean)), pA, pG, mask and ctypes.addressof(mask), float(gamma),
-                         pAi, pGi, None if pi_out is None else pi_out.data_ptr(),
-                         None if info is None else info.data_ptr(), pW, pO)
+    entry = lib().kfac_step_nhwc if nhwc else lib().kfac_step
+    st = entry(ctx.handle, n, ctypes.addressof(arr), int(in_dtype), pa, pg, float(decay),
+               int(bool(g_spatial_mean)), pA, pG, mask and ctypes.addressof(mask), float(gamma),
+               pAi, pGi, None if pi_out is None else pi_out.data_ptr(),
+               None if info is None else info.data_ptr(), pW, pO)
     if st != KFAC_OK:
-        raise KfacError(st, "kfac_step")
+        raise KfacError(st, "kfac_step_nhwc" if nhwc else "kfac_step")
 
 
 def bn_unitwise_precondition(ctx: Context, N: int, C: Sequence[int], g_gamma, g_beta, decay: float, lam: float,

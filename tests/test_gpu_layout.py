@@ -97,3 +97,89 @@ def test_full_resnet50_activation_set(gpu):
     for i in range(len(layers)):
         assert torch.equal(dst[i], src[i].permute(0, 3, 1, 2).reshape(-1)), i
     ctx.close()
+
+
+# pointwise layers whose channel counts are multiples of 4 (contracted in place: interior and ragged tiles, one
+# and several K tiles, a single sample, long contractions that are split), channel counts that are not (converted
+# inside the call), 3x3 / 7x7 / strided layers (converted, then the usual paths), fully connected layers
+NHWC_LAYERS = [wl.conv_layer(3, 8, 12, 1, 1, 0, 6), wl.conv_layer(2, 132, 64, 1, 1, 0, 8), wl.conv_layer(1, 260, 4, 1, 1, 0, 5),
+               wl.conv_layer(4, 64, 256, 1, 1, 0, 28), wl.conv_layer(2, 7, 9, 1, 1, 0, 6), wl.conv_layer(2, 8, 12, 3, 1, 1, 6),
+               wl.conv_layer(2, 5, 6, 3, 2, 1, 9), wl.conv_layer(2, 3, 8, 7, 2, 3, 30), wl.Layer(2, 20, 6, 3, 1, 1, 10, 14, 1),
+               wl.conv_layer(2, 260, 4, 1, 2, 0, 14), wl.fc_layer(37, 64, 32), wl.fc_layer(5, 33, 17, bias=0),
+               wl.conv_layer(9, 16, 300, 1, 1, 0, 14, bias=0)]
+
+
+def _nhwc_inputs(layers, seed):
+    rng = np.random.default_rng(seed)
+    a = [np.maximum(rng.standard_normal(_shape(L, 0)), 0).astype(np.float32) for L in layers]
+    g = [(rng.standard_normal(_shape(L, 1)) * 1e-3).astype(np.float32) for L in layers]
+    return a, g
+
+
+@pytest.mark.parametrize("type_", [kfac.KFAC_F32, kfac.KFAC_BF16])
+@pytest.mark.parametrize("products", ["split", "fp32"])
+def test_statistics_straight_from_nhwc_tensors_match_the_oracle(gpu, type_, products):
+    """kfac_stats_nhwc, two steps with the running average, against the oracle on the same data in NCHW order.
+    fp32 in the default product mode takes the transposed loader for the pointwise tensors; bf16 tensors and
+    the fp32-instruction mode go through the conversion inside the call."""
+    layers = NHWC_LAYERS
+    opts = kfac.options(fp32_products=kfac.KFAC_PRODUCTS_FP32_MFMA) if products == "fp32" else None
+    ctx = kfac.Context(layers, type_, opts=opts)
+    tdt = torch.bfloat16 if type_ == kfac.KFAC_BF16 else torch.float32
+    A = [torch.full((L.dA, L.dA), float("nan"), device="cuda") for L in layers]
+    G = [torch.full((L.dG, L.dG), float("nan"), device="cuda") for L in layers]
+    Ar, Gr = [None] * len(layers), [None] * len(layers)
+    for step in range(2):
+        decay = 0.0 if step == 0 else 0.9
+        a, g = _nhwc_inputs(layers, 40 + step)
+        if type_ == kfac.KFAC_BF16:
+            a, g = [wl.round_to_bf16(x) for x in a], [wl.round_to_bf16(x) for x in g]
+        kfac.kfac_stats(ctx, layers, type_, [torch.from_numpy(x).cuda().to(tdt) for x in a],
+                        [torch.from_numpy(x).cuda().to(tdt) for x in g], decay, step == 1, A, G, nhwc=True)
+        torch.cuda.synchronize()
+        for i, L in enumerate(layers):
+            Ar[i], Gr[i] = oracle.kfac_stats(tuple(L), layout.nhwc_to_nchw(a[i]), layout.nhwc_to_nchw(g[i]), decay,
+                                             step == 1, Ar[i], Gr[i])
+            for got, ref in ((A[i], Ar[i]), (G[i], Gr[i])):
+                h = got.cpu().numpy().astype(np.float64)
+                assert np.array_equal(h, h.T), (i, step)
+                assert np.abs(h - ref).max() <= 1e-4 * np.abs(ref).max(), (i, step, tuple(L))
+    ctx.close()
+
+
+def test_fused_step_straight_from_nhwc_tensors_matches_the_nchw_step(gpu):
+    """kfac_step_nhwc against kfac_step on the converted tensors (same factors up to the order of the sums, so the
+    same inverses and preconditioned gradients to the tolerances of the step) and against the oracle."""
+    layers = [wl.conv_layer(4, 64, 256, 1, 1, 0, 14), wl.conv_layer(2, 40, 130, 3, 1, 1, 10), wl.fc_layer(32, 64, 32),
+              wl.conv_layer(3, 132, 36, 1, 1, 0, 9), wl.conv_layer(3, 5, 6, 3, 2, 1, 9, bias=0)]
+    n = len(layers)
+    ctx = kfac.Context(layers)
+    a, g = _nhwc_inputs(layers, 77)
+    gws = [wl.make_grad_W(L, 300 + i) for i, L in enumerate(layers)]
+    d_w = [torch.from_numpy(x).cuda() for x in gws]
+    res = {}
+    for nhwc in (True, False):
+        conv = (lambda x: x) if nhwc else layout.nhwc_to_nchw
+        d_a = [torch.from_numpy(np.ascontiguousarray(conv(x))).cuda() for x in a]
+        d_g = [torch.from_numpy(np.ascontiguousarray(conv(x))).cuda() for x in g]
+        A = [torch.zeros(L.dA, L.dA, device="cuda") for L in layers]
+        G = [torch.zeros(L.dG, L.dG, device="cuda") for L in layers]
+        Ai, Gi = [torch.zeros_like(x) for x in A], [torch.zeros_like(x) for x in G]
+        U = [torch.zeros(L.dG, L.dA, device="cuda") for L in layers]
+        info = torch.zeros(2 * n, dtype=torch.int32, device="cuda")
+        kfac.kfac_step(ctx, layers, kfac.KFAC_F32, d_a, d_g, 0.0, True, A, G, None, wl.GAMMA, Ai, Gi, None, info, d_w, U,
+                       nhwc=nhwc)
+        torch.cuda.synchronize()
+        assert not info.cpu().numpy().any()
+        res[nhwc] = (A, G, Ai, Gi, U)
+    rel = lambda x, y: float(np.abs(x - y).max() / np.abs(y).max())
+    for i, L in enumerate(layers):
+        Ar, Gr = oracle.kfac_stats(tuple(L), layout.nhwc_to_nchw(a[i]), layout.nhwc_to_nchw(g[i]), 0.0, True, None, None)
+        Air, Gir, _, _ = oracle.kfac_invert(Ar, Gr, wl.GAMMA)
+        Ur = oracle.kfac_precondition(Gir, Air, gws[i])
+        got = [x[i].cpu().numpy().astype(np.float64) for x in res[True]]
+        other = [x[i].cpu().numpy().astype(np.float64) for x in res[False]]
+        assert rel(got[0], Ar) <= 1e-4 and rel(got[1], Gr) <= 1e-4, i
+        assert rel(got[2], Air) <= 1e-3 and rel(got[3], Gir) <= 1e-3 and rel(got[4], Ur) <= 1e-3, i
+        assert rel(got[0], other[0]) <= 1e-5 and rel(got[4], other[4]) <= 1e-4, i
+    ctx.close()
