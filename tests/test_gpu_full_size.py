@@ -247,3 +247,37 @@ def test_v1_5_stride2_3x3_layers_element_by_element(gpu, progress, in_dtype):
         ref = _oracle_set(("v1.5", in_dtype), layers, inputs, r["idx"], progress)
         _compare_all(layers, r, ref, inputs, progress)
     del _ORACLE[("v1.5", in_dtype)]
+
+
+@pytest.mark.timeout(600)
+def test_nhwc_tensors_in_place_element_by_element(gpu, progress):
+    """Tensors kept in NHWC handed to kfac_step_nhwc at the benchmark's sizes: pointwise layers at 56x56, 14x14 and
+    7x7 and the fully connected layer (contracted in place by the transposed loader, contractions up to 100 352
+    long), a 3x3 layer and the 7x7 stem (converted inside the call); the oracle works on the same data in NCHW."""
+    layers = [wl.conv_layer(32, 64, 256, 1, 1, 0, 56), wl.conv_layer(32, 1024, 256, 1, 1, 0, 14),
+              wl.conv_layer(32, 2048, 512, 1, 1, 0, 7), wl.fc_layer(32, 2048, 1000),
+              wl.conv_layer(32, 128, 128, 3, 1, 1, 28), wl.conv_layer(32, 3, 64, 7, 2, 3, 224)]
+    inputs = _inputs(layers, 8, kfac.KFAC_F32)
+    acts, grads, gws = inputs
+    n = len(layers)
+    to_nhwc = lambda x: np.ascontiguousarray(np.transpose(x, (0, 2, 3, 1)))
+    d_act = [torch.from_numpy(to_nhwc(a)).cuda() for a in acts]
+    d_grad = [torch.from_numpy(to_nhwc(g)).cuda() for g in grads]
+    d_gw = [torch.from_numpy(g).cuda() for g in gws]
+    ctx = kfac.Context(layers)
+    A = [torch.full((L.dA, L.dA), float("nan"), device="cuda") for L in layers]
+    G = [torch.full((L.dG, L.dG), float("nan"), device="cuda") for L in layers]
+    Ai = [torch.zeros(L.dA, L.dA, device="cuda") for L in layers]
+    Gi = [torch.zeros(L.dG, L.dG, device="cuda") for L in layers]
+    U = [torch.zeros(L.dG, L.dA, device="cuda") for L in layers]
+    pi = torch.zeros(n, device="cuda")
+    info = torch.zeros(2 * n, dtype=torch.int32, device="cuda")
+    kfac.kfac_step(ctx, layers, kfac.KFAC_F32, d_act, d_grad, 0.0, True, A, G, None, wl.GAMMA, Ai, Gi, pi, info, d_gw, U,
+                   nhwc=True)
+    torch.cuda.synchronize()
+    ctx.close()
+    assert not info.cpu().numpy().any()
+    r = dict(A=A, G=G, Ai=Ai, Gi=Gi, U=U, pi=host(pi), idx=list(range(n)), stale={})
+    ref = _oracle_set("nhwc", layers, inputs, r["idx"], progress)
+    _compare_all(layers, r, ref, inputs, progress)
+    del _ORACLE["nhwc"]
