@@ -365,8 +365,9 @@ kfac_status kfac_nhwc_to_nchw(kfac_ctx *ctx, int32_t n_layers, const kfac_layer 
  * grad_out[l] dev [N, h, w, c_out]; every other argument, every result and every error as for
  * kfac_stats / kfac_step (the statistics of Sec. 3.3 do not depend on the storage order).
  * Tensors of pointwise layers (1 x 1, stride 1, no padding, fully connected) and all output
- * gradients are contracted where they are when they are fp32, the context forms products in its
- * default mode (KFAC_PRODUCTS_SPLIT_BF16) and the channel count is a multiple of 4; all other
+ * gradients are contracted where they are if their channel count is a whole number of 16-byte
+ * chunks (fp32: a multiple of 4, and the context forms products in its default mode
+ * KFAC_PRODUCTS_SPLIT_BF16; bf16: a multiple of 8 and a 16-byte aligned pointer); all other
  * tensors are first brought into NCHW order inside the workspace (the conversion of
  * kfac_nhwc_to_nchw, the scratch is part of kfac_workspace_bytes).
  */

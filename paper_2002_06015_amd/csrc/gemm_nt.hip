@@ -852,14 +852,14 @@ __device__ __forceinline__ void gemm_split_mainloop_trans(const GemmProblem &P, 
 
 // Row sums of a diagonal tile whose operand is stored transposed: a thread holds the sums of its four rows over
 // the m positions it loaded; the 256 / (BM / 4) threads that share a row chunk are added up through LDS.
-template <int BM>
+template <int BM, int E>
 __device__ __forceinline__ void finish_row_sums_trans(const GemmProblem &P, float *lds, int tm, int tile, int split,
-                                                      int tid, const float (&rs)[4])
+                                                      int tid, const float (&rs)[E])
 {
-    constexpr int CG = BM / 4, PARTS = 256 / CG;
+    constexpr int CG = BM / E, PARTS = 256 / CG;
     __syncthreads();   // the operand stages are dead
 #pragma unroll
-    for (int e = 0; e < 4; ++e) lds[(tid / CG) * BM + 4 * (tid % CG) + e] = rs[e];
+    for (int e = 0; e < E; ++e) lds[(tid / CG) * BM + E * (tid % CG) + e] = rs[e];
     __syncthreads();
     if (tid < BM) {
         float total = 0.f;
@@ -942,7 +942,7 @@ __device__ __forceinline__ void gemm_nt_f32_body(const GemmProblem *__restrict__
         if (border) {
             if (live) gemm_split_mainloop_trans<TM, TN, true, true>(P, tm, tn, tid, l16, k0, k1, wave_m, wave_n, lane, acc, rst);
             else      gemm_split_mainloop_trans<TM, TN, false, true>(P, tm, tn, tid, l16, k0, k1, wave_m, wave_n, lane, acc, rst);
-            finish_row_sums_trans<BM>(P, lds, tm, tile, split, tid, rst);
+            finish_row_sums_trans<BM, 4>(P, lds, tm, tile, split, tid, rst);
         } else {
             if (live) gemm_split_mainloop_trans<TM, TN, true, false>(P, tm, tn, tid, l16, k0, k1, wave_m, wave_n, lane, acc, rst);
             else      gemm_split_mainloop_trans<TM, TN, false, false>(P, tm, tn, tid, l16, k0, k1, wave_m, wave_n, lane, acc, rst);
@@ -1333,9 +1333,124 @@ __device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm,
     for (; it < nk; ++it) step(it);
 }
 
+// ------------------------------------------------------------------ bf16 operands stored transposed
+// As LoaderF32T / gemm_split_mainloop_trans with one plane and no conversion: a thread loads 16 bytes = eight
+// adjacent rows at one m and stores them as they are into the [m][row] tile; rows % 8 == 0, 16-byte aligned base.
+template <int BR>
+struct LoaderBF16T {
+    static constexpr int CG = BR / 8;
+    static constexpr int MSTEP = 256 / CG;
+    static constexpr int SLOTS = KT / MSTEP;   // K tiles of 32 here
+    static constexpr int RS = BR + 16;
+    gushort_ptr base;
+    long long ld;
+    int c_local, c_load, mk, K;
+    bool dead;
+
+    __device__ __forceinline__ void init(const Operand &op, int tile_row0, int tid, int K_)
+    {
+        base = (gushort_ptr)op.base;
+        ld = op.row_stride;
+        c_local = 8 * (tid % CG);
+        mk = tid / CG;
+        const int c = tile_row0 + c_local;
+        dead = c >= op.rows;
+        c_load = min(c, op.rows - 8);
+        K = K_;
+    }
+    __device__ __forceinline__ void load(ushortx8 (&reg)[SLOTS], int tile_m0) const
+    {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const int m = min(tile_m0 + mk + MSTEP * s, K - 1);
+            reg[s] = *(gushort8_ptr)(base + (long long)m * ld + c_load);
+        }
+    }
+    template <bool RSUM>
+    __device__ __forceinline__ void store(const ushortx8 (&reg)[SLOTS], unsigned short *rows, int tile_m0, int mend,
+                                          float (&rs)[8]) const
+    {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            ushortx8 v = reg[s];
+            const int ml = mk + MSTEP * s;
+            if (dead || tile_m0 + ml >= mend) v = ushortx8{0, 0, 0, 0, 0, 0, 0, 0};
+            if constexpr (RSUM) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) rs[e] += __uint_as_float((unsigned)v[e] << 16);
+            }
+            *(ushortx8 *)(rows + ml * RS + c_local) = v;
+        }
+    }
+};
+
+template <int TM, int TN, bool LIVE, bool RSUM>
+__device__ __forceinline__ void gemm_bf16_mainloop_trans(const GemmProblem &P, int tm, int tn, int tid,
+                                                         unsigned short *lds, int k0, int k1, int wave_m, int wave_n,
+                                                         int lane, floatx16 (&acc)[TM][TN], float (&rs)[8])
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int RSA = LoaderBF16T<BM>::RS, RSB = LoaderBF16T<BN>::RS;
+    unsigned short *lds_b = lds + KT * RSA;
+    LoaderBF16T<BM> la;
+    LoaderBF16T<BN> lb;
+    la.init(P.a, tm * BM, tid, P.K);
+    lb.init(P.b, tn * BN, tid, P.K);
+    const int nk = (max(k1 - k0, 0) + KT - 1) / KT;
+    if (nk == 0) return;
+    ushortx8 ra0[LoaderBF16T<BM>::SLOTS], rb0[LoaderBF16T<BN>::SLOTS], ra1[LoaderBF16T<BM>::SLOTS], rb1[LoaderBF16T<BN>::SLOTS];
+    const int frag_m = 8 * (lane >> 5) + ((lane & 15) >> 2);
+    const int frag_r = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    const int off_a = frag_m * RSA + wave_m * 32 * TM + frag_r;
+    const int off_b = frag_m * RSB + wave_n * 32 * TN + frag_r;
+    auto compute = [&]() {
+        if constexpr (LIVE) {
+            auto rd = [&](const unsigned short *tile, int rs_, int off, int u) {
+                const unsigned short *p = tile + off + 16 * u * rs_;
+                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4_ptr)p);
+                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4_ptr)(p + 4 * rs_));
+                typedef short shortx8 __attribute__((ext_vector_type(8)));
+                return __builtin_bit_cast(bf16x8, shortx8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
+            };
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                bf16x8 a[TM], b[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) a[i] = rd(lds, RSA, off_a + i * 32, u);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) b[j] = rd(lds_b, RSB, off_b + j * 32, u);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+            }
+        }
+    };
+    float unused[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    la.load(ra0, k0); lb.load(rb0, k0);
+    la.load(ra1, k0 + KT); lb.load(rb1, k0 + KT);
+    for (int it = 0; it < nk; it += 2) {
+        if (it > 0) __syncthreads();
+        la.template store<RSUM>(ra0, lds, k0 + it * KT, k1, rs);
+        lb.template store<false>(rb0, lds_b, k0 + it * KT, k1, unused);
+        la.load(ra0, k0 + (it + 2) * KT); lb.load(rb0, k0 + (it + 2) * KT);
+        __syncthreads();
+        compute();
+        if (it + 1 < nk) {
+            __syncthreads();
+            la.template store<RSUM>(ra1, lds, k0 + (it + 1) * KT, k1, rs);
+            lb.template store<false>(rb1, lds_b, k0 + (it + 1) * KT, k1, unused);
+            la.load(ra1, k0 + (it + 3) * KT); lb.load(rb1, k0 + (it + 3) * KT);
+            __syncthreads();
+            compute();
+        }
+    }
+}
+
 // TAIL: an operand of the problem has runs with a four-element tail (Operand::tail); a variant of its
 // own, so that the loads of all other problems stay single 16-byte loads without a branch.
-template <int TM, int TN, bool TAIL>
+template <int TM, int TN, bool TAIL, bool TRANS = false>
 __device__ __forceinline__ void gemm_nt_bf16_body(const GemmProblem &P, int local, float *lds)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
@@ -1373,7 +1488,17 @@ __device__ __forceinline__ void gemm_nt_bf16_body(const GemmProblem &P, int loca
     float rs[BM / 32], rs_rem = 0.f;
 #pragma unroll
     for (int s = 0; s < BM / 32; ++s) rs[s] = 0.f;
-    if (border) {
+    if constexpr (TRANS) {
+        float rst[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (border) {
+            if (live) gemm_bf16_mainloop_trans<TM, TN, true, true>(P, tm, tn, tid, lds16, k0, k1, wave_m, wave_n, lane, acc, rst);
+            else      gemm_bf16_mainloop_trans<TM, TN, false, true>(P, tm, tn, tid, lds16, k0, k1, wave_m, wave_n, lane, acc, rst);
+            finish_row_sums_trans<BM, 8>(P, lds, tm, tile, split, tid, rst);
+        } else {
+            if (live) gemm_bf16_mainloop_trans<TM, TN, true, false>(P, tm, tn, tid, lds16, k0, k1, wave_m, wave_n, lane, acc, rst);
+            else      gemm_bf16_mainloop_trans<TM, TN, false, false>(P, tm, tn, tid, lds16, k0, k1, wave_m, wave_n, lane, acc, rst);
+        }
+    } else if (border) {
         if (live) gemm_bf16_mainloop<TM, TN, true, true, TAIL>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
         else      gemm_bf16_mainloop<TM, TN, false, true, TAIL>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
         finish_row_sums<BM>(P, lds, tm, tile, split, tid, rs, rs_rem);
@@ -1508,6 +1633,20 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmProblem *__
     else                     gemm_nt_bf16_body<TM, TN, false>(P, local, lds);
 }
 template <int TM, int TN>
+__global__ __launch_bounds__(256) void gemm_nt_bf16_trans_kernel(const GemmProblem *__restrict__ probs,
+                                                                 const int *__restrict__ tile_start, int n_probs)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int wg = blockIdx.x;
+    const int pi = find_problem(tile_start, n_probs, wg);
+    const GemmProblem &P = probs[pi];
+    const int n_local = P.n_tiles * P.splits;
+    const int local = xcd_remap(wg - tile_start[pi], (n_local + 7) & ~7);
+    if (local >= n_local) return;
+    gemm_nt_bf16_body<TM, TN, false, true>(P, local, lds);
+}
+
+template <int TM, int TN>
 constexpr size_t gemm_lds_bytes()
 {
     const size_t stages = 2 * (64 * TM + 64 * TN) * LDF * sizeof(float);   // same size for LDH bf16 rows
@@ -1524,7 +1663,8 @@ static hipError_t launch_one(const GemmProblem *probs_dev, const int *tile_start
     static_assert(3 * (64 * TM + 64 * TN) * LDQ * sizeof(unsigned short) <= gemm_lds_bytes<TM, TN>(), "the three planes fit");
     static_assert(3 * KT * (64 * TM + 16 + 64 * TN + 16) * sizeof(unsigned short) <= gemm_lds_bytes<TM, TN>(), "and so do the transposed ones");
     auto kernel = DT == 0 ? gemm_nt_f32_kernel<TM, TN> : DT == 2 ? gemm_nt_f32_split_kernel<TM, TN>
-                  : DT == 3 ? gemm_nt_f32_split_trans_kernel<TM, TN> : gemm_nt_bf16_kernel<TM, TN>;
+                  : DT == 3 ? gemm_nt_f32_split_trans_kernel<TM, TN> : DT == 4 ? gemm_nt_bf16_trans_kernel<TM, TN>
+                  : gemm_nt_bf16_kernel<TM, TN>;
     static bool configured = false;   // the attribute is per function, set once per process
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1543,6 +1683,10 @@ hipError_t launch_gemm(const GemmProblem *probs_dev, const int *tile_start_dev, 
     if (dtype == 0) {
         if (tile_cfg == 0) return launch_one<2, 2, 0>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
         return launch_one<1, 1, 0>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
+    }
+    if (dtype == 4) {   // bf16 operands stored transposed
+        if (tile_cfg == 0) return launch_one<2, 2, 4>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
+        return launch_one<1, 1, 4>(probs_dev, tile_start_dev, n_probs, total_wgs, s);
     }
     if (dtype == 3) {   // the same on operands stored transposed
         if (tile_cfg == 0) return launch_one<2, 2, 3>(probs_dev, tile_start_dev, n_probs, total_wgs, s);

@@ -467,9 +467,10 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
     std::vector<LayoutJob> ljobs;      // NHWC tensors whose layer needs the NCHW order: converted into scratch first
     long long layout_wgs = 0;
     double layout_bytes = 0;
-    // An NHWC tensor is contracted in place by the transposed loader if it belongs to a pointwise layer, is fp32,
-    // the products run in the three-plane mode and the channel count is a whole number of 16-byte chunks;
-    // everything else is first brought into NCHW order (the kernel of kfac_nhwc_to_nchw) and then treated as usual.
+    // An NHWC tensor is contracted in place by the transposed loader if it belongs to a pointwise layer and its
+    // channel count is a whole number of 16-byte chunks (fp32: in the three-plane product mode only; bf16: base
+    // 16-byte aligned); everything else is first brought into NCHW order (the kernel of kfac_nhwc_to_nchw) and
+    // then treated as usual.
     auto to_nchw = [&](const void *src, int N, int c, int hw_in) -> const void * {
         void *dst = arena.take((size_t)N * c * hw_in * esize);
         LayoutJob J{};
@@ -495,7 +496,9 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
         Operand op{};
         const bool pointwise = k == 1 && stride == 1 && pad == 0;
         if (a.nhwc) {
-            if (pointwise && a.in == KFAC_F32 && tun.split && c % 4 == 0 && (dry || ((uintptr_t)src % 4) == 0)) {
+            const bool in_place = a.in == KFAC_F32 ? (tun.split && c % 4 == 0)
+                                                   : (c % 8 == 0 && (dry || ((uintptr_t)src % 16) == 0));
+            if (pointwise && in_place) {
                 op.base = src;
                 op.row_stride = c;     // from one position to the next
                 op.batch_stride = 0;
@@ -780,7 +783,7 @@ void plan_stats(Plan &plan, Arena &arena, const Tunables &tun, const StatsArgs &
             for (auto &c : chunks)
                 emit_gemm_phase(plan, arena, tun, c, a.in == KFAC_BF16 ? 1 : 0, true, false, post > 0 ? &reductions : nullptr);
         }
-        emit_gemm_phase(plan, arena, tun, tprobs, 3, true, false, post > 0 ? &reductions : nullptr);
+        emit_gemm_phase(plan, arena, tun, tprobs, a.in == KFAC_BF16 ? 4 : 3, true, false, post > 0 ? &reductions : nullptr);
     }
     if (post > 0) {
         plan.sync(L_RECORD, split->ev_gemm, 0);

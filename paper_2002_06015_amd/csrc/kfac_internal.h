@@ -27,9 +27,9 @@ struct Operand {
     int rows;
     int hw;
     int tail;   // 0, or 4 (bf16 only): valid elements in the last 8-element chunk of a run
-    int trans;  // 1 (fp32, product mode of three bf16 planes only): the operand is stored with its rows as the
-                // contiguous direction, element (r, m) at base + m * row_stride + r (an NHWC tensor [N*hw, rows]
-                // contracted in place); rows % 4 == 0, a chunk is four adjacent rows at one m
+    int trans;  // 1 (fp32 in the product mode of three bf16 planes, or bf16): the operand is stored with its rows as
+                // the contiguous direction, element (r, m) at base + m * row_stride + r (an NHWC tensor [N*hw, rows]
+                // contracted in place); a chunk is 16 bytes of adjacent rows at one m, rows a whole number of chunks
 };
 
 // GEMM_SYM:    M == N and a == b; only tiles tm >= tn are computed and mirrored.

@@ -147,27 +147,31 @@ def test_statistics_straight_from_nhwc_tensors_match_the_oracle(gpu, type_, prod
     ctx.close()
 
 
-def test_fused_step_straight_from_nhwc_tensors_matches_the_nchw_step(gpu):
+@pytest.mark.parametrize("type_", [kfac.KFAC_F32, kfac.KFAC_BF16])
+def test_fused_step_straight_from_nhwc_tensors_matches_the_nchw_step(gpu, type_):
     """kfac_step_nhwc against kfac_step on the converted tensors (same factors up to the order of the sums, so the
     same inverses and preconditioned gradients to the tolerances of the step) and against the oracle."""
     layers = [wl.conv_layer(4, 64, 256, 1, 1, 0, 14), wl.conv_layer(2, 40, 130, 3, 1, 1, 10), wl.fc_layer(32, 64, 32),
               wl.conv_layer(3, 132, 36, 1, 1, 0, 9), wl.conv_layer(3, 5, 6, 3, 2, 1, 9, bias=0)]
     n = len(layers)
-    ctx = kfac.Context(layers)
+    ctx = kfac.Context(layers, type_)
+    tdt = torch.bfloat16 if type_ == kfac.KFAC_BF16 else torch.float32
     a, g = _nhwc_inputs(layers, 77)
+    if type_ == kfac.KFAC_BF16:
+        a, g = [wl.round_to_bf16(x) for x in a], [wl.round_to_bf16(x) for x in g]
     gws = [wl.make_grad_W(L, 300 + i) for i, L in enumerate(layers)]
     d_w = [torch.from_numpy(x).cuda() for x in gws]
     res = {}
     for nhwc in (True, False):
         conv = (lambda x: x) if nhwc else layout.nhwc_to_nchw
-        d_a = [torch.from_numpy(np.ascontiguousarray(conv(x))).cuda() for x in a]
-        d_g = [torch.from_numpy(np.ascontiguousarray(conv(x))).cuda() for x in g]
+        d_a = [torch.from_numpy(np.ascontiguousarray(conv(x))).cuda().to(tdt) for x in a]
+        d_g = [torch.from_numpy(np.ascontiguousarray(conv(x))).cuda().to(tdt) for x in g]
         A = [torch.zeros(L.dA, L.dA, device="cuda") for L in layers]
         G = [torch.zeros(L.dG, L.dG, device="cuda") for L in layers]
         Ai, Gi = [torch.zeros_like(x) for x in A], [torch.zeros_like(x) for x in G]
         U = [torch.zeros(L.dG, L.dA, device="cuda") for L in layers]
         info = torch.zeros(2 * n, dtype=torch.int32, device="cuda")
-        kfac.kfac_step(ctx, layers, kfac.KFAC_F32, d_a, d_g, 0.0, True, A, G, None, wl.GAMMA, Ai, Gi, None, info, d_w, U,
+        kfac.kfac_step(ctx, layers, type_, d_a, d_g, 0.0, True, A, G, None, wl.GAMMA, Ai, Gi, None, info, d_w, U,
                        nhwc=nhwc)
         torch.cuda.synchronize()
         assert not info.cpu().numpy().any()
