@@ -285,6 +285,10 @@ kfac_status bn_full_precondition(kfac_ctx *ctx, int32_t n_layers, int32_t N, con
 kfac_status bn_unitwise_reduce_nchw(kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,
                                     const int32_t *HW, const float *const *dy, const float *const *xhat,
                                     float *const *g_gamma, float *const *g_beta);
+/* The same from tensors kept in NHWC (Sec. 5.2): dy[l], xhat[l]: dev fp32 [N, HW[l], C[l]]. */
+kfac_status bn_unitwise_reduce_nhwc(kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,
+                                    const int32_t *HW, const float *const *dy, const float *const *xhat,
+                                    float *const *g_gamma, float *const *g_beta);
 
 /*
  * Staleness of statistics, Sec. 4.3 (the similarity criterion under Algorithm 2).

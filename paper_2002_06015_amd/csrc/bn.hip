@@ -56,6 +56,63 @@ __global__ __launch_bounds__(256) void bn_reduce_kernel(const BnReduceJob *__res
     }
 }
 
+// The same from NHWC tensors ([N, HW, C]): a workgroup takes 64 channels of one sample, lanes along the channels
+// (16 lanes x 16 bytes per position when C % 4 == 0, else 64 lanes x 4 bytes), 16 (4) positions at a time; the
+// partial sums of the threads that share a channel are added through LDS in a fixed order.
+__global__ __launch_bounds__(256) void bn_reduce_nhwc_kernel(const BnReduceJob *__restrict__ jobs, int n_jobs, int N)
+{
+    __shared__ float red[2][16][64];
+    const int wg = blockIdx.x;
+    int lo = 0, hi = n_jobs;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (jobs[mid].wg_start <= wg) lo = mid; else hi = mid;
+    }
+    const BnReduceJob J = jobs[lo];
+    const int chunks = (J.C + 63) / 64;
+    const int local = wg - J.wg_start;
+    const int n = local / chunks, c0 = (local - n * chunks) * 64;
+    const float *dy = J.dy + (long long)n * J.HW * J.C;
+    const float *xh = J.xhat + (long long)n * J.HW * J.C;
+    const bool vec = ((J.C & 3) == 0) && ((((uintptr_t)J.dy | (uintptr_t)J.xhat) & 15) == 0);
+    const int tid = threadIdx.x;
+    if (vec) {
+        const int c = c0 + 4 * (tid & 15), part = tid >> 4;   // 16 parts
+        floatx4 sg = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+        if (c < J.C)
+            for (int t = part; t < J.HW; t += 16) {
+                const floatx4 a = *(const floatx4 *)(dy + (long long)t * J.C + c);
+                const floatx4 b = *(const floatx4 *)(xh + (long long)t * J.C + c);
+                sg += a * b;
+                sb += a;
+            }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            red[0][part][4 * (tid & 15) + e] = sg[e];
+            red[1][part][4 * (tid & 15) + e] = sb[e];
+        }
+    } else {
+        const int c = c0 + (tid & 63), part = tid >> 6;       // 4 parts
+        float sg = 0.f, sb = 0.f;
+        if (c < J.C)
+            for (int t = part; t < J.HW; t += 4) {
+                const float a = dy[(long long)t * J.C + c];
+                sg += a * xh[(long long)t * J.C + c];
+                sb += a;
+            }
+        red[0][part][tid & 63] = sg;
+        red[1][part][tid & 63] = sb;
+    }
+    __syncthreads();
+    if (tid < 128) {
+        const int which = tid >> 6, cl = tid & 63;
+        const int parts = vec ? 16 : 4;
+        float sum = 0.f;
+        for (int q = 0; q < parts; ++q) sum += red[which][q][cl];
+        if (c0 + cl < J.C) (which ? J.g_beta : J.g_gamma)[(long long)n * J.C + c0 + cl] = sum;
+    }
+}
+
 __global__ __launch_bounds__(256) void bn_unit_kernel(const BnJob *__restrict__ jobs, int n_jobs, int N,
                                                       float decay, float lambda)
 {
@@ -96,10 +153,11 @@ hipError_t launch_bn(const BnJob *jobs_dev, int n_jobs, int total_wgs, int N, fl
     return hipGetLastError();
 }
 
-hipError_t launch_bn_reduce(const BnReduceJob *jobs_dev, int n_jobs, int total_wgs, int N, hipStream_t s)
+hipError_t launch_bn_reduce(const BnReduceJob *jobs_dev, int n_jobs, int total_wgs, int N, int nhwc, hipStream_t s)
 {
     if (total_wgs <= 0) return hipSuccess;
-    bn_reduce_kernel<<<dim3(total_wgs), dim3(256), 0, s>>>(jobs_dev, n_jobs, N);
+    if (nhwc) bn_reduce_nhwc_kernel<<<dim3(total_wgs), dim3(256), 0, s>>>(jobs_dev, n_jobs, N);
+    else      bn_reduce_kernel<<<dim3(total_wgs), dim3(256), 0, s>>>(jobs_dev, n_jobs, N);
     return hipGetLastError();
 }
 

@@ -1520,7 +1520,7 @@ kfac_status run_plan(kfac_ctx *ctx, Plan &plan, Arena &arena)
                 e = launch_bn((const BnJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, L.f0, L.f1, ls);
                 break;
             case L_BNRED:
-                e = launch_bn_reduce((const BnReduceJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, ls);
+                e = launch_bn_reduce((const BnReduceJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, L.dtype, ls);
                 break;
             case L_LAYOUT:
                 e = launch_nhwc_to_nchw((const LayoutJob *)(tab_dev + L.off_a), L.n, L.total_wgs, L.cfg, ls);
@@ -2092,7 +2092,7 @@ kfac_status bn_full_precondition(kfac_ctx *ctx, int32_t n_layers, int32_t N, con
     return run_plan(ctx, plan, arena);
 }
 
-kfac_status bn_unitwise_reduce_nchw(kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,
+static kfac_status bn_reduce_call(int nhwc, kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,
                                     const int32_t *HW, const float *const *dy, const float *const *xhat,
                                     float *const *g_gamma, float *const *g_beta)
 {
@@ -2107,7 +2107,7 @@ kfac_status bn_unitwise_reduce_nchw(kfac_ctx *ctx, int32_t n_layers, int32_t N, 
         J.dy = dy[l]; J.xhat = xhat[l]; J.g_gamma = g_gamma[l]; J.g_beta = g_beta[l];
         J.C = C[l]; J.HW = HW[l];
         J.wg_start = (int)wgs;
-        wgs += ((long long)N * C[l] + 3) / 4;
+        wgs += nhwc ? (long long)N * ((C[l] + 63) / 64) : ((long long)N * C[l] + 3) / 4;
         if (wgs > (1LL << 30)) return KFAC_ERR_INVALID;
         jobs.push_back(J);
     }
@@ -2119,8 +2119,23 @@ kfac_status bn_unitwise_reduce_nchw(kfac_ctx *ctx, int32_t n_layers, int32_t N, 
     Lc.n = n_layers;
     Lc.total_wgs = (int)wgs;
     Lc.cfg = N;
+    Lc.dtype = nhwc;
     plan.launches.push_back(Lc);
     return run_plan(ctx, plan, arena);
+}
+
+kfac_status bn_unitwise_reduce_nchw(kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,
+                                    const int32_t *HW, const float *const *dy, const float *const *xhat,
+                                    float *const *g_gamma, float *const *g_beta)
+{
+    return bn_reduce_call(0, ctx, n_layers, N, C, HW, dy, xhat, g_gamma, g_beta);
+}
+
+kfac_status bn_unitwise_reduce_nhwc(kfac_ctx *ctx, int32_t n_layers, int32_t N, const int32_t *C,
+                                    const int32_t *HW, const float *const *dy, const float *const *xhat,
+                                    float *const *g_gamma, float *const *g_beta)
+{
+    return bn_reduce_call(1, ctx, n_layers, N, C, HW, dy, xhat, g_gamma, g_beta);
 }
 
 kfac_status kfac_staleness(kfac_ctx *ctx, int32_t n, const int32_t *dims, const float *const *X,

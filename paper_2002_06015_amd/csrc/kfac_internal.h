@@ -180,7 +180,7 @@ struct BnReduceJob {
     const float *dy, *xhat;
     float *g_gamma, *g_beta;
     int C, HW;
-    int wg_start;   // one wave per (n, c) row; 4 rows per workgroup
+    int wg_start;   // NCHW: one wave per (n, c) row, 4 rows per workgroup; NHWC: one workgroup per sample and 64 channels
 };
 
 // One tensor [N, HW, C] -> [N, C, HW] (NHWC -> NCHW).
@@ -279,7 +279,7 @@ hipError_t launch_bn(const BnJob *jobs_dev, int n_jobs, int total_wgs, int N, fl
 hipError_t launch_bn_full(const BnFullJob *jobs_dev, int n_jobs, int total_wgs, int pass, int N, float decay,
                           float lambda, float *damp, hipStream_t s);
 hipError_t launch_nhwc_to_nchw(const LayoutJob *jobs_dev, int n_jobs, int total_wgs, int esize, hipStream_t s);
-hipError_t launch_bn_reduce(const BnReduceJob *jobs_dev, int n_jobs, int total_wgs, int N, hipStream_t s);
+hipError_t launch_bn_reduce(const BnReduceJob *jobs_dev, int n_jobs, int total_wgs, int N, int nhwc, hipStream_t s);
 // pass 0: per-chunk sums (total_wgs workgroups); pass 1: one workgroup per job adds them up and writes the ratios
 hipError_t launch_pack(const PackJob *jobs_dev, int n_jobs, int total_wgs, int bf16, int unpack, void *packed,
                        hipStream_t s);

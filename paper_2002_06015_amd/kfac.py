@@ -24,7 +24,7 @@ EXPORTS = [
     "kfac_status_string", "kfac_layer_dims", "kfac_workspace_bytes", "kfac_create", "kfac_destroy",
     "kfac_options_default", "kfac_workspace_bytes_opt", "kfac_create_opt", "kfac_step_workspace_bytes",
     "kfac_im2col", "kfac_stats", "kfac_invert", "kfac_precondition", "kfac_step",
-    "bn_unitwise_precondition", "bn_unitwise_reduce_nchw", "kfac_profile_enable", "kfac_profile_read",
+    "bn_unitwise_precondition", "bn_unitwise_reduce_nchw", "bn_unitwise_reduce_nhwc", "kfac_profile_enable", "kfac_profile_read",
     "kfac_packed_elems", "kfac_pack_upper", "kfac_unpack_upper",
     "kfac_lr_polynomial", "kfac_momentum_coupled", "kfac_update_weights",
     "bn_full_workspace_bytes", "bn_full_precondition", "kfac_nhwc_to_nchw", "kfac_stats_nhwc", "kfac_step_nhwc",
@@ -123,6 +123,7 @@ def lib() -> ctypes.CDLL:
         L.kfac_step_nhwc.argtypes = L.kfac_step.argtypes
         L.bn_unitwise_precondition.argtypes = [vp, i32, i32, vp, vp, vp, f32, f32, vp, vp, vp]
         L.bn_unitwise_reduce_nchw.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
+        L.bn_unitwise_reduce_nhwc.argtypes = L.bn_unitwise_reduce_nchw.argtypes
         L.kfac_profile_enable.argtypes = [vp, i32]
         L.kfac_profile_read.restype = i32
         L.kfac_profile_read.argtypes = [vp, vp, i32]
@@ -392,16 +393,21 @@ def bn_unitwise_precondition(ctx: Context, N: int, C: Sequence[int], g_gamma, g_
 
 
 def bn_unitwise_reduce_nchw(ctx: Context, N: int, C: Sequence[int], HW: Sequence[int], dy, xhat,
-                            g_gamma, g_beta) -> None:
+                            g_gamma, g_beta, nhwc: bool = False) -> None:
+    """nhwc: dy / xhat are stored [N, HW, C] (bn_unitwise_reduce_nhwc)."""
     n = len(C)
     cs, hs = _i32(C), _i32(HW)
     big = [int(N) * int(c) * int(h) for c, h in zip(C, HW)]
     nc = [int(N) * int(c) for c in C]
     ps = [_ptrs(x, n, torch.float32, m, w) for x, m, w in ((dy, big, "dy"), (xhat, big, "xhat"), (g_gamma, nc, "g_gamma"), (g_beta, nc, "g_beta"))]
-    st = lib().bn_unitwise_reduce_nchw(ctx.handle, n, int(N), ctypes.addressof(cs), ctypes.addressof(hs),
-                                       *[p and ctypes.addressof(p) for p in ps])
+    entry = lib().bn_unitwise_reduce_nhwc if nhwc else lib().bn_unitwise_reduce_nchw
+    st = entry(ctx.handle, n, int(N), ctypes.addressof(cs), ctypes.addressof(hs), *[p and ctypes.addressof(p) for p in ps])
     if st != KFAC_OK:
-        raise KfacError(st, "bn_unitwise_reduce_nchw")
+        raise KfacError(st, "bn_unitwise_reduce_nhwc" if nhwc else "bn_unitwise_reduce_nchw")
+
+
+def bn_unitwise_reduce_nhwc(ctx: Context, N: int, C: Sequence[int], HW: Sequence[int], dy, xhat, g_gamma, g_beta) -> None:
+    bn_unitwise_reduce_nchw(ctx, N, C, HW, dy, xhat, g_gamma, g_beta, nhwc=True)
 
 
 def kfac_nhwc_to_nchw(ctx: Context, layers: Sequence, which: int, type_: int, src, dst) -> None:

@@ -370,6 +370,26 @@ def test_bn_reduce_nchw_matches_oracle(gpu):
         assert relerr(host(gb[i]), gbr) <= TOL_FACTOR
 
 
+def test_bn_reduce_nhwc_matches_oracle(gpu):
+    """The same sums from tensors stored [N, HW, C]: channel counts that are and are not multiples of 4 and of
+    the 64 channels a workgroup takes, one position, several hundred positions."""
+    N = 5
+    Cs, HWs = [8, 3, 16, 130, 64, 257], [196, 49, 1, 36, 784, 9]
+    ctx = kfac.Context([wl.fc_layer(2, 4, 4)])
+    data = [wl.make_bn_nchw(N, C, HW, 170 + i) for i, (C, HW) in enumerate(zip(Cs, HWs))]
+    to_nhwc = lambda x: np.ascontiguousarray(np.transpose(x, (0, 2, 1)))
+    gg = [torch.full((N, C), float("nan"), device="cuda") for C in Cs]
+    gb = [torch.full((N, C), float("nan"), device="cuda") for C in Cs]
+    kfac.bn_unitwise_reduce_nhwc(ctx, N, Cs, HWs, [dev(to_nhwc(d[0])) for d in data], [dev(to_nhwc(d[1])) for d in data],
+                                 gg, gb)
+    torch.cuda.synchronize()
+    ctx.close()
+    for i in range(len(Cs)):
+        ggr, gbr = oracle.bn_reduce_nchw(*data[i])
+        assert relerr(host(gg[i]), ggr) <= TOL_FACTOR
+        assert relerr(host(gb[i]), gbr) <= TOL_FACTOR
+
+
 # ------------------------------------------------------------------ whole step, configurations 1 and 2
 def _full_step(layers, config, spatial_mean, steps=2):
     ctx = kfac.Context(layers)
