@@ -95,6 +95,19 @@ def test_calls_reject_bad_arguments_without_a_gpu():
     assert L.kfac_stats(h, 1, lp, 0, None, None, 0.0, 0, fp, fp) == INV       # nothing to do
     assert L.kfac_stats(h, 1, lp, 0, fp, fp, 0.0, 0, None, fp) == INV          # act given, A_ema missing
     assert L.kfac_stats(h, 1, lp, 0, fp, fp, 0.0, 0, fp, np_) == INV
+    # the NHWC entry points validate like the NCHW ones
+    assert L.kfac_stats_nhwc(None, 1, lp, 0, fp, fp, 0.0, 0, fp, fp) == INV
+    assert L.kfac_stats_nhwc(h, 1, lp, 7, fp, fp, 0.0, 0, fp, fp) == INV
+    assert L.kfac_stats_nhwc(h, 1, lp, 0, fp, fp, 1.0, 0, fp, fp) == INV
+    assert L.kfac_stats_nhwc(h, 1, lp, 0, fp, fp, 0.0, 0, None, fp) == INV
+    assert L.kfac_step_nhwc(None, 1, lp, 0, fp, fp, 0.0, 0, fp, fp, None, 1e-3, fp, fp, None, None, fp, fp) == INV
+    assert L.kfac_step_nhwc(h, 1, lp, 0, fp, fp, 0.0, 0, fp, fp, None, -1.0, fp, fp, None, None, fp, fp) == INV
+    assert L.kfac_step_nhwc(h, 1, lp, 0, fp, None, 0.0, 0, fp, fp, None, 1e-3, fp, fp, None, None, fp, fp) == INV
+    one = (ctypes.c_int32 * 1)(4)
+    op = ctypes.addressof(one)
+    assert L.bn_unitwise_reduce_nhwc(None, 1, 2, op, op, fp, fp, fp, fp) == INV
+    assert L.bn_unitwise_reduce_nhwc(h, 1, 0, op, op, fp, fp, fp, fp) == INV
+    assert L.bn_unitwise_reduce_nhwc(h, 1, 2, op, op, fp, None, fp, fp) == INV
     # kfac_invert
     assert L.kfac_invert(h, 1, lp, fp, fp, -1.0, fp, fp, None, None) == INV
     assert L.kfac_invert(h, 1, lp, fp, fp, 1e-3, fp, fp, None, None) == INV   # in == out
