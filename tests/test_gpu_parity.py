@@ -51,6 +51,9 @@ SMALL_LAYERS = [
     wl.conv_layer(2, 8, 5, 1, 1, 0, 7),            # direct, hw = 49 (unaligned runs)
     wl.conv_layer(3, 6, 4, 1, 2, 0, 8, bias=0),    # strided 1x1
     wl.conv_layer(2, 3, 8, 7, 2, 3, 30),           # 7x7 stem shape, d_A = 148
+    wl.conv_layer(2, 3, 8, 7, 2, 3, 32),           # 7x7 / stride 2 with output rows of 16: the windowed patch path
+    wl.Layer(3, 2, 5, 7, 2, 0, 19, 29, 0),         # the same without padding, 7 x 12 outputs
+    wl.Layer(2, 3, 4, 7, 2, 2, 9, 33, 1),          # ... and with padding 2, 4 x 16 outputs
     wl.conv_layer(4, 16, 70, 3, 1, 1, 12),         # d_A = 145: two 128-tiles with a ragged tail
     wl.conv_layer(2, 40, 130, 3, 1, 1, 10),        # d_A = 361: several tiles, d_G = 130
     wl.Layer(2, 5, 6, 3, 1, 1, 10, 14, 1),         # 3x3 on a non-square image (correlation form, padded 12 x 16)
