@@ -120,8 +120,9 @@ def _nhwc_inputs(layers, seed):
 @pytest.mark.parametrize("products", ["split", "fp32"])
 def test_statistics_straight_from_nhwc_tensors_match_the_oracle(gpu, type_, products):
     """kfac_stats_nhwc, two steps with the running average, against the oracle on the same data in NCHW order.
-    fp32 in the default product mode takes the transposed loader for the pointwise tensors; bf16 tensors and
-    the fp32-instruction mode go through the conversion inside the call."""
+    In the default product mode the pointwise tensors with whole 16-byte channel runs are contracted in place by
+    the transposed-operand kernels (fp32: channels a multiple of 4, bf16: of 8); everything else, and every
+    tensor in the fp32-instruction mode, goes through the conversion inside the call."""
     layers = NHWC_LAYERS
     opts = kfac.options(fp32_products=kfac.KFAC_PRODUCTS_FP32_MFMA) if products == "fp32" else None
     ctx = kfac.Context(layers, type_, opts=opts)

@@ -111,3 +111,53 @@ def test_random_layer_groups_match_the_oracle(gpu, seed, in_dtype):
             assert relerr(host(Ai[i]), Air) <= TOL_INVERSE, what
             assert relerr(host(Gi[i]), Gir) <= TOL_INVERSE, what
             assert relerr(host(U[i]), Ur) <= TOL_PRECOND, what
+
+
+def random_pointwise_layers(seed, count):
+    """1x1 / stride-1 layers (the ones contracted in place from NHWC tensors) with channel counts that are and are
+    not multiples of 4 and 8, images from one pixel to a few hundred, one to 33 samples; two other layers so that
+    the conversion inside the call runs beside them."""
+    rng = np.random.default_rng(seed)
+    layers = []
+    while len(layers) < count:
+        mult = int(rng.choice([1, 4, 8, 8]))
+        c_in, c_out = mult * int(rng.integers(1, 300 // mult)), mult * int(rng.integers(1, 200 // mult))
+        h, w = int(rng.integers(1, 20)), int(rng.integers(1, 20))
+        N = int(rng.choice([1, 2, 3, 8, 33]))
+        layers.append(wl.Layer(N, c_in, c_out, 1, 1, 0, h, w, int(rng.integers(0, 2))))
+    layers.append(wl.conv_layer(3, 16, 24, 3, 1, 1, int(rng.integers(4, 15))))
+    layers.append(wl.fc_layer(int(rng.integers(1, 40)), 48, 16))
+    return layers
+
+
+@pytest.mark.parametrize("in_dtype", [kfac.KFAC_F32, kfac.KFAC_BF16])
+@pytest.mark.parametrize("seed", [21, 22, 23])
+def test_random_pointwise_groups_from_nhwc_tensors_match_the_oracle(gpu, seed, in_dtype):
+    layers = random_pointwise_layers(seed, 10)
+    tdt = torch.bfloat16 if in_dtype == kfac.KFAC_BF16 else torch.float32
+    ctx = kfac.Context(layers, in_dtype)
+    A = [torch.full((L.dA, L.dA), float("nan"), device="cuda") for L in layers]
+    G = [torch.full((L.dG, L.dG), float("nan"), device="cuda") for L in layers]
+    Ar, Gr = [None] * len(layers), [None] * len(layers)
+    for step in range(2):
+        decay = 0.0 if step == 0 else 0.75
+        d_act, d_grad = [], []
+        for i, L in enumerate(layers):
+            a, g = wl.make_act(L, 1000 * seed + 10 * i + step), wl.make_grad_out(L, 1000 * seed + 10 * i + step)
+            if in_dtype == kfac.KFAC_BF16:
+                a, g = wl.round_to_bf16(a), wl.round_to_bf16(g)
+            Ar[i], Gr[i] = oracle.kfac_stats(tuple(L), a, g, decay, False, Ar[i], Gr[i])
+            h, w = kfac.kfac_layer_dims(L)[2:]
+            a = np.ascontiguousarray(a.reshape(L.N, L.c_in, L.h_in, L.w_in).transpose(0, 2, 3, 1))
+            g = np.ascontiguousarray(g.reshape(L.N, L.c_out, h, w).transpose(0, 2, 3, 1))
+            d_act.append(torch.from_numpy(a).cuda().to(tdt))
+            d_grad.append(torch.from_numpy(g).cuda().to(tdt))
+        kfac.kfac_stats(ctx, layers, in_dtype, d_act, d_grad, decay, False, A, G, nhwc=True)
+        torch.cuda.synchronize()
+        for i, L in enumerate(layers):
+            what = "seed %d step %d layer %d %s" % (seed, step, i, tuple(L))
+            hA, hG = host(A[i]), host(G[i])
+            assert np.array_equal(hA, hA.T) and np.array_equal(hG, hG.T), what
+            assert relerr(hA, Ar[i]) <= TOL_FACTOR, what
+            assert relerr(hG, Gr[i]) <= TOL_FACTOR, what
+    ctx.close()
