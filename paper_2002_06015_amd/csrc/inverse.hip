@@ -206,8 +206,8 @@ hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t s)
 // D comes from a scalar sweep of the 32x32 diagonal tile inside its owner wavefront, also on
 // the matrix core: pivot p is the rank-1 update S += a b^T with b = row p (one accumulator
 // register across the lanes) and a = -row p / d (the tile is symmetric), patched so that the
-// same update leaves column p = old column / d (b_p = d - 1; no cancellation because d <= 1);
-// row p and the pivot itself are overwritten directly.  A non-positive pivot is reported.
+// same update leaves row and column p divided by d (a_p = 1/d - 1, b_p = d - 1; no cancellation
+// because d <= 1); two pivots share one 32x32x2 instruction.  A non-positive pivot is reported.
 typedef float lb_floatx16 __attribute__((ext_vector_type(16)));
 typedef float lb_floatx4 __attribute__((ext_vector_type(4)));
 constexpr int LB_MAXN = 288;
@@ -277,7 +277,7 @@ __device__ __forceinline__ void lb_store_cols(unsigned short *panel, int plane, 
 }
 
 // Scalar sweep of the 32x32 diagonal tile of block k inside the wavefront that holds it
-// (register slot `slot`): leaves D = (-N_kk)^-1 in the slot and in Dl.  Returns the 1-based
+// (register slot `slot`): leaves D = (-N_kk)^-1 in the slot and in Dq.  Returns the 1-based
 // index (within the matrix) of the first non-positive pivot, or 0.
 template <int NSLOT>
 __device__ __forceinline__ int lb_sweep_diag(lb_floatx16 (&acc)[NSLOT], int slot, int k, int l32, int h, unsigned short *Dq)
@@ -290,42 +290,71 @@ __device__ __forceinline__ int lb_sweep_diag(lb_floatx16 (&acc)[NSLOT], int slot
         for (int s = 1; s < NSLOT; ++s) x = (slot == s) ? acc[s][v] : x;
         sg[v] = -x;
     }
-    // Pivot p is one rank-2 MFMA.  Its k = 0 slot (lanes 0..31) carries the rank-1 update
+    // Pivot p is the rank-1 update S += a b^T with
     //     a_i = -x_i / d (i != p),  a_p = 1/d - 1;    b_j = x_j (j != p),  b_p = d - 1
-    // with x = row p and d = x_p: besides S_ij -= x_i x_j / d this leaves row and column p
-    // multiplied by 1/d (sums of equal-signed terms, because d <= 1) and S_pp = 2 - 1/d; the
-    // k = 1 slot (lanes 32..63) adds -2 at (p, p), which makes it -1/d.  Nothing is written to
-    // the tile between the MFMAs, so they follow each other through the accumulator, and the
-    // row of the next pivot is obtained ahead of the MFMA from the tile as it was before:
-    //     x'_j = S_{p+1,j} + a_{p+1} b_j.
+    // where x = row p and d = x_p: besides S_ij -= x_i x_j / d this leaves row and column p multiplied by
+    // 1/d (sums of equal-signed terms, because d <= 1) and S_pp = 2 - 1/d instead of -1/d.  No later pivot
+    // reads S_pp (pivot q reads row q only, and adds to S_pp), so the 2 is taken off once, at the end.
+    // A wavefront cannot issue its vector arithmetic beside its own matrix instruction, so the pivots go
+    // two per instruction: the rows of pivots p and p + 1 (p even: both in the same half-wave) are brought up
+    // to date with fmas, row p + 1 by pivot p, and the two updates ride in the two k slots of one
+    // 32x32x2 instruction (one half-wave each; v_permlane32_swap puts the second pair of vectors there).  The
+    // row of pivot p + 2 is read from the tile as the previous instruction left it and corrected by both.
     int badl = 0;
     float xcur = sg[0];                 // row 0, valid in the half-wave that holds it
 #pragma unroll
-    for (int p = 0; p < 32; ++p) {
-        const int hp = (p >> 2) & 1;    // half-wave holding row p
-        const auto both = __builtin_amdgcn_permlane32_swap(__float_as_uint(xcur), __float_as_uint(xcur), false, false);
-        const float xb = __uint_as_float(hp == 0 ? both[0] : both[1]);   // row p in both half-waves
-        const float dp = lb_readlane(xb, p);
-        badl = (badl == 0 && !(dp > 0.f)) ? 32 * k + p + 1 : badl;
-        const float rinv = __builtin_amdgcn_rcpf(dp);
-        const bool isp = l32 == p, k0 = h == 0;
-        const float xr = xb * rinv;
-        const float b0 = isp ? dp - 1.f : xb;
-        const float a = k0 ? (isp ? rinv - 1.f : -xr) : (isp ? -2.f : 0.f);
-        const float b = k0 ? b0 : (isp ? 1.f : 0.f);
+    for (int p = 0; p < 32; p += 2) {
+        const int hp = (p >> 2) & 1;    // half-wave holding rows p and p + 1
+        // pivot p
+        const float d0 = lb_readlane(xcur, p + 32 * hp);
+        badl = (badl == 0 && !(d0 > 0.f)) ? 32 * k + p + 1 : badl;
+        const float r0 = __builtin_amdgcn_rcpf(d0);
+        const float xr0 = xcur * r0;
+        float b0 = l32 == p ? d0 - 1.f : xcur;
+        float a0 = l32 == p ? r0 - 1.f : -xr0;
+        // row p + 1 after pivot p, then pivot p + 1
+        const int v1 = 4 * ((p + 1) >> 3) + ((p + 1) & 3);
+        const float x1 = fmaf(-lb_readlane(xr0, p + 1 + 32 * hp), b0, sg[v1]);
+        const float d1 = lb_readlane(x1, p + 1 + 32 * hp);
+        badl = (badl == 0 && !(d1 > 0.f)) ? 32 * k + p + 2 : badl;
+        const float r1 = __builtin_amdgcn_rcpf(d1);
+        const float xr1 = x1 * r1;
+        float b1 = l32 == p + 1 ? d1 - 1.f : x1;
+        float a1 = l32 == p + 1 ? r1 - 1.f : -xr1;
         float xnext = 0.f;
-        if (p < 31) {
-            const int vn = 4 * ((p + 1) >> 3) + ((p + 1) & 3);
-            const float alpha = lb_readlane(xr, p + 1);
-            xnext = fmaf(-alpha, b0, sg[vn]);
+        if (p + 2 < 32) {
+            const int hn = ((p + 2) >> 2) & 1;
+            const int v2 = 4 * ((p + 2) >> 3) + ((p + 2) & 3);
+            const float al0 = lb_readlane(xr0, p + 2 + 32 * hp), al1 = lb_readlane(xr1, p + 2 + 32 * hp);
+            float c0 = b0, c1 = b1;
+            if (hn != hp) {             // row p + 2 lives in the other half-wave: the two b vectors go there
+                const auto s0 = __builtin_amdgcn_permlane32_swap(__float_as_uint(b0), __float_as_uint(b0), false, false);
+                const auto s1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(b1), __float_as_uint(b1), false, false);
+                c0 = __uint_as_float(hp == 0 ? s0[0] : s0[1]);
+                c1 = __uint_as_float(hp == 0 ? s1[0] : s1[1]);
+            }
+            xnext = fmaf(-al1, c1, fmaf(-al0, c0, sg[v2]));
+        }
+        // operands: the half-wave that holds the rows keeps pivot p, the other one receives pivot p + 1
+        // (swap(x, y) exchanges the upper half of x with the lower half of y)
+        float a, b;
+        if (hp == 0) {
+            const auto sa = __builtin_amdgcn_permlane32_swap(__float_as_uint(a0), __float_as_uint(a1), false, false);
+            const auto sb = __builtin_amdgcn_permlane32_swap(__float_as_uint(b0), __float_as_uint(b1), false, false);
+            a = __uint_as_float(sa[0]); b = __uint_as_float(sb[0]);
+        } else {
+            const auto sa = __builtin_amdgcn_permlane32_swap(__float_as_uint(a1), __float_as_uint(a0), false, false);
+            const auto sb = __builtin_amdgcn_permlane32_swap(__float_as_uint(b1), __float_as_uint(b0), false, false);
+            a = __uint_as_float(sa[1]); b = __uint_as_float(sb[1]);
         }
         sg = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, sg, 0, 0, 0);
         xcur = xnext;
     }
-    // sg = -(that tile)^-1 = -D;  D is symmetric, so its planes can be written transposed (8-byte stores)
+    // sg = -(that tile)^-1 + 2 I = 2 I - D;  D is symmetric, so its planes can be written transposed (8-byte stores)
+    const int drow = l32 - 4 * h;       // register v holds the diagonal element of its lane where this is 8 (v / 4) + v % 4
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-        sg[v] = -sg[v];
+        sg[v] = (drow == 8 * (v >> 2) + (v & 3) ? 2.f : 0.f) - sg[v];
 #pragma unroll
         for (int s = 0; s < NSLOT; ++s) acc[s][v] = (slot == s) ? sg[v] : acc[s][v];
     }
@@ -333,20 +362,21 @@ __device__ __forceinline__ int lb_sweep_diag(lb_floatx16 (&acc)[NSLOT], int slot
     return badl;
 }
 
-// Which wavefront holds which tile.  In step k the tiles of block row / column k only copy the
-// panel, the other 36 (of 45, for 9 blocks) take 16 matrix instructions each and the sweep of the
-// next diagonal tile another 32, all on the SIMD of their wavefront (wavefront % 4).  Dealing
-// the tiles out in order (tile t to wavefront t % 16) loads the busiest SIMD with 176 of the
-// 608 matrix instructions of a step on average; the table below (found by local search over
-// assignments with at most 3 tiles per wavefront) brings every step to 160, the least
-// possible at 16 per tile.  Other sizes keep the plain order.
-__constant__ signed char kLeafTile9[16][3] = {{2, 22, 39}, {5, 9, 23}, {0, 31, 41}, {8, 29, 34}, {17, 19, 21}, {16, 33, 44},
-                                              {3, 18, 42}, {6, 37, 38}, {20, 30, 40}, {28, -1, -1}, {4, 25, 32}, {13, 24, 43},
-                                              {1, 10, -1}, {11, 27, 35}, {7, 12, 36}, {14, 15, 26}};
-__constant__ signed char kLeafWave9[45] = {2, 12, 0, 6, 10, 1, 7, 14, 3, 1, 12, 13, 14, 11, 15, 15, 5, 4, 6, 4, 8, 4, 0,
-                                           1, 11, 10, 15, 13, 9, 3, 8, 2, 10, 5, 3, 13, 14, 7, 7, 0, 8, 2, 6, 11, 5};
-__constant__ signed char kLeafSlot9[45] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 1, 1, 0, 1, 0, 0, 1, 0, 0, 1, 1, 0, 2, 1,
-                                           2, 1, 1, 2, 1, 0, 1, 1, 1, 2, 1, 2, 2, 2, 1, 2, 2, 2, 2, 2, 2, 2};
+// Which wavefront holds which tile.  In step k the tiles of block row / column k only form the
+// panel P, the other 36 (of 45, for 9 blocks) take 12 matrix instructions each, and the wavefront
+// that holds the diagonal tile of block k + 1 updates and then sweeps it, which is the longest
+// chain of the step.  The table below (found by annealing over assignments with at most 3 tiles per
+// wavefront) gives every diagonal tile a wavefront of its own, lets the owner of diagonal tile b
+// hold nothing else but tiles of block row / column b - 1 (idle while it sweeps), puts at most two
+// panel tiles of a step on one wavefront and spreads the rest evenly over the four SIMDs (wavefront
+// % 4).  Other sizes keep the plain order (tile t to wavefront t % 16).
+__constant__ signed char kLeafTile9[16][3] = {{20, 25, -1}, {2, 3, 10}, {15, 23, 28}, {6, 14, 39}, {32, 43, 44}, {19, 29, 42},
+                                              {4, 9, 12}, {11, 17, 21}, {27, 41, -1}, {0, 8, 36}, {5, 7, 37}, {22, 30, 38},
+                                              {26, 35, -1}, {16, 24, 31}, {18, 34, 40}, {1, 13, 33}};
+__constant__ signed char kLeafWave9[45] = {9, 15, 1, 1, 6, 10, 3, 10, 9, 6, 1, 7, 6, 15, 3, 2, 13, 7, 14, 5, 0, 7, 11,
+                                           2, 13, 0, 12, 8, 2, 5, 11, 13, 4, 15, 14, 12, 9, 10, 11, 3, 14, 8, 5, 4, 4};
+__constant__ signed char kLeafSlot9[45] = {0, 0, 0, 1, 0, 0, 0, 1, 1, 1, 2, 0, 2, 1, 1, 0, 0, 1, 0, 0, 0, 2, 0,
+                                           1, 1, 1, 0, 0, 2, 1, 1, 2, 0, 2, 1, 1, 2, 2, 2, 2, 2, 1, 2, 1, 2};
 
 template <int NSLOT>
 __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restrict__ jobs,
@@ -460,16 +490,19 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
         const bool sweeps_next = k + 1 < T && w == diag_owner(k + 1);   // holds the diagonal tile of block k + 1
         if (sweeps_next) {
             const int slot = diag_slot(k + 1);
+            // the update of that tile and its sweep are one long dependent chain and bound the step: they issue
+            // ahead of the other wavefronts' products, which also leave the first LDS reads to this wavefront
+            __builtin_amdgcn_s_setprio(3);
 #pragma unroll
             for (int s = 0; s < NSLOT; ++s)
                 if (s == slot)
                     lb_mma_planes(acc[s], Pq + (32 * (k + 1) + l32) * LB_LQ + 8 * h, LB_PLANE,
                                   Rq + (32 * (k + 1) + l32) * LB_LQ + 8 * h, LB_PLANE);
-            // the sweep is one long dependent chain: let it issue ahead of the other wavefronts' products
-            __builtin_amdgcn_s_setprio(3);
             const int badl = lb_sweep_diag<NSLOT>(acc, slot, k + 1, l32, h, Dq);
             __builtin_amdgcn_s_setprio(0);
             if (badl != 0 && lane == 0 && bad_s == 0) bad_s = badl;   // blocks are swept in order: the first one stays
+        } else if (k + 1 < T) {
+            __builtin_amdgcn_s_sleep(3);
         }
 #pragma unroll
         for (int s = 0; s < NSLOT; ++s) {
