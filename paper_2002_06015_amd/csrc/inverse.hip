@@ -454,6 +454,7 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
         const int badl = lb_sweep_diag<NSLOT>(acc, diag_slot(0), 0, l32, h, Dq);
         if (badl != 0 && lane == 0) bad_s = badl;
     }
+    __syncthreads();   // D of block 0 is in LDS
     for (int k = 0; k < T; ++k) {
         // (per-step copies of the lane coordinates: as loop invariants, the 32 lane masks of the
         // sweep and the LDS addresses below would be hoisted and kept live across the whole loop)
@@ -467,7 +468,12 @@ __global__ __launch_bounds__(1024) void leaf_block_kernel(const LeafJob *__restr
             if (tj[s] == k && ti[s] > k) lb_store_rows(Rq, LB_PLANE, 32 * ti[s], acc[s], l32, h);
             else if (ti[s] == k && tj[s] < k) lb_store_cols(Rq, LB_PLANE, 32 * tj[s], acc[s], l32, h);
         }
-        __syncthreads();   // R and (from the previous step or the prologue) D of block k are in LDS
+        // A wavefront forms P from the panel rows it has just written itself and from D (in LDS since the
+        // barrier that ended the previous step or the prologue): its own LDS accesses stay in order, so no
+        // workgroup barrier is needed here, only the guarantee that they are not reordered.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         // ---- the tiles of block row / column k take their new value P_i = R_i D (tile (i,k)) or its transpose
         // D R_i^T (tile (k,i)) straight from the product, and put P into LDS for everybody else
 #pragma unroll
