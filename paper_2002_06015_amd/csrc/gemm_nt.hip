@@ -57,6 +57,43 @@ __device__ __forceinline__ void tri_decode(int t, int &tm, int &tn)
     tn = t - r * (r + 1) / 2;
 }
 
+// Tile index -> tile coordinates.  The tiles are numbered in bands of g tile rows, column by column inside a
+// band, so that the run of consecutive tiles which an XCD works on at one time is a g x (run / g) block:
+// it touches g + run / g operand panels instead of 1 + run (one tile row), and each panel is brought into that
+// XCD's L2 once for the whole block.  g grows with the problem (about the square root of an XCD's share of the
+// tiles, at most 8).  Symmetric problems number the tiles of the lower triangle (tn <= tm) the same way; the
+// band that crosses the diagonal ends in a small triangle.  Bijective on [0, n_tiles); the partial tiles of
+// split contractions and their reduction use the same numbering.
+__device__ __forceinline__ void decode_tile(const GemmProblem &P, int t, int &tm, int &tn)
+{
+    const int g = min(8, max(1, (int)ceilf(sqrtf((float)P.n_tiles * 0.125f))));
+    if (P.flags & GEMM_SYM) {
+        // band s holds rows s g .. s g + rows - 1 and starts at tile number T(s g), T(r) = r (r + 1) / 2
+        int r0;
+        tri_decode(t, r0, tn);                       // r0: the row whose plain numbering contains t
+        const int s = r0 / g, first = s * g;
+        const int rows = min(g, P.tiles_m - first);
+        const int u = t - first * (first + 1) / 2;   // index inside the band
+        const int full = first * rows;               // tiles of the band left of its diagonal block
+        if (u < full) {
+            tn = u / rows;
+            tm = first + (u - tn * rows);
+        } else {
+            int rr, cc;
+            tri_decode(u - full, rr, cc);
+            tm = first + rr;
+            tn = first + cc;
+        }
+    } else {
+        const int band = g * P.tiles_n;
+        const int s = t / band, first = s * g;
+        const int rows = min(g, P.tiles_m - first);
+        const int u = t - s * band;
+        tn = u / rows;
+        tm = first + (u - tn * rows);
+    }
+}
+
 // Final write of a ROWS x COLS slab of accumulated sums held in LDS (T[r][c] at
 // T[r * (COLS + 1) + c], global position (gi0 + r, gj0 + c)):
 //     C[i][j] = alpha * T + beta * C[i][j]
@@ -892,8 +929,7 @@ __device__ __forceinline__ void gemm_nt_f32_body(const GemmProblem *__restrict__
     const int split = local / P.n_tiles;
     const int tile = local - split * P.n_tiles;
     int tm, tn;
-    if (P.flags & GEMM_SYM) tri_decode(tile, tm, tn);
-    else { tm = tile / P.tiles_n; tn = tile - tm * P.tiles_n; }
+    decode_tile(P, tile, tm, tn);
     const int k0 = split * P.k_per_split;
     const int k1 = min(P.K, k0 + P.k_per_split);
     const int tid = threadIdx.x;
@@ -1457,8 +1493,7 @@ __device__ __forceinline__ void gemm_nt_bf16_body(const GemmProblem &P, int loca
     const int split = local / P.n_tiles;
     const int tile = local - split * P.n_tiles;
     int tm, tn;
-    if (P.flags & GEMM_SYM) tri_decode(tile, tm, tn);
-    else { tm = tile / P.tiles_n; tn = tile - tm * P.tiles_n; }
+    decode_tile(P, tile, tm, tn);
     const int k0 = split * P.k_per_split;
     const int k1 = min(P.K, k0 + P.k_per_split);
     const int tid = threadIdx.x;
@@ -1608,8 +1643,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmProblem *__r
     const int tile = local / slabs;
     const int slab = local - tile * slabs;
     int tm, tn;
-    if (P.flags & GEMM_SYM) tri_decode(tile, tm, tn);
-    else { tm = tile / P.tiles_n; tn = tile - tm * P.tiles_n; }
+    decode_tile(P, tile, tm, tn);
     if (tm * B + slab * 32 >= P.M) return;
     if (B == 128) reduce_slab<128>(P, tile, slab, tm, tn, T);
     else          reduce_slab<64>(P, tile, slab, tm, tn, T);
