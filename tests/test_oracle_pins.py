@@ -386,3 +386,37 @@ def test_accumulating_micro_batches_gives_the_whole_batch_statistics():
     whole = layer._replace(N=12)
     Ar, Gr = oracle.kfac_stats(tuple(whole), np.concatenate(acts), np.concatenate(grads), 0.0, True, None, None)
     assert np.allclose(A, Ar, rtol=1e-12, atol=1e-18) and np.allclose(G, Gr, rtol=1e-12, atol=1e-18)
+
+
+def test_whole_chain_on_a_small_convolution_is_the_dense_damped_solve():
+    """Two mini-batches through stats (running average) -> invert -> precondition on a 3x3 convolution with bias
+    and spatially averaged gradients, against the same quantities written out with library routines only:
+    patches from torch's unfold, the averages as plain sums, pi from the traces (Sec. 3.3, Eq. 12), and the
+    preconditioned gradient as the solution of the dense system (G + gamma/pi I) (x) (A + gamma pi I) u = vec(grad W)."""
+    layer = (3, 2, 4, 3, 1, 1, 5, 4, 1)
+    N, c_in, c_out, k, s, p, h_in, w_in, _ = layer
+    dA, dG, h, w = oracle.layer_dims(layer)
+    decay, gamma = 0.8, 0.05
+    A = G = None
+    A_ref, G_ref = np.zeros((dA, dA)), np.zeros((dG, dG))
+    for step in range(2):
+        act, grad = _rand_act(layer), _rand_grad(layer) * 1e3
+        d = 0.0 if step == 0 else decay
+        A, G = oracle.kfac_stats(layer, act, grad, d, True, A, G)
+        cols = torch.nn.functional.unfold(torch.from_numpy(act), k, padding=p, stride=s).numpy()   # [N, c_in k^2, h w]
+        rows = np.concatenate([cols, np.ones((N, 1, h * w))], axis=1)                            # the bias row
+        A_new = sum(rows[n] @ rows[n].T for n in range(N)) / (N * h * w)
+        gm = grad.reshape(N, c_out, h * w)
+        G_new = sum(gm[n] @ gm[n].T for n in range(N)) / (N * h * w)
+        A_ref = d * A_ref + (1 - d) * A_new
+        G_ref = d * G_ref + (1 - d) * G_new
+    np.testing.assert_allclose(A, A_ref, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(G, G_ref, rtol=1e-12, atol=1e-14)
+    V = RNG.standard_normal((dG, dA))
+    Ai, Gi, pi, info = oracle.kfac_invert(A, G, gamma)
+    assert not info.any()
+    U = oracle.kfac_precondition(Gi, Ai, V)
+    pi_ref = math.sqrt((np.trace(A_ref) / dA) / (np.trace(G_ref) / dG))
+    assert pi == pytest.approx(pi_ref, rel=1e-12)
+    dense = np.kron(G_ref + gamma / pi_ref * np.eye(dG), A_ref + gamma * pi_ref * np.eye(dA))
+    np.testing.assert_allclose(U.reshape(-1), np.linalg.solve(dense, V.reshape(-1)), rtol=1e-9, atol=1e-12)
