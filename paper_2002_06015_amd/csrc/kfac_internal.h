@@ -32,7 +32,8 @@ struct Operand {
                 // contracted in place); a chunk is 16 bytes of adjacent rows at one m, rows a whole number of chunks
 };
 
-// GEMM_SYM:    M == N and a == b; only tiles tm >= tn are computed and mirrored.
+// GEMM_SYM:    M == N and the product is symmetric (a == b, or a b^T symmetric by construction as in the Schur
+//              complements of the inversion); only tiles tm >= tn are computed and mirrored.
 // GEMM_BORDER: (with GEMM_SYM) C is (M+1) x (M+1): the product of the operand extended by
 //              an all-ones row (the bias row of the patch matrix, Sec. 3.3).  The border is
 //              not multiplied out: C[i][M] = C[M][i] = alpha * sum_m a(i, m) + beta * old
