@@ -622,7 +622,9 @@ __device__ __forceinline__ float fill_remainder_split(const Operand &op, int til
     return x[0] + x[1] + x[2];
 }
 
-template <int TM, int TN, bool LIVE, bool RS>
+// SAME: a and b are the same operand tile (a diagonal tile of a Gram matrix): it is loaded, split and stored
+// once, and the fragments of b are read from the rows of a.
+template <int TM, int TN, bool LIVE, bool RS, bool SAME>
 __device__ __forceinline__ void gemm_split_mainloop(const GemmProblem &P, int tm, int tn, int tid,
                                                     LoaderF32<64 * TM> &la, LoaderF32<64 * TN> &lb, unsigned short *lds,
                                                     int k0, int k1, int wave_m, int wave_n, int l32, int half,
@@ -645,11 +647,21 @@ __device__ __forceinline__ void gemm_split_mainloop(const GemmProblem &P, int tm
 
     auto load_tile = [&](int it, auto &ra, auto &rb, bool &za, bool &zb) {
         if (it < nfull) {
-            if (it > 0) { la.advance(); lb.advance(); }
-            la.load_full(ra); lb.load_full(rb);
+            if constexpr (SAME) {
+                if (it > 0) la.advance();
+                la.load_full(ra);
+            } else {
+                if (it > 0) { la.advance(); lb.advance(); }
+                la.load_full(ra); lb.load_full(rb);
+            }
         } else if (it < nvec) {
             if (careful) {
-                la.load_careful(ra, k0 + klen4); lb.load_careful(rb, k0 + klen4);
+                la.load_careful(ra, k0 + klen4);
+                if constexpr (!SAME) lb.load_careful(rb, k0 + klen4);
+            } else if constexpr (SAME) {
+                la.seek(k0 + klen4 - KT);
+                la.load_full(ra);
+                la.zero_below(k0 + nfull * KT);
             } else {
                 la.seek(k0 + klen4 - KT); lb.seek(k0 + klen4 - KT);
                 la.load_full(ra); lb.load_full(rb);
@@ -663,16 +675,16 @@ __device__ __forceinline__ void gemm_split_mainloop(const GemmProblem &P, int tm
             float unused[BN / 32];
             la.zero_all = za; lb.zero_all = zb;
             store_split<BM, RS>(la, ra, lds, PLANE, rs);
-            store_split<BN, false>(lb, rb, lds + BM * LDQ, PLANE, unused);
+            if constexpr (!SAME) store_split<BN, false>(lb, rb, lds + BM * LDQ, PLANE, unused);
         } else {
             rs_rem = fill_remainder_split<BM>(P.a, tm * BM, k0 + klen4, k1, tid, lds, PLANE);
-            fill_remainder_split<BN>(P.b, tn * BN, k0 + klen4, k1, tid, lds + BM * LDQ, PLANE);
+            if constexpr (!SAME) fill_remainder_split<BN>(P.b, tn * BN, k0 + klen4, k1, tid, lds + BM * LDQ, PLANE);
         }
     };
     // v_mfma_f32_32x32x16_bf16: a lane supplies 8 consecutive k of row lane % 32, the half-waves
     // two different groups of 8; step u of a tile uses k = 16u + 8*half + 0..7 for both operands
     const int off_a = (wave_m * 32 * TM + lds_row(l32)) * LDQ + 8 * half;
-    const int off_b = BM * LDQ + (wave_n * 32 * TN + lds_row(l32)) * LDQ + 8 * half;
+    const int off_b = (SAME ? 0 : BM * LDQ) + (wave_n * 32 * TN + lds_row(l32)) * LDQ + 8 * half;
     // One step: the fragments of the h and m planes and of l' are requested up front, the l
     // fragments of the a operand take over the registers of h once its products are issued (their
     // latency lies under the m products).  Fixed order (the scheduling barriers keep the compiler
@@ -719,7 +731,8 @@ __device__ __forceinline__ void gemm_split_mainloop(const GemmProblem &P, int tm
         }
     };
 
-    la.seek(k0); lb.seek(k0);
+    if constexpr (SAME) la.seek(k0);
+    else { la.seek(k0); lb.seek(k0); }
     load_tile(0, ra0, rb0, za0, zb0);
     load_tile(1, ra1, rb1, za1, zb1);
     for (int it = 0; it < nk; it += 2) {
@@ -962,12 +975,21 @@ __device__ __forceinline__ void gemm_nt_f32_body(const GemmProblem *__restrict__
     float rs[BM / 32], rs_rem = 0.f;
 #pragma unroll
     for (int s = 0; s < BM / 32; ++s) rs[s] = 0.f;
+    // a diagonal tile of a Gram matrix (a and b the same operand) stages its operand tile once (64 x 64 tiles
+    // only: the large tile has no registers to spare for one more copy of the main loop)
+    constexpr bool CAN_SHARE = SPLIT && TM == 1 && TN == 1;
+    const bool same = CAN_SHARE && tm == tn && P.a.base == P.b.base && P.a.row_stride == P.b.row_stride &&
+                      P.a.batch_stride == P.b.batch_stride && P.a.hw == P.b.hw && P.a.rows == P.b.rows;
     auto mainloop = [&](auto live_c, auto rs_c) {
         constexpr bool LV = decltype(live_c)::value, RSUM = decltype(rs_c)::value;
-        if constexpr (SPLIT)
-            gemm_split_mainloop<TM, TN, LV, RSUM>(P, tm, tn, tid, la, lb, (unsigned short *)lds, k0, k1, wave_m, wave_n,
-                                                  l32, half, acc, rs, rs_rem);
-        else
+        if constexpr (SPLIT) {
+            if (CAN_SHARE && same)
+                gemm_split_mainloop<TM, TN, LV, RSUM, CAN_SHARE>(P, tm, tn, tid, la, lb, (unsigned short *)lds, k0, k1,
+                                                                 wave_m, wave_n, l32, half, acc, rs, rs_rem);
+            else
+                gemm_split_mainloop<TM, TN, LV, RSUM, false>(P, tm, tn, tid, la, lb, (unsigned short *)lds, k0, k1, wave_m,
+                                                             wave_n, l32, half, acc, rs, rs_rem);
+        } else
             gemm_f32_mainloop<TM, TN, LV, RSUM>(P, tm, tn, tid, la, lb, lds, k0, k1, wave_m, wave_n, l32, half, acc, rs,
                                                 rs_rem);
     };
@@ -1239,7 +1261,8 @@ __device__ __forceinline__ void mma_frag16(const FragBF16<TM, TN> &f, floatx16 (
                                                                 __builtin_bit_cast(bf16x8, f.b[j]), acc[i][j], 0, 0, 0);
 }
 
-template <int TM, int TN, bool LIVE, bool RS, bool TAIL>
+// SAME: as in gemm_split_mainloop (a diagonal tile of a Gram matrix stages its operand tile once).
+template <int TM, int TN, bool LIVE, bool RS, bool TAIL, bool SAME>
 __device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm, int tn, int tid,
                                                    LoaderBF16<64 * TM, TAIL> &la, LoaderBF16<64 * TN, TAIL> &lb,
                                                    unsigned short *lds, int k0, int k1, int wave_m, int wave_n,
@@ -1260,11 +1283,21 @@ __device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm,
 
     auto load_tile = [&](int it) {
         if (it < nfull) {
-            if (it > 0) { la.advance(); lb.advance(); }
-            la.load_full(ra); lb.load_full(rb);
+            if constexpr (SAME) {
+                if (it > 0) la.advance();
+                la.load_full(ra);
+            } else {
+                if (it > 0) { la.advance(); lb.advance(); }
+                la.load_full(ra); lb.load_full(rb);
+            }
         } else if (it < nvec) {
             if (careful) {
-                la.load_careful(ra, k0 + klen8); lb.load_careful(rb, k0 + klen8);
+                la.load_careful(ra, k0 + klen8);
+                if constexpr (!SAME) lb.load_careful(rb, k0 + klen8);
+            } else if constexpr (SAME) {
+                la.seek(k0 + klen8 - KTH);
+                la.load_full(ra);
+                la.zero_below(k0 + nfull * KTH);
             } else {
                 la.seek(k0 + klen8 - KTH); lb.seek(k0 + klen8 - KTH);
                 la.load_full(ra); lb.load_full(rb);
@@ -1277,16 +1310,17 @@ __device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm,
         if (it < nvec) {
             float unused[BN / 32];
             la.template store_lds<RS>(ra, sa, rs);
-            lb.template store_lds<false>(rb, sb, unused);
+            if constexpr (!SAME) lb.template store_lds<false>(rb, sb, unused);
         } else {
             rs_rem = LoaderBF16<BM>::fill_remainder(P.a, tm * BM, k0 + klen8, k1, tid, sa);
-            LoaderBF16<BN>::fill_remainder(P.b, tn * BN, k0 + klen8, k1, tid, sb);
+            if constexpr (!SAME) LoaderBF16<BN>::fill_remainder(P.b, tn * BN, k0 + klen8, k1, tid, sb);
         }
     };
     const int off_a = (wave_m * 32 * TM + l32) * LDH + 8 * half;
-    const int off_b = BM * LDH + (wave_n * 32 * TN + l32) * LDH + 8 * half;
+    const int off_b = (SAME ? 0 : BM * LDH) + (wave_n * 32 * TN + l32) * LDH + 8 * half;
 
-    la.seek(k0); lb.seek(k0);
+    if constexpr (SAME) la.seek(k0);
+    else { la.seek(k0); lb.seek(k0); }
     load_tile(0);
     store_tile(0);
     load_tile(1);
@@ -1314,20 +1348,25 @@ __device__ __forceinline__ void gemm_bf16_mainloop(const GemmProblem &P, int tm,
     auto fast_step = [&](int it) {
         const unsigned short *cur = lds + (it & 1) * STAGE;
         unsigned short *nxt = lds + ((it + 1) & 1) * STAGE;
-        constexpr int SA = BM / 32, SB = BN / 32, NOPS = 2 * (SA + SB);
+        constexpr int SA = BM / 32, SB = SAME ? 0 : BN / 32, NOPS = 2 * (SA + SB);
         constexpr int NMMA = LIVE ? 3 * TM * TN : 1;   // matrix instructions ahead of the barrier
         constexpr int PER = (NOPS + NMMA - 1) / NMMA;
         auto side_op = [&](int k) {   // k-th of: stores of a, stores of b, loads of a, loads of b
             if (k < SA) {
                 la.template store_slot<RS>(ra, nxt, rs, k);
             } else if (k < SA + SB) {
-                float unused[SB];
-                lb.template store_slot<false>(rb, nxt + BM * LDH, unused, k - SA);
+                if constexpr (!SAME) {
+                    float unused[BN / 32];
+                    lb.template store_slot<false>(rb, nxt + BM * LDH, unused, k - SA);
+                }
             } else if (k < 2 * SA + SB) {
-                if (k == SA + SB) { la.advance_once(); lb.advance_once(); }
+                if (k == SA + SB) {
+                    if constexpr (SAME) la.advance_once();
+                    else { la.advance_once(); lb.advance_once(); }
+                }
                 la.load_slot(ra, k - SA - SB);
             } else if (k < NOPS) {
-                lb.load_slot(rb, k - 2 * SA - SB);
+                if constexpr (!SAME) lb.load_slot(rb, k - 2 * SA - SB);
             }
         };
         if constexpr (LIVE) {
@@ -1533,13 +1572,27 @@ __device__ __forceinline__ void gemm_nt_bf16_body(const GemmProblem &P, int loca
             if (live) gemm_bf16_mainloop_trans<TM, TN, true, false>(P, tm, tn, tid, lds16, k0, k1, wave_m, wave_n, lane, acc, rst);
             else      gemm_bf16_mainloop_trans<TM, TN, false, false>(P, tm, tn, tid, lds16, k0, k1, wave_m, wave_n, lane, acc, rst);
         }
-    } else if (border) {
-        if (live) gemm_bf16_mainloop<TM, TN, true, true, TAIL>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
-        else      gemm_bf16_mainloop<TM, TN, false, true, TAIL>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
-        finish_row_sums<BM>(P, lds, tm, tile, split, tid, rs, rs_rem);
     } else {
-        if (live) gemm_bf16_mainloop<TM, TN, true, false, TAIL>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
-        else      gemm_bf16_mainloop<TM, TN, false, false, TAIL>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        // a diagonal tile of a Gram matrix (a and b the same operand) stages its operand tile once (64 x 64 tiles
+        // only: the large tile has no registers to spare for one more copy of the main loop)
+        constexpr bool CAN_SHARE = TM == 1 && TN == 1;
+        const bool same = CAN_SHARE && tm == tn && P.a.base == P.b.base && P.a.row_stride == P.b.row_stride &&
+                          P.a.batch_stride == P.b.batch_stride && P.a.hw == P.b.hw && P.a.rows == P.b.rows;
+        auto mainloop = [&](auto live_c, auto rs_c) {
+            constexpr bool LV = decltype(live_c)::value, RSUM = decltype(rs_c)::value;
+            if (CAN_SHARE && same)
+                gemm_bf16_mainloop<TM, TN, LV, RSUM, TAIL, CAN_SHARE>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+            else
+                gemm_bf16_mainloop<TM, TN, LV, RSUM, TAIL, false>(P, tm, tn, tid, la, lb, lds16, k0, k1, wave_m, wave_n, l32, half, acc, rs, rs_rem);
+        };
+        if (border) {
+            if (live) mainloop(std::true_type{}, std::true_type{});
+            else      mainloop(std::false_type{}, std::true_type{});
+            finish_row_sums<BM>(P, lds, tm, tile, split, tid, rs, rs_rem);
+        } else {
+            if (live) mainloop(std::true_type{}, std::false_type{});
+            else      mainloop(std::false_type{}, std::false_type{});
+        }
     }
 
     if (P.splits > 1) {
